@@ -1,0 +1,118 @@
+/*
+ * CPU oracle for segmented / full sum-reduction and inclusive scan of binary16 data.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the yardstick the HIP library is checked
+ * against; nothing in the product path may call it.  It shares no code, header,
+ * table or helper with the HIP sources.
+ *
+ * What it computes is the plain definition given at the start of Section 3 of the
+ * paper ("Reduction and Scan on GPUs"):
+ *   - the reduction of a vector is the sum of its elements;
+ *   - the scan (prefix sum) of a vector is the vector of running sums, the first
+ *     entry being the first element and the last entry being the total, i.e. the
+ *     scan is inclusive;
+ *   - the regular segmented forms apply the same operation independently to
+ *     consecutive, equally sized pieces of the input.
+ * The matrix-product algorithms of Sections 4 and 5 reach exactly these results (up
+ * to the order of floating-point additions), so the oracle is the definition written
+ * out: one left-to-right loop per segment, accumulating in binary64.  Each binary16
+ * input is widened exactly (every binary16 value is representable in binary64) by a
+ * bit-level decoder written here; no half-precision library type is used.
+ *
+ * All pointers are host pointers.  Functions return 0 on success, 1 on a bad argument
+ * (null pointer with n > 0, seg_len == 0, or n not a multiple of seg_len).
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+/* binary16 bit pattern -> binary64 value: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+double oracle_half_to_double(uint16_t h)
+{
+    const int sign = (h >> 15) & 1;
+    const int expo = (h >> 10) & 0x1f;
+    const int frac = h & 0x3ff;
+    double v;
+    if (expo == 0) {
+        v = ldexp((double)frac, -24);                 /* zero and subnormals: frac * 2^-24 */
+    } else if (expo == 31) {
+        v = frac ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(1024 + frac), expo - 25);  /* (1 + frac/1024) * 2^(expo-15) */
+    }
+    return sign ? -v : v;
+}
+
+static int bad_args(const void *in, const void *out, uint64_t n, uint64_t seg_len)
+{
+    if (seg_len == 0) return 1;
+    if (n % seg_len != 0) return 1;
+    if (n > 0 && (in == NULL || out == NULL)) return 1;
+    return 0;
+}
+
+/* out[s] = sum_{k=0}^{seg_len-1} in[s*seg_len + k],   s = 0 .. n/seg_len - 1. */
+int oracle_segmented_reduce(const uint16_t *in, double *out, uint64_t n, uint64_t seg_len)
+{
+    if (bad_args(in, out, n, seg_len)) return 1;
+    const uint64_t segs = n / seg_len;
+    for (uint64_t s = 0; s < segs; ++s) {
+        double acc = 0.0;
+        for (uint64_t k = 0; k < seg_len; ++k)
+            acc += oracle_half_to_double(in[s * seg_len + k]);
+        out[s] = acc;
+    }
+    return 0;
+}
+
+/* out[s*seg_len + k] = sum_{j=0}^{k} in[s*seg_len + j]   (inclusive). */
+int oracle_segmented_scan(const uint16_t *in, double *out, uint64_t n, uint64_t seg_len)
+{
+    if (bad_args(in, out, n, seg_len)) return 1;
+    const uint64_t segs = n / seg_len;
+    for (uint64_t s = 0; s < segs; ++s) {
+        double acc = 0.0;
+        for (uint64_t k = 0; k < seg_len; ++k) {
+            acc += oracle_half_to_double(in[s * seg_len + k]);
+            out[s * seg_len + k] = acc;
+        }
+    }
+    return 0;
+}
+
+/* Full (unsegmented) forms: one segment that spans the whole input. */
+int oracle_reduce(const uint16_t *in, double *out, uint64_t n)
+{
+    if (n == 0) {
+        if (out) out[0] = 0.0;
+        return out ? 0 : 1;
+    }
+    return oracle_segmented_reduce(in, out, n, n);
+}
+
+int oracle_scan(const uint16_t *in, double *out, uint64_t n)
+{
+    if (n == 0) return 0;
+    return oracle_segmented_scan(in, out, n, n);
+}
+
+/*
+ * Sampled inclusive-scan outputs, one by one: out[q] = sum of in[first .. idx[q]] where
+ * first is the start of the segment containing idx[q].  Used to check a few outputs of
+ * an input too large to scan and hold on the host in binary64.
+ */
+int oracle_segmented_scan_at(const uint16_t *in, uint64_t n, uint64_t seg_len,
+                             const uint64_t *idx, uint64_t count, double *out)
+{
+    if (seg_len == 0 || n % seg_len != 0) return 1;
+    if (count > 0 && (in == NULL || idx == NULL || out == NULL)) return 1;
+    for (uint64_t q = 0; q < count; ++q) {
+        if (idx[q] >= n) return 1;
+        const uint64_t first = idx[q] - idx[q] % seg_len;
+        double acc = 0.0;
+        for (uint64_t k = first; k <= idx[q]; ++k)
+            acc += oracle_half_to_double(in[k]);
+        out[q] = acc;
+    }
+    return 0;
+}
