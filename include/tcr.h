@@ -1,0 +1,106 @@
+/*
+ * tcr -- segmented and full sum-reduction and inclusive prefix scan of IEEE binary16 data
+ * with binary32 accumulation and output, for AMD MI355X (gfx950).
+ *
+ * The operations are the ones defined at the start of Section 3 of "Accelerating Reduction
+ * and Scan Using Tensor Core Units" (ICS'19): reduction is the sum of a vector, scan is its
+ * vector of running sums (inclusive: first entry = first element, last entry = total), and
+ * the regular segmented forms apply them to consecutive pieces of equal length.  They are
+ * evaluated the way Sections 4 and 5 describe -- as small matrix products of the data with
+ * constant ones / triangular matrices on the matrix cores -- re-derived for CDNA4 MFMA.
+ *
+ * Conventions common to every call
+ *   in      DEVICE pointer to n binary16 values, contiguous, 16-byte aligned, read only.
+ *   out     DEVICE pointer, caller owned, must not overlap `in`; alignment stated per call.
+ *   stream  a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *           and return; they never synchronise with the host.
+ *   Inputs must be finite.  (A zero entry of a constant matrix times an infinity is NaN, so
+ *   non-finite inputs poison outputs that the plain definition would leave finite.)
+ *   Results for integer-valued inputs whose partial sums stay below 2^24 in magnitude are
+ *   exact.  For other inputs the order of the binary32 additions is unspecified and, for
+ *   operations that need a cross-workgroup carry, may differ from run to run.
+ *   Argument errors are reported synchronously and nothing is enqueued.  Device-side faults
+ *   surface at the caller's next synchronisation.
+ *   The library keeps one small workspace per (device, stream), grown on demand by the first
+ *   call that needs it; calls issued on one stream are ordered by the stream.  Calls that
+ *   share a stream from several host threads must be serialised by the caller.
+ *   There is no CPU fallback: without a usable HIP device every call returns TCR_ERR_HIP.
+ */
+#ifndef TCR_H
+#define TCR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TCR_OK = 0,
+    TCR_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, seg_len == 0, n % seg_len != 0 */
+    TCR_ERR_UNSUPPORTED = 2,   /* a size or variant this build has no kernel for */
+    TCR_ERR_WORKSPACE = 3,     /* workspace allocation failed */
+    TCR_ERR_HIP = 4            /* a HIP runtime call failed (see tcr_last_hip_error) */
+} tcr_status;
+
+/*
+ * Regular segmented sum reduction (Section 3; algorithms of Section 4).
+ *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
+ * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
+ */
+tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
+
+/*
+ * Regular segmented inclusive scan (Section 3; algorithms of Section 5).
+ *   out[s*seg_len + k] = sum_{j <= k} in[s*seg_len + j].
+ * out: n floats, 16-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
+ */
+tcr_status tcr_segmented_scan(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
+
+/*
+ * Full reduction (device level, Section 4): out[0] = sum of all n inputs (0 for n == 0).
+ * Any n is accepted.  out: 1 float.
+ */
+tcr_status tcr_reduce(const void *in, float *out, uint64_t n, void *stream);
+
+/*
+ * Full inclusive scan (device level, Section 5): out[k] = sum_{j <= k} in[j].
+ * Any n is accepted.  out: n floats, 16-byte aligned.
+ */
+tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
+
+/*
+ * Bench / test hook: choose among measured alternatives.  Keys and values:
+ *   "formulation"  "mfma" (default: matrix-core products) | "dpp" (cross-lane wavefront primitives)
+ *   "scan_carry"   "lookback" (default: single pass, decoupled look-back) | "reduce_then_scan"
+ *   "reset"        any value: back to the defaults
+ * Returns TCR_ERR_INVALID_ARG for an unknown key or value.  Process-wide; not thread safe.
+ */
+tcr_status tcr_set_variant(const char *key, const char *value);
+
+/*
+ * Name of the kernel the dispatcher would launch for (op, n, seg_len) under the current
+ * variant settings; op is 0 = segmented_reduce, 1 = segmented_scan, 2 = reduce, 3 = scan.
+ * Returns a static string ("" when nothing would be launched); never NULL.
+ */
+const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);
+
+/*
+ * Waits for `stream` and reports whether any scan kernel issued so far on the current
+ * device gave up waiting for a predecessor tile's carry (a bounded wait that should never
+ * expire).  Returns TCR_OK if none did, TCR_ERR_HIP otherwise.  Synchronises; for tests.
+ */
+tcr_status tcr_check_device_flags(void *stream);
+
+/* Frees every library-owned workspace.  The caller must have synchronised all streams. */
+void tcr_release(void);
+
+const char *tcr_status_string(tcr_status s);
+
+/* Text of the last HIP error seen by this library on the calling thread ("" if none). */
+const char *tcr_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TCR_H */

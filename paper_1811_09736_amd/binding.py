@@ -1,0 +1,167 @@
+"""Thin ctypes binding over the C ABI of libtcr.so (include/tcr.h).
+
+Argument marshalling only: device pointers, sizes and the stream handle are passed
+through; every step of the computation runs in the HIP kernels.  PyTorch supplies
+device memory and streams, nothing else.  If the library has not been built the
+import of this module fails -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .build import LIB_PATH
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
+OP_SEGMENTED_REDUCE, OP_SEGMENTED_SCAN, OP_REDUCE, OP_SCAN = range(4)
+
+EXPORTS = (
+    "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan", "tcr_set_variant",
+    "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
+)
+
+
+class TcrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.tcr_status_string(status).decode()
+        if status == ERR_HIP:
+            msg += " (" + _lib.tcr_last_hip_error().decode() + ")"
+        super().__init__(f"{where}: {msg}")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, u64, fp = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p
+    lib.tcr_segmented_reduce.argtypes = [vp, fp, u64, u64, vp]
+    lib.tcr_segmented_scan.argtypes = [vp, fp, u64, u64, vp]
+    lib.tcr_reduce.argtypes = [vp, fp, u64, vp]
+    lib.tcr_scan.argtypes = [vp, fp, u64, vp]
+    for name in ("tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.tcr_set_variant.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+    lib.tcr_set_variant.restype = ctypes.c_int
+    lib.tcr_kernel_name.argtypes = [ctypes.c_int, u64, u64]
+    lib.tcr_kernel_name.restype = ctypes.c_char_p
+    lib.tcr_check_device_flags.argtypes = [vp]
+    lib.tcr_check_device_flags.restype = ctypes.c_int
+    lib.tcr_release.argtypes = []
+    lib.tcr_release.restype = None
+    lib.tcr_status_string.argtypes = [ctypes.c_int]
+    lib.tcr_status_string.restype = ctypes.c_char_p
+    lib.tcr_last_hip_error.argtypes = []
+    lib.tcr_last_hip_error.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = _load()
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _check_input(x: torch.Tensor) -> None:
+    if not (x.is_cuda and x.dtype == torch.float16 and x.dim() == 1 and x.is_contiguous()):
+        raise TypeError("input must be a contiguous 1-D float16 CUDA tensor")
+
+
+def _check_output(out: torch.Tensor, numel: int, like: torch.Tensor) -> None:
+    if not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == numel
+            and out.device == like.device):
+        raise TypeError(f"out must be a contiguous float32 CUDA tensor of {numel} elements on the input's device")
+
+
+def segmented_reduce(x: torch.Tensor, seg_len: int, out: Optional[torch.Tensor] = None,
+                     stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_segmented_reduce: out[s] = sum of x[s*seg_len : (s+1)*seg_len]."""
+    _check_input(x)
+    n = x.numel()
+    if seg_len <= 0 or n % seg_len:
+        raise TcrError(ERR_INVALID_ARG, "tcr_segmented_reduce")
+    if out is None:
+        out = torch.empty(n // seg_len, dtype=torch.float32, device=x.device)
+    _check_output(out, n // seg_len, x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_segmented_reduce(x.data_ptr(), out.data_ptr(), n, seg_len, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_segmented_reduce")
+    return out
+
+
+def segmented_scan(x: torch.Tensor, seg_len: int, out: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_segmented_scan: inclusive running sums restarting every seg_len elements."""
+    _check_input(x)
+    n = x.numel()
+    if seg_len <= 0 or n % seg_len:
+        raise TcrError(ERR_INVALID_ARG, "tcr_segmented_scan")
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=x.device)
+    _check_output(out, n, x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_segmented_scan(x.data_ptr(), out.data_ptr(), n, seg_len, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_segmented_scan")
+    return out
+
+
+def reduce(x: torch.Tensor, out: Optional[torch.Tensor] = None,
+           stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_reduce: one-element tensor holding the sum of x."""
+    _check_input(x)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check_output(out, 1, x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_reduce(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_reduce")
+    return out
+
+
+def scan(x: torch.Tensor, out: Optional[torch.Tensor] = None,
+         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_scan: inclusive running sums of x."""
+    _check_input(x)
+    if out is None:
+        out = torch.empty(x.numel(), dtype=torch.float32, device=x.device)
+    _check_output(out, x.numel(), x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_scan(x.data_ptr(), out.data_ptr(), x.numel(), _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_scan")
+    return out
+
+
+def set_variant(key: str, value: str = "") -> None:
+    st = _lib.tcr_set_variant(key.encode(), value.encode())
+    if st != OK:
+        raise TcrError(st, f"tcr_set_variant({key!r}, {value!r})")
+
+
+def kernel_name(op: int, n: int, seg_len: int) -> str:
+    return _lib.tcr_kernel_name(op, n, seg_len).decode()
+
+
+def check_device_flags(stream: Optional[torch.cuda.Stream] = None) -> None:
+    st = _lib.tcr_check_device_flags(_stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_check_device_flags")
+
+
+def release() -> None:
+    _lib.tcr_release()
+
+
+def raw() -> ctypes.CDLL:
+    """The loaded library, for tests that exercise the C ABI's own error paths."""
+    return _lib

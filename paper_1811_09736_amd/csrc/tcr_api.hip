@@ -1,0 +1,421 @@
+// C ABI of the library (declared in include/tcr.h): argument validation, the dispatch from
+// segment length to kernel and launch shape (the role the paper gives its auto-tuner,
+// Section 6), and the per-(device, stream) workspace for cross-workgroup carries.
+#include "../../include/tcr.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <utility>
+
+#include "tcr_reduce.hpp"
+#include "tcr_scan.hpp"
+
+namespace {
+
+using namespace tcr;
+
+thread_local std::string g_hip_error;
+
+bool hip_failed(hipError_t e, const char* what) {
+    if (e == hipSuccess) return false;
+    g_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return true;
+}
+#define TCR_HIP(call)                                   \
+    do {                                                \
+        if (hip_failed((call), #call)) return TCR_ERR_HIP; \
+    } while (0)
+
+// ---------------------------------------------------------------------------- variant settings
+struct Variant {
+    int formulation = kMfma;
+    int scan_carry = kLookback;
+};
+Variant g_variant;
+
+// Launch-shape constants (tiles per wavefront).  A workgroup is 4 wavefronts.
+constexpr int kSmallU = 4;            // reduce_small / scan_small: 4 tiles per wavefront, 8192 elements per workgroup
+constexpr int kScanU = 4;             // scan_block: 8192 elements per workgroup
+constexpr int kReduceU = 4;           // reduce_span: tiles in flight per wavefront
+constexpr uint64_t kReduceSpan = 16384;   // elements one wavefront folds before emitting a partial
+constexpr uint64_t kScanBlockTile = (uint64_t)kTile * kScanU * kWavesPerBlock;
+constexpr uint64_t kMaxElements = 1ull << 40;
+
+// ---------------------------------------------------------------------------- workspace
+struct Workspace {
+    unsigned long long* desc = nullptr;
+    uint64_t desc_capacity = 0;     // tiles
+    float* partials = nullptr;
+    uint64_t partials_capacity = 0; // floats
+    uint32_t* counters = nullptr;   // [0] = ticket, [1] = gave_up flag
+    uint32_t tickets_issued = 0;    // host mirror of counters[0] once all enqueued launches finish
+    uint32_t epoch = 0;
+    bool dirty = true;              // counters / descriptors must be re-zeroed before use
+};
+
+std::mutex g_mutex;
+std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
+
+tcr_status get_workspace(hipStream_t stream, Workspace** out) {
+    int dev = 0;
+    TCR_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    *out = &g_workspaces[std::make_pair(dev, stream)];
+    return TCR_OK;
+}
+
+tcr_status ensure_partials(Workspace* ws, hipStream_t stream, uint64_t floats) {
+    if (floats <= ws->partials_capacity) return TCR_OK;
+    TCR_HIP(hipStreamSynchronize(stream));
+    if (ws->partials) TCR_HIP(hipFree(ws->partials));
+    ws->partials = nullptr;
+    ws->partials_capacity = 0;
+    uint64_t cap = 1;
+    while (cap < floats) cap <<= 1;
+    if (hipMalloc(&ws->partials, cap * sizeof(float)) != hipSuccess) {
+        (void)hipGetLastError();
+        return TCR_ERR_WORKSPACE;
+    }
+    ws->partials_capacity = cap;
+    return TCR_OK;
+}
+
+// Makes room for `tiles` look-back descriptors and starts a new epoch.
+tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, ScanWorkspace* dev) {
+    if (ws->counters == nullptr) {
+        if (hipMalloc(&ws->counters, 2 * sizeof(uint32_t)) != hipSuccess) {
+            (void)hipGetLastError();
+            return TCR_ERR_WORKSPACE;
+        }
+        TCR_HIP(hipMemset(ws->counters, 0, 2 * sizeof(uint32_t)));
+        ws->tickets_issued = 0;
+        ws->dirty = true;
+    }
+    if (tiles > ws->desc_capacity) {
+        TCR_HIP(hipStreamSynchronize(stream));
+        if (ws->desc) TCR_HIP(hipFree(ws->desc));
+        ws->desc = nullptr;
+        ws->desc_capacity = 0;
+        uint64_t cap = 1024;
+        while (cap < tiles) cap <<= 1;
+        if (hipMalloc(&ws->desc, cap * sizeof(unsigned long long)) != hipSuccess) {
+            (void)hipGetLastError();
+            return TCR_ERR_WORKSPACE;
+        }
+        ws->desc_capacity = cap;
+        ws->dirty = true;
+    }
+    if (ws->dirty || ws->epoch >= (1u << 30) - 2u) {
+        // first use, growth, a failed launch, or epoch wrap: start from a clean slate
+        TCR_HIP(hipStreamSynchronize(stream));
+        TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
+        uint32_t keep_flag = 0;
+        TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        uint32_t init[2] = {0u, keep_flag};
+        TCR_HIP(hipMemcpy(ws->counters, init, sizeof(init), hipMemcpyHostToDevice));
+        ws->tickets_issued = 0;
+        ws->epoch = 0;
+        ws->dirty = false;
+    }
+    ws->epoch += 1;
+    dev->desc = ws->desc;
+    dev->ticket = ws->counters;
+    dev->gave_up = ws->counters + 1;
+    dev->ticket_base = ws->tickets_issued;
+    dev->epoch = ws->epoch;
+    return TCR_OK;
+}
+
+// ---------------------------------------------------------------------------- helpers
+__global__ void fill_zero_kernel(float* out, uint64_t count) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) out[i] = 0.0f;
+}
+
+bool is_pow2(uint64_t v) { return v != 0 && (v & (v - 1)) == 0; }
+int log2u(uint64_t v) {
+    int l = 0;
+    while ((1ull << l) < v) ++l;
+    return l;
+}
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+tcr_status check_launch(const char* what) {
+    if (hip_failed(hipGetLastError(), what)) return TCR_ERR_HIP;
+    return TCR_OK;
+}
+
+// ---------------------------------------------------------------------------- reduce dispatch
+template <int FORM>
+tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
+    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * kSmallU * kWavesPerBlock);
+    const dim3 grid((unsigned)blocks), block(kBlockThreads);
+    switch (log2l) {
+        case 4: reduce_small_kernel<FORM, 4, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 5: reduce_small_kernel<FORM, 5, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 6: reduce_small_kernel<FORM, 6, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 7: reduce_small_kernel<FORM, 7, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 8: reduce_small_kernel<FORM, 8, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 9: reduce_small_kernel<FORM, 9, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        default: return TCR_ERR_UNSUPPORTED;
+    }
+    return check_launch("reduce_small_kernel");
+}
+
+// seg_len >= 1024 (power of two) or one segment of any length.
+tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    const uint64_t nseg = n / seg_len;
+    const uint64_t span = seg_len < kReduceSpan ? ceil_div(seg_len, kTile) * kTile : kReduceSpan;
+    const uint64_t per = ceil_div(seg_len, span);          // partials per segment
+    const uint64_t nspans = nseg * per;
+    float* dst = out;
+    Workspace* ws = nullptr;
+    if (per > 1) {
+        tcr_status st = get_workspace(s, &ws);
+        if (st != TCR_OK) return st;
+        st = ensure_partials(ws, s, nspans);
+        if (st != TCR_OK) return st;
+        dst = ws->partials;
+    }
+    const dim3 grid((unsigned)ceil_div(nspans, kWavesPerBlock)), block(kBlockThreads);
+    // spans tile the input uniformly: span w covers [w*span, (w+1)*span) because per*span == seg_len
+    // whenever per > 1 (seg_len is then a power of two >= kReduceSpan) or nseg == 1.
+    if (g_variant.formulation == kMfma)
+        reduce_span_kernel<kMfma, kReduceU><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
+    else
+        reduce_span_kernel<kDpp, kReduceU><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
+    tcr_status st = check_launch("reduce_span_kernel");
+    if (st != TCR_OK) return st;
+    if (per > 1) {
+        reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kBlockThreads), 0, s>>>(dst, out, per);
+        st = check_launch("reduce_final_kernel");
+    }
+    return st;
+}
+
+// ---------------------------------------------------------------------------- scan dispatch
+template <int FORM>
+tcr_status launch_scan_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
+    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * kSmallU * kWavesPerBlock);
+    const dim3 grid((unsigned)blocks), block(kBlockThreads);
+    switch (log2l) {
+        case 4: scan_small_kernel<FORM, 4, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 5: scan_small_kernel<FORM, 5, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 6: scan_small_kernel<FORM, 6, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 7: scan_small_kernel<FORM, 7, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 8: scan_small_kernel<FORM, 8, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 9: scan_small_kernel<FORM, 9, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        default: return TCR_ERR_UNSUPPORTED;
+    }
+    return check_launch("scan_small_kernel");
+}
+
+template <int FORM, int CARRY>
+void launch_scan_block(const _Float16* in, float* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+                       const ScanWorkspace& dev, const float* prefix, unsigned blocks, hipStream_t s) {
+    scan_block_kernel<FORM, kScanU, CARRY><<<dim3(blocks), dim3(kBlockThreads), 0, s>>>(in, out, n, seg_mask, seg_len,
+                                                                                         dev, prefix);
+}
+
+// seg_len >= 1024 (power of two), or the full scan (seg_len == n, any n).
+tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, bool whole, hipStream_t s) {
+    const uint64_t seg_mask = whole ? ~0ull : seg_len - 1;
+    const uint64_t host_seg_len = seg_len;            // decides the launch; the kernels see a saturated
+    if (whole) seg_len = ~0ull;                       // length for the one-segment case (n need not be a power of two)
+    const uint64_t tiles = ceil_div(n, kScanBlockTile);
+    const unsigned blocks = (unsigned)tiles;
+    const bool mfma_form = g_variant.formulation == kMfma;
+    ScanWorkspace dev = {};
+    if (host_seg_len <= kScanBlockTile) {
+        if (mfma_form) launch_scan_block<kMfma, kNoCarry>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
+        else launch_scan_block<kDpp, kNoCarry>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
+        return check_launch("scan_block_kernel");
+    }
+    Workspace* ws = nullptr;
+    tcr_status st = get_workspace(s, &ws);
+    if (st != TCR_OK) return st;
+    if (g_variant.scan_carry == kLookback) {
+        st = begin_lookback(ws, s, tiles, &dev);
+        if (st != TCR_OK) return st;
+        if (mfma_form) launch_scan_block<kMfma, kLookback>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
+        else launch_scan_block<kDpp, kLookback>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
+        st = check_launch("scan_block_kernel");
+        if (st != TCR_OK) {
+            ws->dirty = true;
+            return st;
+        }
+        ws->tickets_issued += blocks;      // wraps modulo 2^32 like the device counter
+        return TCR_OK;
+    }
+    // reduce-then-scan: workgroup totals, their exclusive scan per segment, then the scan proper
+    st = ensure_partials(ws, s, tiles);
+    if (st != TCR_OK) return st;
+    const dim3 block(kBlockThreads);
+    // one span per workgroup tile; spans are uniform because seg_len is a multiple of the tile (or one segment)
+    if (mfma_form)
+        reduce_span_kernel<kMfma, kReduceU><<<dim3((unsigned)ceil_div(tiles, kWavesPerBlock)), block, 0, s>>>(
+            in, ws->partials, n, kScanBlockTile, tiles);
+    else
+        reduce_span_kernel<kDpp, kReduceU><<<dim3((unsigned)ceil_div(tiles, kWavesPerBlock)), block, 0, s>>>(
+            in, ws->partials, n, kScanBlockTile, tiles);
+    st = check_launch("reduce_span_kernel");
+    if (st != TCR_OK) return st;
+    const uint64_t per = whole ? tiles : host_seg_len / kScanBlockTile;
+    const uint64_t groups = whole ? 1 : n / host_seg_len;
+    scan_partials_kernel<<<dim3((unsigned)groups), block, 0, s>>>(ws->partials, per);
+    st = check_launch("scan_partials_kernel");
+    if (st != TCR_OK) return st;
+    if (mfma_form) launch_scan_block<kMfma, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, blocks, s);
+    else launch_scan_block<kDpp, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, blocks, s);
+    return check_launch("scan_block_kernel");
+}
+
+tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {
+    if (seg_len == 0) return TCR_ERR_INVALID_ARG;
+    if (n % seg_len != 0) return TCR_ERR_INVALID_ARG;
+    if (n == 0) return TCR_OK;
+    if (in == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 16) || !aligned(out, out_align)) return TCR_ERR_INVALID_ARG;
+    if (n > kMaxElements) return TCR_ERR_UNSUPPORTED;
+    return TCR_OK;
+}
+
+}  // namespace
+
+// ================================================================================ C ABI
+
+extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
+    tcr_status st = validate(in, out, n, seg_len, 4);
+    if (st != TCR_OK || n == 0) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const _Float16* x = static_cast<const _Float16*>(in);
+    if (seg_len == n) return reduce_long(x, out, n, n, s);
+    if (!is_pow2(seg_len) || seg_len < 16) return TCR_ERR_UNSUPPORTED;
+    if (seg_len <= kTile)
+        return g_variant.formulation == kMfma ? launch_reduce_small<kMfma>(x, out, n, log2u(seg_len), s)
+                                              : launch_reduce_small<kDpp>(x, out, n, log2u(seg_len), s);
+    return reduce_long(x, out, n, seg_len, s);
+}
+
+extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
+    tcr_status st = validate(in, out, n, seg_len, 16);
+    if (st != TCR_OK || n == 0) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const _Float16* x = static_cast<const _Float16*>(in);
+    if (seg_len == n) return scan_long(x, out, n, n, true, s);
+    if (!is_pow2(seg_len) || seg_len < 16) return TCR_ERR_UNSUPPORTED;
+    if (seg_len <= kTile)
+        return g_variant.formulation == kMfma ? launch_scan_small<kMfma>(x, out, n, log2u(seg_len), s)
+                                              : launch_scan_small<kDpp>(x, out, n, log2u(seg_len), s);
+    return scan_long(x, out, n, seg_len, false, s);
+}
+
+extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* stream) {
+    if (out == nullptr) return TCR_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) {
+        fill_zero_kernel<<<dim3(1), dim3(64), 0, s>>>(out, 1);
+        return check_launch("fill_zero_kernel");
+    }
+    tcr_status st = validate(in, out, n, n, 4);
+    if (st != TCR_OK) return st;
+    return reduce_long(static_cast<const _Float16*>(in), out, n, n, s);
+}
+
+extern "C" tcr_status tcr_scan(const void* in, float* out, uint64_t n, void* stream) {
+    if (n == 0) return TCR_OK;
+    tcr_status st = validate(in, out, n, n, 16);
+    if (st != TCR_OK) return st;
+    return scan_long(static_cast<const _Float16*>(in), out, n, n, true, static_cast<hipStream_t>(stream));
+}
+
+extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
+    if (key == nullptr || value == nullptr) return TCR_ERR_INVALID_ARG;
+    if (std::strcmp(key, "reset") == 0) {
+        g_variant = Variant();
+        return TCR_OK;
+    }
+    if (std::strcmp(key, "formulation") == 0) {
+        if (std::strcmp(value, "mfma") == 0) g_variant.formulation = kMfma;
+        else if (std::strcmp(value, "dpp") == 0) g_variant.formulation = kDpp;
+        else return TCR_ERR_INVALID_ARG;
+        return TCR_OK;
+    }
+    if (std::strcmp(key, "scan_carry") == 0) {
+        if (std::strcmp(value, "lookback") == 0) g_variant.scan_carry = kLookback;
+        else if (std::strcmp(value, "reduce_then_scan") == 0) g_variant.scan_carry = kTable;
+        else return TCR_ERR_INVALID_ARG;
+        return TCR_OK;
+    }
+    return TCR_ERR_INVALID_ARG;
+}
+
+extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
+    if (n == 0 || seg_len == 0 || n % seg_len != 0) return "";
+    const bool mf = g_variant.formulation == kMfma;
+    const bool whole = (op == 2 || op == 3 || seg_len == n);
+    if (op == 2) seg_len = n;
+    if (op == 3) seg_len = n;
+    if (!whole && (!is_pow2(seg_len) || seg_len < 16)) return "";
+    if (op == 0 || op == 2) {
+        if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";
+        if (seg_len <= kReduceSpan) return mf ? "reduce_span_kernel<mfma>" : "reduce_span_kernel<dpp>";
+        return mf ? "reduce_span_kernel<mfma>+reduce_final_kernel" : "reduce_span_kernel<dpp>+reduce_final_kernel";
+    }
+    if (op == 1 || op == 3) {
+        if (!whole && seg_len <= kTile) return mf ? "scan_small_kernel<mfma>" : "scan_small_kernel<dpp>";
+        if (seg_len <= kScanBlockTile) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
+        if (g_variant.scan_carry == kLookback) return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";
+        return mf ? "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<mfma,table>"
+                  : "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<dpp,table>";
+    }
+    return "";
+}
+
+extern "C" tcr_status tcr_check_device_flags(void* stream) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    TCR_HIP(hipStreamSynchronize(s));
+    int dev = 0;
+    TCR_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (auto& kv : g_workspaces) {
+        if (kv.first.first != dev || kv.second.counters == nullptr) continue;
+        uint32_t flag = 0;
+        TCR_HIP(hipMemcpy(&flag, kv.second.counters + 1, sizeof(flag), hipMemcpyDeviceToHost));
+        if (flag != 0) {
+            g_hip_error = "a look-back wait expired";
+            return TCR_ERR_HIP;
+        }
+    }
+    return TCR_OK;
+}
+
+extern "C" void tcr_release(void) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    for (auto& kv : g_workspaces) {
+        Workspace& w = kv.second;
+        if (w.desc) (void)hipFree(w.desc);
+        if (w.partials) (void)hipFree(w.partials);
+        if (w.counters) (void)hipFree(w.counters);
+    }
+    g_workspaces.clear();
+}
+
+extern "C" const char* tcr_status_string(tcr_status s) {
+    switch (s) {
+        case TCR_OK: return "ok";
+        case TCR_ERR_INVALID_ARG: return "invalid argument";
+        case TCR_ERR_UNSUPPORTED: return "unsupported size or variant";
+        case TCR_ERR_WORKSPACE: return "workspace allocation failed";
+        case TCR_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+extern "C" const char* tcr_last_hip_error(void) { return g_hip_error.c_str(); }

@@ -1,0 +1,182 @@
+// Device-side building blocks: 64-lane cross-lane (DPP) primitives, the constant operand
+// matrices, and the 16x16x32 MFMA tile operations on which every kernel is built.
+//
+// Tile convention (the "operand map").  One wavefront owns a tile of 512 consecutive
+// elements, viewed as a row-major 16 x 32 matrix X (row j = elements 32j .. 32j+31).
+// Lane l = j + 16 g (j = l % 16, g = l / 16) loads the 8 binary16 values X[j][8g .. 8g+7]
+// with one 128-bit load; that register quadruple is exactly the B operand of
+// v_mfma_f32_16x16x32_f16 for the product  D = C_const . X^T + Acc,
+//     D[i][j] = sum_k C_const[i][k] * X[j][k] + Acc[i][j],
+// and lane (j, g) receives D[4g .. 4g+3][j] in its four accumulator registers.
+// This is the transposed form of the paper's products (Section 4: P.A reduces columns of a
+// column-major tile; Section 5: A.U scans rows of a row-major tile): the constant sits on
+// the left so that a lane's four results are four *consecutive* elements of the output and
+// go out as one 128-bit store.
+//
+// Only raw input ever enters an MFMA A/B operand (those are binary16).  Every derived
+// quantity -- row totals, carries, running sums -- travels through the binary32 accumulator
+// or through binary32 cross-lane adds, which is what keeps integer-valued results exact.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tcr {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kTile = 512;          // elements per wavefront tile (16 rows x 32)
+constexpr int kRow = 32;            // elements per tile row
+constexpr int kBlockThreads = 256;  // 4 wavefronts per workgroup
+constexpr int kWavesPerBlock = kBlockThreads / kWave;
+
+// ---------------------------------------------------------------- cross-lane primitives
+
+// Value of the lane `N` places lower inside the same row of 16 lanes; 0 where that lane
+// would fall outside the row.
+template <int N>
+__device__ __forceinline__ float row_shr(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x110 + N, 0xf, 0xf, true));
+}
+
+// Inclusive scan over the 16 lanes of each row, restricted to aligned groups of GROUP lanes.
+template <int GROUP>
+__device__ __forceinline__ float row_scan_inclusive(float x, int j) {
+    static_assert(GROUP == 1 || GROUP == 2 || GROUP == 4 || GROUP == 8 || GROUP == 16, "");
+    const int p = j & (GROUP - 1);
+    if constexpr (GROUP > 1) { float v = row_shr<1>(x); x += (p >= 1) ? v : 0.0f; }
+    if constexpr (GROUP > 2) { float v = row_shr<2>(x); x += (p >= 2) ? v : 0.0f; }
+    if constexpr (GROUP > 4) { float v = row_shr<4>(x); x += (p >= 4) ? v : 0.0f; }
+    if constexpr (GROUP > 8) { float v = row_shr<8>(x); x += (p >= 8) ? v : 0.0f; }
+    return x;
+}
+
+// Sum over aligned groups of GROUP lanes of a row; valid in the last lane of each group.
+template <int GROUP>
+__device__ __forceinline__ float row_sum_to_last(float x) {
+    if constexpr (GROUP > 1) x += row_shr<1>(x);
+    if constexpr (GROUP > 2) x += row_shr<2>(x);
+    if constexpr (GROUP > 4) x += row_shr<4>(x);
+    if constexpr (GROUP > 8) x += row_shr<8>(x);
+    return x;
+}
+
+// Inclusive scan over all 64 lanes (rows chained through row-broadcast steps).
+__device__ __forceinline__ float wave_scan_inclusive(float x) {
+    x += row_shr<1>(x);
+    x += row_shr<2>(x);
+    x += row_shr<4>(x);
+    x += row_shr<8>(x);
+    // lane 15 of rows 0 and 2 -> every lane of rows 1 and 3
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142, 0xa, 0xf, false));
+    // lane 31 -> every lane of rows 2 and 3
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143, 0xc, 0xf, false));
+    return x;
+}
+
+__device__ __forceinline__ float read_lane(float x, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), lane));
+}
+
+// Sum over all 64 lanes, returned uniformly.
+__device__ __forceinline__ float wave_sum(float x) { return read_lane(wave_scan_inclusive(x), 63); }
+
+// ---------------------------------------------------------------- constant operand matrices
+
+// A-operand registers of lane (i, g): entries C[i][8g .. 8g+7] of a 16 x 32 constant matrix.
+struct LaneId {
+    int lane, j, g;
+    __device__ __forceinline__ LaneId() {
+        lane = threadIdx.x & (kWave - 1);
+        j = lane & 15;
+        g = lane >> 4;
+    }
+};
+
+// All-ones matrix (the paper's underlined 1; every row plays the role of P's first row, so
+// every accumulator row ends up holding the sums).
+__device__ __forceinline__ half8 const_ones() {
+    half8 c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = (_Float16)1.0f;
+    return c;
+}
+
+// Lower-triangular-with-diagonal pieces of U^T (Section 5's U, transposed because the constant
+// is on the left here).  Output row i of the first product is position i of a tile row,
+// output row i of the second product is position 16 + i:
+//   tri_lo[i][k] = 1  iff  k <= i            tri_hi[i][k] = 1  iff  k <= 16 + i
+__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) {
+    half8 c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = (8 * id.g + e <= id.j) ? (_Float16)1.0f : (_Float16)0.0f;
+    return c;
+}
+__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) {
+    half8 c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = (8 * id.g + e <= 16 + id.j) ? (_Float16)1.0f : (_Float16)0.0f;
+    return c;
+}
+// Same, for rows that hold two independent segments of 16: the second half starts afresh.
+__device__ __forceinline__ half8 const_tri_hi_seg16(const LaneId& id) {
+    half8 c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int k = 8 * id.g + e;
+        c[e] = (k >= 16 && k <= 16 + id.j) ? (_Float16)1.0f : (_Float16)0.0f;
+    }
+    return c;
+}
+// Two half-row sums at once: output rows 0..7 add up k < 16, rows 8..15 add up k >= 16.
+__device__ __forceinline__ half8 const_half_rows(const LaneId& id) {
+    const bool one = (id.g >= 2) == (id.j >= 8);
+    half8 c;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) c[e] = one ? (_Float16)1.0f : (_Float16)0.0f;
+    return c;
+}
+
+__device__ __forceinline__ float4v mfma(half8 constant, half8 data, float4v acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(constant, data, acc, 0, 0, 0);
+}
+
+__device__ __forceinline__ float4v splat(float v) { return (float4v){v, v, v, v}; }
+
+// ---------------------------------------------------------------- loads and stores
+
+// 8 consecutive binary16 values starting at element `off` (a multiple of 8); elements at or
+// beyond n read as zero (the paper's zero padding of a short last tile, Section 4).
+__device__ __forceinline__ half8 load8_guarded(const _Float16* __restrict__ in, uint64_t off, uint64_t n) {
+    half8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (_Float16)0.0f;
+    if (off + 8 <= n) {
+        v = *reinterpret_cast<const half8*>(in + off);
+    } else if (off < n) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (off + e < n) v[e] = in[off + e];
+    }
+    return v;
+}
+__device__ __forceinline__ half8 load8(const _Float16* __restrict__ in, uint64_t off) {
+    return *reinterpret_cast<const half8*>(in + off);
+}
+
+__device__ __forceinline__ void store4_guarded(float* __restrict__ out, uint64_t off, uint64_t n, float4v v) {
+    if (off + 4 <= n) {
+        *reinterpret_cast<float4v*>(out + off) = v;
+    } else if (off < n) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (off + e < n) out[off + e] = v[e];
+    }
+}
+__device__ __forceinline__ void store4(float* __restrict__ out, uint64_t off, float4v v) {
+    *reinterpret_cast<float4v*>(out + off) = v;
+}
+
+}  // namespace tcr

@@ -1,0 +1,152 @@
+// Segmented / full sum-reduction kernels (Section 4 of the paper, re-derived for MFMA).
+//
+//   reduce_small_kernel   seg_len in {16, 32, ..., 512}: a segment is part of one wavefront tile.
+//                         One "ones" product per tile gives the 16 row sums (the paper's
+//                         Reduction_16: P.A, here with every row of the constant equal to P's
+//                         first row); rows of one segment are folded with binary32 cross-lane
+//                         adds (where Reduction_256 uses a second product with P^T).
+//   reduce_span_kernel    seg_len >= 1024 and the full reduction: each wavefront walks a span of
+//                         consecutive tiles and keeps the 16 running row sums in the accumulator,
+//                         V_i = ones.A_i + V_{i-1} (the work-efficient Reduction_256N), folding
+//                         the 16 sums once at the end.
+//   reduce_final_kernel   device level: binary32 partials of one segment -> its result (the
+//                         second kernel of the paper's grid-level reduction).
+//
+// FORM selects the arithmetic inside a tile: kMfma (matrix cores) or kDpp (convert, add in
+// binary32, cross-lane DPP adds) -- the wavefront-primitive alternative kept for measurement.
+#pragma once
+#include "tcr_device.hpp"
+
+namespace tcr {
+
+enum Formulation { kMfma = 0, kDpp = 1 };
+
+// Sum over aligned groups of GROUP lanes (GROUP up to 64); valid in the last lane of a group.
+template <int GROUP>
+__device__ __forceinline__ float lanes_sum_to_last(float x) {
+    x = row_sum_to_last<(GROUP < 16 ? GROUP : 16)>(x);
+    if constexpr (GROUP > 16)
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142, 0xa, 0xf, false));
+    if constexpr (GROUP > 32)
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143, 0xc, 0xf, false));
+    return x;
+}
+
+__device__ __forceinline__ float sum8(half8 v) {
+    float a = (float)v[0] + (float)v[1];
+    float b = (float)v[2] + (float)v[3];
+    float c = (float)v[4] + (float)v[5];
+    float d = (float)v[6] + (float)v[7];
+    return (a + b) + (c + d);
+}
+
+// ------------------------------------------------------------------------------ small segments
+// Grid: one workgroup per 4*U tiles.  n is a multiple of seg_len = 1 << LOG2L.
+template <int FORM, int LOG2L, int U>
+__global__ __launch_bounds__(kBlockThreads) void reduce_small_kernel(const _Float16* __restrict__ in,
+                                                                     float* __restrict__ out, uint64_t n) {
+    static_assert(LOG2L >= 4 && LOG2L <= 9, "");
+    const LaneId id;
+    const int wave = threadIdx.x >> 6;
+    const uint64_t base = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * (uint64_t)(kTile * U);
+    if (base >= n) return;
+    const uint64_t nseg = n >> LOG2L;
+    // element offset of this lane's 8 values inside a tile
+    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
+
+    half8 x[U];
+    if (base + (uint64_t)(kTile * U) <= n) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8(in, base + (uint64_t)(kTile * u + lane_off));
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + lane_off), n);
+    }
+
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t seg0 = (base + (uint64_t)(kTile * u)) >> LOG2L;   // first segment of the tile
+        if constexpr (FORM == kMfma) {
+            if constexpr (LOG2L == 4) {
+                // two segments per row: rows 0..7 of the product carry the first, 8..15 the second
+                const float4v d = mfma(const_half_rows(id), x[u], splat(0.0f));
+                const uint64_t s = seg0 + (uint64_t)(2 * id.j + (id.g >> 1));
+                if ((id.g & 1) == 0 && s < nseg) out[s] = d[0];
+            } else {
+                constexpr int ROWS = 1 << (LOG2L - 5);               // tile rows per segment
+                const float4v d = mfma(const_ones(), x[u], splat(0.0f));
+                const float t = row_sum_to_last<ROWS>(d[0]);
+                const uint64_t s = seg0 + (uint64_t)(id.j >> (LOG2L - 5));
+                if (id.g == 0 && (id.j & (ROWS - 1)) == ROWS - 1 && s < nseg) out[s] = t;
+            }
+        } else {
+            constexpr int LANES = 1 << (LOG2L - 3);                  // lanes per segment
+            const float t = lanes_sum_to_last<LANES>(sum8(x[u]));
+            const uint64_t s = seg0 + (uint64_t)(id.lane >> (LOG2L - 3));
+            if ((id.lane & (LANES - 1)) == LANES - 1 && s < nseg) out[s] = t;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ long spans
+// Wavefront w reduces elements [w*span, min((w+1)*span, n)) into dst[w].  span is a multiple of
+// the tile size.  When span == seg_len, dst is the output itself.
+template <int FORM, int U>
+__global__ __launch_bounds__(kBlockThreads) void reduce_span_kernel(const _Float16* __restrict__ in,
+                                                                    float* __restrict__ dst, uint64_t n,
+                                                                    uint64_t span, uint64_t nspans) {
+    const LaneId id;
+    const uint64_t w = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (w >= nspans) return;
+    const uint64_t begin = w * span;
+    const uint64_t end = (begin + span < n) ? begin + span : n;
+    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
+
+    float4v acc = splat(0.0f);          // MFMA: running row sums (the accumulator matrix V)
+    float s0 = 0.0f, s1 = 0.0f;         // DPP: per-lane running sums
+    uint64_t t = begin;
+    for (; t + (uint64_t)(kTile * U) <= end; t += (uint64_t)(kTile * U)) {
+        half8 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8(in, t + (uint64_t)(kTile * u + lane_off));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if constexpr (FORM == kMfma) acc = mfma(const_ones(), x[u], acc);
+            else if (u & 1) s1 += sum8(x[u]);
+            else s0 += sum8(x[u]);
+        }
+    }
+    for (; t < end; t += kTile) {
+        const half8 x = load8_guarded(in, t + (uint64_t)lane_off, end);
+        if constexpr (FORM == kMfma) acc = mfma(const_ones(), x, acc);
+        else s0 += sum8(x);
+    }
+    float total;
+    if constexpr (FORM == kMfma) total = row_sum_to_last<16>(acc[0]);   // lane 15: sum over the 16 rows
+    else total = lanes_sum_to_last<64>(s0 + s1);              // lane 63
+    const int last = (FORM == kMfma) ? 15 : 63;
+    if (id.lane == last) dst[w] = total;
+}
+
+// ------------------------------------------------------------------------------ partials -> result
+// Workgroup s adds the `per` binary32 partials of segment s in a fixed order.
+__global__ __launch_bounds__(kBlockThreads) void reduce_final_kernel(const float* __restrict__ partials,
+                                                                     float* __restrict__ out, uint64_t per) {
+    __shared__ float wave_tot[kWavesPerBlock];
+    const float* p = partials + (uint64_t)blockIdx.x * per;
+    float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+    uint64_t i = threadIdx.x;
+    for (; i + 3 * kBlockThreads < per; i += 4 * kBlockThreads) {
+        a0 += p[i];
+        a1 += p[i + kBlockThreads];
+        a2 += p[i + 2 * kBlockThreads];
+        a3 += p[i + 3 * kBlockThreads];
+    }
+    for (; i < per; i += kBlockThreads) a0 += p[i];
+    const float t = wave_sum((a0 + a1) + (a2 + a3));
+    if ((threadIdx.x & 63) == 0) wave_tot[threadIdx.x >> 6] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) out[blockIdx.x] = (wave_tot[0] + wave_tot[1]) + (wave_tot[2] + wave_tot[3]);
+}
+
+}  // namespace tcr

@@ -1,0 +1,338 @@
+// Segmented / full inclusive-scan kernels (Section 5 of the paper, re-derived for MFMA).
+//
+// Inside a tile (16 rows of 32 elements) the scan is the paper's  Scan(V) = G + A.U :
+//   * A.U, the inclusive scan of every row, is two products with the triangular constants
+//     (positions 0..15 and 16..31 of a row);
+//   * G, "everything before this row", starts from a product with the all-ones matrix, which
+//     leaves every row's total in every lane of that row's column; the exclusive scan of those
+//     16 totals is done with binary32 cross-lane adds (the paper multiplies L.A by the ones
+//     matrix instead, which would push binary32 sums through a binary16 operand);
+//   * G plus the running carry of earlier tiles (the paper's S matrix) enters the triangular
+//     products through the accumulator, so adding the carry costs nothing.
+//
+//   scan_small_kernel     seg_len in {16, ..., 512}: segments never leave a tile (Scan_16 and
+//                         Scan_16N / Scan_256 territory).
+//   scan_block_kernel     seg_len >= 1024 and the full scan: a workgroup scans 4*U consecutive
+//                         tiles (Scan_256N per wavefront, the block-level combination through
+//                         LDS), and a segment longer than a workgroup's share gets its carry
+//                         from earlier workgroups either by single-pass decoupled look-back
+//                         (CARRY == kLookback) or from a precomputed table of exclusive prefixes
+//                         (CARRY == kTable, the reduce-then-scan alternative).
+//   scan_partials_kernel  exclusive scan of per-workgroup totals for kTable.
+#pragma once
+#include "tcr_device.hpp"
+#include "tcr_reduce.hpp"
+
+namespace tcr {
+
+enum CarryMode { kNoCarry = 0, kLookback = 1, kTable = 2 };
+
+// Inclusive scan over aligned groups of GROUP lanes (GROUP up to 64).
+template <int GROUP>
+__device__ __forceinline__ float lanes_scan_inclusive(float x, int lane) {
+    if constexpr (GROUP <= 16) return row_scan_inclusive<GROUP>(x, lane & 15);
+    x = row_scan_inclusive<16>(x, lane & 15);
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x142, 0xa, 0xf, false));
+    if constexpr (GROUP > 32)
+        x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x143, 0xc, 0xf, false));
+    return x;
+}
+
+// Value of the previous lane of the wavefront (0 for lane 0).
+__device__ __forceinline__ float wave_shr1(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x138, 0xf, 0xf, true));
+}
+
+// In-lane inclusive scan of 8 values, binary32.
+__device__ __forceinline__ void scan8(half8 v, float (&p)[8]) {
+    p[0] = (float)v[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) p[e] = p[e - 1] + (float)v[e];
+}
+
+// ------------------------------------------------------------------------------ small segments
+template <int FORM, int LOG2L, int U>
+__global__ __launch_bounds__(kBlockThreads) void scan_small_kernel(const _Float16* __restrict__ in,
+                                                                   float* __restrict__ out, uint64_t n) {
+    static_assert(LOG2L >= 4 && LOG2L <= 9, "");
+    const LaneId id;
+    const int wave = threadIdx.x >> 6;
+    const uint64_t base = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * (uint64_t)(kTile * U);
+    if (base >= n) return;
+    const bool full = base + (uint64_t)(kTile * U) <= n;
+    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
+
+    half8 x[U];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8(in, base + (uint64_t)(kTile * u + lane_off));
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + lane_off), n);
+    }
+
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t tbase = base + (uint64_t)(kTile * u);
+        float4v lo, hi;
+        uint64_t off_lo, off_hi;
+        if constexpr (FORM == kMfma) {
+            if constexpr (LOG2L == 4) {
+                lo = mfma(const_tri_lo(id), x[u], splat(0.0f));
+                hi = mfma(const_tri_hi_seg16(id), x[u], splat(0.0f));
+            } else if constexpr (LOG2L == 5) {
+                lo = mfma(const_tri_lo(id), x[u], splat(0.0f));
+                hi = mfma(const_tri_hi(id), x[u], splat(0.0f));
+            } else {
+                constexpr int ROWS = 1 << (LOG2L - 5);
+                const float4v tot = mfma(const_ones(), x[u], splat(0.0f));
+                const float incl = row_scan_inclusive<ROWS>(tot[0], id.j);
+                const float prev = row_shr<1>(incl);
+                const float g = ((id.j & (ROWS - 1)) == 0) ? 0.0f : prev;     // rows before mine, same segment
+                lo = mfma(const_tri_lo(id), x[u], splat(g));
+                hi = mfma(const_tri_hi(id), x[u], splat(g));
+            }
+            off_lo = tbase + (uint64_t)(kRow * id.j + 4 * id.g);
+            off_hi = off_lo + 16;
+        } else {
+            constexpr int LANES = 1 << (LOG2L - 3);
+            float p[8];
+            scan8(x[u], p);
+            const float incl = lanes_scan_inclusive<LANES>(p[7], id.lane);
+            const float prev = wave_shr1(incl);
+            const float g = ((id.lane & (LANES - 1)) == 0) ? 0.0f : prev;
+            lo = (float4v){p[0] + g, p[1] + g, p[2] + g, p[3] + g};
+            hi = (float4v){p[4] + g, p[5] + g, p[6] + g, p[7] + g};
+            off_lo = tbase + (uint64_t)(8 * id.lane);
+            off_hi = off_lo + 4;
+        }
+        if (full) {
+            store4(out, off_lo, lo);
+            store4(out, off_hi, hi);
+        } else {
+            store4_guarded(out, off_lo, n, lo);
+            store4_guarded(out, off_hi, n, hi);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ look-back state
+// One 64-bit word per workgroup tile: high half = tag, low half = binary32 value.
+// tag = epoch * 4 + status; a word whose epoch differs from the launch's is "not yet written",
+// so the table never needs clearing between launches.
+constexpr uint32_t kStatusAggregate = 1;   // value = total of this tile only
+constexpr uint32_t kStatusPrefix = 2;      // value = total of this tile and all earlier tiles of its segment
+constexpr int kSpinLimit = 1 << 20;        // polls of one look-back window before giving up
+
+struct ScanWorkspace {
+    unsigned long long* desc;   // [tiles]
+    uint32_t* ticket;           // running count of tiles handed out since the workspace was created
+    uint32_t* gave_up;          // set to 1 if a bounded wait expired
+    uint32_t ticket_base;       // value of *ticket when this launch starts
+    uint32_t epoch;
+};
+
+__device__ __forceinline__ unsigned long long pack_desc(uint32_t epoch, uint32_t status, float v) {
+    return ((unsigned long long)(epoch * 4u + status) << 32) | (unsigned long long)__builtin_bit_cast(uint32_t, v);
+}
+
+// Executed by one whole wavefront.  Returns (uniformly) the sum of the totals of all earlier
+// tiles of this tile's segment and publishes this tile's own state.
+//   pos        index of this tile inside its segment (0 = first tile of the segment)
+__device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint64_t pos,
+                                                           float total, int lane) {
+    if (pos == 0) {
+        if (lane == 0)
+            __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, total), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        return 0.0f;
+    }
+    if (lane == 0)
+        __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusAggregate, total), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    float acc = 0.0f;
+    uint64_t dist = (uint64_t)lane + 1;          // this lane inspects tile - dist
+    bool done = false;
+    while (!done) {
+        const bool valid = dist <= pos;          // never look past the first tile of the segment
+        uint32_t status = kStatusPrefix;         // lanes past the segment start act as "prefix 0"
+        float value = 0.0f;
+        bool ready = !valid;
+        int polls = 0;
+        while (true) {
+            if (!ready) {
+                const unsigned long long d = __hip_atomic_load(&ws.desc[tile - (uint32_t)dist], __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t tag = (uint32_t)(d >> 32);
+                if ((tag >> 2) == ws.epoch && (tag & 3u) != 0u) {
+                    status = tag & 3u;
+                    value = __builtin_bit_cast(float, (uint32_t)d);
+                    ready = true;
+                }
+            }
+            if (__ballot(!ready) == 0ull) break;
+            if (++polls > kSpinLimit) {          // should be unreachable: predecessors hold earlier tickets
+                if (lane == 0) __hip_atomic_store(ws.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        const unsigned long long prefix_lanes = __ballot(status == kStatusPrefix);
+        if (prefix_lanes != 0ull) {
+            const int nearest = __builtin_ctzll(prefix_lanes);
+            acc += wave_sum(lane <= nearest ? value : 0.0f);
+            done = true;
+        } else {
+            acc += wave_sum(value);
+            dist += kWave;
+        }
+    }
+    if (lane == 0)
+        __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, acc + total), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    return acc;
+}
+
+// ------------------------------------------------------------------------------ long segments
+// seg_mask  = seg_len - 1 for a power-of-two seg_len, all ones for the full scan (one segment).
+// seg_len   only compared against the wavefront / workgroup share (saturated for the full scan).
+// Grid: one workgroup per 4*U tiles.
+template <int FORM, int U, int CARRY>
+__global__ __launch_bounds__(kBlockThreads) void scan_block_kernel(const _Float16* __restrict__ in,
+                                                                   float* __restrict__ out, uint64_t n,
+                                                                   uint64_t seg_mask, uint64_t seg_len,
+                                                                   ScanWorkspace ws,
+                                                                   const float* __restrict__ tile_prefix) {
+    constexpr uint64_t kChunk = (uint64_t)kTile * U;             // one wavefront's share
+    constexpr uint64_t kBlockTile = kChunk * kWavesPerBlock;     // one workgroup's share
+    __shared__ float s_wave_total[kWavesPerBlock];
+    __shared__ float s_prefix;
+    __shared__ uint32_t s_tile;
+
+    const LaneId id;
+    const int wave = threadIdx.x >> 6;
+    uint32_t tile = blockIdx.x;
+    if constexpr (CARRY == kLookback) {
+        // tiles are handed out in launch order, so every predecessor of a waiting tile is
+        // already running or finished
+        if (threadIdx.x == 0)
+            s_tile = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+        __syncthreads();
+        tile = s_tile;
+    }
+    const uint64_t block_base = (uint64_t)tile * kBlockTile;
+    const uint64_t base = block_base + (uint64_t)wave * kChunk;
+    const bool full = base + kChunk <= n;
+    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
+
+    half8 x[U];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8(in, base + (uint64_t)(kTile * u + lane_off));
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + lane_off), n);
+    }
+
+    // per tile: exclusive carry of this lane's row (MFMA) or lane (DPP) inside the tile, and the tile total
+    float inner[U], tile_total[U];
+    float p[(FORM == kDpp) ? U : 1][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (FORM == kMfma) {
+            const float4v tot = mfma(const_ones(), x[u], splat(0.0f));
+            const float incl = row_scan_inclusive<16>(tot[0], id.j);
+            inner[u] = row_shr<1>(incl);
+            tile_total[u] = read_lane(incl, 15);
+        } else {
+            scan8(x[u], p[u]);
+            const float incl = wave_scan_inclusive(p[u][7]);
+            inner[u] = wave_shr1(incl);
+            tile_total[u] = read_lane(incl, 63);
+        }
+    }
+    // running carry over this wavefront's tiles (the S matrix of Scan_256N); restarts where a segment starts
+    float before[U];
+    float run = 0.0f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (((base + (uint64_t)(kTile * u)) & seg_mask) == 0) run = 0.0f;
+        before[u] = run;
+        run += tile_total[u];
+    }
+    // carry from earlier wavefronts / workgroups of the same segment (only when a segment is
+    // longer than one wavefront's share; then the share lies inside a single segment)
+    float ext = 0.0f;
+    if (seg_len > kChunk) {
+        if (id.lane == 0) s_wave_total[wave] = run;
+        __syncthreads();
+        const int first_wave = (seg_len >= kBlockTile) ? 0 : (wave & ~((int)(seg_len / kChunk) - 1));
+        for (int w = first_wave; w < wave; ++w) ext += s_wave_total[w];
+        if (CARRY != kNoCarry && seg_len > kBlockTile) {
+            if constexpr (CARRY == kLookback) {
+                if (wave == 0) {
+                    const float total = (s_wave_total[0] + s_wave_total[1]) + (s_wave_total[2] + s_wave_total[3]);
+                    const uint64_t pos = (block_base & seg_mask) / kBlockTile;
+                    const float pre = lookback_exclusive_prefix(ws, tile, pos, total, id.lane);
+                    if (id.lane == 0) s_prefix = pre;
+                }
+                __syncthreads();
+                ext += s_prefix;
+            } else {
+                ext += tile_prefix[tile];
+            }
+        }
+    }
+
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t tbase = base + (uint64_t)(kTile * u);
+        const float carry = inner[u] + (before[u] + ext);
+        float4v lo, hi;
+        uint64_t off_lo, off_hi;
+        if constexpr (FORM == kMfma) {
+            lo = mfma(const_tri_lo(id), x[u], splat(carry));
+            hi = mfma(const_tri_hi(id), x[u], splat(carry));
+            off_lo = tbase + (uint64_t)(kRow * id.j + 4 * id.g);
+            off_hi = off_lo + 16;
+        } else {
+            const float* q = p[(FORM == kDpp) ? u : 0];
+            lo = (float4v){q[0] + carry, q[1] + carry, q[2] + carry, q[3] + carry};
+            hi = (float4v){q[4] + carry, q[5] + carry, q[6] + carry, q[7] + carry};
+            off_lo = tbase + (uint64_t)(8 * id.lane);
+            off_hi = off_lo + 4;
+        }
+        if (full) {
+            store4(out, off_lo, lo);
+            store4(out, off_hi, hi);
+        } else {
+            store4_guarded(out, off_lo, n, lo);
+            store4_guarded(out, off_hi, n, hi);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ reduce-then-scan helper
+// Workgroup s turns the `per` workgroup totals of segment s into exclusive prefixes, in place.
+__global__ __launch_bounds__(kBlockThreads) void scan_partials_kernel(float* __restrict__ totals, uint64_t per) {
+    __shared__ float s_wave[kWavesPerBlock];
+    float* p = totals + (uint64_t)blockIdx.x * per;
+    const uint64_t run_len = (per + kBlockThreads - 1) / kBlockThreads;
+    const uint64_t lo = (uint64_t)threadIdx.x * run_len;
+    const uint64_t hi = (lo + run_len < per) ? lo + run_len : per;
+    float sum = 0.0f;
+    for (uint64_t i = lo; i < hi; ++i) sum += p[i];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float incl = wave_scan_inclusive(sum);
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    float carry = wave_shr1(incl);
+    for (int w = 0; w < wave; ++w) carry += s_wave[w];
+    for (uint64_t i = lo; i < hi; ++i) {
+        const float v = p[i];
+        p[i] = carry;
+        carry += v;
+    }
+}
+
+}  // namespace tcr

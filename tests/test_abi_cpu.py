@@ -1,0 +1,100 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the
+header declares, rejects bad arguments before touching a device, and its dispatch table
+names the kernels expected for each segment-length class."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tcr.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_1811_09736_amd import build as b
+    if not os.path.exists(b.LIB_PATH):
+        b.build_library()
+    from paper_1811_09736_amd import binding
+    return binding
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tcr_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_symbols()
+    assert len(names) >= 10
+    raw = lib.raw()
+    for name in names:
+        assert hasattr(raw, name), name
+    assert sorted(lib.EXPORTS) == names
+
+
+def test_status_strings(lib):
+    raw = lib.raw()
+    seen = {raw.tcr_status_string(i).decode() for i in range(5)}
+    assert len(seen) == 5 and "ok" in seen
+    assert raw.tcr_status_string(99).decode() == "unknown status"
+
+
+def test_argument_validation_happens_before_any_device_work(lib):
+    raw = lib.raw()
+    buf = ctypes.create_string_buffer(4096 + 64)
+    base = (ctypes.addressof(buf) + 63) & ~63           # a 64-byte aligned host address (never dereferenced)
+    inv = lib.ERR_INVALID_ARG
+    assert raw.tcr_segmented_reduce(base, base + 2048, 64, 0, None) == inv       # seg_len == 0
+    assert raw.tcr_segmented_reduce(base, base + 2048, 100, 16, None) == inv     # n % seg_len != 0
+    assert raw.tcr_segmented_scan(base, base + 2048, 64, 0, None) == inv
+    assert raw.tcr_segmented_scan(base, base + 2048, 65, 16, None) == inv
+    assert raw.tcr_segmented_reduce(None, base, 64, 16, None) == inv             # null input
+    assert raw.tcr_segmented_scan(base, None, 64, 16, None) == inv               # null output
+    assert raw.tcr_segmented_scan(base + 2, base + 2048, 64, 16, None) == inv    # misaligned input
+    assert raw.tcr_segmented_scan(base, base + 2048 + 4, 64, 16, None) == inv    # misaligned output
+    assert raw.tcr_segmented_reduce(base, base + 2048 + 2, 64, 16, None) == inv
+    assert raw.tcr_reduce(base, None, 64, None) == inv
+    assert raw.tcr_scan(base + 8, base + 2048, 64, None) == inv
+    # n == 0 is a no-op for everything that writes no output
+    assert raw.tcr_segmented_reduce(None, None, 0, 16, None) == lib.OK
+    assert raw.tcr_segmented_scan(None, None, 0, 16, None) == lib.OK
+    assert raw.tcr_scan(None, None, 0, None) == lib.OK
+    # sizes without a kernel
+    assert raw.tcr_segmented_scan(base, base + 2048, 1 << 41, 1 << 41, None) == lib.ERR_UNSUPPORTED
+
+
+def test_variant_switch(lib):
+    with pytest.raises(lib.TcrError):
+        lib.set_variant("formulation", "tensor")
+    with pytest.raises(lib.TcrError):
+        lib.set_variant("nonsense", "x")
+    try:
+        lib.set_variant("formulation", "dpp")
+        assert "dpp" in lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 20, 256)
+        lib.set_variant("scan_carry", "reduce_then_scan")
+        assert "table" in lib.kernel_name(lib.OP_SCAN, 1 << 28, 1 << 28)
+    finally:
+        lib.set_variant("reset")
+    assert "mfma" in lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 20, 256)
+    assert "lookback" in lib.kernel_name(lib.OP_SCAN, 1 << 28, 1 << 28)
+
+
+def test_dispatch_by_segment_length(lib):
+    n = 1 << 28
+    k = lib.kernel_name
+    for e in range(4, 10):
+        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e).startswith("reduce_small_kernel")
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e).startswith("scan_small_kernel")
+    for e in (10, 12, 14):
+        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma>"
+    for e in (16, 20):
+        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e).endswith("+reduce_final_kernel")
+        assert "lookback" in k(lib.OP_SEGMENTED_SCAN, n, 1 << e)
+    for e in (10, 12):
+        assert "nocarry" in k(lib.OP_SEGMENTED_SCAN, n, 1 << e)
+    assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
+    assert k(lib.OP_SEGMENTED_SCAN, n, 48) == ""          # no kernel: the call reports "unsupported"
+    assert k(lib.OP_SEGMENTED_SCAN, 0, 16) == ""

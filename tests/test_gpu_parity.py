@@ -1,0 +1,258 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, element by element.
+
+Bar: integer-valued inputs -> the binary32 outputs equal the oracle's binary64 values
+exactly; real-valued inputs -> |y - ref| <= 1e-3 * max(|ref|, rho) per output, where rho is
+the root-sum-square of the inputs that output adds up (the natural scale of a zero-mean sum;
+for the smallest outputs of zero-mean data a pure relative error is unbounded).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1811_09736_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def tcr():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1811_09736_amd import binding      # fails loudly if libtcr.so is missing
+    binding.set_variant("reset")
+    yield binding
+    binding.set_variant("reset")
+    binding.check_device_flags()
+
+
+@pytest.fixture(params=["mfma", "dpp"])
+def form(request, tcr):
+    tcr.set_variant("formulation", request.param)
+    yield request.param
+    tcr.set_variant("reset")
+
+
+def dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(x).cuda()
+
+
+def assert_exact(got: torch.Tensor, ref: np.ndarray, what: str):
+    g = got.cpu().numpy().astype(np.float64)
+    if not np.array_equal(g, ref):
+        bad = np.flatnonzero(g != ref)
+        raise AssertionError(f"{what}: {bad.size} mismatches, first at {bad[0]}: got {g[bad[0]]!r} want {ref[bad[0]]!r}")
+
+
+def assert_close_scan(got: torch.Tensor, ref: np.ndarray, x: np.ndarray, seg: int, what: str):
+    g = got.cpu().numpy().astype(np.float64)
+    x64 = x.astype(np.float64)
+    rho = np.sqrt(np.cumsum((x64 * x64).reshape(-1, seg), axis=1)).reshape(-1)
+    tol = REL_TOL * np.maximum(np.abs(ref), rho)
+    err = np.abs(g - ref)
+    if not np.all(err <= tol):
+        bad = int(np.argmax(err - tol))
+        raise AssertionError(f"{what}: worst at {bad}: got {g[bad]!r} want {ref[bad]!r} tol {tol[bad]!r}")
+
+
+def assert_close_reduce(got: torch.Tensor, ref: np.ndarray, x: np.ndarray, seg: int, what: str):
+    g = got.cpu().numpy().astype(np.float64)
+    x64 = x.astype(np.float64)
+    rho = np.sqrt((x64 * x64).reshape(-1, seg).sum(axis=1))
+    tol = REL_TOL * np.maximum(np.abs(ref), rho)
+    err = np.abs(g - ref)
+    if not np.all(err <= tol):
+        bad = int(np.argmax(err - tol))
+        raise AssertionError(f"{what}: worst at segment {bad}: got {g[bad]!r} want {ref[bad]!r} tol {tol[bad]!r}")
+
+
+def ragged_n(seg: int) -> int:
+    """A few workgroup shares (8192 elements each) plus a tail that fills neither a workgroup nor,
+    for short segments, a 512-element tile."""
+    whole = 3 * 8192
+    tail_segments = 3 if seg <= 512 else 1
+    return (whole // seg + tail_segments) * seg if seg <= 8192 else 3 * seg
+
+
+SMALL_SEGS = [16, 32, 64, 128, 256, 512]
+LONG_SEGS = [1024, 2048, 4096, 8192, 16384, 32768, 1 << 16, 1 << 18]
+
+
+# ------------------------------------------------------------------ segmented, moderate sizes
+
+@pytest.mark.parametrize("seg", SMALL_SEGS + LONG_SEGS)
+def test_segmented_exact(tcr, oracle, form, seg):
+    n = ragged_n(seg)
+    x = workloads.make_input(n, "int8", 40 + seg % 97)
+    xd = dev(x)
+    assert_exact(tcr.segmented_scan(xd, seg), oracle.segmented_scan(x, seg), f"scan L={seg} n={n} {form}")
+    assert_exact(tcr.segmented_reduce(xd, seg), oracle.segmented_reduce(x, seg), f"reduce L={seg} n={n} {form}")
+
+
+@pytest.mark.parametrize("seg", SMALL_SEGS + LONG_SEGS)
+@pytest.mark.parametrize("dist", ["uniform_pm1", "uniform_01"])
+def test_segmented_real(tcr, oracle, form, seg, dist):
+    n = ragged_n(seg)
+    x = workloads.make_input(n, dist, 7)
+    xd = dev(x)
+    assert_close_scan(tcr.segmented_scan(xd, seg), oracle.segmented_scan(x, seg), x, seg, f"scan L={seg} {dist} {form}")
+    assert_close_reduce(tcr.segmented_reduce(xd, seg), oracle.segmented_reduce(x, seg), x, seg,
+                        f"reduce L={seg} {dist} {form}")
+
+
+@pytest.mark.parametrize("seg", [16, 64, 512, 1024, 1 << 15])
+def test_single_segment_and_tiny_inputs(tcr, oracle, form, seg):
+    for nseg in (1, 2, 5):
+        x = workloads.make_input(seg * nseg, "int4", nseg)
+        xd = dev(x)
+        assert_exact(tcr.segmented_scan(xd, seg), oracle.segmented_scan(x, seg), f"scan L={seg} x{nseg}")
+        assert_exact(tcr.segmented_reduce(xd, seg), oracle.segmented_reduce(x, seg), f"reduce L={seg} x{nseg}")
+
+
+# ------------------------------------------------------------------ full operations, any n
+
+FULL_NS = [1, 2, 7, 8, 9, 15, 16, 17, 511, 512, 513, 1000, 4095, 8191, 8192, 8193, 16384, 16385,
+           100003, (1 << 20) + 5, 3 * (1 << 20) - 1]
+
+
+@pytest.mark.parametrize("n", FULL_NS)
+def test_full_exact_any_n(tcr, oracle, form, n):
+    x = workloads.make_input(n, "int4", n % 1000)
+    xd = dev(x)
+    assert_exact(tcr.scan(xd), oracle.scan(x), f"scan n={n} {form}")
+    assert float(tcr.reduce(xd).cpu()[0]) == oracle.reduce(x), f"reduce n={n} {form}"
+    # the segmented entry points with one segment are the full operations
+    assert_exact(tcr.segmented_scan(xd, n), oracle.scan(x), f"segmented_scan L=n={n}")
+    assert float(tcr.segmented_reduce(xd, n).cpu()[0]) == oracle.reduce(x)
+
+
+@pytest.mark.parametrize("n", [1000, 8193, 100003, (1 << 20) + 5])
+def test_full_real_any_n(tcr, oracle, form, n):
+    x = workloads.make_input(n, "normal", 2)
+    xd = dev(x)
+    assert_close_scan(tcr.scan(xd), oracle.scan(x), x, n, f"scan n={n} {form}")
+    assert_close_reduce(tcr.reduce(xd), np.array([oracle.reduce(x)]), x, n, f"reduce n={n} {form}")
+
+
+def test_empty_inputs(tcr):
+    e = torch.empty(0, dtype=torch.float16, device="cuda")
+    assert tcr.scan(e).numel() == 0
+    assert tcr.segmented_scan(e, 16).numel() == 0
+    assert tcr.segmented_reduce(e, 16).numel() == 0
+    out = torch.full((1,), 7.0, dtype=torch.float32, device="cuda")
+    tcr.reduce(e, out=out)
+    assert float(out.cpu()[0]) == 0.0
+
+
+# ------------------------------------------------------------------ closed forms and invariants on the device
+
+@pytest.mark.parametrize("seg", [16, 256, 4096, 1 << 16, 1 << 22])
+def test_all_ones_closed_form(tcr, form, seg):
+    n = max(seg, 1 << 18)
+    xd = torch.ones(n, dtype=torch.float16, device="cuda")
+    scan = tcr.segmented_scan(xd, seg).cpu().numpy()
+    assert np.array_equal(scan, (np.arange(n) % seg + 1).astype(np.float32))      # < 2^24: exact in binary32
+    assert np.array_equal(tcr.segmented_reduce(xd, seg).cpu().numpy(), np.full(n // seg, float(seg), np.float32))
+
+
+@pytest.mark.parametrize("m", [16, 512, 2048])
+def test_ramp_closed_form(tcr, form, m):
+    ramp = np.arange(1, m + 1, dtype=np.float64)
+    x = np.tile(ramp, 24).astype(np.float16)
+    xd = dev(x)
+    assert np.array_equal(tcr.segmented_reduce(xd, m).cpu().numpy().astype(np.float64), np.full(24, m * (m + 1) / 2.0))
+    assert np.array_equal(tcr.segmented_scan(xd, m).cpu().numpy().astype(np.float64), np.tile(ramp * (ramp + 1) / 2, 24))
+
+
+@pytest.mark.parametrize("seg", [16, 128, 512, 2048, 1 << 15])
+def test_subnormal_inputs_are_not_flushed(tcr, oracle, form, seg):
+    # sums of binary16 subnormals are small multiples of 2^-24: exact in binary32 unless inputs are flushed to zero
+    n = ragged_n(seg)
+    x = workloads.make_input(n, "subnormal", 9)
+    xd = dev(x)
+    assert_exact(tcr.segmented_scan(xd, seg), oracle.segmented_scan(x, seg), f"subnormal scan L={seg}")
+    assert_exact(tcr.segmented_reduce(xd, seg), oracle.segmented_reduce(x, seg), f"subnormal reduce L={seg}")
+
+
+@pytest.mark.parametrize("seg", [64, 1024, 1 << 17])
+def test_last_scan_element_is_the_reduction(tcr, form, seg):
+    x = workloads.make_input(4 * max(seg, 8192), "int8", 12)
+    xd = dev(x)
+    scan = tcr.segmented_scan(xd, seg)
+    red = tcr.segmented_reduce(xd, seg)
+    assert torch.equal(scan[seg - 1:: seg], red)
+    # first differences give back the input
+    d = torch.diff(scan.view(-1, seg), dim=1)
+    assert torch.equal(d, xd.view(-1, seg)[:, 1:].float())
+
+
+# ------------------------------------------------------------------ cross-workgroup carry
+
+@pytest.mark.parametrize("carry", ["lookback", "reduce_then_scan"])
+def test_carry_strategies_agree_with_oracle(tcr, oracle, form, carry):
+    tcr.set_variant("scan_carry", carry)
+    for n, seg in (((1 << 21) + 12345, None), (1 << 21, 1 << 16), (3 << 19, 1 << 19)):
+        x = workloads.make_input(n, "int8", 77)
+        xd = dev(x)
+        if seg is None:
+            assert_exact(tcr.scan(xd), oracle.scan(x), f"scan n={n} {carry} {form}")
+        else:
+            assert_exact(tcr.segmented_scan(xd, seg), oracle.segmented_scan(x, seg), f"scan L={seg} {carry} {form}")
+
+
+def test_lookback_repeated_launches(tcr, oracle):
+    # many back-to-back launches reuse the descriptor table through its epoch tag and the running
+    # ticket counter; any early or lost carry shows up as a wrong integer
+    n = (1 << 22) + 777
+    x = workloads.make_input(n, "int8", 5)
+    xd = dev(x)
+    ref = torch.from_numpy(oracle.scan(x).astype(np.float32)).cuda()
+    outs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(4)]
+    for it in range(100):
+        tcr.scan(xd, out=outs[it % 4])
+        if it % 4 == 3:
+            for o in outs:
+                assert torch.equal(o, ref), f"iteration {it}"
+    # interleave a differently shaped problem on the same stream
+    y = workloads.make_input(1 << 20, "int4", 6)
+    yd = dev(y)
+    yref = oracle.segmented_scan(y, 1 << 18)
+    for it in range(10):
+        a = tcr.segmented_scan(yd, 1 << 18)
+        b = tcr.scan(xd)
+        assert_exact(a, yref, "interleaved segmented scan")
+        assert torch.equal(b, ref)
+    tcr.check_device_flags()
+
+
+def test_non_default_stream(tcr, oracle):
+    x = workloads.make_input((1 << 20) + 24, "int8", 8)
+    xd = dev(x)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        scan = tcr.scan(xd, stream=s)
+        red = tcr.segmented_reduce(xd[: 1 << 20], 1 << 18, stream=s)
+    s.synchronize()
+    assert_exact(scan, oracle.scan(x), "scan on a side stream")
+    assert_exact(red, oracle.segmented_reduce(np.ascontiguousarray(x[: 1 << 20]), 1 << 18), "reduce on a side stream")
+    tcr.check_device_flags(s)
+
+
+# ------------------------------------------------------------------ C ABI error paths on a live device
+
+def test_errors_on_device(tcr):
+    x = torch.zeros(4096 + 8, dtype=torch.float16, device="cuda")
+    out = torch.zeros(4096 + 8, dtype=torch.float32, device="cuda")
+    raw = tcr.raw()
+    assert raw.tcr_segmented_scan(x.data_ptr(), out.data_ptr(), 4096, 48, None) == tcr.ERR_INVALID_ARG   # 48 does not divide 4096
+    assert raw.tcr_segmented_scan(x.data_ptr(), out.data_ptr(), 4080, 48, None) == tcr.ERR_UNSUPPORTED
+    assert raw.tcr_segmented_reduce(x.data_ptr(), out.data_ptr(), 4096, 8, None) == tcr.ERR_UNSUPPORTED
+    assert raw.tcr_segmented_scan(x.data_ptr() + 2, out.data_ptr(), 4096, 16, None) == tcr.ERR_INVALID_ARG
+    assert raw.tcr_scan(x.data_ptr(), out.data_ptr() + 4, 4096, None) == tcr.ERR_INVALID_ARG
+    with pytest.raises(TypeError):
+        tcr.scan(x.float())
+    with pytest.raises(tcr.TcrError):
+        tcr.segmented_reduce(x[:4096], 100)
+    torch.cuda.synchronize()
