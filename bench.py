@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Throughput of the segmented reduce / scan hot path on one MI355X.
+
+One *step* is one pass of the whole hot path over one synthetic batch: the segment-length
+sweep at n = 2^28 binary16 elements (uniform[0,1), seed 4) -- a segmented reduction and a
+segmented inclusive scan for each seg_len in 2^4, 2^6, ..., 2^16, 2^20 (16 library calls).
+That sweep crosses every stage: in-tile products, wavefront and workgroup combines, the
+multi-workgroup carry, the partials pass of the long reductions, and the dispatch.
+
+Printed: ONE JSON line.  `value` is input bytes consumed per second over the whole step
+(16 x 512 MiB per step), inputs resident in HBM before the timed region starts.
+`roofline` describes the kernel that takes the most time in the step; its duration is
+measured with HIP events around each call on the launch stream in a second pass of the same
+steps.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+SWEEP = (4, 6, 8, 10, 12, 14, 16, 20)
+LOG2N = 28
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--log2n", type=int, default=LOG2N, help="elements = 2^log2n (default: the headline size)")
+    ap.add_argument("--formulation", default="mfma", choices=["mfma", "dpp"])
+    ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (segmented reduce/scan needs no second one); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1811_09736_amd import binding as tcr
+    from paper_1811_09736_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 3
+    tcr.set_variant("reset")
+    tcr.set_variant("formulation", args.formulation)
+    tcr.set_variant("scan_carry", args.scan_carry)
+
+    n = 1 << args.log2n
+    sweep = [e for e in SWEEP if e <= args.log2n]
+    x_host = workloads.make_input(n, "uniform_01", 4)
+    x = torch.from_numpy(x_host).cuda()
+    out_scan = torch.empty(n, dtype=torch.float32, device="cuda")
+    out_red = {e: torch.empty(n >> e, dtype=torch.float32, device="cuda") for e in sweep}
+    calls = [("segmented_reduce", e) for e in sweep] + [("segmented_scan", e) for e in sweep]
+
+    def run(op, e):
+        if op == "segmented_reduce":
+            tcr.segmented_reduce(x, 1 << e, out=out_red[e])
+        else:
+            tcr.segmented_scan(x, 1 << e, out=out_scan)
+
+    def step():
+        for op, e in calls:
+            run(op, e)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    in_bytes_per_step = 2 * n * len(calls)
+    value = in_bytes_per_step / (elapsed / args.steps) * 1e-9
+
+    # second pass: HIP events around every call (same stream the kernels are launched on)
+    stream = torch.cuda.current_stream()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+          for _ in range(args.steps)]
+    for s in range(args.steps):
+        for c, (op, e) in enumerate(calls):
+            ev[s][c][0].record(stream)
+            run(op, e)
+            ev[s][c][1].record(stream)
+    torch.cuda.synchronize()
+    tcr.check_device_flags()
+    rows = []
+    per_kernel = {}
+    op_id = {"segmented_reduce": tcr.OP_SEGMENTED_REDUCE, "segmented_scan": tcr.OP_SEGMENTED_SCAN}
+    for c, (op, e) in enumerate(calls):
+        ms = [ev[s][c][0].elapsed_time(ev[s][c][1]) for s in range(args.steps)]
+        avg = sum(ms) / len(ms)
+        rd, wr = workloads.algorithmic_bytes(op, n, 1 << e)
+        kname = tcr.kernel_name(op_id[op], n, 1 << e)
+        rows.append({"op": op, "seg_len_log2": e, "kernel": kname, "avg_us": round(avg * 1e3, 2),
+                     "min_us": round(min(ms) * 1e3, 2), "elem_per_s": n / (avg * 1e-3),
+                     "input_GBps": round(2 * n / (avg * 1e-3) * 1e-9, 1),
+                     "total_GBps": round((rd + wr) / (avg * 1e-3) * 1e-9, 1),
+                     "pct_of_hbm_peak": round((rd + wr) / (avg * 1e-3) * 1e-9 / HBM_PEAK_GBS * 100, 1)})
+        k = per_kernel.setdefault(kname, {"ms": 0.0, "bytes": 0, "launches": 0})
+        k["ms"] += sum(ms)
+        k["bytes"] += (rd + wr) * len(ms)
+        k["launches"] += len(ms)
+    dom_name, dom = max(per_kernel.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["bytes"] / (dom["ms"] * 1e-3) * 1e-9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath) and args.log2n == LOG2N:
+        with open(tpath) as fh:
+            traffic = json.load(fh).get(dom_name)
+    roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
+                "algorithmic_bytes_per_launch": dom["bytes"] // dom["launches"]}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample_log2 = min(args.log2n, 26)
+        xs = np.ascontiguousarray(x_host[: 1 << sample_log2])
+        t0 = time.perf_counter()
+        for op, e in calls:
+            if e > sample_log2:
+                e = sample_log2
+            if op == "segmented_reduce":
+                oracle.segmented_reduce(xs, 1 << e)
+            else:
+                oracle.segmented_scan(xs, 1 << e)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(2 * (1 << sample_log2) * len(calls) / dt * 1e-9, 4), "unit": "GB/s", "cores": 1,
+               "kind": "oracle",
+               "sample": f"the same 16 calls on the first 2^{sample_log2} elements of the input (seg_len capped at the sample), "
+                         f"sequential binary64 C loops, {dt:.1f} s"}
+
+    line = {
+        "metric": "effective input GB/s for segmented reduce + inclusive scan, seg_len sweep at N=2^%d" % args.log2n,
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg5 sweep: n=2^%d fp16 uniform[0,1) seed 4; segmented_reduce and segmented_scan at "
+                               "seg_len=2^{%s}; fp32 accumulate and output" % (args.log2n, ",".join(map(str, sweep))),
+                   "formulation": args.formulation, "scan_carry": args.scan_carry,
+                   "input_sha256": workloads.sha256(x_host)[:16]},
+        "roofline": roofline, "cpu_baseline": cpu, "rows": rows,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -38,12 +38,16 @@ struct Variant {
 };
 Variant g_variant;
 
-// Launch-shape constants (tiles per wavefront).  A workgroup is 4 wavefronts.
-constexpr int kSmallU = 4;            // reduce_small / scan_small: 4 tiles per wavefront, 8192 elements per workgroup
-constexpr int kScanU = 4;             // scan_block: 8192 elements per workgroup
-constexpr int kReduceU = 4;           // reduce_span: tiles in flight per wavefront
-constexpr uint64_t kReduceSpan = 16384;   // elements one wavefront folds before emitting a partial
-constexpr uint64_t kScanBlockTile = (uint64_t)kTile * kScanU * kWavesPerBlock;
+// Launch shapes (U = tiles of 512 elements per wavefront, W = wavefronts per workgroup) come from
+// timing sweeps at n = 2^28 on MI355X: short-lived wavefronts with one tile each stream best, so
+// every shape is the smallest workgroup share that still contains a whole segment; only segments
+// longer than 65536 elements (and the full scan) take a cross-workgroup carry.
+constexpr int kSmallScanW = 2;                       // scan_small: U = 1
+constexpr int kSmallReduceU = 2, kSmallReduceW = 4;  // reduce_small
+constexpr uint64_t kWaveSpanMax = 65536;             // reduce: longest span one wavefront folds
+constexpr int kReduceBlockW = 16;                    // reduce: wavefronts combined through LDS for longer segments
+constexpr int kCarryU = 8, kCarryW = 16;             // scan with cross-workgroup carry: 65536 elements per workgroup
+constexpr uint64_t kCarryTile = (uint64_t)kTile * kCarryU * kCarryW;
 constexpr uint64_t kMaxElements = 1ull << 40;
 
 // ---------------------------------------------------------------------------- workspace
@@ -154,46 +158,88 @@ tcr_status check_launch(const char* what) {
 // ---------------------------------------------------------------------------- reduce dispatch
 template <int FORM>
 tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
-    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * kSmallU * kWavesPerBlock);
-    const dim3 grid((unsigned)blocks), block(kBlockThreads);
+    constexpr int U = kSmallReduceU, W = kSmallReduceW;
+    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * U * W);
+    const dim3 grid((unsigned)blocks), block(W * kWave);
     switch (log2l) {
-        case 4: reduce_small_kernel<FORM, 4, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 5: reduce_small_kernel<FORM, 5, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 6: reduce_small_kernel<FORM, 6, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 7: reduce_small_kernel<FORM, 7, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 8: reduce_small_kernel<FORM, 8, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 9: reduce_small_kernel<FORM, 9, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 4: reduce_small_kernel<FORM, 4, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 5: reduce_small_kernel<FORM, 5, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 6: reduce_small_kernel<FORM, 6, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 7: reduce_small_kernel<FORM, 7, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 8: reduce_small_kernel<FORM, 8, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 9: reduce_small_kernel<FORM, 9, U, W><<<grid, block, 0, s>>>(in, out, n); break;
         default: return TCR_ERR_UNSUPPORTED;
     }
     return check_launch("reduce_small_kernel");
 }
 
-// seg_len >= 1024 (power of two) or one segment of any length.
-tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
-    const uint64_t nseg = n / seg_len;
-    const uint64_t span = seg_len < kReduceSpan ? ceil_div(seg_len, kTile) * kTile : kReduceSpan;
-    const uint64_t per = ceil_div(seg_len, span);          // partials per segment
-    const uint64_t nspans = nseg * per;
+template <int FORM>
+tcr_status launch_reduce_span(const _Float16* in, float* dst, uint64_t n, uint64_t span, uint64_t nspans,
+                              bool combine, hipStream_t s) {
+    if (combine) {
+        constexpr int W = kReduceBlockW;
+        reduce_span_kernel<FORM, 8, W, true><<<dim3((unsigned)ceil_div(nspans, W)), dim3(W * kWave), 0, s>>>(
+            in, dst, n, span, nspans);
+    } else {
+        const dim3 grid((unsigned)nspans), block(kWave);
+        if (span >= 8 * kTile) reduce_span_kernel<FORM, 8, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
+        else if (span >= 4 * kTile) reduce_span_kernel<FORM, 4, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
+        else reduce_span_kernel<FORM, 2, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
+    }
+    return check_launch("reduce_span_kernel");
+}
+
+struct ReducePlan {
+    uint64_t span;      // elements per wavefront
+    bool combine;       // workgroup of kReduceBlockW wavefronts adds its sums through LDS
+    uint64_t per;       // partials per segment left for reduce_final_kernel (1: results go straight to out)
+    uint64_t nspans;    // wavefronts in total
+};
+
+// seg_len >= 1024 (a power of two), or one segment of any length (whole).
+ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
+    ReducePlan p;
+    if (!whole && seg_len <= kWaveSpanMax) {             // one wavefront per segment
+        p.span = seg_len; p.combine = false; p.per = 1; p.nspans = n / seg_len;
+        return p;
+    }
+    if (whole) {
+        // enough wavefronts to fill the chip, spans between 4096 and 65536 elements
+        uint64_t span = 4096;
+        while (span < kWaveSpanMax && n / span > 8192) span <<= 1;
+        p.span = span;
+        p.nspans = ceil_div(n, span);
+        p.combine = p.nspans > 1;
+        p.per = p.combine ? ceil_div(p.nspans, (uint64_t)kReduceBlockW) : 1;
+        if (!p.combine) p.span = ceil_div(n, kTile) * kTile;
+        return p;
+    }
+    // power-of-two segment longer than one wavefront span: kReduceBlockW spans per workgroup
+    p.span = kWaveSpanMax;
+    while (p.span * kReduceBlockW > seg_len) p.span >>= 1;      // seg_len >= 2^17, so span >= 8192
+    p.combine = true;
+    p.per = seg_len / (p.span * kReduceBlockW);
+    p.nspans = n / p.span;
+    return p;
+}
+
+tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, bool whole, hipStream_t s) {
+    const ReducePlan p = plan_reduce(n, seg_len, whole);
+    const uint64_t nseg = whole ? 1 : n / seg_len;
     float* dst = out;
-    Workspace* ws = nullptr;
-    if (per > 1) {
+    if (p.per > 1) {
+        Workspace* ws = nullptr;
         tcr_status st = get_workspace(s, &ws);
         if (st != TCR_OK) return st;
-        st = ensure_partials(ws, s, nspans);
+        st = ensure_partials(ws, s, nseg * p.per);
         if (st != TCR_OK) return st;
         dst = ws->partials;
     }
-    const dim3 grid((unsigned)ceil_div(nspans, kWavesPerBlock)), block(kBlockThreads);
-    // spans tile the input uniformly: span w covers [w*span, (w+1)*span) because per*span == seg_len
-    // whenever per > 1 (seg_len is then a power of two >= kReduceSpan) or nseg == 1.
-    if (g_variant.formulation == kMfma)
-        reduce_span_kernel<kMfma, kReduceU><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
-    else
-        reduce_span_kernel<kDpp, kReduceU><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
-    tcr_status st = check_launch("reduce_span_kernel");
+    tcr_status st = g_variant.formulation == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s)
+                                                   : launch_reduce_span<kDpp>(in, dst, n, p.span, p.nspans, p.combine, s);
     if (st != TCR_OK) return st;
-    if (per > 1) {
-        reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kBlockThreads), 0, s>>>(dst, out, per);
+    if (p.per > 1) {
+        reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kFinalThreads), 0, s>>>(dst, out, p.per);
         st = check_launch("reduce_final_kernel");
     }
     return st;
@@ -202,25 +248,41 @@ tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_
 // ---------------------------------------------------------------------------- scan dispatch
 template <int FORM>
 tcr_status launch_scan_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
-    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * kSmallU * kWavesPerBlock);
-    const dim3 grid((unsigned)blocks), block(kBlockThreads);
+    constexpr int W = kSmallScanW;
+    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * W);
+    const dim3 grid((unsigned)blocks), block(W * kWave);
     switch (log2l) {
-        case 4: scan_small_kernel<FORM, 4, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 5: scan_small_kernel<FORM, 5, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 6: scan_small_kernel<FORM, 6, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 7: scan_small_kernel<FORM, 7, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 8: scan_small_kernel<FORM, 8, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
-        case 9: scan_small_kernel<FORM, 9, kSmallU><<<grid, block, 0, s>>>(in, out, n); break;
+        case 4: scan_small_kernel<FORM, 4, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 5: scan_small_kernel<FORM, 5, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 6: scan_small_kernel<FORM, 6, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 7: scan_small_kernel<FORM, 7, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 8: scan_small_kernel<FORM, 8, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 9: scan_small_kernel<FORM, 9, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
         default: return TCR_ERR_UNSUPPORTED;
     }
     return check_launch("scan_small_kernel");
 }
 
-template <int FORM, int CARRY>
+template <int FORM, int U, int W, int CARRY>
 void launch_scan_block(const _Float16* in, float* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
-                       const ScanWorkspace& dev, const float* prefix, unsigned blocks, hipStream_t s) {
-    scan_block_kernel<FORM, kScanU, CARRY><<<dim3(blocks), dim3(kBlockThreads), 0, s>>>(in, out, n, seg_mask, seg_len,
-                                                                                         dev, prefix);
+                       const ScanWorkspace& dev, const float* prefix, hipStream_t s) {
+    const unsigned blocks = (unsigned)ceil_div(n, (uint64_t)kTile * U * W);
+    scan_block_kernel<FORM, U, W, CARRY><<<dim3(blocks), dim3(W * kWave), 0, s>>>(in, out, n, seg_mask, seg_len, dev,
+                                                                                   prefix);
+}
+
+// Segments that fit one workgroup: the smallest workgroup share that holds a whole segment.
+template <int FORM>
+void launch_scan_nocarry(const _Float16* in, float* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+                         uint64_t fit, hipStream_t s) {
+    const ScanWorkspace none = {};
+    if (fit <= 1024) launch_scan_block<FORM, 1, 2, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 2048) launch_scan_block<FORM, 1, 4, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 4096) launch_scan_block<FORM, 1, 8, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 8192) launch_scan_block<FORM, 1, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 16384) launch_scan_block<FORM, 2, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 32768) launch_scan_block<FORM, 4, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else launch_scan_block<FORM, 8, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
 }
 
 // seg_len >= 1024 (power of two), or the full scan (seg_len == n, any n).
@@ -228,51 +290,44 @@ tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_le
     const uint64_t seg_mask = whole ? ~0ull : seg_len - 1;
     const uint64_t host_seg_len = seg_len;            // decides the launch; the kernels see a saturated
     if (whole) seg_len = ~0ull;                       // length for the one-segment case (n need not be a power of two)
-    const uint64_t tiles = ceil_div(n, kScanBlockTile);
-    const unsigned blocks = (unsigned)tiles;
     const bool mfma_form = g_variant.formulation == kMfma;
-    ScanWorkspace dev = {};
-    if (host_seg_len <= kScanBlockTile) {
-        if (mfma_form) launch_scan_block<kMfma, kNoCarry>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
-        else launch_scan_block<kDpp, kNoCarry>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
+    if (host_seg_len <= kCarryTile) {
+        if (mfma_form) launch_scan_nocarry<kMfma>(in, out, n, seg_mask, seg_len, host_seg_len, s);
+        else launch_scan_nocarry<kDpp>(in, out, n, seg_mask, seg_len, host_seg_len, s);
         return check_launch("scan_block_kernel");
     }
+    const uint64_t tiles = ceil_div(n, kCarryTile);
+    ScanWorkspace dev = {};
     Workspace* ws = nullptr;
     tcr_status st = get_workspace(s, &ws);
     if (st != TCR_OK) return st;
     if (g_variant.scan_carry == kLookback) {
         st = begin_lookback(ws, s, tiles, &dev);
         if (st != TCR_OK) return st;
-        if (mfma_form) launch_scan_block<kMfma, kLookback>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
-        else launch_scan_block<kDpp, kLookback>(in, out, n, seg_mask, seg_len, dev, nullptr, blocks, s);
+        if (mfma_form) launch_scan_block<kMfma, kCarryU, kCarryW, kLookback>(in, out, n, seg_mask, seg_len, dev, nullptr, s);
+        else launch_scan_block<kDpp, kCarryU, kCarryW, kLookback>(in, out, n, seg_mask, seg_len, dev, nullptr, s);
         st = check_launch("scan_block_kernel");
         if (st != TCR_OK) {
             ws->dirty = true;
             return st;
         }
-        ws->tickets_issued += blocks;      // wraps modulo 2^32 like the device counter
+        ws->tickets_issued += (uint32_t)tiles;      // wraps modulo 2^32 like the device counter
         return TCR_OK;
     }
     // reduce-then-scan: workgroup totals, their exclusive scan per segment, then the scan proper
     st = ensure_partials(ws, s, tiles);
     if (st != TCR_OK) return st;
-    const dim3 block(kBlockThreads);
-    // one span per workgroup tile; spans are uniform because seg_len is a multiple of the tile (or one segment)
-    if (mfma_form)
-        reduce_span_kernel<kMfma, kReduceU><<<dim3((unsigned)ceil_div(tiles, kWavesPerBlock)), block, 0, s>>>(
-            in, ws->partials, n, kScanBlockTile, tiles);
-    else
-        reduce_span_kernel<kDpp, kReduceU><<<dim3((unsigned)ceil_div(tiles, kWavesPerBlock)), block, 0, s>>>(
-            in, ws->partials, n, kScanBlockTile, tiles);
-    st = check_launch("reduce_span_kernel");
+    // one wavefront span per workgroup tile; spans are uniform because seg_len is a multiple of the tile (or one segment)
+    st = mfma_form ? launch_reduce_span<kMfma>(in, ws->partials, n, kCarryTile, tiles, false, s)
+                   : launch_reduce_span<kDpp>(in, ws->partials, n, kCarryTile, tiles, false, s);
     if (st != TCR_OK) return st;
-    const uint64_t per = whole ? tiles : host_seg_len / kScanBlockTile;
+    const uint64_t per = whole ? tiles : host_seg_len / kCarryTile;
     const uint64_t groups = whole ? 1 : n / host_seg_len;
-    scan_partials_kernel<<<dim3((unsigned)groups), block, 0, s>>>(ws->partials, per);
+    scan_partials_kernel<<<dim3((unsigned)groups), dim3(kPartialsThreads), 0, s>>>(ws->partials, per);
     st = check_launch("scan_partials_kernel");
     if (st != TCR_OK) return st;
-    if (mfma_form) launch_scan_block<kMfma, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, blocks, s);
-    else launch_scan_block<kDpp, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, blocks, s);
+    if (mfma_form) launch_scan_block<kMfma, kCarryU, kCarryW, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, s);
+    else launch_scan_block<kDpp, kCarryU, kCarryW, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, s);
     return check_launch("scan_block_kernel");
 }
 
@@ -295,12 +350,12 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     if (st != TCR_OK || n == 0) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const _Float16* x = static_cast<const _Float16*>(in);
-    if (seg_len == n) return reduce_long(x, out, n, n, s);
+    if (seg_len == n) return reduce_long(x, out, n, n, true, s);
     if (!is_pow2(seg_len) || seg_len < 16) return TCR_ERR_UNSUPPORTED;
     if (seg_len <= kTile)
         return g_variant.formulation == kMfma ? launch_reduce_small<kMfma>(x, out, n, log2u(seg_len), s)
                                               : launch_reduce_small<kDpp>(x, out, n, log2u(seg_len), s);
-    return reduce_long(x, out, n, seg_len, s);
+    return reduce_long(x, out, n, seg_len, false, s);
 }
 
 extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
@@ -325,7 +380,7 @@ extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* s
     }
     tcr_status st = validate(in, out, n, n, 4);
     if (st != TCR_OK) return st;
-    return reduce_long(static_cast<const _Float16*>(in), out, n, n, s);
+    return reduce_long(static_cast<const _Float16*>(in), out, n, n, true, s);
 }
 
 extern "C" tcr_status tcr_scan(const void* in, float* out, uint64_t n, void* stream) {
@@ -357,20 +412,21 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
 }
 
 extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
+    if (op == 2 || op == 3) seg_len = n;
     if (n == 0 || seg_len == 0 || n % seg_len != 0) return "";
     const bool mf = g_variant.formulation == kMfma;
-    const bool whole = (op == 2 || op == 3 || seg_len == n);
-    if (op == 2) seg_len = n;
-    if (op == 3) seg_len = n;
+    const bool whole = seg_len == n;
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) return "";
     if (op == 0 || op == 2) {
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";
-        if (seg_len <= kReduceSpan) return mf ? "reduce_span_kernel<mfma>" : "reduce_span_kernel<dpp>";
-        return mf ? "reduce_span_kernel<mfma>+reduce_final_kernel" : "reduce_span_kernel<dpp>+reduce_final_kernel";
+        const ReducePlan p = plan_reduce(n, seg_len, whole);
+        if (!p.combine) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
+        if (p.per == 1) return mf ? "reduce_span_kernel<mfma,block>" : "reduce_span_kernel<dpp,block>";
+        return mf ? "reduce_span_kernel<mfma,block>+reduce_final_kernel" : "reduce_span_kernel<dpp,block>+reduce_final_kernel";
     }
     if (op == 1 || op == 3) {
         if (!whole && seg_len <= kTile) return mf ? "scan_small_kernel<mfma>" : "scan_small_kernel<dpp>";
-        if (seg_len <= kScanBlockTile) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
+        if (seg_len <= kCarryTile) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
         if (g_variant.scan_carry == kLookback) return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";
         return mf ? "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<mfma,table>"
                   : "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<dpp,table>";

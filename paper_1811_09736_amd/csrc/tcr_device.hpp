@@ -29,8 +29,6 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 constexpr int kWave = 64;
 constexpr int kTile = 512;          // elements per wavefront tile (16 rows x 32)
 constexpr int kRow = 32;            // elements per tile row
-constexpr int kBlockThreads = 256;  // 4 wavefronts per workgroup
-constexpr int kWavesPerBlock = kBlockThreads / kWave;
 
 // ---------------------------------------------------------------- cross-lane primitives
 

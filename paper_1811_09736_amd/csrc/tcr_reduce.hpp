@@ -8,7 +8,8 @@
 //   reduce_span_kernel    seg_len >= 1024 and the full reduction: each wavefront walks a span of
 //                         consecutive tiles and keeps the 16 running row sums in the accumulator,
 //                         V_i = ones.A_i + V_{i-1} (the work-efficient Reduction_256N), folding
-//                         the 16 sums once at the end.
+//                         the 16 sums once at the end; optionally the wavefronts of a workgroup
+//                         combine their sums through LDS (block-level Reduction_256N).
 //   reduce_final_kernel   device level: binary32 partials of one segment -> its result (the
 //                         second kernel of the paper's grid-level reduction).
 //
@@ -41,14 +42,14 @@ __device__ __forceinline__ float sum8(half8 v) {
 }
 
 // ------------------------------------------------------------------------------ small segments
-// Grid: one workgroup per 4*U tiles.  n is a multiple of seg_len = 1 << LOG2L.
-template <int FORM, int LOG2L, int U>
-__global__ __launch_bounds__(kBlockThreads) void reduce_small_kernel(const _Float16* __restrict__ in,
+// Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.  n is a multiple of seg_len = 1 << LOG2L.
+template <int FORM, int LOG2L, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Float16* __restrict__ in,
                                                                      float* __restrict__ out, uint64_t n) {
     static_assert(LOG2L >= 4 && LOG2L <= 9, "");
     const LaneId id;
     const int wave = threadIdx.x >> 6;
-    const uint64_t base = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * (uint64_t)(kTile * U);
+    const uint64_t base = ((uint64_t)blockIdx.x * WAVES + wave) * (uint64_t)(kTile * U);
     if (base >= n) return;
     const uint64_t nseg = n >> LOG2L;
     // element offset of this lane's 8 values inside a tile
@@ -89,50 +90,67 @@ __global__ __launch_bounds__(kBlockThreads) void reduce_small_kernel(const _Floa
 }
 
 // ------------------------------------------------------------------------------ long spans
-// Wavefront w reduces elements [w*span, min((w+1)*span, n)) into dst[w].  span is a multiple of
-// the tile size.  When span == seg_len, dst is the output itself.
-template <int FORM, int U>
-__global__ __launch_bounds__(kBlockThreads) void reduce_span_kernel(const _Float16* __restrict__ in,
+// Wavefront w (global index) reduces elements [w*span, min((w+1)*span, n)); span is a multiple
+// of the tile size.  COMBINE == false: dst[w] receives that sum (one wavefront per segment or per
+// partial).  COMBINE == true: the WAVES sums of a workgroup are added through LDS in wavefront
+// order and dst[blockIdx.x] receives the result (block-level Reduction_256N: one workgroup per
+// segment or per partial).
+template <int FORM, int U, int WAVES, bool COMBINE>
+__global__ __launch_bounds__(WAVES * kWave) void reduce_span_kernel(const _Float16* __restrict__ in,
                                                                     float* __restrict__ dst, uint64_t n,
                                                                     uint64_t span, uint64_t nspans) {
+    __shared__ float s_total[WAVES];
     const LaneId id;
-    const uint64_t w = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (w >= nspans) return;
-    const uint64_t begin = w * span;
-    const uint64_t end = (begin + span < n) ? begin + span : n;
-    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
-
-    float4v acc = splat(0.0f);          // MFMA: running row sums (the accumulator matrix V)
-    float s0 = 0.0f, s1 = 0.0f;         // DPP: per-lane running sums
-    uint64_t t = begin;
-    for (; t + (uint64_t)(kTile * U) <= end; t += (uint64_t)(kTile * U)) {
-        half8 x[U];
+    const int wave = threadIdx.x >> 6;
+    const uint64_t w = (uint64_t)blockIdx.x * WAVES + wave;
+    float total = 0.0f;
+    if (w < nspans) {
+        const uint64_t begin = w * span;
+        const uint64_t end = (begin + span < n) ? begin + span : n;
+        const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
+        float4v acc = splat(0.0f);          // MFMA: running row sums (the accumulator matrix V)
+        float s0 = 0.0f, s1 = 0.0f;         // DPP: per-lane running sums
+        uint64_t t = begin;
+        for (; t + (uint64_t)(kTile * U) <= end; t += (uint64_t)(kTile * U)) {
+            half8 x[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = load8(in, t + (uint64_t)(kTile * u + lane_off));
+            for (int u = 0; u < U; ++u) x[u] = load8(in, t + (uint64_t)(kTile * u + lane_off));
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if constexpr (FORM == kMfma) acc = mfma(const_ones(), x[u], acc);
-            else if (u & 1) s1 += sum8(x[u]);
-            else s0 += sum8(x[u]);
+            for (int u = 0; u < U; ++u) {
+                if constexpr (FORM == kMfma) acc = mfma(const_ones(), x[u], acc);
+                else if (u & 1) s1 += sum8(x[u]);
+                else s0 += sum8(x[u]);
+            }
+        }
+        for (; t < end; t += kTile) {
+            const half8 x = load8_guarded(in, t + (uint64_t)lane_off, end);
+            if constexpr (FORM == kMfma) acc = mfma(const_ones(), x, acc);
+            else s0 += sum8(x);
+        }
+        if constexpr (FORM == kMfma) total = read_lane(row_sum_to_last<16>(acc[0]), 15);   // fold the 16 row sums
+        else total = read_lane(lanes_sum_to_last<64>(s0 + s1), 63);
+    }
+    if constexpr (!COMBINE) {
+        if (w < nspans && id.lane == 0) dst[w] = total;
+    } else {
+        if (id.lane == 0) s_total[wave] = total;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int k = 0; k < WAVES; ++k) sum += s_total[k];
+            dst[blockIdx.x] = sum;
         }
     }
-    for (; t < end; t += kTile) {
-        const half8 x = load8_guarded(in, t + (uint64_t)lane_off, end);
-        if constexpr (FORM == kMfma) acc = mfma(const_ones(), x, acc);
-        else s0 += sum8(x);
-    }
-    float total;
-    if constexpr (FORM == kMfma) total = row_sum_to_last<16>(acc[0]);   // lane 15: sum over the 16 rows
-    else total = lanes_sum_to_last<64>(s0 + s1);              // lane 63
-    const int last = (FORM == kMfma) ? 15 : 63;
-    if (id.lane == last) dst[w] = total;
 }
 
 // ------------------------------------------------------------------------------ partials -> result
 // Workgroup s adds the `per` binary32 partials of segment s in a fixed order.
-__global__ __launch_bounds__(kBlockThreads) void reduce_final_kernel(const float* __restrict__ partials,
+constexpr int kFinalThreads = 256;
+__global__ __launch_bounds__(kFinalThreads) void reduce_final_kernel(const float* __restrict__ partials,
                                                                      float* __restrict__ out, uint64_t per) {
-    __shared__ float wave_tot[kWavesPerBlock];
+    constexpr int kBlockThreads = kFinalThreads;
+    __shared__ float wave_tot[kFinalThreads / kWave];
     const float* p = partials + (uint64_t)blockIdx.x * per;
     float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
     uint64_t i = threadIdx.x;

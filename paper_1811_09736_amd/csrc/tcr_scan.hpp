@@ -23,6 +23,11 @@
 #include "tcr_device.hpp"
 #include "tcr_reduce.hpp"
 
+#ifndef TCR_TRACE_POINT
+#define TCR_TRACE_POINT(i)
+#define TCR_TRACE_ENTRY()
+#endif
+
 namespace tcr {
 
 enum CarryMode { kNoCarry = 0, kLookback = 1, kTable = 2 };
@@ -51,13 +56,13 @@ __device__ __forceinline__ void scan8(half8 v, float (&p)[8]) {
 }
 
 // ------------------------------------------------------------------------------ small segments
-template <int FORM, int LOG2L, int U>
-__global__ __launch_bounds__(kBlockThreads) void scan_small_kernel(const _Float16* __restrict__ in,
+template <int FORM, int LOG2L, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float16* __restrict__ in,
                                                                    float* __restrict__ out, uint64_t n) {
     static_assert(LOG2L >= 4 && LOG2L <= 9, "");
     const LaneId id;
     const int wave = threadIdx.x >> 6;
-    const uint64_t base = ((uint64_t)blockIdx.x * kWavesPerBlock + wave) * (uint64_t)(kTile * U);
+    const uint64_t base = ((uint64_t)blockIdx.x * WAVES + wave) * (uint64_t)(kTile * U);
     if (base >= n) return;
     const bool full = base + (uint64_t)(kTile * U) <= n;
     const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
@@ -138,7 +143,11 @@ __device__ __forceinline__ unsigned long long pack_desc(uint32_t epoch, uint32_t
 
 // Executed by one whole wavefront.  Returns (uniformly) the sum of the totals of all earlier
 // tiles of this tile's segment and publishes this tile's own state.
-//   pos        index of this tile inside its segment (0 = first tile of the segment)
+//   pos   index of this tile inside its segment (0 = first tile of the segment)
+//   K     descriptors inspected per lane and round: the window is the 64*K nearest predecessors.
+// The front of finished prefixes can advance by at most one window per memory round trip, so
+// the window times the tile size bounds the throughput of the whole scan.
+template <int K>
 __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint64_t pos,
                                                            float total, int lane) {
     if (pos == 0) {
@@ -150,42 +159,62 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
     if (lane == 0)
         __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusAggregate, total), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
+    constexpr int kNone = 1 << 30;
     float acc = 0.0f;
-    uint64_t dist = (uint64_t)lane + 1;          // this lane inspects tile - dist
-    bool done = false;
-    while (!done) {
-        const bool valid = dist <= pos;          // never look past the first tile of the segment
-        uint32_t status = kStatusPrefix;         // lanes past the segment start act as "prefix 0"
-        float value = 0.0f;
-        bool ready = !valid;
+    uint64_t base = 0;                           // this round inspects distances base+1 .. base+64K
+    while (true) {
+        uint32_t status[K];
+        float value[K];
+        bool ready[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const bool valid = base + 1 + (uint64_t)(kWave * k + lane) <= pos;   // not past the segment's first tile
+            status[k] = kStatusPrefix;           // slots past the segment start act as "prefix 0"
+            value[k] = 0.0f;
+            ready[k] = !valid;
+        }
+        int nearest = kNone;                     // window slot (64k + lane) of the nearest finished prefix
         int polls = 0;
         while (true) {
-            if (!ready) {
-                const unsigned long long d = __hip_atomic_load(&ws.desc[tile - (uint32_t)dist], __ATOMIC_RELAXED,
-                                                               __HIP_MEMORY_SCOPE_AGENT);
-                const uint32_t tag = (uint32_t)(d >> 32);
-                if ((tag >> 2) == ws.epoch && (tag & 3u) != 0u) {
-                    status = tag & 3u;
-                    value = __builtin_bit_cast(float, (uint32_t)d);
-                    ready = true;
+            // all K reads are issued before any is examined, so a round costs one memory round trip
+            unsigned long long d[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t dist = (uint32_t)base + 1u + (uint32_t)(kWave * k + lane);
+                d[k] = ready[k] ? 0ull
+                                : __hip_atomic_load(&ws.desc[tile - dist], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t tag = (uint32_t)(d[k] >> 32);
+                if (!ready[k] && (tag >> 2) == ws.epoch && (tag & 3u) != 0u) {
+                    status[k] = tag & 3u;
+                    value[k] = __builtin_bit_cast(float, (uint32_t)d[k]);
+                    ready[k] = true;
                 }
             }
-            if (__ballot(!ready) == 0ull) break;
+            nearest = kNone;
+#pragma unroll
+            for (int k = K - 1; k >= 0; --k) {
+                const unsigned long long m = __ballot(ready[k] && status[k] == kStatusPrefix);
+                if (m != 0ull) nearest = kWave * k + __builtin_ctzll(m);
+            }
+            bool waiting = false;                // a slot nearer than that prefix is still unwritten
+#pragma unroll
+            for (int k = 0; k < K; ++k) waiting = waiting || (!ready[k] && kWave * k + lane < nearest);
+            if (__ballot(waiting) == 0ull) break;
             if (++polls > kSpinLimit) {          // should be unreachable: predecessors hold earlier tickets
                 if (lane == 0) __hip_atomic_store(ws.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        const unsigned long long prefix_lanes = __ballot(status == kStatusPrefix);
-        if (prefix_lanes != 0ull) {
-            const int nearest = __builtin_ctzll(prefix_lanes);
-            acc += wave_sum(lane <= nearest ? value : 0.0f);
-            done = true;
-        } else {
-            acc += wave_sum(value);
-            dist += kWave;
-        }
+        float part = 0.0f;
+#pragma unroll
+        for (int k = 0; k < K; ++k) part += (ready[k] && kWave * k + lane <= nearest) ? value[k] : 0.0f;
+        acc += wave_sum(part);
+        if (nearest != kNone) break;
+        base += (uint64_t)(kWave * K);
     }
     if (lane == 0)
         __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, acc + total), __ATOMIC_RELAXED,
@@ -196,23 +225,24 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
 // ------------------------------------------------------------------------------ long segments
 // seg_mask  = seg_len - 1 for a power-of-two seg_len, all ones for the full scan (one segment).
 // seg_len   only compared against the wavefront / workgroup share (saturated for the full scan).
-// Grid: one workgroup per 4*U tiles.
-template <int FORM, int U, int CARRY>
-__global__ __launch_bounds__(kBlockThreads) void scan_block_kernel(const _Float16* __restrict__ in,
+// Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.
+template <int FORM, int U, int WAVES, int CARRY, int LBK = 1, bool TICKET = true>
+__global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float16* __restrict__ in,
                                                                    float* __restrict__ out, uint64_t n,
                                                                    uint64_t seg_mask, uint64_t seg_len,
                                                                    ScanWorkspace ws,
                                                                    const float* __restrict__ tile_prefix) {
     constexpr uint64_t kChunk = (uint64_t)kTile * U;             // one wavefront's share
-    constexpr uint64_t kBlockTile = kChunk * kWavesPerBlock;     // one workgroup's share
-    __shared__ float s_wave_total[kWavesPerBlock];
+    constexpr uint64_t kBlockTile = kChunk * WAVES;              // one workgroup's share
+    __shared__ float s_wave_total[WAVES];
     __shared__ float s_prefix;
     __shared__ uint32_t s_tile;
 
     const LaneId id;
     const int wave = threadIdx.x >> 6;
     uint32_t tile = blockIdx.x;
-    if constexpr (CARRY == kLookback) {
+    TCR_TRACE_ENTRY();
+    if constexpr (CARRY == kLookback && TICKET) {
         // tiles are handed out in launch order, so every predecessor of a waiting tile is
         // already running or finished
         if (threadIdx.x == 0)
@@ -220,6 +250,7 @@ __global__ __launch_bounds__(kBlockThreads) void scan_block_kernel(const _Float1
         __syncthreads();
         tile = s_tile;
     }
+    TCR_TRACE_POINT(0);
     const uint64_t block_base = (uint64_t)tile * kBlockTile;
     const uint64_t base = block_base + (uint64_t)wave * kChunk;
     const bool full = base + kChunk <= n;
@@ -271,9 +302,13 @@ __global__ __launch_bounds__(kBlockThreads) void scan_block_kernel(const _Float1
         if (CARRY != kNoCarry && seg_len > kBlockTile) {
             if constexpr (CARRY == kLookback) {
                 if (wave == 0) {
-                    const float total = (s_wave_total[0] + s_wave_total[1]) + (s_wave_total[2] + s_wave_total[3]);
+                    float total = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w) total += s_wave_total[w];
                     const uint64_t pos = (block_base & seg_mask) / kBlockTile;
-                    const float pre = lookback_exclusive_prefix(ws, tile, pos, total, id.lane);
+                    TCR_TRACE_POINT(1);
+                    const float pre = lookback_exclusive_prefix<LBK>(ws, tile, pos, total, id.lane);
+                    TCR_TRACE_POINT(2);
                     if (id.lane == 0) s_prefix = pre;
                 }
                 __syncthreads();
@@ -310,12 +345,15 @@ __global__ __launch_bounds__(kBlockThreads) void scan_block_kernel(const _Float1
             store4_guarded(out, off_hi, n, hi);
         }
     }
+    TCR_TRACE_POINT(3);
 }
 
 // ------------------------------------------------------------------------------ reduce-then-scan helper
 // Workgroup s turns the `per` workgroup totals of segment s into exclusive prefixes, in place.
-__global__ __launch_bounds__(kBlockThreads) void scan_partials_kernel(float* __restrict__ totals, uint64_t per) {
-    __shared__ float s_wave[kWavesPerBlock];
+constexpr int kPartialsThreads = 256;
+__global__ __launch_bounds__(kPartialsThreads) void scan_partials_kernel(float* __restrict__ totals, uint64_t per) {
+    constexpr int kBlockThreads = kPartialsThreads;
+    __shared__ float s_wave[kPartialsThreads / kWave];
     float* p = totals + (uint64_t)blockIdx.x * per;
     const uint64_t run_len = (per + kBlockThreads - 1) / kBlockThreads;
     const uint64_t lo = (uint64_t)threadIdx.x * run_len;

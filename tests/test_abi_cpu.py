@@ -88,13 +88,15 @@ def test_dispatch_by_segment_length(lib):
     for e in range(4, 10):
         assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e).startswith("reduce_small_kernel")
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e).startswith("scan_small_kernel")
-    for e in (10, 12, 14):
-        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma>"
-    for e in (16, 20):
-        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e).endswith("+reduce_final_kernel")
-        assert "lookback" in k(lib.OP_SEGMENTED_SCAN, n, 1 << e)
-    for e in (10, 12):
-        assert "nocarry" in k(lib.OP_SEGMENTED_SCAN, n, 1 << e)
+    for e in (10, 12, 14, 16):
+        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma,wave>"
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,nocarry>"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20) == "reduce_span_kernel<mfma,block>"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 24).endswith("+reduce_final_kernel")
+    assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 20) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
+    assert k(lib.OP_REDUCE, 1000, 1000) == "reduce_span_kernel<mfma,wave>"
+    assert k(lib.OP_SCAN, n, n) == "scan_block_kernel<mfma,lookback>"
+    assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SEGMENTED_SCAN, n, 48) == ""          # no kernel: the call reports "unsupported"
     assert k(lib.OP_SEGMENTED_SCAN, 0, 16) == ""

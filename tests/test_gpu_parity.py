@@ -76,7 +76,7 @@ def ragged_n(seg: int) -> int:
 
 
 SMALL_SEGS = [16, 32, 64, 128, 256, 512]
-LONG_SEGS = [1024, 2048, 4096, 8192, 16384, 32768, 1 << 16, 1 << 18]
+LONG_SEGS = [1024, 2048, 4096, 8192, 16384, 32768, 1 << 16, 1 << 17, 1 << 18, 1 << 20, 1 << 21]
 
 
 # ------------------------------------------------------------------ segmented, moderate sizes
