@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--formulation", default="mfma", choices=["mfma", "dpp"])
     ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (read 1 GiB, write 1 GiB) three times before the timed "
+                         "region, as the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (segmented reduce/scan needs no second one); "
@@ -75,6 +78,13 @@ def main() -> int:
         for op, e in calls:
             run(op, e)
 
+    if args.calibration_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

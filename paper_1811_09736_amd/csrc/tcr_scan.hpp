@@ -23,11 +23,6 @@
 #include "tcr_device.hpp"
 #include "tcr_reduce.hpp"
 
-#ifndef TCR_TRACE_POINT
-#define TCR_TRACE_POINT(i)
-#define TCR_TRACE_ENTRY()
-#endif
-
 namespace tcr {
 
 enum CarryMode { kNoCarry = 0, kLookback = 1, kTable = 2 };
@@ -117,6 +112,57 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
         } else {
             store4_guarded(out, off_lo, n, lo);
             store4_guarded(out, off_hi, n, hi);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------ one wavefront per segment
+// Scan_256N as a stream: wavefront w walks segment w tile by tile, U tiles in flight, and the
+// running total of the tiles already done (the paper's S matrix) enters each tile's products
+// through the accumulator.  No LDS, no barrier, no dependence between wavefronts.
+// n is a multiple of seg_len; seg_len is a multiple of the tile size.
+template <int FORM, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void scan_wave_kernel(const _Float16* __restrict__ in,
+                                                                  float* __restrict__ out, uint64_t n,
+                                                                  uint64_t seg_len) {
+    const LaneId id;
+    const uint64_t seg = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t begin = seg * seg_len;
+    if (begin >= n) return;
+    const uint64_t end = begin + seg_len;
+    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
+    const int store_off = (FORM == kMfma) ? (kRow * id.j + 4 * id.g) : (8 * id.lane);
+    constexpr int kHi = (FORM == kMfma) ? 16 : 4;      // distance between a lane's two 4-element outputs
+    float run = 0.0f;                                  // total of the tiles of this segment already done
+    for (uint64_t t = begin; t < end; t += (uint64_t)(kTile * U)) {
+        half8 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (t + (uint64_t)(kTile * u) < end) x[u] = load8(in, t + (uint64_t)(kTile * u + lane_off));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t tbase = t + (uint64_t)(kTile * u);
+            if (tbase < end) {
+                float4v lo, hi;
+                if constexpr (FORM == kMfma) {
+                    const float4v tot = mfma(const_ones(), x[u], splat(0.0f));
+                    const float incl = row_scan_inclusive<16>(tot[0], id.j);
+                    const float carry = row_shr<1>(incl) + run;
+                    lo = mfma(const_tri_lo(id), x[u], splat(carry));
+                    hi = mfma(const_tri_hi(id), x[u], splat(carry));
+                    run += read_lane(incl, 15);
+                } else {
+                    float p[8];
+                    scan8(x[u], p);
+                    const float incl = wave_scan_inclusive(p[7]);
+                    const float carry = wave_shr1(incl) + run;
+                    lo = (float4v){p[0] + carry, p[1] + carry, p[2] + carry, p[3] + carry};
+                    hi = (float4v){p[4] + carry, p[5] + carry, p[6] + carry, p[7] + carry};
+                    run += read_lane(incl, 63);
+                }
+                store4(out, tbase + (uint64_t)store_off, lo);
+                store4(out, tbase + (uint64_t)(store_off + kHi), hi);
+            }
         }
     }
 }
@@ -241,7 +287,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
     const LaneId id;
     const int wave = threadIdx.x >> 6;
     uint32_t tile = blockIdx.x;
-    TCR_TRACE_ENTRY();
     if constexpr (CARRY == kLookback && TICKET) {
         // tiles are handed out in launch order, so every predecessor of a waiting tile is
         // already running or finished
@@ -250,7 +295,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
         __syncthreads();
         tile = s_tile;
     }
-    TCR_TRACE_POINT(0);
     const uint64_t block_base = (uint64_t)tile * kBlockTile;
     const uint64_t base = block_base + (uint64_t)wave * kChunk;
     const bool full = base + kChunk <= n;
@@ -306,9 +350,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
 #pragma unroll
                     for (int w = 0; w < WAVES; ++w) total += s_wave_total[w];
                     const uint64_t pos = (block_base & seg_mask) / kBlockTile;
-                    TCR_TRACE_POINT(1);
                     const float pre = lookback_exclusive_prefix<LBK>(ws, tile, pos, total, id.lane);
-                    TCR_TRACE_POINT(2);
                     if (id.lane == 0) s_prefix = pre;
                 }
                 __syncthreads();
@@ -345,7 +387,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
             store4_guarded(out, off_hi, n, hi);
         }
     }
-    TCR_TRACE_POINT(3);
 }
 
 // ------------------------------------------------------------------------------ reduce-then-scan helper
