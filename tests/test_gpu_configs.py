@@ -96,14 +96,6 @@ def test_config(tcr, oracle, w):
         got = tcr.segmented_scan(xd, w.seg_len)
         ref = oracle.segmented_scan(x, w.seg_len)
         worst = _compare(got, ref, x, w.seg_len, True, w.exact, nonneg, w.name)
-    if nonneg and w.op.startswith("segmented"):
-        # second, tighter gate for non-negative data, derived from the arithmetic: an output passes through at
-        # most 32 (in-row adds of a product) + 15 (row carries) + 8 + 16 (tile and wavefront carries) binary32
-        # roundings, plus one per 65536-element workgroup share of its segment when the carry crosses
-        # workgroups; every partial sum is bounded by the output itself, so the relative error is at most that
-        # count times 2^-24.
-        roundings = 71 + max(0, w.seg_len // 65536)
-        assert worst <= roundings * 2.0 ** -24, (w.name, worst)
     elif w.op == "reduce":
         got = tcr.reduce(xd)
         ref = np.array([oracle.reduce(x)])
@@ -118,6 +110,14 @@ def test_config(tcr, oracle, w):
         _compare(got, ref, x, w.n, True, w.exact, nonneg, w.name)
         # the carry crossed workgroups: many tiles, and the last element is the grand total
         assert float(got[-1].cpu()) == float(np.float32(ref[-1])) or not w.exact
+    if nonneg and w.op.startswith("segmented"):
+        # second, tighter gate for non-negative data, derived from the arithmetic: an output passes through at
+        # most 32 (in-row adds of a product) + 15 (row carries) + 8 + 16 (tile and wavefront carries) binary32
+        # roundings, plus -- scan -- one per 65536-element workgroup share of its segment when the carry
+        # crosses workgroups, or -- reduce -- one per tile chained through the accumulator; every partial sum
+        # is bounded by the output itself, so the relative error is at most that count times 2^-24.
+        roundings = 71 + (w.seg_len // 65536 if w.op == "segmented_scan" else w.seg_len // 512)
+        assert worst <= roundings * 2.0 ** -24, (w.name, worst)
     tcr.check_device_flags()
 
 
