@@ -45,7 +45,7 @@ Variant g_variant;
 constexpr int kSmallScanW = 2;                       // scan_small: U = 1
 constexpr int kSmallReduceU = 2, kSmallReduceW = 4;  // reduce_small
 constexpr uint64_t kWaveSpanMax = 65536;             // reduce: longest span one wavefront folds
-constexpr int kReduceBlockW = 16;                    // reduce: wavefronts combined through LDS for longer segments
+constexpr int kReduceBlockW = 4;                     // reduce: wavefronts combined through LDS for longer segments
 constexpr int kCarryU = 8, kCarryW = 16;             // scan with cross-workgroup carry: 65536 elements per workgroup
 constexpr uint64_t kCarryTile = (uint64_t)kTile * kCarryU * kCarryW;
 constexpr uint64_t kMaxElements = 1ull << 40;
@@ -175,10 +175,12 @@ tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n, int l
 
 template <int FORM>
 tcr_status launch_reduce_span(const _Float16* in, float* dst, uint64_t n, uint64_t span, uint64_t nspans,
-                              bool combine, hipStream_t s) {
-    if (combine) {
-        constexpr int W = kReduceBlockW;
-        reduce_span_kernel<FORM, 8, W, true><<<dim3((unsigned)ceil_div(nspans, W)), dim3(W * kWave), 0, s>>>(
+                              int combine_waves, hipStream_t s) {
+    if (combine_waves == 4) {
+        reduce_span_kernel<FORM, 8, 4, true><<<dim3((unsigned)ceil_div(nspans, 4)), dim3(4 * kWave), 0, s>>>(
+            in, dst, n, span, nspans);
+    } else if (combine_waves == 2) {
+        reduce_span_kernel<FORM, 8, 2, true><<<dim3((unsigned)ceil_div(nspans, 2)), dim3(2 * kWave), 0, s>>>(
             in, dst, n, span, nspans);
     } else {
         const dim3 grid((unsigned)nspans), block(kWave);
@@ -191,7 +193,7 @@ tcr_status launch_reduce_span(const _Float16* in, float* dst, uint64_t n, uint64
 
 struct ReducePlan {
     uint64_t span;      // elements per wavefront
-    bool combine;       // workgroup of kReduceBlockW wavefronts adds its sums through LDS
+    int combine;        // wavefronts per workgroup whose sums are added through LDS (1: none)
     uint64_t per;       // partials per segment left for reduce_final_kernel (1: results go straight to out)
     uint64_t nspans;    // wavefronts in total
 };
@@ -200,25 +202,25 @@ struct ReducePlan {
 ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
     ReducePlan p;
     if (!whole && seg_len <= kWaveSpanMax) {             // one wavefront per segment
-        p.span = seg_len; p.combine = false; p.per = 1; p.nspans = n / seg_len;
+        p.span = seg_len; p.combine = 1; p.per = 1; p.nspans = n / seg_len;
         return p;
     }
     if (whole) {
         // enough wavefronts to fill the chip, spans between 4096 and 65536 elements
         uint64_t span = 4096;
-        while (span < kWaveSpanMax && n / span > 8192) span <<= 1;
-        p.span = span;
+        while (span < kWaveSpanMax && n / span > 4096) span <<= 1;
         p.nspans = ceil_div(n, span);
-        p.combine = p.nspans > 1;
-        p.per = p.combine ? ceil_div(p.nspans, (uint64_t)kReduceBlockW) : 1;
-        if (!p.combine) p.span = ceil_div(n, kTile) * kTile;
+        if (p.nspans == 1) {
+            p.span = ceil_div(n, kTile) * kTile; p.combine = 1; p.per = 1;
+        } else {
+            p.span = span; p.combine = kReduceBlockW; p.per = ceil_div(p.nspans, (uint64_t)kReduceBlockW);
+        }
         return p;
     }
-    // power-of-two segment longer than one wavefront span: kReduceBlockW spans per workgroup
+    // power-of-two segment of 2^17 elements or more: spans of 65536, up to kReduceBlockW per workgroup
     p.span = kWaveSpanMax;
-    while (p.span * kReduceBlockW > seg_len) p.span >>= 1;      // seg_len >= 2^17, so span >= 8192
-    p.combine = true;
-    p.per = seg_len / (p.span * kReduceBlockW);
+    p.combine = (seg_len / p.span >= (uint64_t)kReduceBlockW) ? kReduceBlockW : 2;
+    p.per = seg_len / (p.span * (uint64_t)p.combine);
     p.nspans = n / p.span;
     return p;
 }
@@ -318,8 +320,8 @@ tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_le
     st = ensure_partials(ws, s, tiles);
     if (st != TCR_OK) return st;
     // one wavefront span per workgroup tile; spans are uniform because seg_len is a multiple of the tile (or one segment)
-    st = mfma_form ? launch_reduce_span<kMfma>(in, ws->partials, n, kCarryTile, tiles, false, s)
-                   : launch_reduce_span<kDpp>(in, ws->partials, n, kCarryTile, tiles, false, s);
+    st = mfma_form ? launch_reduce_span<kMfma>(in, ws->partials, n, kCarryTile, tiles, 1, s)
+                   : launch_reduce_span<kDpp>(in, ws->partials, n, kCarryTile, tiles, 1, s);
     if (st != TCR_OK) return st;
     const uint64_t per = whole ? tiles : host_seg_len / kCarryTile;
     const uint64_t groups = whole ? 1 : n / host_seg_len;
@@ -420,7 +422,7 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     if (op == 0 || op == 2) {
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";
         const ReducePlan p = plan_reduce(n, seg_len, whole);
-        if (!p.combine) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
+        if (p.combine == 1) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
         if (p.per == 1) return mf ? "reduce_span_kernel<mfma,block>" : "reduce_span_kernel<dpp,block>";
         return mf ? "reduce_span_kernel<mfma,block>+reduce_final_kernel" : "reduce_span_kernel<dpp,block>+reduce_final_kernel";
     }

@@ -64,29 +64,45 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Floa
         for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + lane_off), n);
     }
 
+    // Per tile, the segment sums sit in scattered lanes (the last lane of each row group).  They are
+    // gathered with one cross-lane read per tile so that the wavefront's U * 512 / seg_len results leave
+    // as one run of consecutive 32-bit stores in lane order.
+    constexpr int RT = kTile >> LOG2L;                   // results per tile
+    static_assert(RT * U <= kWave, "one result per lane at most");
+    float t[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint64_t seg0 = (base + (uint64_t)(kTile * u)) >> LOG2L;   // first segment of the tile
         if constexpr (FORM == kMfma) {
             if constexpr (LOG2L == 4) {
-                // two segments per row: rows 0..7 of the product carry the first, 8..15 the second
-                const float4v d = mfma(const_half_rows(id), x[u], splat(0.0f));
-                const uint64_t s = seg0 + (uint64_t)(2 * id.j + (id.g >> 1));
-                if ((id.g & 1) == 0 && s < nseg) out[s] = d[0];
+                // two segments per row: rows 0..7 of the product carry the first, 8..15 the second;
+                // segment 2j + h of the tile ends up in lane (j, g = 2h)
+                t[u] = mfma(const_half_rows(id), x[u], splat(0.0f))[0];
             } else {
-                constexpr int ROWS = 1 << (LOG2L - 5);               // tile rows per segment
-                const float4v d = mfma(const_ones(), x[u], splat(0.0f));
-                const float t = row_sum_to_last<ROWS>(d[0]);
-                const uint64_t s = seg0 + (uint64_t)(id.j >> (LOG2L - 5));
-                if (id.g == 0 && (id.j & (ROWS - 1)) == ROWS - 1 && s < nseg) out[s] = t;
+                constexpr int ROWS = 1 << (LOG2L - 5);   // tile rows per segment; sum valid in the group's last row
+                t[u] = row_sum_to_last<ROWS>(mfma(const_ones(), x[u], splat(0.0f))[0]);
             }
         } else {
-            constexpr int LANES = 1 << (LOG2L - 3);                  // lanes per segment
-            const float t = lanes_sum_to_last<LANES>(sum8(x[u]));
-            const uint64_t s = seg0 + (uint64_t)(id.lane >> (LOG2L - 3));
-            if ((id.lane & (LANES - 1)) == LANES - 1 && s < nseg) out[s] = t;
+            constexpr int LANES = 1 << (LOG2L - 3);      // lanes per segment; sum valid in the group's last lane
+            t[u] = lanes_sum_to_last<LANES>(sum8(x[u]));
         }
     }
+    const int slot = id.lane;                            // this lane stores result `slot` of the wavefront
+    const int slot_tile = slot / RT, slot_seg = slot % RT;
+    int src;                                             // lane that holds segment slot_seg of a tile
+    if constexpr (FORM == kMfma) {
+        if constexpr (LOG2L == 4) src = (slot_seg >> 1) + 32 * (slot_seg & 1);
+        else src = ((slot_seg + 1) << (LOG2L - 5)) - 1;
+    } else {
+        src = ((slot_seg + 1) << (LOG2L - 3)) - 1;
+    }
+    float v = 0.0f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float got = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, t[u])));
+        if (u == slot_tile) v = got;
+    }
+    const uint64_t s = (base >> LOG2L) + (uint64_t)slot;
+    if (slot < RT * U && s < nseg) out[s] = v;
 }
 
 // ------------------------------------------------------------------------------ long spans

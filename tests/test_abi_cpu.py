@@ -91,7 +91,8 @@ def test_dispatch_by_segment_length(lib):
     for e in (10, 12, 14, 16):
         assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma,wave>"
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,nocarry>"
-    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20) == "reduce_span_kernel<mfma,block>"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,block>"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20).endswith("block>+reduce_final_kernel")
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 24).endswith("+reduce_final_kernel")
     assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 20) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
