@@ -272,7 +272,7 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
 // seg_mask  = seg_len - 1 for a power-of-two seg_len, all ones for the full scan (one segment).
 // seg_len   only compared against the wavefront / workgroup share (saturated for the full scan).
 // Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.
-template <int FORM, int U, int WAVES, int CARRY, int LBK = 1, bool TICKET = true>
+template <int FORM, int U, int WAVES, int CARRY, int LBK = 1, bool TICKET = true, bool XCDPART = false>
 __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float16* __restrict__ in,
                                                                    float* __restrict__ out, uint64_t n,
                                                                    uint64_t seg_mask, uint64_t seg_len,
@@ -287,6 +287,12 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
     const LaneId id;
     const int wave = threadIdx.x >> 6;
     uint32_t tile = blockIdx.x;
+    if constexpr (XCDPART) {
+        // workgroups go round-robin to the 8 XCDs: give each XCD one contiguous eighth of the tiles
+        const uint32_t per_xcd = (gridDim.x + 7u) >> 3;
+        tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+        if ((uint64_t)tile * ((uint64_t)kTile * U * WAVES) >= n) return;
+    }
     if constexpr (CARRY == kLookback && TICKET) {
         // tiles are handed out in launch order, so every predecessor of a waiting tile is
         // already running or finished

@@ -90,7 +90,11 @@ def test_dispatch_by_segment_length(lib):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e).startswith("scan_small_kernel")
     for e in (10, 12, 14, 16):
         assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma,wave>"
+    for e in (10, 12, 13):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,nocarry>"
+    for e in (14, 15):
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,ticket>"
+    assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,block>"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20).endswith("block>+reduce_final_kernel")
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 24).endswith("+reduce_final_kernel")
