@@ -102,31 +102,31 @@ __device__ __forceinline__ half8 const_ones() {
     return c;
 }
 
+// Eight binary16 values of which the first `count` (clamped to 0..8) are 1 and the rest 0: one
+// register quadruple of a triangular constant.  Built with two 64-bit shifts instead of eight
+// compares so that a one-tile wavefront spends few VALU instructions on its constants.
+typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ half8 leading_ones(int count) {
+    const unsigned long long ones = 0x3C003C003C003C00ull;          // four binary16 ones
+    const int c = count < 0 ? 0 : (count > 8 ? 8 : count);
+    const int clo = c < 4 ? c : 4, chi = c - clo;
+    u64x2 v;
+    v[0] = clo ? ones >> (16 * (4 - clo)) : 0ull;
+    v[1] = chi ? ones >> (16 * (4 - chi)) : 0ull;
+    return __builtin_bit_cast(half8, v);
+}
+
 // Lower-triangular-with-diagonal pieces of U^T (Section 5's U, transposed because the constant
 // is on the left here).  Output row i of the first product is position i of a tile row,
 // output row i of the second product is position 16 + i:
 //   tri_lo[i][k] = 1  iff  k <= i            tri_hi[i][k] = 1  iff  k <= 16 + i
-__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) {
-    half8 c;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) c[e] = (8 * id.g + e <= id.j) ? (_Float16)1.0f : (_Float16)0.0f;
-    return c;
-}
-__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) {
-    half8 c;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) c[e] = (8 * id.g + e <= 16 + id.j) ? (_Float16)1.0f : (_Float16)0.0f;
-    return c;
-}
-// Same, for rows that hold two independent segments of 16: the second half starts afresh.
+// Lane (i, g) holds k = 8g .. 8g+7, so its registers are a run of ones followed by zeros.
+__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) { return leading_ones(id.j - 8 * id.g + 1); }
+__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) { return leading_ones(16 + id.j - 8 * id.g + 1); }
+// Same, for rows that hold two independent segments of 16: the second half starts afresh
+// (1 iff 16 <= k <= 16 + i).
 __device__ __forceinline__ half8 const_tri_hi_seg16(const LaneId& id) {
-    half8 c;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int k = 8 * id.g + e;
-        c[e] = (k >= 16 && k <= 16 + id.j) ? (_Float16)1.0f : (_Float16)0.0f;
-    }
-    return c;
+    return leading_ones(id.g >= 2 ? id.j - 8 * (id.g - 2) + 1 : 0);
 }
 // Two half-row sums at once: output rows 0..7 add up k < 16, rows 8..15 add up k >= 16.
 __device__ __forceinline__ half8 const_half_rows(const LaneId& id) {

@@ -48,7 +48,7 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Floa
                                                                      float* __restrict__ out, uint64_t n) {
     static_assert(LOG2L >= 4 && LOG2L <= 9, "");
     const LaneId id;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
     const uint64_t base = ((uint64_t)blockIdx.x * WAVES + wave) * (uint64_t)(kTile * U);
     if (base >= n) return;
     const uint64_t nseg = n >> LOG2L;
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_span_kernel(const _Float
                                                                     uint64_t span, uint64_t nspans) {
     __shared__ float s_total[WAVES];
     const LaneId id;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
     const uint64_t w = (uint64_t)blockIdx.x * WAVES + wave;
     float total = 0.0f;
     if (w < nspans) {

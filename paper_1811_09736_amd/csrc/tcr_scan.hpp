@@ -56,7 +56,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
                                                                    float* __restrict__ out, uint64_t n) {
     static_assert(LOG2L >= 4 && LOG2L <= 9, "");
     const LaneId id;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
     const uint64_t base = ((uint64_t)blockIdx.x * WAVES + wave) * (uint64_t)(kTile * U);
     if (base >= n) return;
     const bool full = base + (uint64_t)(kTile * U) <= n;
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_wave_kernel(const _Float16
                                                                   float* __restrict__ out, uint64_t n,
                                                                   uint64_t seg_len) {
     const LaneId id;
-    const uint64_t seg = (uint64_t)blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const uint64_t seg = (uint64_t)blockIdx.x * WAVES + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint64_t begin = seg * seg_len;
     if (begin >= n) return;
     const uint64_t end = begin + seg_len;
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
     __shared__ uint32_t s_tile;
 
     const LaneId id;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
     uint32_t tile = blockIdx.x;
     if constexpr (XCDPART) {
         // workgroups go round-robin to the 8 XCDs: give each XCD one contiguous eighth of the tiles
