@@ -47,6 +47,8 @@ typedef enum {
  * Regular segmented sum reduction (Section 3; algorithms of Section 4).
  *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
+ * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
+ * seg_len == n, other lengths run untuned kernels (the paper pads such segments, Section 4).
  */
 tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 
@@ -54,6 +56,7 @@ tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t
  * Regular segmented inclusive scan (Section 3; algorithms of Section 5).
  *   out[s*seg_len + k] = sum_{j <= k} in[s*seg_len + j].
  * out: n floats, 16-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
+ * Every seg_len >= 1 is accepted, as for tcr_segmented_reduce.
  */
 tcr_status tcr_segmented_scan(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 

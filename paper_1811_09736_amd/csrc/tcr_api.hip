@@ -14,6 +14,7 @@
 
 #include "tcr_reduce.hpp"
 #include "tcr_scan.hpp"
+#include "tcr_generic.hpp"
 
 namespace {
 
@@ -354,6 +355,22 @@ tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_le
     return check_launch("scan_block_kernel");
 }
 
+// Any other seg_len >= 1: the untuned kernels.
+constexpr uint64_t kGenericThreadMax = 96;      // up to here one thread walks a segment, beyond a wavefront does
+
+template <bool SCAN>
+tcr_status launch_generic(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    const uint64_t nseg = n / seg_len;
+    if (seg_len <= kGenericThreadMax) {
+        generic_thread_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
+            in, out, nseg, seg_len);
+        return check_launch("generic_thread_kernel");
+    }
+    generic_wave_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
+        in, out, nseg, seg_len);
+    return check_launch("generic_wave_kernel");
+}
+
 tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {
     if (seg_len == 0) return TCR_ERR_INVALID_ARG;
     if (n % seg_len != 0) return TCR_ERR_INVALID_ARG;
@@ -374,7 +391,7 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const _Float16* x = static_cast<const _Float16*>(in);
     if (seg_len == n) return reduce_long(x, out, n, n, true, s);
-    if (!is_pow2(seg_len) || seg_len < 16) return TCR_ERR_UNSUPPORTED;
+    if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<false>(x, out, n, seg_len, s);
     if (seg_len <= kTile)
         return g_variant.formulation == kMfma ? launch_reduce_small<kMfma>(x, out, n, log2u(seg_len), s)
                                               : launch_reduce_small<kDpp>(x, out, n, log2u(seg_len), s);
@@ -387,7 +404,7 @@ extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const _Float16* x = static_cast<const _Float16*>(in);
     if (seg_len == n) return scan_long(x, out, n, n, true, s);
-    if (!is_pow2(seg_len) || seg_len < 16) return TCR_ERR_UNSUPPORTED;
+    if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<true>(x, out, n, seg_len, s);
     if (seg_len <= kTile)
         return g_variant.formulation == kMfma ? launch_scan_small<kMfma>(x, out, n, log2u(seg_len), s)
                                               : launch_scan_small<kDpp>(x, out, n, log2u(seg_len), s);
@@ -439,7 +456,10 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     if (n == 0 || seg_len == 0 || n % seg_len != 0) return "";
     const bool mf = g_variant.formulation == kMfma;
     const bool whole = seg_len == n;
-    if (!whole && (!is_pow2(seg_len) || seg_len < 16)) return "";
+    if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
+        if (op != 0 && op != 1) return "";
+        return seg_len <= kGenericThreadMax ? "generic_thread_kernel" : "generic_wave_kernel";
+    }
     if (op == 0 || op == 2) {
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";
         const ReducePlan p = plan_reduce(n, seg_len, whole);

@@ -103,5 +103,7 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_REDUCE, 1000, 1000) == "reduce_span_kernel<mfma,wave>"
     assert k(lib.OP_SCAN, n, n) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
-    assert k(lib.OP_SEGMENTED_SCAN, n, 48) == ""          # no kernel: the call reports "unsupported"
+    assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "generic_thread_kernel"     # untuned lengths
+    assert k(lib.OP_SEGMENTED_REDUCE, 3 << 20, 3 << 10) == "generic_wave_kernel"
+    assert k(lib.OP_SEGMENTED_SCAN, n, 3) == ""           # 3 does not divide n: the call reports an invalid argument
     assert k(lib.OP_SEGMENTED_SCAN, 0, 16) == ""
