@@ -131,7 +131,7 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if os.path.exists(tpath) and args.log2n == LOG2N:
         with open(tpath) as fh:
-            traffic = json.load(fh).get(dom_name)
+            traffic = (json.load(fh).get(dom_name) or {}).get("total_bytes")
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
