@@ -137,10 +137,37 @@ def main() -> int:
                 "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
                 "algorithmic_bytes_per_launch": dom["bytes"] // dom["launches"]}
 
+    # context rows outside the step: the full (unsegmented) operations on the same input, and one segment
+    # length without a tuned path
+    extra = []
+    out_one = torch.empty(1, dtype=torch.float32, device="cuda")
+    n3 = (n // 3000) * 3000
+    out_g = torch.empty(n3 // 3000, dtype=torch.float32, device="cuda")
+    for label, fn, nn, rd_wr in (
+            ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
+            ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
+            ("segmented_reduce seg_len=3000 (untuned path)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
+             (2 * n3, 4 * (n3 // 3000))),
+            ("segmented_scan seg_len=3000 (untuned path)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
+             (2 * n3, 4 * n3))):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / reps * 1e3
+        extra.append({"call": label, "avg_us": round(us, 2), "total_GBps": round(sum(rd_wr) / us * 1e-3, 1),
+                      "pct_of_hbm_peak": round(sum(rd_wr) / us * 1e-3 / HBM_PEAK_GBS * 100, 1)})
+    tcr.check_device_flags()
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        sample_log2 = min(args.log2n, 26)
+        sample_log2 = min(args.log2n, 27)
         xs = np.ascontiguousarray(x_host[: 1 << sample_log2])
         t0 = time.perf_counter()
         for op, e in calls:
@@ -165,7 +192,7 @@ def main() -> int:
                                "seg_len=2^{%s}; fp32 accumulate and output" % (args.log2n, ",".join(map(str, sweep))),
                    "formulation": args.formulation, "scan_carry": args.scan_carry,
                    "input_sha256": workloads.sha256(x_host)[:16]},
-        "roofline": roofline, "cpu_baseline": cpu, "rows": rows,
+        "roofline": roofline, "cpu_baseline": cpu, "rows": rows, "context_rows": extra,
     }
     print(json.dumps(line))
     return 0
