@@ -143,13 +143,22 @@ def main() -> int:
     out_one = torch.empty(1, dtype=torch.float32, device="cuda")
     n3 = (n // 3000) * 3000
     out_g = torch.empty(n3 // 3000, dtype=torch.float32, device="cuda")
-    for label, fn, nn, rd_wr in (
+    out_h = torch.empty(n, dtype=torch.float16, device="cuda")
+    variant_rows = []
+    for e in (8, 12, 16, 20):
+        if e <= args.log2n and args.formulation == "mfma":
+            variant_rows.append((f"segmented_scan_ex seg_len=2^{e} binary16 output (the paper's precision, 4 B/elem)",
+                                 (lambda e=e: tcr.segmented_scan_ex(x, 1 << e, tcr.OUT_F16, out=out_h)), n, (2 * n, 2 * n)))
+    if args.formulation == "mfma":
+        variant_rows.append(("segmented_scan_ex seg_len=2^12 exclusive",
+                             lambda: tcr.segmented_scan_ex(x, 1 << 12, tcr.SCAN_EXCLUSIVE, out=out_scan), n, (2 * n, 4 * n)))
+    for label, fn, nn, rd_wr in variant_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
             ("segmented_reduce seg_len=3000 (untuned path)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
             ("segmented_scan seg_len=3000 (untuned path)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
-             (2 * n3, 4 * n3))):
+             (2 * n3, 4 * n3))]:
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -61,6 +61,22 @@ tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t
 tcr_status tcr_segmented_scan(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 
 /*
+ * Scan variants.  flags is a combination of
+ *   TCR_SCAN_EXCLUSIVE  out[s*seg_len + k] = sum_{j < k} in[s*seg_len + j] (the first output of a segment
+ *                       is 0): the exclusive scan that Section 5 uses for its column scans;
+ *   TCR_OUT_F16         results are rounded (to nearest even) to binary16 and `out` points to n binary16
+ *                       values -- the paper's own output precision (Section 6 counts 4 bytes per scanned
+ *                       element).  Accumulation stays binary32; sums beyond 65504 become infinities.
+ * flags == 0 is tcr_segmented_scan / tcr_scan.  out: n elements, 16-byte aligned.  Unknown flag bits
+ * return TCR_ERR_INVALID_ARG.  Under the "dpp" formulation only flags == 0 has tuned kernels
+ * (TCR_ERR_UNSUPPORTED otherwise); segment lengths without a tuned path accept every flag.
+ */
+#define TCR_SCAN_EXCLUSIVE 1u
+#define TCR_OUT_F16 2u
+tcr_status tcr_segmented_scan_ex(const void *in, void *out, uint64_t n, uint64_t seg_len, uint32_t flags, void *stream);
+tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, void *stream);
+
+/*
  * Full reduction (device level, Section 4): out[0] = sum of all n inputs (0 for n == 0).
  * Any n is accepted.  out: 1 float.
  */

@@ -43,6 +43,7 @@ def _bind(path: str):
     for name, args in (
         ("oracle_segmented_reduce", [u16p, f64p, u64, u64]),
         ("oracle_segmented_scan", [u16p, f64p, u64, u64]),
+        ("oracle_segmented_scan_exclusive", [u16p, f64p, u64, u64]),
         ("oracle_reduce", [u16p, f64p, u64]),
         ("oracle_scan", [u16p, f64p, u64]),
         ("oracle_segmented_scan_at", [u16p, u64, u64, u64p, u64, f64p]),
@@ -92,6 +93,15 @@ class Oracle:
             raise ValueError("oracle_segmented_scan rejected its arguments")
         return out
 
+    def segmented_scan_exclusive(self, x: np.ndarray, seg_len: int) -> np.ndarray:
+        n = x.shape[0]
+        if seg_len <= 0 or n % seg_len:
+            raise ValueError("seg_len must be positive and divide n")
+        out = np.empty(n, dtype=np.float64)
+        if self._lib.oracle_segmented_scan_exclusive(_in_ptr(x), _out_ptr(out), n, seg_len):
+            raise ValueError("oracle_segmented_scan_exclusive rejected its arguments")
+        return out
+
     def reduce(self, x: np.ndarray) -> float:
         out = np.zeros(1, dtype=np.float64)
         if self._lib.oracle_reduce(_in_ptr(x), _out_ptr(out), x.shape[0]):
@@ -135,6 +145,10 @@ def segmented_reduce(x, seg_len):
 
 def segmented_scan(x, seg_len):
     return _get().segmented_scan(x, seg_len)
+
+
+def segmented_scan_exclusive(x, seg_len):
+    return _get().segmented_scan_exclusive(x, seg_len)
 
 
 def reduce(x):

@@ -12,7 +12,8 @@
  *     entry being the first element and the last entry being the total, i.e. the
  *     scan is inclusive;
  *   - the regular segmented forms apply the same operation independently to
- *     consecutive, equally sized pieces of the input.
+ *     consecutive, equally sized pieces of the input;
+ * plus the exclusive variant of the scan (each output leaves out its own element).
  * The matrix-product algorithms of Sections 4 and 5 reach exactly these results (up
  * to the order of floating-point additions), so the oracle is the definition written
  * out: one left-to-right loop per segment, accumulating in binary64.  Each binary16
@@ -75,6 +76,26 @@ int oracle_segmented_scan(const uint16_t *in, double *out, uint64_t n, uint64_t 
         for (uint64_t k = 0; k < seg_len; ++k) {
             acc += oracle_half_to_double(in[s * seg_len + k]);
             out[s * seg_len + k] = acc;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Exclusive form: out[s*seg_len + k] = sum_{j=0}^{k-1} in[s*seg_len + j]; the first output of a
+ * segment is 0.  (Section 5 of the paper uses exclusive scans of tile columns internally; as a
+ * user-facing variant it is the inclusive scan of Section 3 with each output leaving out its own
+ * element.)
+ */
+int oracle_segmented_scan_exclusive(const uint16_t *in, double *out, uint64_t n, uint64_t seg_len)
+{
+    if (bad_args(in, out, n, seg_len)) return 1;
+    const uint64_t segs = n / seg_len;
+    for (uint64_t s = 0; s < segs; ++s) {
+        double acc = 0.0;
+        for (uint64_t k = 0; k < seg_len; ++k) {
+            out[s * seg_len + k] = acc;
+            acc += oracle_half_to_double(in[s * seg_len + k]);
         }
     }
     return 0;

@@ -18,8 +18,11 @@ from .build import LIB_PATH
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 OP_SEGMENTED_REDUCE, OP_SEGMENTED_SCAN, OP_REDUCE, OP_SCAN = range(4)
 
+SCAN_EXCLUSIVE, OUT_F16 = 1, 2
+
 EXPORTS = (
-    "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan", "tcr_set_variant",
+    "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
+    "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
 )
 
@@ -42,6 +45,10 @@ def _load() -> ctypes.CDLL:
     vp, u64, fp = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p
     lib.tcr_segmented_reduce.argtypes = [vp, fp, u64, u64, vp]
     lib.tcr_segmented_scan.argtypes = [vp, fp, u64, u64, vp]
+    lib.tcr_segmented_scan_ex.argtypes = [vp, vp, u64, u64, ctypes.c_uint32, vp]
+    lib.tcr_scan_ex.argtypes = [vp, vp, u64, ctypes.c_uint32, vp]
+    lib.tcr_segmented_scan_ex.restype = ctypes.c_int
+    lib.tcr_scan_ex.restype = ctypes.c_int
     lib.tcr_reduce.argtypes = [vp, fp, u64, vp]
     lib.tcr_scan.argtypes = [vp, fp, u64, vp]
     for name in ("tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan"):
@@ -111,6 +118,42 @@ def segmented_scan(x: torch.Tensor, seg_len: int, out: Optional[torch.Tensor] = 
         st = _lib.tcr_segmented_scan(x.data_ptr(), out.data_ptr(), n, seg_len, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_segmented_scan")
+    return out
+
+
+def segmented_scan_ex(x: torch.Tensor, seg_len: int, flags: int, out: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_segmented_scan_ex: flags = SCAN_EXCLUSIVE | OUT_F16 (float16 output tensor when OUT_F16 is set)."""
+    _check_input(x)
+    n = x.numel()
+    if seg_len <= 0 or n % seg_len:
+        raise TcrError(ERR_INVALID_ARG, "tcr_segmented_scan_ex")
+    dtype = torch.float16 if flags & OUT_F16 else torch.float32
+    if out is None:
+        out = torch.empty(n, dtype=dtype, device=x.device)
+    if not (out.is_cuda and out.dtype == dtype and out.is_contiguous() and out.numel() == n and out.device == x.device):
+        raise TypeError(f"out must be a contiguous {dtype} CUDA tensor of {n} elements on the input's device")
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_segmented_scan_ex(x.data_ptr(), out.data_ptr(), n, seg_len, flags, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_segmented_scan_ex")
+    return out
+
+
+def scan_ex(x: torch.Tensor, flags: int, out: Optional[torch.Tensor] = None,
+            stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_scan_ex: the full scan with flags = SCAN_EXCLUSIVE | OUT_F16."""
+    _check_input(x)
+    n = x.numel()
+    dtype = torch.float16 if flags & OUT_F16 else torch.float32
+    if out is None:
+        out = torch.empty(n, dtype=dtype, device=x.device)
+    if not (out.is_cuda and out.dtype == dtype and out.is_contiguous() and out.numel() == n and out.device == x.device):
+        raise TypeError(f"out must be a contiguous {dtype} CUDA tensor of {n} elements on the input's device")
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_scan_ex(x.data_ptr(), out.data_ptr(), n, flags, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_scan_ex")
     return out
 
 

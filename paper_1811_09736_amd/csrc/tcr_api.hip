@@ -279,43 +279,44 @@ tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_
 }
 
 // ---------------------------------------------------------------------------- scan dispatch
-template <int FORM>
-tcr_status launch_scan_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
+// MODE bit 0: exclusive, bit 1: binary16 output (TCR_SCAN_EXCLUSIVE, TCR_OUT_F16).
+template <int FORM, int MODE>
+tcr_status launch_scan_small(const _Float16* in, void* out, uint64_t n, int log2l, hipStream_t s) {
     constexpr int W = kSmallScanW;
     const uint64_t blocks = ceil_div(n, (uint64_t)kTile * W);
     const dim3 grid((unsigned)blocks), block(W * kWave);
     switch (log2l) {
-        case 4: scan_small_kernel<FORM, 4, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
-        case 5: scan_small_kernel<FORM, 5, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
-        case 6: scan_small_kernel<FORM, 6, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
-        case 7: scan_small_kernel<FORM, 7, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
-        case 8: scan_small_kernel<FORM, 8, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
-        case 9: scan_small_kernel<FORM, 9, 1, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 4: scan_small_kernel<FORM, 4, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 5: scan_small_kernel<FORM, 5, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 6: scan_small_kernel<FORM, 6, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 7: scan_small_kernel<FORM, 7, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 8: scan_small_kernel<FORM, 8, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 9: scan_small_kernel<FORM, 9, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
         default: return TCR_ERR_UNSUPPORTED;
     }
     return check_launch("scan_small_kernel");
 }
 
-template <int FORM, int U, int W, int CARRY>
-void launch_scan_block(const _Float16* in, float* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+template <int FORM, int U, int W, int CARRY, int MODE>
+void launch_scan_block(const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
                        const ScanWorkspace& dev, const float* prefix, hipStream_t s) {
     const unsigned blocks = (unsigned)ceil_div(n, (uint64_t)kTile * U * W);
-    scan_block_kernel<FORM, U, W, CARRY><<<dim3(blocks), dim3(W * kWave), 0, s>>>(in, out, n, seg_mask, seg_len, dev,
-                                                                                   prefix);
+    scan_block_kernel<FORM, U, W, CARRY, 64, true, false, MODE><<<dim3(blocks), dim3(W * kWave), 0, s>>>(
+        in, out, n, seg_mask, seg_len, dev, prefix);
 }
 
 // Segments that fit one workgroup: the smallest workgroup share that holds a whole segment.
-template <int FORM>
-void launch_scan_nocarry(const _Float16* in, float* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+template <int FORM, int MODE>
+void launch_scan_nocarry(const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
                          uint64_t fit, hipStream_t s) {
     const ScanWorkspace none = {};
-    if (fit <= 1024) launch_scan_block<FORM, 1, 2, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 2048) launch_scan_block<FORM, 1, 4, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 4096) launch_scan_block<FORM, 1, 8, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 8192) launch_scan_block<FORM, 1, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 16384) launch_scan_block<FORM, 2, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 32768) launch_scan_block<FORM, 4, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else launch_scan_block<FORM, 8, 16, kNoCarry>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    if (fit <= 1024) launch_scan_block<FORM, 1, 2, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 2048) launch_scan_block<FORM, 1, 4, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 4096) launch_scan_block<FORM, 1, 8, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 8192) launch_scan_block<FORM, 1, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 16384) launch_scan_block<FORM, 2, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else if (fit <= 32768) launch_scan_block<FORM, 4, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+    else launch_scan_block<FORM, 8, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
 }
 
 // Workgroup share used when tiles are handed out by ticket (segments of 16384 elements and more).
@@ -323,12 +324,12 @@ void launch_scan_nocarry(const _Float16* in, float* out, uint64_t n, uint64_t se
 // contiguous in memory, which measured 5-9 % faster than blockIdx order for 1024-thread
 // workgroups even when no carry crosses workgroups; one ticket costs about 12 ns of a serial
 // resource, so it only pays from 16384 elements per workgroup upwards.
-template <int FORM, int CARRY>
-void launch_scan_ticketed(const _Float16* in, float* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+template <int FORM, int CARRY, int MODE>
+void launch_scan_ticketed(const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
                           uint64_t tile, const ScanWorkspace& dev, const float* prefix, hipStream_t s) {
-    if (tile == 16384) launch_scan_block<FORM, 2, 16, CARRY>(in, out, n, seg_mask, seg_len, dev, prefix, s);
-    else if (tile == 32768) launch_scan_block<FORM, 4, 16, CARRY>(in, out, n, seg_mask, seg_len, dev, prefix, s);
-    else launch_scan_block<FORM, kCarryU, kCarryW, CARRY>(in, out, n, seg_mask, seg_len, dev, prefix, s);
+    if (tile == 16384) launch_scan_block<FORM, 2, 16, CARRY, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s);
+    else if (tile == 32768) launch_scan_block<FORM, 4, 16, CARRY, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s);
+    else launch_scan_block<FORM, kCarryU, kCarryW, CARRY, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s);
 }
 
 uint64_t ticketed_tile(uint64_t seg_len, bool whole) {
@@ -338,15 +339,14 @@ uint64_t ticketed_tile(uint64_t seg_len, bool whole) {
 }
 
 // seg_len >= 1024 (power of two), or the full scan (seg_len == n, any n).
-tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, bool whole, hipStream_t s) {
+template <int FORM, int MODE>
+tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, bool whole, hipStream_t s) {
     const uint64_t seg_mask = whole ? ~0ull : seg_len - 1;
     const uint64_t host_seg_len = seg_len;            // decides the launch; the kernels see a saturated
     if (whole) seg_len = ~0ull;                       // length for the one-segment case (n need not be a power of two)
-    const bool mfma_form = g_variant.formulation == kMfma;
     const bool table = g_variant.scan_carry == kTable;
     if (host_seg_len <= 8192 || (table && host_seg_len <= kCarryTile)) {
-        if (mfma_form) launch_scan_nocarry<kMfma>(in, out, n, seg_mask, seg_len, host_seg_len, s);
-        else launch_scan_nocarry<kDpp>(in, out, n, seg_mask, seg_len, host_seg_len, s);
+        launch_scan_nocarry<FORM, MODE>(in, out, n, seg_mask, seg_len, host_seg_len, s);
         return check_launch("scan_block_kernel");
     }
     const uint64_t tile = table ? kCarryTile : ticketed_tile(host_seg_len, whole);
@@ -358,8 +358,7 @@ tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_le
     if (!table) {
         st = begin_lookback(ws, s, tiles, &dev);
         if (st != TCR_OK) return st;
-        if (mfma_form) launch_scan_ticketed<kMfma, kLookback>(in, out, n, seg_mask, seg_len, tile, dev, nullptr, s);
-        else launch_scan_ticketed<kDpp, kLookback>(in, out, n, seg_mask, seg_len, tile, dev, nullptr, s);
+        launch_scan_ticketed<FORM, kLookback, MODE>(in, out, n, seg_mask, seg_len, tile, dev, nullptr, s);
         st = check_launch("scan_block_kernel");
         if (st != TCR_OK) {
             ws->dirty = true;
@@ -372,16 +371,14 @@ tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_le
     st = ensure_partials(ws, s, tiles);
     if (st != TCR_OK) return st;
     // one wavefront span per workgroup tile; spans are uniform because seg_len is a multiple of the tile (or one segment)
-    st = mfma_form ? launch_reduce_span<kMfma>(in, ws->partials, n, kCarryTile, tiles, 1, s)
-                   : launch_reduce_span<kDpp>(in, ws->partials, n, kCarryTile, tiles, 1, s);
+    st = launch_reduce_span<FORM>(in, ws->partials, n, kCarryTile, tiles, 1, s);
     if (st != TCR_OK) return st;
     const uint64_t per = whole ? tiles : host_seg_len / kCarryTile;
     const uint64_t groups = whole ? 1 : n / host_seg_len;
     scan_partials_kernel<<<dim3((unsigned)groups), dim3(kPartialsThreads), 0, s>>>(ws->partials, per);
     st = check_launch("scan_partials_kernel");
     if (st != TCR_OK) return st;
-    if (mfma_form) launch_scan_block<kMfma, kCarryU, kCarryW, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, s);
-    else launch_scan_block<kDpp, kCarryU, kCarryW, kTable>(in, out, n, seg_mask, seg_len, dev, ws->partials, s);
+    launch_scan_block<FORM, kCarryU, kCarryW, kTable, MODE>(in, out, n, seg_mask, seg_len, dev, ws->partials, s);
     return check_launch("scan_block_kernel");
 }
 
@@ -389,16 +386,42 @@ tcr_status scan_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_le
 constexpr uint64_t kGenericThreadMax = 96;      // up to here one thread walks a segment, beyond a wavefront does
 
 template <bool SCAN>
-tcr_status launch_generic(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
     const uint64_t nseg = n / seg_len;
+    const bool excl = (flags & TCR_SCAN_EXCLUSIVE) != 0, f16 = (flags & TCR_OUT_F16) != 0;
     if (seg_len <= kGenericThreadMax) {
         generic_thread_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
-            in, out, nseg, seg_len);
+            in, out, nseg, seg_len, excl, f16);
         return check_launch("generic_thread_kernel");
     }
     generic_wave_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
-        in, out, nseg, seg_len);
+        in, out, nseg, seg_len, excl, f16);
     return check_launch("generic_wave_kernel");
+}
+
+// The tuned scan paths for one (formulation, mode) pair.
+template <int FORM, int MODE>
+tcr_status scan_tuned(const _Float16* x, void* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    if (seg_len == n) return scan_long<FORM, MODE>(x, out, n, n, true, s);
+    if (seg_len <= kTile) return launch_scan_small<FORM, MODE>(x, out, n, log2u(seg_len), s);
+    return scan_long<FORM, MODE>(x, out, n, seg_len, false, s);
+}
+
+tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
+    const _Float16* x = static_cast<const _Float16*>(in);
+    if (seg_len != n && (!is_pow2(seg_len) || seg_len < 16)) return launch_generic<true>(x, out, n, seg_len, flags, s);
+    const int mode = (int)(flags & 3u);
+    if (g_variant.formulation == kDpp) {
+        // the wavefront-primitive alternative is kept for the default mode only
+        if (mode != 0) return TCR_ERR_UNSUPPORTED;
+        return scan_tuned<kDpp, 0>(x, out, n, seg_len, s);
+    }
+    switch (mode) {
+        case 0: return scan_tuned<kMfma, 0>(x, out, n, seg_len, s);
+        case 1: return scan_tuned<kMfma, 1>(x, out, n, seg_len, s);
+        case 2: return scan_tuned<kMfma, 2>(x, out, n, seg_len, s);
+        default: return scan_tuned<kMfma, 3>(x, out, n, seg_len, s);
+    }
 }
 
 tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {
@@ -421,24 +444,28 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const _Float16* x = static_cast<const _Float16*>(in);
     if (seg_len == n) return reduce_long(x, out, n, n, true, s);
-    if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<false>(x, out, n, seg_len, s);
+    if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<false>(x, out, n, seg_len, 0u, s);
     if (seg_len <= kTile)
         return g_variant.formulation == kMfma ? launch_reduce_small<kMfma>(x, out, n, log2u(seg_len), s)
                                               : launch_reduce_small<kDpp>(x, out, n, log2u(seg_len), s);
     return reduce_long(x, out, n, seg_len, false, s);
 }
 
-extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
+extern "C" tcr_status tcr_segmented_scan_ex(const void* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags,
+                                            void* stream) {
+    if ((flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) != 0) return TCR_ERR_INVALID_ARG;
     tcr_status st = validate(in, out, n, seg_len, 16);
     if (st != TCR_OK || n == 0) return st;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const _Float16* x = static_cast<const _Float16*>(in);
-    if (seg_len == n) return scan_long(x, out, n, n, true, s);
-    if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<true>(x, out, n, seg_len, s);
-    if (seg_len <= kTile)
-        return g_variant.formulation == kMfma ? launch_scan_small<kMfma>(x, out, n, log2u(seg_len), s)
-                                              : launch_scan_small<kDpp>(x, out, n, log2u(seg_len), s);
-    return scan_long(x, out, n, seg_len, false, s);
+    return scan_any(in, out, n, seg_len, flags, static_cast<hipStream_t>(stream));
+}
+
+extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
+    return tcr_segmented_scan_ex(in, out, n, seg_len, 0u, stream);
+}
+
+extern "C" tcr_status tcr_scan_ex(const void* in, void* out, uint64_t n, uint32_t flags, void* stream) {
+    if (n == 0) return (flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) ? TCR_ERR_INVALID_ARG : TCR_OK;
+    return tcr_segmented_scan_ex(in, out, n, n, flags, stream);
 }
 
 extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* stream) {
@@ -454,10 +481,7 @@ extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* s
 }
 
 extern "C" tcr_status tcr_scan(const void* in, float* out, uint64_t n, void* stream) {
-    if (n == 0) return TCR_OK;
-    tcr_status st = validate(in, out, n, n, 16);
-    if (st != TCR_OK) return st;
-    return scan_long(static_cast<const _Float16*>(in), out, n, n, true, static_cast<hipStream_t>(stream));
+    return tcr_scan_ex(in, out, n, 0u, stream);
 }
 
 extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {

@@ -121,12 +121,17 @@ __device__ __forceinline__ half8 leading_ones(int count) {
 // output row i of the second product is position 16 + i:
 //   tri_lo[i][k] = 1  iff  k <= i            tri_hi[i][k] = 1  iff  k <= 16 + i
 // Lane (i, g) holds k = 8g .. 8g+7, so its registers are a run of ones followed by zeros.
-__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) { return leading_ones(id.j - 8 * id.g + 1); }
-__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) { return leading_ones(16 + id.j - 8 * id.g + 1); }
+// EXCL = 1 drops the diagonal (k < i): the exclusive scan, the strict triangle that Section 5
+// uses for its column scans.
+template <int EXCL = 0>
+__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) { return leading_ones(id.j - 8 * id.g + 1 - EXCL); }
+template <int EXCL = 0>
+__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) { return leading_ones(16 + id.j - 8 * id.g + 1 - EXCL); }
 // Same, for rows that hold two independent segments of 16: the second half starts afresh
 // (1 iff 16 <= k <= 16 + i).
+template <int EXCL = 0>
 __device__ __forceinline__ half8 const_tri_hi_seg16(const LaneId& id) {
-    return leading_ones(id.g >= 2 ? id.j - 8 * (id.g - 2) + 1 : 0);
+    return leading_ones(id.g >= 2 ? id.j - 8 * (id.g - 2) + 1 - EXCL : 0);
 }
 // Two half-row sums at once: output rows 0..7 add up k < 16, rows 8..15 add up k >= 16.
 __device__ __forceinline__ half8 const_half_rows(const LaneId& id) {
@@ -175,6 +180,33 @@ __device__ __forceinline__ void store4_guarded(float* __restrict__ out, uint64_t
 }
 __device__ __forceinline__ void store4(float* __restrict__ out, uint64_t off, float4v v) {
     *reinterpret_cast<float4v*>(out + off) = v;
+}
+
+// Output in binary32 (F16 = 0) or rounded to binary16 (F16 = 1, the paper's own output precision):
+// four consecutive results of one lane, `off` counted in elements.
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+template <int F16>
+__device__ __forceinline__ void store4_t(void* __restrict__ out, uint64_t off, float4v v) {
+    if constexpr (F16) {
+        const half4 h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+        *reinterpret_cast<half4*>(static_cast<_Float16*>(out) + off) = h;
+    } else {
+        *reinterpret_cast<float4v*>(static_cast<float*>(out) + off) = v;
+    }
+}
+template <int F16>
+__device__ __forceinline__ void store4_guarded_t(void* __restrict__ out, uint64_t off, uint64_t n, float4v v) {
+    if (off + 4 <= n) {
+        store4_t<F16>(out, off, v);
+    } else if (off < n) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (off + e < n) {
+                if constexpr (F16) static_cast<_Float16*>(out)[off + e] = (_Float16)v[e];
+                else static_cast<float*>(out)[off + e] = v[e];
+            }
+        }
+    }
 }
 
 }  // namespace tcr

@@ -14,33 +14,40 @@ namespace tcr {
 constexpr int kGenericThreads = 256;
 
 // One thread per segment (short segments).
+__device__ __forceinline__ void put(void* out, uint64_t i, float v, bool f16) {
+    if (f16) static_cast<_Float16*>(out)[i] = (_Float16)v;
+    else static_cast<float*>(out)[i] = v;
+}
+
+// exclusive: each output leaves out its own element; f16: outputs rounded to binary16.
 template <bool SCAN>
 __global__ __launch_bounds__(kGenericThreads) void generic_thread_kernel(const _Float16* __restrict__ in,
-                                                                         float* __restrict__ out, uint64_t nseg,
-                                                                         uint64_t seg_len) {
+                                                                         void* __restrict__ out, uint64_t nseg,
+                                                                         uint64_t seg_len, bool exclusive, bool f16) {
     const uint64_t s = (uint64_t)blockIdx.x * kGenericThreads + threadIdx.x;
     if (s >= nseg) return;
     const _Float16* p = in + s * seg_len;
     float acc = 0.0f;
     for (uint64_t k = 0; k < seg_len; ++k) {
-        acc += (float)p[k];
-        if (SCAN) out[s * seg_len + k] = acc;
+        const float v = (float)p[k];
+        if (SCAN) put(out, s * seg_len + k, exclusive ? acc : acc + v, f16);
+        acc += v;
     }
-    if (!SCAN) out[s] = acc;
+    if (!SCAN) put(out, s, acc, f16);
 }
 
 // One wavefront per segment: 64 elements per step, four steps in flight.
 template <bool SCAN>
 __global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Float16* __restrict__ in,
-                                                                       float* __restrict__ out, uint64_t nseg,
-                                                                       uint64_t seg_len) {
+                                                                       void* __restrict__ out, uint64_t nseg,
+                                                                       uint64_t seg_len, bool exclusive, bool f16) {
     constexpr int kSteps = 4;
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t s = (uint64_t)blockIdx.x * (kGenericThreads / kWave) +
                        (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (s >= nseg) return;
     const _Float16* p = in + s * seg_len;
-    float* q = out + s * seg_len;
+    const uint64_t q = s * seg_len;
     float carry = 0.0f;      // SCAN: total of the steps already done (uniform)
     float acc = 0.0f;        // REDUCE: this lane's running sum
     for (uint64_t k0 = 0; k0 < seg_len; k0 += (uint64_t)(kWave * kSteps)) {
@@ -55,7 +62,8 @@ __global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Fl
             if (SCAN) {
                 const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
                 const float incl = wave_scan_inclusive(v[i]);
-                if (k < seg_len) q[k] = incl + carry;
+                const float excl = wave_shr1(incl);          // sum of the lower lanes only (no subtraction)
+                if (k < seg_len) put(out, q + k, (exclusive ? excl : incl) + carry, f16);
                 carry += read_lane(incl, 63);
             } else {
                 acc += v[i];
@@ -64,7 +72,7 @@ __global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Fl
     }
     if (!SCAN) {
         const float total = wave_sum(acc);
-        if (lane == 0) out[s] = total;
+        if (lane == 0) put(out, s, total, f16);
     }
 }
 

@@ -43,17 +43,26 @@ __device__ __forceinline__ float wave_shr1(float x) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x138, 0xf, 0xf, true));
 }
 
-// In-lane inclusive scan of 8 values, binary32.
-__device__ __forceinline__ void scan8(half8 v, float (&p)[8]) {
-    p[0] = (float)v[0];
+// In-lane scan of 8 values, binary32: inclusive (EXCL = 0) or exclusive (EXCL = 1).  Returns the
+// sum of all eight.
+template <int EXCL = 0>
+__device__ __forceinline__ float scan8(half8 v, float (&p)[8]) {
+    float run = 0.0f;
 #pragma unroll
-    for (int e = 1; e < 8; ++e) p[e] = p[e - 1] + (float)v[e];
+    for (int e = 0; e < 8; ++e) {
+        if constexpr (EXCL) p[e] = run;
+        run += (float)v[e];
+        if constexpr (!EXCL) p[e] = run;
+    }
+    return run;
 }
 
 // ------------------------------------------------------------------------------ small segments
-template <int FORM, int LOG2L, int U, int WAVES>
+// MODE bit 0: exclusive scan; bit 1: binary16 output.
+template <int FORM, int LOG2L, int U, int WAVES, int MODE = 0>
 __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float16* __restrict__ in,
-                                                                   float* __restrict__ out, uint64_t n) {
+                                                                   void* __restrict__ out, uint64_t n) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
     static_assert(LOG2L >= 4 && LOG2L <= 9, "");
     const LaneId id;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
@@ -78,27 +87,27 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
         uint64_t off_lo, off_hi;
         if constexpr (FORM == kMfma) {
             if constexpr (LOG2L == 4) {
-                lo = mfma(const_tri_lo(id), x[u], splat(0.0f));
-                hi = mfma(const_tri_hi_seg16(id), x[u], splat(0.0f));
+                lo = mfma(const_tri_lo<EXCL>(id), x[u], splat(0.0f));
+                hi = mfma(const_tri_hi_seg16<EXCL>(id), x[u], splat(0.0f));
             } else if constexpr (LOG2L == 5) {
-                lo = mfma(const_tri_lo(id), x[u], splat(0.0f));
-                hi = mfma(const_tri_hi(id), x[u], splat(0.0f));
+                lo = mfma(const_tri_lo<EXCL>(id), x[u], splat(0.0f));
+                hi = mfma(const_tri_hi<EXCL>(id), x[u], splat(0.0f));
             } else {
                 constexpr int ROWS = 1 << (LOG2L - 5);
                 const float4v tot = mfma(const_ones(), x[u], splat(0.0f));
                 const float incl = row_scan_inclusive<ROWS>(tot[0], id.j);
                 const float prev = row_shr<1>(incl);
                 const float g = ((id.j & (ROWS - 1)) == 0) ? 0.0f : prev;     // rows before mine, same segment
-                lo = mfma(const_tri_lo(id), x[u], splat(g));
-                hi = mfma(const_tri_hi(id), x[u], splat(g));
+                lo = mfma(const_tri_lo<EXCL>(id), x[u], splat(g));
+                hi = mfma(const_tri_hi<EXCL>(id), x[u], splat(g));
             }
             off_lo = tbase + (uint64_t)(kRow * id.j + 4 * id.g);
             off_hi = off_lo + 16;
         } else {
             constexpr int LANES = 1 << (LOG2L - 3);
             float p[8];
-            scan8(x[u], p);
-            const float incl = lanes_scan_inclusive<LANES>(p[7], id.lane);
+            const float lane_total = scan8<EXCL>(x[u], p);
+            const float incl = lanes_scan_inclusive<LANES>(lane_total, id.lane);
             const float prev = wave_shr1(incl);
             const float g = ((id.lane & (LANES - 1)) == 0) ? 0.0f : prev;
             lo = (float4v){p[0] + g, p[1] + g, p[2] + g, p[3] + g};
@@ -107,11 +116,11 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
             off_hi = off_lo + 4;
         }
         if (full) {
-            store4(out, off_lo, lo);
-            store4(out, off_hi, hi);
+            store4_t<F16>(out, off_lo, lo);
+            store4_t<F16>(out, off_hi, hi);
         } else {
-            store4_guarded(out, off_lo, n, lo);
-            store4_guarded(out, off_hi, n, hi);
+            store4_guarded_t<F16>(out, off_lo, n, lo);
+            store4_guarded_t<F16>(out, off_hi, n, hi);
         }
     }
 }
@@ -153,8 +162,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_wave_kernel(const _Float16
                     run += read_lane(incl, 15);
                 } else {
                     float p[8];
-                    scan8(x[u], p);
-                    const float incl = wave_scan_inclusive(p[7]);
+                    const float lane_total = scan8(x[u], p);
+                    const float incl = wave_scan_inclusive(lane_total);
                     const float carry = wave_shr1(incl) + run;
                     lo = (float4v){p[0] + carry, p[1] + carry, p[2] + carry, p[3] + carry};
                     hi = (float4v){p[4] + carry, p[5] + carry, p[6] + carry, p[7] + carry};
@@ -261,12 +270,14 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
 // seg_mask  = seg_len - 1 for a power-of-two seg_len, all ones for the full scan (one segment).
 // seg_len   only compared against the wavefront / workgroup share (saturated for the full scan).
 // Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.
-template <int FORM, int U, int WAVES, int CARRY, int LBK = 64, bool TICKET = true, bool XCDPART = false>
+// MODE bit 0: exclusive scan; bit 1: binary16 output.
+template <int FORM, int U, int WAVES, int CARRY, int LBK = 64, bool TICKET = true, bool XCDPART = false, int MODE = 0>
 __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float16* __restrict__ in,
-                                                                   float* __restrict__ out, uint64_t n,
+                                                                   void* __restrict__ out, uint64_t n,
                                                                    uint64_t seg_mask, uint64_t seg_len,
                                                                    ScanWorkspace ws,
                                                                    const float* __restrict__ tile_prefix) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
     constexpr uint64_t kChunk = (uint64_t)kTile * U;             // one wavefront's share
     constexpr uint64_t kBlockTile = kChunk * WAVES;              // one workgroup's share
     __shared__ float s_wave_total[WAVES];
@@ -315,8 +326,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
             inner[u] = row_shr<1>(incl);
             tile_total[u] = read_lane(incl, 15);
         } else {
-            scan8(x[u], p[u]);
-            const float incl = wave_scan_inclusive(p[u][7]);
+            const float lane_total = scan8<EXCL>(x[u], p[u]);
+            const float incl = wave_scan_inclusive(lane_total);
             inner[u] = wave_shr1(incl);
             tile_total[u] = read_lane(incl, 63);
         }
@@ -363,8 +374,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
         float4v lo, hi;
         uint64_t off_lo, off_hi;
         if constexpr (FORM == kMfma) {
-            lo = mfma(const_tri_lo(id), x[u], splat(carry));
-            hi = mfma(const_tri_hi(id), x[u], splat(carry));
+            lo = mfma(const_tri_lo<EXCL>(id), x[u], splat(carry));
+            hi = mfma(const_tri_hi<EXCL>(id), x[u], splat(carry));
             off_lo = tbase + (uint64_t)(kRow * id.j + 4 * id.g);
             off_hi = off_lo + 16;
         } else {
@@ -375,11 +386,11 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
             off_hi = off_lo + 4;
         }
         if (full) {
-            store4(out, off_lo, lo);
-            store4(out, off_hi, hi);
+            store4_t<F16>(out, off_lo, lo);
+            store4_t<F16>(out, off_hi, hi);
         } else {
-            store4_guarded(out, off_lo, n, lo);
-            store4_guarded(out, off_hi, n, hi);
+            store4_guarded_t<F16>(out, off_lo, n, lo);
+            store4_guarded_t<F16>(out, off_hi, n, hi);
         }
     }
 }

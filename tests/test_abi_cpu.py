@@ -58,6 +58,11 @@ def test_argument_validation_happens_before_any_device_work(lib):
     assert raw.tcr_segmented_reduce(base, base + 2048 + 2, 64, 16, None) == inv
     assert raw.tcr_reduce(base, None, 64, None) == inv
     assert raw.tcr_scan(base + 8, base + 2048, 64, None) == inv
+    # unknown flag bits of the scan variants
+    assert raw.tcr_segmented_scan_ex(base, base + 2048, 64, 16, 4, None) == inv
+    assert raw.tcr_scan_ex(base, base + 2048, 64, 8, None) == inv
+    assert raw.tcr_segmented_scan_ex(base, base + 2048, 65, 16, 1, None) == inv
+    assert raw.tcr_scan_ex(None, None, 0, 3, None) == lib.OK
     # n == 0 is a no-op for everything that writes no output
     assert raw.tcr_segmented_reduce(None, None, 0, 16, None) == lib.OK
     assert raw.tcr_segmented_scan(None, None, 0, 16, None) == lib.OK

@@ -1,0 +1,118 @@
+"""Scan variants (exclusive, binary16 output) through tcr_segmented_scan_ex / tcr_scan_ex against the oracle.
+
+Exclusive: the oracle's own exclusive scan.  Binary16 output: the oracle's binary64 value rounded to binary16
+(numpy, round to nearest even, overflow to infinity).  Integer-valued inputs must match exactly -- the binary32
+sum is exact, so its rounding equals the rounding of the exact value.  For real-valued inputs the binary32 sum
+carries a few ulps of error, which can tip a value that lies next to a rounding boundary to the neighbouring
+binary16 number, so the bar is one binary16 spacing.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_1811_09736_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+EXCL, F16 = 1, 2
+
+
+@pytest.fixture(scope="module")
+def tcr():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1811_09736_amd import binding
+    binding.set_variant("reset")
+    yield binding
+    binding.set_variant("reset")
+    binding.check_device_flags()
+
+
+def reference(oracle, x, seg, flags):
+    ref = oracle.segmented_scan_exclusive(x, seg) if flags & EXCL else oracle.segmented_scan(x, seg)
+    return ref
+
+
+def check(got, ref, flags, exact, what):
+    g = got.cpu().numpy()
+    if flags & F16:
+        assert g.dtype == np.float16
+        with np.errstate(over="ignore"):
+            want = ref.astype(np.float16)
+        if exact:
+            same = (g == want) | (np.isinf(g) & np.isinf(want) & (np.sign(g) == np.sign(want)))
+            assert same.all(), f"{what}: first mismatch at {np.flatnonzero(~same)[0]}"
+        else:
+            fin = np.isfinite(want) & (np.abs(ref) < 65504.0 * (1 - 2.0 ** -10))
+            g64 = g[fin].astype(np.float64)
+            spacing = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref[fin]), 2.0 ** -14))) - 10), 2.0 ** -24)
+            assert np.all(np.abs(g64 - ref[fin]) <= spacing), what
+    else:
+        g64 = g.astype(np.float64)
+        if exact:
+            assert np.array_equal(g64, ref), f"{what}: first mismatch at {np.flatnonzero(g64 != ref)[0]}"
+        else:
+            assert np.all(np.abs(g64 - ref) <= 1e-3 * np.maximum(np.abs(ref), 1.0)), what
+
+
+SEGS = [16, 32, 64, 256, 512, 1024, 4096, 8192, 16384, 32768, 1 << 16, 1 << 17, 1 << 20]
+GENERIC = [1, 3, 24, 97, 100, 1000, 4097]
+
+
+@pytest.mark.parametrize("flags", [EXCL, F16, EXCL | F16])
+@pytest.mark.parametrize("seg", SEGS + GENERIC)
+def test_variants_exact(tcr, oracle, seg, flags):
+    nseg = 3 if seg >= 8192 else (3 * 8192 // seg + 3)
+    n = seg * nseg
+    x = workloads.make_input(n, "int4", 500 + seg % 89)
+    xd = torch.from_numpy(x).cuda()
+    got = tcr.segmented_scan_ex(xd, seg, flags)
+    check(got, reference(oracle, x, seg, flags), flags, True, f"L={seg} flags={flags}")
+
+
+@pytest.mark.parametrize("flags", [EXCL, F16, EXCL | F16])
+@pytest.mark.parametrize("seg", [16, 256, 2048, 16384, 1 << 17, 100])
+def test_variants_real(tcr, oracle, seg, flags):
+    nseg = 3 if seg >= 8192 else (3 * 8192 // seg + 3)
+    n = seg * nseg
+    x = workloads.make_input(n, "uniform_01", 4)
+    xd = torch.from_numpy(x).cuda()
+    got = tcr.segmented_scan_ex(xd, seg, flags)
+    check(got, reference(oracle, x, seg, flags), flags, False, f"L={seg} flags={flags} real")
+
+
+@pytest.mark.parametrize("flags", [EXCL, F16, EXCL | F16])
+@pytest.mark.parametrize("n", [1, 7, 513, 8193, 100003, (1 << 21) + 9])
+def test_full_scan_variants(tcr, oracle, n, flags):
+    x = workloads.make_input(n, "int4", n % 777)
+    xd = torch.from_numpy(x).cuda()
+    got = tcr.scan_ex(xd, flags)
+    check(got, reference(oracle, x, n, flags), flags, True, f"full n={n} flags={flags}")
+
+
+def test_flags_zero_is_the_plain_scan(tcr):
+    x = torch.from_numpy(workloads.make_input(1 << 16, "int8", 1)).cuda()
+    assert torch.equal(tcr.segmented_scan_ex(x, 256, 0), tcr.segmented_scan(x, 256))
+    assert torch.equal(tcr.scan_ex(x, 0), tcr.scan(x))
+
+
+def test_exclusive_plus_input_is_inclusive(tcr):
+    x = torch.from_numpy(workloads.make_input(1 << 20, "int8", 2)).cuda()
+    for seg in (64, 4096, 1 << 18, 1 << 20):
+        inc = tcr.segmented_scan(x, seg)
+        exc = tcr.segmented_scan_ex(x, seg, EXCL)
+        assert torch.equal(exc + x.float(), inc)
+        assert not exc[::seg].any()
+
+
+def test_dpp_formulation_has_no_tuned_variant_kernels(tcr):
+    x = torch.from_numpy(workloads.make_input(1 << 12, "int4", 3)).cuda()
+    tcr.set_variant("formulation", "dpp")
+    try:
+        with pytest.raises(tcr.TcrError) as e:
+            tcr.segmented_scan_ex(x, 256, EXCL)
+        assert e.value.status == tcr.ERR_UNSUPPORTED
+        assert torch.equal(tcr.segmented_scan_ex(x, 256, 0), tcr.segmented_scan(x, 256))
+        tcr.segmented_scan_ex(x[:4095], 3, EXCL)   # untuned lengths take every flag
+    finally:
+        tcr.set_variant("reset")

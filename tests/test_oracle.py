@@ -172,6 +172,33 @@ def test_invariants(oracle, n, seg):
         assert oracle.reduce(x) == red[0]
 
 
+# ------------------------------------------------------------------ exclusive scan
+
+def test_exclusive_scan_hand_values(oracle):
+    # worked by hand from the definition: each output leaves out its own element
+    x = np.array([1, 2, 3, 4, 5, 6, 7, 8], dtype=np.float16)
+    assert oracle.segmented_scan_exclusive(x, 8).tolist() == [0, 1, 3, 6, 10, 15, 21, 28]
+    assert oracle.segmented_scan_exclusive(x, 4).tolist() == [0, 1, 3, 6, 0, 5, 11, 18]
+    assert oracle.segmented_scan_exclusive(x, 1).tolist() == [0] * 8
+    y = np.array([0.5, -0.25, 8, -8], dtype=np.float16)
+    assert oracle.segmented_scan_exclusive(y, 2).tolist() == [0, 0.5, 0, 8]
+    assert oracle.segmented_scan_exclusive(np.ones(6, dtype=np.float16), 3).tolist() == [0, 1, 2, 0, 1, 2]
+
+
+@pytest.mark.parametrize("n,seg", [(1 << 12, 16), (1 << 12, 1 << 12), (3 * 5 * 7 * 8, 35), (60, 1)])
+def test_exclusive_scan_relations(oracle, n, seg):
+    x = workloads.make_input(n, "uniform_pm1", 3)
+    xd = x.astype(np.float64)
+    ex = oracle.segmented_scan_exclusive(x, seg).reshape(-1, seg)
+    inc = oracle.segmented_scan(x, seg).reshape(-1, seg)
+    assert not ex[:, 0].any()                                   # starts at zero
+    assert np.array_equal(ex[:, 1:], inc[:, :-1])               # shifted inclusive scan
+    assert np.array_equal(ex + xd.reshape(-1, seg), inc)        # exact: values are multiples of 2^-24
+    q = np.rint(xd * 2.0 ** 24).astype(np.int64).reshape(-1, seg)
+    exq = np.cumsum(q, axis=1) - q                              # exact integer arithmetic
+    assert np.array_equal(ex * 2.0 ** 24, exq.astype(np.float64))
+
+
 def test_reduce_is_permutation_invariant_on_integers(oracle):
     x = workloads.make_input(1 << 12, "int8", 5)
     rng = np.random.default_rng(11)
