@@ -41,6 +41,10 @@ def main() -> int:
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (read 1 GiB, write 1 GiB) three times before the timed "
                          "region, as the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--sustain", type=float, default=0.0,
+                    help="instead of the benchmark, repeat ONE call (see --only) for this many seconds, for power "
+                         "sampling with an external tool; prints calls per second")
+    ap.add_argument("--only", default="segmented_scan:12", help="op:log2(seg_len) for --sustain")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (segmented reduce/scan needs no second one); "
@@ -78,6 +82,24 @@ def main() -> int:
         for op, e in calls:
             run(op, e)
 
+    if args.sustain > 0:
+        op, e = args.only.split(":")
+        e = int(e)
+        if op == "segmented_reduce" and e not in out_red:
+            out_red[e] = torch.empty(n >> e, dtype=torch.float32, device="cuda")
+        run(op, e)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        count = 0
+        while time.perf_counter() - t0 < args.sustain:
+            for _ in range(200):
+                run(op, e)
+            torch.cuda.synchronize()
+            count += 200
+        dt = time.perf_counter() - t0
+        print(json.dumps({"sustain": args.only, "formulation": args.formulation, "calls": count, "seconds": round(dt, 3),
+                          "us_per_call": round(dt / count * 1e6, 2)}))
+        return 0
     if args.calibration_copy:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -193,7 +215,9 @@ def main() -> int:
                          f"sequential binary64 C loops, {dt:.1f} s"}
 
     line = {
-        "metric": "effective input GB/s for segmented reduce + inclusive scan, seg_len sweep at N=2^%d" % args.log2n,
+        "metric": "effective input GB/s (% of HBM peak) for seg-reduce/scan at N=2^" + str(args.log2n),
+        "pct_of_hbm_peak": round(sum(sum(workloads.algorithmic_bytes(op, n, 1 << e)) for op, e in calls)
+                                 / (elapsed / args.steps) * 1e-9 / HBM_PEAK_GBS * 100, 1),
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",

@@ -50,7 +50,7 @@ constexpr uint64_t kWaveSpanMax = 65536;             // reduce: longest span one
 constexpr int kReduceBlockW = 4;                     // reduce: wavefronts combined through LDS for longer segments
 constexpr int kCarryU = 8, kCarryW = 16;             // scan with cross-workgroup carry: 65536 elements per workgroup
 constexpr uint64_t kCarryTile = (uint64_t)kTile * kCarryU * kCarryW;
-constexpr uint64_t kMaxElements = 1ull << 40;
+constexpr uint64_t kMaxElements = 1ull << 38;        // keeps every grid below 2^31 workgroups
 
 // ---------------------------------------------------------------------------- workspace
 struct Workspace {

@@ -68,7 +68,7 @@ def test_argument_validation_happens_before_any_device_work(lib):
     assert raw.tcr_segmented_scan(None, None, 0, 16, None) == lib.OK
     assert raw.tcr_scan(None, None, 0, None) == lib.OK
     # sizes without a kernel
-    assert raw.tcr_segmented_scan(base, base + 2048, 1 << 41, 1 << 41, None) == lib.ERR_UNSUPPORTED
+    assert raw.tcr_segmented_scan(base, base + 2048, 1 << 39, 1 << 39, None) == lib.ERR_UNSUPPORTED
 
 
 def test_variant_switch(lib):
