@@ -77,6 +77,20 @@ tcr_status tcr_segmented_scan_ex(const void *in, void *out, uint64_t n, uint64_t
 tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, void *stream);
 
 /*
+ * Irregular segments (the paper pads them to regular ones, footnote in Section 3; here the segment
+ * boundaries are read directly).  Segment s is in[offsets[s] .. offsets[s+1]); offsets is a DEVICE pointer to
+ * nseg + 1 non-decreasing element indices, 8-byte aligned; empty segments are allowed.
+ *   tcr_irregular_reduce  out[s] = sum of segment s (0 for an empty one); out: nseg floats.
+ *   tcr_irregular_scan    out[k] = sum of in[offsets[s] .. k] for k in segment s; out is indexed like `in`
+ *                         (positions outside [offsets[0], offsets[nseg]) are not written).
+ * in and out need only their natural alignment (2 and 4 bytes).  The offsets are not validated (they live on
+ * the device); indices beyond the caller's arrays are the caller's error.  Untuned kernels, one wavefront per
+ * segment.  nseg == 0 is a no-op.
+ */
+tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *out, uint64_t nseg, void *stream);
+tcr_status tcr_irregular_scan(const void *in, const uint64_t *offsets, float *out, uint64_t nseg, void *stream);
+
+/*
  * Full reduction (device level, Section 4): out[0] = sum of all n inputs (0 for n == 0).
  * Any n is accepted.  out: 1 float.
  */

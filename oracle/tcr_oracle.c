@@ -101,6 +101,41 @@ int oracle_segmented_scan_exclusive(const uint16_t *in, double *out, uint64_t n,
     return 0;
 }
 
+/*
+ * Irregular segments (the paper mentions them in a footnote of Section 3 and reduces them to the
+ * regular case by padding; the result is the same as applying the definition to each piece):
+ * segment s is in[offsets[s] .. offsets[s+1]), offsets has nseg + 1 non-decreasing entries.
+ *   reduce: out[s] = sum of segment s (0 if empty).
+ *   scan:   out[k] = sum of in[offsets[s] .. k] for every k in segment s (out indexed like in;
+ *           entries outside the segments are left untouched).
+ */
+int oracle_irregular_reduce(const uint16_t *in, const uint64_t *offsets, double *out, uint64_t nseg)
+{
+    if (nseg > 0 && (in == NULL || offsets == NULL || out == NULL)) return 1;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        if (offsets[s + 1] < offsets[s]) return 1;
+        double acc = 0.0;
+        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k)
+            acc += oracle_half_to_double(in[k]);
+        out[s] = acc;
+    }
+    return 0;
+}
+
+int oracle_irregular_scan(const uint16_t *in, const uint64_t *offsets, double *out, uint64_t nseg)
+{
+    if (nseg > 0 && (in == NULL || offsets == NULL || out == NULL)) return 1;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        if (offsets[s + 1] < offsets[s]) return 1;
+        double acc = 0.0;
+        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {
+            acc += oracle_half_to_double(in[k]);
+            out[k] = acc;
+        }
+    }
+    return 0;
+}
+
 /* Full (unsegmented) forms: one segment that spans the whole input. */
 int oracle_reduce(const uint16_t *in, double *out, uint64_t n)
 {

@@ -22,6 +22,7 @@ SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
+    "tcr_irregular_reduce", "tcr_irregular_scan",
     "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
 )
@@ -49,6 +50,10 @@ def _load() -> ctypes.CDLL:
     lib.tcr_scan_ex.argtypes = [vp, vp, u64, ctypes.c_uint32, vp]
     lib.tcr_segmented_scan_ex.restype = ctypes.c_int
     lib.tcr_scan_ex.restype = ctypes.c_int
+    lib.tcr_irregular_reduce.argtypes = [vp, vp, fp, u64, vp]
+    lib.tcr_irregular_scan.argtypes = [vp, vp, fp, u64, vp]
+    lib.tcr_irregular_reduce.restype = ctypes.c_int
+    lib.tcr_irregular_scan.restype = ctypes.c_int
     lib.tcr_reduce.argtypes = [vp, fp, u64, vp]
     lib.tcr_scan.argtypes = [vp, fp, u64, vp]
     for name in ("tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan"):
@@ -154,6 +159,45 @@ def scan_ex(x: torch.Tensor, flags: int, out: Optional[torch.Tensor] = None,
         st = _lib.tcr_scan_ex(x.data_ptr(), out.data_ptr(), n, flags, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_scan_ex")
+    return out
+
+
+def _check_offsets(x: torch.Tensor, offsets: torch.Tensor) -> int:
+    if not (offsets.is_cuda and offsets.dtype == torch.int64 and offsets.dim() == 1 and offsets.is_contiguous()
+            and offsets.numel() >= 1 and offsets.device == x.device):
+        raise TypeError("offsets must be a contiguous 1-D int64 CUDA tensor of nseg + 1 entries on the input's device")
+    return offsets.numel() - 1
+
+
+def irregular_reduce(x: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.Tensor] = None,
+                     stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_irregular_reduce: out[s] = sum of x[offsets[s]:offsets[s+1]]."""
+    if not (x.is_cuda and x.dtype == torch.float16 and x.dim() == 1 and x.is_contiguous()):
+        raise TypeError("input must be a contiguous 1-D float16 CUDA tensor")
+    nseg = _check_offsets(x, offsets)
+    if out is None:
+        out = torch.empty(nseg, dtype=torch.float32, device=x.device)
+    _check_output(out, nseg, x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_irregular_reduce(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), nseg, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_irregular_reduce")
+    return out
+
+
+def irregular_scan(x: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_irregular_scan: inclusive running sums restarting at every offsets[s]; out is indexed like x."""
+    if not (x.is_cuda and x.dtype == torch.float16 and x.dim() == 1 and x.is_contiguous()):
+        raise TypeError("input must be a contiguous 1-D float16 CUDA tensor")
+    nseg = _check_offsets(x, offsets)
+    if out is None:
+        out = torch.zeros(x.numel(), dtype=torch.float32, device=x.device)
+    _check_output(out, x.numel(), x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_irregular_scan(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), nseg, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_irregular_scan")
     return out
 
 

@@ -468,6 +468,28 @@ extern "C" tcr_status tcr_scan_ex(const void* in, void* out, uint64_t n, uint32_
     return tcr_segmented_scan_ex(in, out, n, n, flags, stream);
 }
 
+extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offsets, float* out, uint64_t nseg,
+                                           void* stream) {
+    if (nseg == 0) return TCR_OK;
+    if (in == nullptr || offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
+    if (nseg > kMaxElements) return TCR_ERR_UNSUPPORTED;
+    irregular_wave_kernel<false><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0,
+                                   static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
+    return check_launch("irregular_wave_kernel");
+}
+
+extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets, float* out, uint64_t nseg,
+                                         void* stream) {
+    if (nseg == 0) return TCR_OK;
+    if (in == nullptr || offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
+    if (nseg > kMaxElements) return TCR_ERR_UNSUPPORTED;
+    irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0,
+                                  static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
+    return check_launch("irregular_wave_kernel");
+}
+
 extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* stream) {
     if (out == nullptr) return TCR_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -76,4 +76,43 @@ __global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Fl
     }
 }
 
+// Irregular segments: segment s is [offsets[s], offsets[s+1]).  One wavefront per segment, same
+// arithmetic as generic_wave_kernel.  (The paper reduces the irregular case to the regular one by
+// padding the input, Section 3 footnote; reading the offsets directly needs no padded copy.)
+template <bool SCAN>
+__global__ __launch_bounds__(kGenericThreads) void irregular_wave_kernel(const _Float16* __restrict__ in,
+                                                                         const uint64_t* __restrict__ offsets,
+                                                                         float* __restrict__ out, uint64_t nseg) {
+    constexpr int kSteps = 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t s = (uint64_t)blockIdx.x * (kGenericThreads / kWave) +
+                       (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (s >= nseg) return;
+    const uint64_t begin = offsets[s], end = offsets[s + 1];
+    float carry = 0.0f, acc = 0.0f;
+    for (uint64_t k0 = begin; k0 < end; k0 += (uint64_t)(kWave * kSteps)) {
+        float v[kSteps];
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
+            v[i] = (k < end) ? (float)in[k] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            if (SCAN) {
+                const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
+                const float incl = wave_scan_inclusive(v[i]);
+                if (k < end) out[k] = incl + carry;
+                carry += read_lane(incl, 63);
+            } else {
+                acc += v[i];
+            }
+        }
+    }
+    if (!SCAN) {
+        const float total = wave_sum(acc);
+        if (lane == 0) out[s] = total;
+    }
+}
+
 }  // namespace tcr

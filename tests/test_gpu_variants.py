@@ -116,3 +116,45 @@ def test_dpp_formulation_has_no_tuned_variant_kernels(tcr):
         tcr.segmented_scan_ex(x[:4095], 3, EXCL)   # untuned lengths take every flag
     finally:
         tcr.set_variant("reset")
+
+
+# ------------------------------------------------------------------ irregular segments
+
+def _random_offsets(n, nseg, seed):
+    rng = np.random.default_rng(seed)
+    cuts = np.sort(rng.integers(0, n + 1, nseg - 1))
+    return np.concatenate([[0], cuts, [n]]).astype(np.int64)
+
+
+@pytest.mark.parametrize("n,nseg", [(1000, 7), (100003, 400), (1 << 20, 5000), (1 << 20, 3)])
+def test_irregular_segments(tcr, oracle, n, nseg):
+    x = workloads.make_input(n, "int8", n % 321)
+    off = _random_offsets(n, nseg, nseg)
+    off[nseg // 2 + 1] = off[nseg // 2]                      # at least one empty segment
+    xd = torch.from_numpy(x).cuda()
+    od = torch.from_numpy(off).cuda()
+    red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
+    assert np.array_equal(red, oracle.irregular_reduce(x, off))
+    scan = tcr.irregular_scan(xd, od).cpu().numpy().astype(np.float64)
+    assert np.array_equal(scan, oracle.irregular_scan(x, off))
+    y = workloads.make_input(n, "uniform_pm1", 5)
+    yd = torch.from_numpy(y).cuda()
+    got = tcr.irregular_scan(yd, od).cpu().numpy().astype(np.float64)
+    ref = oracle.irregular_scan(y, off)
+    assert np.all(np.abs(got - ref) <= 1e-3 * np.maximum(np.abs(ref), 1.0))
+
+
+def test_irregular_partial_cover_and_uniform(tcr, oracle):
+    x = workloads.make_input(4096 + 3, "int4", 1)
+    xd = torch.from_numpy(x).cuda()
+    off = np.array([5, 5, 130, 1000, 4000], dtype=np.int64)   # does not cover the input; x[5:] is only 2-byte aligned
+    od = torch.from_numpy(off).cuda()
+    out = torch.full((x.size,), -1.0, dtype=torch.float32, device="cuda")
+    tcr.irregular_scan(xd, od, out=out)
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.irregular_scan(x, off)
+    assert np.array_equal(got[5:4000], ref[5:4000])
+    assert np.all(got[:5] == -1.0) and np.all(got[4000:] == -1.0)          # untouched outside the segments
+    reg = torch.arange(0, 4097, 256, dtype=torch.int64, device="cuda")
+    assert torch.equal(tcr.irregular_reduce(xd, reg), tcr.segmented_reduce(xd[:4096].clone(), 256))
+    assert tcr.irregular_reduce(xd, torch.zeros(1, dtype=torch.int64, device="cuda")).numel() == 0

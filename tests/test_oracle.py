@@ -199,6 +199,45 @@ def test_exclusive_scan_relations(oracle, n, seg):
     assert np.array_equal(ex * 2.0 ** 24, exq.astype(np.float64))
 
 
+# ------------------------------------------------------------------ irregular segments
+
+def test_irregular_hand_values(oracle):
+    x = np.array([1, 2, 3, 4, 5, 6, 7, 8], dtype=np.float16)
+    off = [0, 3, 3, 4, 8]                                    # lengths 3, 0, 1, 4 -- worked by hand
+    assert oracle.irregular_reduce(x, off).tolist() == [6, 0, 4, 26]
+    assert oracle.irregular_scan(x, off).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
+    # segments need not cover the input: untouched outputs stay zero
+    assert oracle.irregular_scan(x, [2, 5]).tolist() == [0, 0, 3, 7, 12, 0, 0, 0]
+    assert oracle.irregular_reduce(x, [2, 5]).tolist() == [12]
+    assert oracle.irregular_reduce(x, [0]).size == 0
+    with pytest.raises(ValueError):
+        oracle.irregular_reduce(x, [0, 9])
+    with pytest.raises(ValueError):
+        oracle.irregular_scan(x, [4, 2])
+
+
+def test_irregular_equals_per_piece_definition(oracle):
+    rng = np.random.default_rng(8)
+    x = workloads.make_input(5000, "uniform_pm1", 8)
+    cuts = np.sort(rng.integers(0, 5001, 40))
+    off = np.concatenate([[0], cuts, [5000]])
+    red = oracle.irregular_reduce(x, off)
+    scan = oracle.irregular_scan(x, off)
+    xd = x.astype(np.float64)
+    q = np.rint(xd * 2.0 ** 24).astype(np.int64)
+    for s in range(off.size - 1):
+        a, b = int(off[s]), int(off[s + 1])
+        piece = np.ascontiguousarray(x[a:b])
+        assert red[s] * 2.0 ** 24 == float(q[a:b].sum())                       # exact integer arithmetic
+        if b > a:
+            assert np.array_equal(scan[a:b], oracle.scan(piece))               # the definition, piece by piece
+            assert np.array_equal(scan[a:b] * 2.0 ** 24, np.cumsum(q[a:b]).astype(np.float64))
+    # uniform offsets are the regular segmented forms
+    reg = np.arange(0, 5001, 125)
+    assert np.array_equal(oracle.irregular_reduce(x, reg), oracle.segmented_reduce(x, 125))
+    assert np.array_equal(oracle.irregular_scan(x, reg), oracle.segmented_scan(x, 125))
+
+
 def test_reduce_is_permutation_invariant_on_integers(oracle):
     x = workloads.make_input(1 << 12, "int8", 5)
     rng = np.random.default_rng(11)

@@ -27,6 +27,10 @@ MUTANTS = {
     "scan_wrong_output_index": ("out[s * seg_len + k] = acc;", "out[s + k] = acc;"),
     "exclusive_made_inclusive": ("            out[s * seg_len + k] = acc;\n            acc += oracle_half_to_double(in[s * seg_len + k]);",
                                  "            acc += oracle_half_to_double(in[s * seg_len + k]);\n            out[s * seg_len + k] = acc;"),
+    "irregular_reduce_includes_end": ("for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k)\n            acc += ",
+                                      "for (uint64_t k = offsets[s]; k <= offsets[s + 1]; ++k)\n            acc += "),
+    "irregular_scan_carry_not_reset": ("        double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {",
+                                       "        static double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {"),
     "sampled_scan_starts_at_zero": ("const uint64_t first = idx[q] - idx[q] % seg_len;", "const uint64_t first = 0;"),
     "sampled_scan_exclusive": ("k <= idx[q]; ++k)", "k < idx[q]; ++k)"),
 }
@@ -43,6 +47,8 @@ def _pins(o) -> None:
     assert o.segmented_reduce(x, 2).tolist() == [3, 7, 11, 15]
     assert o.scan(x).tolist() == [1, 3, 6, 10, 15, 21, 28, 36]
     assert o.segmented_scan_exclusive(x, 4).tolist() == [0, 1, 3, 6, 0, 5, 11, 18]
+    assert o.irregular_reduce(x, [0, 3, 3, 4, 7]).tolist() == [6, 0, 4, 18]
+    assert o.irregular_scan(x, [0, 3, 3, 4, 8]).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
     assert o.reduce(x) == 36.0
     for dist, seed in (("uniform_pm1", 0), ("subnormal", 9)):
         y = workloads.make_input(1 << 12, dist, seed)
