@@ -273,3 +273,58 @@ def test_errors_on_device(tcr):
     with pytest.raises(tcr.TcrError):
         tcr.segmented_reduce(x[:4096], 100)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ workspace life cycle and concurrency
+
+def test_two_streams_run_chained_scans_concurrently(tcr, oracle):
+    # each (device, stream) pair owns its look-back table and ticket counter, so chained scans issued on two
+    # streams at the same time must not disturb each other
+    n = (1 << 22) + 4096
+    x = workloads.make_input(n, "int8", 21)
+    y = workloads.make_input(n, "int4", 22)
+    xd, yd = dev(x), dev(y)
+    xref = torch.from_numpy(oracle.scan(x).astype(np.float32)).cuda()
+    yref = torch.from_numpy(oracle.segmented_scan(y[: 1 << 22], 1 << 20).astype(np.float32)).cuda()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs1 = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+    outs2 = [torch.empty(1 << 22, dtype=torch.float32, device="cuda") for _ in range(3)]
+    for it in range(60):
+        tcr.scan(xd, out=outs1[it % 3], stream=s1)
+        tcr.segmented_scan(yd[: 1 << 22], 1 << 20, out=outs2[it % 3], stream=s2)
+    s1.synchronize()
+    s2.synchronize()
+    for o in outs1:
+        assert torch.equal(o, xref)
+    for o in outs2:
+        assert torch.equal(o, yref)
+    tcr.check_device_flags(s1)
+    tcr.check_device_flags(s2)
+
+
+def test_workspace_grows_shrinks_and_survives_release(tcr, oracle):
+    small = workloads.make_input((1 << 18) + 8, "int8", 31)
+    large = workloads.make_input((1 << 24) + 8, "int8", 32)
+    sd, ld = dev(small), dev(large)
+    sref, lref = oracle.scan(small), oracle.scan(large)
+    for _ in range(2):
+        assert_exact(tcr.scan(sd), sref, "small before growth")
+        assert_exact(tcr.scan(ld), lref, "large (table grows)")
+        assert_exact(tcr.scan(sd), sref, "small after growth")
+        assert float(tcr.reduce(ld).cpu()[0]) == oracle.reduce(large)
+        torch.cuda.synchronize()
+        tcr.release()                                   # next round starts from a released library
+    tcr.check_device_flags()
+
+
+def test_outputs_do_not_depend_on_previous_contents(tcr, oracle):
+    x = workloads.make_input((1 << 20) + 24, "int8", 33)
+    xd = dev(x)
+    ref = oracle.scan(x)
+    out = torch.full((x.size,), float("nan"), dtype=torch.float32, device="cuda")
+    tcr.scan(xd, out=out)
+    assert_exact(out, ref, "scan into a NaN-filled buffer")
+    red = torch.full((1 << 8,), float("nan"), dtype=torch.float32, device="cuda")
+    tcr.segmented_reduce(xd[: 1 << 20], 1 << 12, out=red)
+    assert_exact(red, oracle.segmented_reduce(np.ascontiguousarray(x[: 1 << 20]), 1 << 12), "reduce into NaNs")
