@@ -36,7 +36,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--log2n", type=int, default=LOG2N, help="elements = 2^log2n (default: the headline size)")
     ap.add_argument("--formulation", default="mfma", choices=["mfma", "dpp"])
-    ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan"])
+    ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan", "scan_then_propagate"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (read 1 GiB, write 1 GiB) three times before the timed "
@@ -168,7 +168,7 @@ def main() -> int:
     out_h = torch.empty(n, dtype=torch.float16, device="cuda")
     variant_rows = []
     for e in (8, 12, 16, 20):
-        if e <= args.log2n and args.formulation == "mfma":
+        if e <= args.log2n and args.formulation == "mfma" and args.scan_carry != "scan_then_propagate":
             variant_rows.append((f"segmented_scan_ex seg_len=2^{e} binary16 output (the paper's precision, 4 B/elem)",
                                  (lambda e=e: tcr.segmented_scan_ex(x, 1 << e, tcr.OUT_F16, out=out_h)), n, (2 * n, 2 * n)))
     if args.formulation == "mfma":

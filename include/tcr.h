@@ -105,7 +105,9 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
 /*
  * Bench / test hook: choose among measured alternatives.  Keys and values:
  *   "formulation"  "mfma" (default: matrix-core products) | "dpp" (cross-lane wavefront primitives)
- *   "scan_carry"   "lookback" (default: single pass, decoupled look-back) | "reduce_then_scan"
+ *   "scan_carry"   "lookback" (default: single pass, decoupled look-back) | "reduce_then_scan" |
+ *                  "scan_then_propagate" (the paper's three-kernel device-level scan, Section 5;
+ *                  plain binary32 inclusive scan only)
  *   "reset"        any value: back to the defaults
  * Returns TCR_ERR_INVALID_ARG for an unknown key or value.  Process-wide; not thread safe.
  */

@@ -36,7 +36,7 @@ bool hip_failed(hipError_t e, const char* what) {
 // ---------------------------------------------------------------------------- variant settings
 struct Variant {
     int formulation = kMfma;
-    int scan_carry = kLookback;
+    int scan_carry = kStrategyLookback;
 };
 Variant g_variant;
 
@@ -344,10 +344,34 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
     const uint64_t seg_mask = whole ? ~0ull : seg_len - 1;
     const uint64_t host_seg_len = seg_len;            // decides the launch; the kernels see a saturated
     if (whole) seg_len = ~0ull;                       // length for the one-segment case (n need not be a power of two)
-    const bool table = g_variant.scan_carry == kTable;
+    const bool table = g_variant.scan_carry != kStrategyLookback;     // the two multi-kernel strategies
     if (host_seg_len <= 8192 || (table && host_seg_len <= kCarryTile)) {
         launch_scan_nocarry<FORM, MODE>(in, out, n, seg_mask, seg_len, host_seg_len, s);
         return check_launch("scan_block_kernel");
+    }
+    if (g_variant.scan_carry == kStrategyScanThenPropagate) {
+        // the paper's three kernels; totals are read back from the binary32 inclusive output
+        if (MODE != 0) return TCR_ERR_UNSUPPORTED;
+        const uint64_t shares = ceil_div(n, kCarryTile);
+        Workspace* w = nullptr;
+        tcr_status st = get_workspace(s, &w);
+        if (st != TCR_OK) return st;
+        st = ensure_partials(w, s, shares);
+        if (st != TCR_OK) return st;
+        const ScanWorkspace none = {};
+        float* o = static_cast<float*>(out);
+        launch_scan_block<FORM, kCarryU, kCarryW, kNoCarry, 0>(in, out, n, kCarryTile - 1, kCarryTile, none, nullptr, s);
+        st = check_launch("scan_block_kernel");
+        if (st != TCR_OK) return st;
+        gather_totals_kernel<<<dim3((unsigned)ceil_div(shares, 256)), dim3(256), 0, s>>>(o, w->partials, kCarryTile, shares, n);
+        st = check_launch("gather_totals_kernel");
+        if (st != TCR_OK) return st;
+        const uint64_t per = whole ? shares : host_seg_len / kCarryTile;
+        scan_partials_kernel<<<dim3((unsigned)(whole ? 1 : n / host_seg_len)), dim3(kPartialsThreads), 0, s>>>(w->partials, per);
+        st = check_launch("scan_partials_kernel");
+        if (st != TCR_OK) return st;
+        uniform_add_kernel<<<dim3((unsigned)ceil_div(n, 4096)), dim3(256), 0, s>>>(o, w->partials, kCarryTile, n);
+        return check_launch("uniform_add_kernel");
     }
     const uint64_t tile = table ? kCarryTile : ticketed_tile(host_seg_len, whole);
     const uint64_t tiles = ceil_div(n, tile);
@@ -519,8 +543,9 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
         return TCR_OK;
     }
     if (std::strcmp(key, "scan_carry") == 0) {
-        if (std::strcmp(value, "lookback") == 0) g_variant.scan_carry = kLookback;
-        else if (std::strcmp(value, "reduce_then_scan") == 0) g_variant.scan_carry = kTable;
+        if (std::strcmp(value, "lookback") == 0) g_variant.scan_carry = kStrategyLookback;
+        else if (std::strcmp(value, "reduce_then_scan") == 0) g_variant.scan_carry = kStrategyReduceThenScan;
+        else if (std::strcmp(value, "scan_then_propagate") == 0) g_variant.scan_carry = kStrategyScanThenPropagate;
         else return TCR_ERR_INVALID_ARG;
         return TCR_OK;
     }
@@ -545,9 +570,12 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     }
     if (op == 1 || op == 3) {
         if (!whole && seg_len <= kTile) return mf ? "scan_small_kernel<mfma>" : "scan_small_kernel<dpp>";
-        const bool table = g_variant.scan_carry == kTable;
+        const bool table = g_variant.scan_carry != kStrategyLookback;
         if (seg_len <= 8192 || (table && seg_len <= kCarryTile))
             return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
+        if (g_variant.scan_carry == kStrategyScanThenPropagate)
+            return mf ? "scan_block_kernel<mfma,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel"
+                      : "scan_block_kernel<dpp,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel";
         if (!table && seg_len <= 32768 && !whole) return mf ? "scan_block_kernel<mfma,ticket>" : "scan_block_kernel<dpp,ticket>";
         if (!table) return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";
         return mf ? "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<mfma,table>"

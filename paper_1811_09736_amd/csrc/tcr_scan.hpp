@@ -26,6 +26,9 @@
 namespace tcr {
 
 enum CarryMode { kNoCarry = 0, kLookback = 1, kTable = 2 };
+// Host-side choice of how a carry crosses workgroups: look-back (default), reduce-then-scan
+// (kTable kernels), or the paper's own three-kernel scan-then-propagate.
+enum CarryStrategy { kStrategyLookback = 0, kStrategyReduceThenScan = 1, kStrategyScanThenPropagate = 2 };
 
 // Inclusive scan over aligned groups of GROUP lanes (GROUP up to 64).
 template <int GROUP>
@@ -417,6 +420,38 @@ __global__ __launch_bounds__(kPartialsThreads) void scan_partials_kernel(float* 
         const float v = p[i];
         p[i] = carry;
         carry += v;
+    }
+}
+
+// ------------------------------------------------------------------------------ scan-then-propagate helpers
+// The paper's device-level scan (Section 5): kernel 1 scans every workgroup share on its own,
+// kernel 2 scans the shares' totals, kernel 3 adds the preceding total to every element of a
+// share.  gather_totals_kernel reads the totals off the end of each share after kernel 1;
+// scan_partials_kernel is kernel 2; uniform_add_kernel is kernel 3.
+__global__ __launch_bounds__(256) void gather_totals_kernel(const float* __restrict__ out, float* __restrict__ totals,
+                                                            uint64_t share, uint64_t shares, uint64_t n) {
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= shares) return;
+    const uint64_t end = ((t + 1) * share < n) ? (t + 1) * share : n;
+    totals[t] = out[end - 1];
+}
+
+__global__ __launch_bounds__(256) void uniform_add_kernel(float* __restrict__ out, const float* __restrict__ offsets,
+                                                          uint64_t share, uint64_t n) {
+    // one workgroup per 4096 elements; share is a multiple of 4096
+    const uint64_t base = (uint64_t)blockIdx.x * 4096 + (uint64_t)threadIdx.x * 4;
+    const float add = offsets[((uint64_t)blockIdx.x * 4096) / share];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const uint64_t off = base + (uint64_t)r * 1024;
+        if (off + 4 <= n) {
+            float4v v = *reinterpret_cast<float4v*>(out + off);
+            v += splat(add);
+            *reinterpret_cast<float4v*>(out + off) = v;
+        } else {
+            for (int e = 0; e < 4; ++e)
+                if (off + e < n) out[off + e] += add;
+        }
     }
 }
 

@@ -81,6 +81,8 @@ def test_variant_switch(lib):
         assert "dpp" in lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 20, 256)
         lib.set_variant("scan_carry", "reduce_then_scan")
         assert "table" in lib.kernel_name(lib.OP_SCAN, 1 << 28, 1 << 28)
+        lib.set_variant("scan_carry", "scan_then_propagate")
+        assert "uniform_add_kernel" in lib.kernel_name(lib.OP_SCAN, 1 << 28, 1 << 28)
     finally:
         lib.set_variant("reset")
     assert "mfma" in lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 20, 256)

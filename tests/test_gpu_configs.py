@@ -127,7 +127,7 @@ def test_config4_integer_variants_both_carry_strategies(tcr, oracle):
     x, xd = _input(w.n, w.dist, w.seed)
     ref = oracle.scan(x)
     try:
-        for key, val in (("scan_carry", "reduce_then_scan"), ("formulation", "dpp")):
+        for key, val in (("scan_carry", "reduce_then_scan"), ("scan_carry", "scan_then_propagate"), ("formulation", "dpp")):
             tcr.set_variant("reset")
             tcr.set_variant(key, val)
             _compare(tcr.scan(xd), ref, x, w.n, True, True, False, f"cfg4 {key}={val}")

@@ -208,7 +208,7 @@ def test_last_scan_element_is_the_reduction(tcr, form, seg):
 
 # ------------------------------------------------------------------ cross-workgroup carry
 
-@pytest.mark.parametrize("carry", ["lookback", "reduce_then_scan"])
+@pytest.mark.parametrize("carry", ["lookback", "reduce_then_scan", "scan_then_propagate"])
 def test_carry_strategies_agree_with_oracle(tcr, oracle, form, carry):
     tcr.set_variant("scan_carry", carry)
     for n, seg in (((1 << 21) + 12345, None), (1 << 21, 1 << 16), (3 << 19, 1 << 19)):
