@@ -38,6 +38,8 @@ def main() -> int:
     ap.add_argument("--formulation", default="mfma", choices=["mfma", "dpp"])
     ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan", "scan_then_propagate"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--autotune", action="store_true",
+                    help="let tcr_autotune re-pick the launch shape of every timed call first (default: shipped shapes)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (read 1 GiB, write 1 GiB) three times before the timed "
                          "region, as the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -107,6 +109,12 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.autotune:
+        ids = {"segmented_reduce": tcr.OP_SEGMENTED_REDUCE, "segmented_scan": tcr.OP_SEGMENTED_SCAN}
+        for op, e in calls:
+            tcr.autotune(ids[op], x, out_scan, 1 << e)
+        tcr.autotune(tcr.OP_REDUCE, x, out_scan, 0)
+        tcr.autotune(tcr.OP_SCAN, x, out_scan, 0)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -225,7 +233,7 @@ def main() -> int:
                                "seg_len=2^{%s}; fp32 accumulate and output" % (args.log2n, ",".join(map(str, sweep))),
                    "formulation": args.formulation, "scan_carry": args.scan_carry,
                    "input_sha256": workloads.sha256(x_host)[:16]},
-        "roofline": roofline, "cpu_baseline": cpu, "rows": rows, "context_rows": extra,
+        "roofline": roofline, "cpu_baseline": cpu, "tuning": tcr.tuning_export(), "rows": rows, "context_rows": extra,
     }
     print(json.dumps(line))
     return 0

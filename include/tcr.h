@@ -114,6 +114,23 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
 tcr_status tcr_set_variant(const char *key, const char *value);
 
 /*
+ * Auto-tuning (the paper picks algorithm, wavefronts per workgroup and coarsening per segment size with an
+ * auto-tuner, Section 6).  The library ships with launch shapes frozen from sweeps on MI355X; tcr_autotune
+ * re-times every candidate shape for this (op, n, seg_len) on the caller's buffers -- op: 0 segmented_reduce,
+ * 1 segmented_scan, 2 reduce, 3 scan (seg_len ignored) -- and makes the fastest one the choice for that class
+ * of segment lengths (same log2(seg_len); one class for the one-segment operations) for the rest of the
+ * process.  It SYNCHRONISES the stream, overwrites `out` with (correct) results several times, and is a no-op
+ * for segment lengths with a single shape (below 1024, or not a power of two).  Every shape gives the same
+ * results up to the order of binary32 additions.
+ * tcr_tuning_export writes the current choices as text ("scan:14=7;reduce:20=1;", NUL terminated, truncated
+ * to `capacity`) and returns the size needed; tcr_tuning_import replaces the choices with such a text
+ * (TCR_ERR_INVALID_ARG if it does not parse; the empty string restores the defaults).  Not thread safe.
+ */
+tcr_status tcr_autotune(int op, const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
+uint64_t tcr_tuning_export(char *buffer, uint64_t capacity);
+tcr_status tcr_tuning_import(const char *text);
+
+/*
  * Name of the kernel the dispatcher would launch for (op, n, seg_len) under the current
  * variant settings; op is 0 = segmented_reduce, 1 = segmented_scan, 2 = reduce, 3 = scan.
  * Returns a static string ("" when nothing would be launched); never NULL.

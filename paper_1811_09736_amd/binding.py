@@ -22,7 +22,7 @@ SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
-    "tcr_irregular_reduce", "tcr_irregular_scan",
+    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
     "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
 )
@@ -58,6 +58,12 @@ def _load() -> ctypes.CDLL:
     lib.tcr_scan.argtypes = [vp, fp, u64, vp]
     for name in ("tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan"):
         getattr(lib, name).restype = ctypes.c_int
+    lib.tcr_autotune.argtypes = [ctypes.c_int, vp, fp, u64, u64, vp]
+    lib.tcr_autotune.restype = ctypes.c_int
+    lib.tcr_tuning_export.argtypes = [ctypes.c_char_p, u64]
+    lib.tcr_tuning_export.restype = u64
+    lib.tcr_tuning_import.argtypes = [ctypes.c_char_p]
+    lib.tcr_tuning_import.restype = ctypes.c_int
     lib.tcr_set_variant.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     lib.tcr_set_variant.restype = ctypes.c_int
     lib.tcr_kernel_name.argtypes = [ctypes.c_int, u64, u64]
@@ -227,6 +233,34 @@ def scan(x: torch.Tensor, out: Optional[torch.Tensor] = None,
     if st != OK:
         raise TcrError(st, "tcr_scan")
     return out
+
+
+def autotune(op: int, x: torch.Tensor, out: torch.Tensor, seg_len: int,
+             stream: Optional[torch.cuda.Stream] = None) -> None:
+    """tcr_autotune: time the candidate launch shapes for (op, x.numel(), seg_len) and keep the fastest."""
+    _check_input(x)
+    if not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.device == x.device):
+        raise TypeError("out must be a contiguous float32 CUDA tensor on the input's device")
+    need = x.numel() if op in (OP_SEGMENTED_SCAN, OP_SCAN) else (1 if op == OP_REDUCE else x.numel() // max(seg_len, 1))
+    if out.numel() < need:
+        raise TypeError(f"out needs at least {need} elements")
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_autotune(op, x.data_ptr(), out.data_ptr(), x.numel(), seg_len, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_autotune")
+
+
+def tuning_export() -> str:
+    size = _lib.tcr_tuning_export(None, 0)
+    buf = ctypes.create_string_buffer(int(size))
+    _lib.tcr_tuning_export(buf, size)
+    return buf.value.decode()
+
+
+def tuning_import(text: str) -> None:
+    st = _lib.tcr_tuning_import(text.encode())
+    if st != OK:
+        raise TcrError(st, "tcr_tuning_import")
 
 
 def set_variant(key: str, value: str = "") -> None:

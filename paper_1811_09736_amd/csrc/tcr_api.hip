@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -229,30 +230,69 @@ struct ReducePlan {
     uint64_t nspans;    // wavefronts in total
 };
 
-// seg_len >= 1024 (a power of two), or one segment of any length (whole).
-ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
-    ReducePlan p;
-    if (!whole && seg_len <= kWaveSpanMax) {             // one wavefront per segment
-        p.span = seg_len; p.combine = 1; p.per = 1; p.nspans = n / seg_len;
-        return p;
+// ---------------------------------------------------------------------------- tuning table
+// The paper selects algorithm, wavefronts per workgroup and coarsening per segment size with an
+// auto-tuner (Section 6).  Here the defaults are frozen from sweeps on MI355X; tcr_autotune can
+// re-time the candidates on the machine at hand and override the default for one class of
+// segment lengths (index log2(seg_len), or kWholeClass for the one-segment operations).
+constexpr int kWholeClass = 41;
+signed char g_tuned_scan[kWholeClass + 1];
+signed char g_tuned_reduce[kWholeClass + 1];
+bool g_tuning_initialised = false;
+void init_tuning() {
+    if (g_tuning_initialised) return;
+    std::memset(g_tuned_scan, -1, sizeof(g_tuned_scan));
+    std::memset(g_tuned_reduce, -1, sizeof(g_tuned_reduce));
+    g_tuning_initialised = true;
+}
+int tuning_class(uint64_t seg_len, bool whole) { return whole ? kWholeClass : log2u(seg_len); }
+
+// Reduce candidates for seg_len >= 1024 (power of two) or one segment: (span, combine) pairs.
+struct ReduceShape { uint64_t span; int combine; };
+int reduce_candidates(uint64_t n, uint64_t seg_len, bool whole, ReduceShape* c) {
+    int k = 0;
+    if (!whole && seg_len <= kWaveSpanMax) {
+        c[k++] = {seg_len, 1};                                   // one wavefront per segment
+        if (seg_len >= 8192) c[k++] = {seg_len / 2, 2};
+        if (seg_len >= 16384) c[k++] = {seg_len / 4, 4};
+        return k;
     }
     if (whole) {
-        // enough wavefronts to fill the chip, spans between 4096 and 65536 elements
         uint64_t span = 4096;
         while (span < kWaveSpanMax && n / span > 4096) span <<= 1;
-        p.nspans = ceil_div(n, span);
-        if (p.nspans == 1) {
-            p.span = ceil_div(n, kTile) * kTile; p.combine = 1; p.per = 1;
-        } else {
-            p.span = span; p.combine = kReduceBlockW; p.per = ceil_div(p.nspans, (uint64_t)kReduceBlockW);
+        if (ceil_div(n, span) == 1) {
+            c[k++] = {ceil_div(n, kTile) * kTile, 1};
+            return k;
         }
-        return p;
+        c[k++] = {span, kReduceBlockW};                          // default
+        c[k++] = {span, 1};
+        if (span > 16384) c[k++] = {span / 4, kReduceBlockW};
+        if (span > 32768) c[k++] = {span / 2, kReduceBlockW};
+        return k;
     }
-    // power-of-two segment of 2^17 elements or more: spans of 65536, up to kReduceBlockW per workgroup
-    p.span = kWaveSpanMax;
-    p.combine = (seg_len / p.span >= (uint64_t)kReduceBlockW) ? kReduceBlockW : 2;
-    p.per = seg_len / (p.span * (uint64_t)p.combine);
-    p.nspans = n / p.span;
+    c[k++] = {kWaveSpanMax, (seg_len / kWaveSpanMax >= (uint64_t)kReduceBlockW) ? kReduceBlockW : 2};   // default
+    c[k++] = {kWaveSpanMax, 1};
+    c[k++] = {16384, 4};
+    c[k++] = {32768, 4};
+    return k;
+}
+
+// seg_len >= 1024 (a power of two), or one segment of any length (whole).
+ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
+    init_tuning();
+    ReduceShape cand[4];
+    const int count = reduce_candidates(n, seg_len, whole, cand);
+    int pick = g_tuned_reduce[tuning_class(seg_len, whole)];
+    if (pick < 0 || pick >= count) {
+        // frozen defaults: segments of 8192 .. 32768 elements are split over 2 or 4 wavefronts
+        pick = (whole || seg_len < 8192 || seg_len > 32768) ? 0 : (seg_len == 8192 ? 1 : 2);
+    }
+    ReducePlan p;
+    p.span = cand[pick].span;
+    p.combine = cand[pick].combine;
+    const uint64_t len = whole ? n : seg_len;
+    p.per = ceil_div(len, p.span * (uint64_t)p.combine);
+    p.nspans = whole ? ceil_div(n, p.span) : n / p.span;
     return p;
 }
 
@@ -305,37 +345,67 @@ void launch_scan_block(const _Float16* in, void* out, uint64_t n, uint64_t seg_m
         in, out, n, seg_mask, seg_len, dev, prefix);
 }
 
-// Segments that fit one workgroup: the smallest workgroup share that holds a whole segment.
-template <int FORM, int MODE>
-void launch_scan_nocarry(const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
-                         uint64_t fit, hipStream_t s) {
-    const ScanWorkspace none = {};
-    if (fit <= 1024) launch_scan_block<FORM, 1, 2, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 2048) launch_scan_block<FORM, 1, 4, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 4096) launch_scan_block<FORM, 1, 8, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 8192) launch_scan_block<FORM, 1, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 16384) launch_scan_block<FORM, 2, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else if (fit <= 32768) launch_scan_block<FORM, 4, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
-    else launch_scan_block<FORM, 8, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, none, nullptr, s);
+// Launch shapes of scan_block_kernel.  Ids 0..6 take tiles in blockIdx order and need a whole
+// segment inside one workgroup share; ids 7..9 hand tiles out by ticket (tiles are then processed
+// in the order workgroups actually start, which keeps the tiles in flight contiguous in memory and
+// measured 5-9 % faster for 1024-thread workgroups even without a carry) and chain workgroups
+// through the look-back when a segment is longer than the share.  One ticket costs about 12 ns of
+// a chip-wide serial resource, so ticketed shares start at 16384 elements.
+struct ScanShape { int u, w; bool ticket; };
+constexpr ScanShape kScanShapes[] = {{1, 2, false}, {1, 4, false}, {1, 8, false}, {1, 16, false}, {2, 16, false},
+                                     {4, 16, false}, {8, 16, false}, {2, 16, true}, {4, 16, true}, {8, 16, true}};
+constexpr int kScanShapeCount = 10;
+uint64_t scan_shape_tile(int id) { return (uint64_t)kTile * kScanShapes[id].u * kScanShapes[id].w; }
+
+bool scan_shape_valid(int id, uint64_t len) {      // len: seg_len, or n for the one-segment scan
+    if (id < 0 || id >= kScanShapeCount) return false;
+    return kScanShapes[id].ticket || scan_shape_tile(id) >= len;
 }
 
-// Workgroup share used when tiles are handed out by ticket (segments of 16384 elements and more).
-// Handing tiles out in the order workgroups actually start keeps the set of tiles in flight
-// contiguous in memory, which measured 5-9 % faster than blockIdx order for 1024-thread
-// workgroups even when no carry crosses workgroups; one ticket costs about 12 ns of a serial
-// resource, so it only pays from 16384 elements per workgroup upwards.
+int default_scan_shape(uint64_t len, bool whole) {
+    if (len <= 1024) return 0;
+    if (len <= 2048) return 1;
+    if (len <= 4096) return 2;
+    if (len < 8192 || (whole && len == 8192)) return 3;
+    if (whole || len >= (1u << 20)) return 9;      // 65536-element shares, chained
+    if (len >= 65536) return 8;                    // chained 32768-element shares
+    return len <= 16384 ? 7 : 8;                   // one ticketed share per segment (two segments of 8192)
+}
+
+int pick_scan_shape(uint64_t len, bool whole) {
+    init_tuning();
+    const int tuned = g_tuned_scan[tuning_class(len, whole)];
+    return scan_shape_valid(tuned, len) ? tuned : default_scan_shape(len, whole);
+}
+
 template <int FORM, int CARRY, int MODE>
-void launch_scan_ticketed(const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
-                          uint64_t tile, const ScanWorkspace& dev, const float* prefix, hipStream_t s) {
-    if (tile == 16384) launch_scan_block<FORM, 2, 16, CARRY, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s);
-    else if (tile == 32768) launch_scan_block<FORM, 4, 16, CARRY, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s);
-    else launch_scan_block<FORM, kCarryU, kCarryW, CARRY, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s);
+void launch_scan_shape(int id, const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+                       const ScanWorkspace& dev, const float* prefix, hipStream_t s) {
+    // CARRY is kNoCarry for ids 0..6 and kLookback for ids 7..9
+    if constexpr (CARRY == kNoCarry) {
+        switch (id) {
+            case 0: launch_scan_block<FORM, 1, 2, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            case 1: launch_scan_block<FORM, 1, 4, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            case 2: launch_scan_block<FORM, 1, 8, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            case 3: launch_scan_block<FORM, 1, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            case 4: launch_scan_block<FORM, 2, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            case 5: launch_scan_block<FORM, 4, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            default: launch_scan_block<FORM, 8, 16, kNoCarry, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+        }
+    } else {
+        switch (id) {
+            case 7: launch_scan_block<FORM, 2, 16, kLookback, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            case 8: launch_scan_block<FORM, 4, 16, kLookback, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+            default: launch_scan_block<FORM, 8, 16, kLookback, MODE>(in, out, n, seg_mask, seg_len, dev, prefix, s); break;
+        }
+    }
 }
 
-uint64_t ticketed_tile(uint64_t seg_len, bool whole) {
-    if (whole || seg_len > 65536) return kCarryTile;     // 65536
-    if (seg_len == 65536) return 32768;                  // two chained workgroups per segment
-    return seg_len;                                      // 16384 or 32768: one workgroup per segment
+// Smallest blockIdx-ordered shape that holds `fit` elements (used by the multi-kernel strategies).
+int nocarry_shape_for(uint64_t fit) {
+    for (int id = 0; id < 7; ++id)
+        if (scan_shape_tile(id) >= fit) return id;
+    return 6;
 }
 
 // seg_len >= 1024 (power of two), or the full scan (seg_len == n, any n).
@@ -345,9 +415,33 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
     const uint64_t host_seg_len = seg_len;            // decides the launch; the kernels see a saturated
     if (whole) seg_len = ~0ull;                       // length for the one-segment case (n need not be a power of two)
     const bool table = g_variant.scan_carry != kStrategyLookback;     // the two multi-kernel strategies
-    if (host_seg_len <= 8192 || (table && host_seg_len <= kCarryTile)) {
-        launch_scan_nocarry<FORM, MODE>(in, out, n, seg_mask, seg_len, host_seg_len, s);
+    if (table && host_seg_len <= kCarryTile) {
+        const ScanWorkspace none = {};
+        launch_scan_shape<FORM, kNoCarry, MODE>(nocarry_shape_for(host_seg_len), in, out, n, seg_mask, seg_len, none, nullptr, s);
         return check_launch("scan_block_kernel");
+    }
+    if (!table) {
+        const int shape = pick_scan_shape(host_seg_len, whole);
+        if (!kScanShapes[shape].ticket) {
+            const ScanWorkspace none = {};
+            launch_scan_shape<FORM, kNoCarry, MODE>(shape, in, out, n, seg_mask, seg_len, none, nullptr, s);
+            return check_launch("scan_block_kernel");
+        }
+        const uint64_t tiles = ceil_div(n, scan_shape_tile(shape));
+        ScanWorkspace dev = {};
+        Workspace* ws = nullptr;
+        tcr_status st = get_workspace(s, &ws);
+        if (st != TCR_OK) return st;
+        st = begin_lookback(ws, s, tiles, &dev);
+        if (st != TCR_OK) return st;
+        launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
+        st = check_launch("scan_block_kernel");
+        if (st != TCR_OK) {
+            ws->dirty = true;
+            return st;
+        }
+        ws->tickets_issued += (uint32_t)tiles;      // wraps modulo 2^32 like the device counter
+        return TCR_OK;
     }
     if (g_variant.scan_carry == kStrategyScanThenPropagate) {
         // the paper's three kernels; totals are read back from the binary32 inclusive output
@@ -373,24 +467,11 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
         uniform_add_kernel<<<dim3((unsigned)ceil_div(n, 4096)), dim3(256), 0, s>>>(o, w->partials, kCarryTile, n);
         return check_launch("uniform_add_kernel");
     }
-    const uint64_t tile = table ? kCarryTile : ticketed_tile(host_seg_len, whole);
-    const uint64_t tiles = ceil_div(n, tile);
+    const uint64_t tiles = ceil_div(n, kCarryTile);
     ScanWorkspace dev = {};
     Workspace* ws = nullptr;
     tcr_status st = get_workspace(s, &ws);
     if (st != TCR_OK) return st;
-    if (!table) {
-        st = begin_lookback(ws, s, tiles, &dev);
-        if (st != TCR_OK) return st;
-        launch_scan_ticketed<FORM, kLookback, MODE>(in, out, n, seg_mask, seg_len, tile, dev, nullptr, s);
-        st = check_launch("scan_block_kernel");
-        if (st != TCR_OK) {
-            ws->dirty = true;
-            return st;
-        }
-        ws->tickets_issued += (uint32_t)tiles;      // wraps modulo 2^32 like the device counter
-        return TCR_OK;
-    }
     // reduce-then-scan: workgroup totals, their exclusive scan per segment, then the scan proper
     st = ensure_partials(ws, s, tiles);
     if (st != TCR_OK) return st;
@@ -552,6 +633,108 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
     return TCR_ERR_INVALID_ARG;
 }
 
+namespace {
+
+// Average time of `reps` back-to-back calls of f on stream s, in microseconds (negative on a HIP error).
+template <typename F>
+float time_calls(F f, hipStream_t s, int reps) {
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return -1.0f;
+    float us = -1.0f;
+    if (f() == TCR_OK && hipStreamSynchronize(s) == hipSuccess && hipEventRecord(e0, s) == hipSuccess) {
+        bool ok = true;
+        for (int r = 0; r < reps && ok; ++r) ok = f() == TCR_OK;
+        float ms = 0.0f;
+        if (ok && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+            hipEventElapsedTime(&ms, e0, e1) == hipSuccess)
+            us = ms * 1000.0f / (float)reps;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return us;
+}
+
+}  // namespace
+
+extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
+    if (op < 0 || op > 3) return TCR_ERR_INVALID_ARG;
+    if (op >= 2) seg_len = n;
+    const bool is_scan = (op == 1 || op == 3);
+    tcr_status st = validate(in, out, n, seg_len, is_scan ? 16 : 4);
+    if (st != TCR_OK) return st;
+    if (n == 0) return TCR_OK;
+    const bool whole = seg_len == n;
+    if (!whole && (!is_pow2(seg_len) || seg_len < 1024)) return TCR_OK;       // a single shape: nothing to choose
+    if (whole && n < 1024) return TCR_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    init_tuning();
+    const int cls = tuning_class(seg_len, whole);
+    signed char* slot = is_scan ? &g_tuned_scan[cls] : &g_tuned_reduce[cls];
+    ReduceShape cand[4];
+    const int count = is_scan ? kScanShapeCount : reduce_candidates(n, seg_len, whole, cand);
+    int best = -1;
+    float best_us = 0.0f;
+    for (int id = 0; id < count; ++id) {
+        if (is_scan && !scan_shape_valid(id, seg_len)) continue;
+        if (is_scan && !kScanShapes[id].ticket && scan_shape_tile(id) > 8 * seg_len && !whole) continue;   // far oversized shares
+        *slot = (signed char)id;
+        const float us = time_calls([&]() -> tcr_status {
+            return is_scan ? tcr_segmented_scan(in, out, n, seg_len, stream) : tcr_segmented_reduce(in, out, n, seg_len, stream);
+        }, s, 5);
+        if (us < 0.0f) {
+            *slot = -1;
+            return TCR_ERR_HIP;
+        }
+        if (best < 0 || us < best_us) {
+            best = id;
+            best_us = us;
+        }
+    }
+    *slot = (signed char)best;
+    return TCR_OK;
+}
+
+extern "C" uint64_t tcr_tuning_export(char* buffer, uint64_t capacity) {
+    init_tuning();
+    std::string text;
+    for (int c = 0; c <= kWholeClass; ++c) {
+        if (g_tuned_scan[c] >= 0) text += "scan:" + std::to_string(c) + "=" + std::to_string((int)g_tuned_scan[c]) + ";";
+        if (g_tuned_reduce[c] >= 0) text += "reduce:" + std::to_string(c) + "=" + std::to_string((int)g_tuned_reduce[c]) + ";";
+    }
+    if (buffer != nullptr && capacity > 0) {
+        const uint64_t m = text.size() < capacity - 1 ? text.size() : capacity - 1;
+        std::memcpy(buffer, text.data(), m);
+        buffer[m] = '\0';
+    }
+    return text.size() + 1;
+}
+
+extern "C" tcr_status tcr_tuning_import(const char* text) {
+    if (text == nullptr) return TCR_ERR_INVALID_ARG;
+    signed char scan[kWholeClass + 1], reduce[kWholeClass + 1];
+    std::memset(scan, -1, sizeof(scan));
+    std::memset(reduce, -1, sizeof(reduce));
+    const char* p = text;
+    while (*p != '\0') {
+        const bool is_scan = std::strncmp(p, "scan:", 5) == 0;
+        const bool is_reduce = std::strncmp(p, "reduce:", 7) == 0;
+        if (!is_scan && !is_reduce) return TCR_ERR_INVALID_ARG;
+        p += is_scan ? 5 : 7;
+        char* end = nullptr;
+        const long cls = std::strtol(p, &end, 10);
+        if (end == p || *end != '=' || cls < 0 || cls > kWholeClass) return TCR_ERR_INVALID_ARG;
+        p = end + 1;
+        const long id = std::strtol(p, &end, 10);
+        if (end == p || *end != ';' || id < 0 || id >= (is_scan ? kScanShapeCount : 4)) return TCR_ERR_INVALID_ARG;
+        p = end + 1;
+        (is_scan ? scan : reduce)[cls] = (signed char)id;
+    }
+    init_tuning();
+    std::memcpy(g_tuned_scan, scan, sizeof(scan));
+    std::memcpy(g_tuned_reduce, reduce, sizeof(reduce));
+    return TCR_OK;
+}
+
 extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     if (op == 2 || op == 3) seg_len = n;
     if (n == 0 || seg_len == 0 || n % seg_len != 0) return "";
@@ -571,13 +754,17 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     if (op == 1 || op == 3) {
         if (!whole && seg_len <= kTile) return mf ? "scan_small_kernel<mfma>" : "scan_small_kernel<dpp>";
         const bool table = g_variant.scan_carry != kStrategyLookback;
-        if (seg_len <= 8192 || (table && seg_len <= kCarryTile))
+        if (table && seg_len <= kCarryTile)
             return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
         if (g_variant.scan_carry == kStrategyScanThenPropagate)
             return mf ? "scan_block_kernel<mfma,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel"
                       : "scan_block_kernel<dpp,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel";
-        if (!table && seg_len <= 32768 && !whole) return mf ? "scan_block_kernel<mfma,ticket>" : "scan_block_kernel<dpp,ticket>";
-        if (!table) return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";
+        if (!table) {
+            const int shape = pick_scan_shape(seg_len, whole);
+            if (!kScanShapes[shape].ticket) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
+            if (scan_shape_tile(shape) >= seg_len) return mf ? "scan_block_kernel<mfma,ticket>" : "scan_block_kernel<dpp,ticket>";
+            return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";
+        }
         return mf ? "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<mfma,table>"
                   : "reduce_span_kernel+scan_partials_kernel+scan_block_kernel<dpp,table>";
     }

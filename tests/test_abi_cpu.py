@@ -95,11 +95,13 @@ def test_dispatch_by_segment_length(lib):
     for e in range(4, 10):
         assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e).startswith("reduce_small_kernel")
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e).startswith("scan_small_kernel")
-    for e in (10, 12, 14, 16):
+    for e in (10, 12, 16):
         assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma,wave>"
-    for e in (10, 12, 13):
+    for e in (13, 14, 15):                                 # segments split over 2 or 4 wavefronts of a workgroup
+        assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma,block>"
+    for e in (10, 11, 12):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,nocarry>"
-    for e in (14, 15):
+    for e in (13, 14, 15):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,ticket>"
     assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,block>"
@@ -110,7 +112,31 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_REDUCE, 1000, 1000) == "reduce_span_kernel<mfma,wave>"
     assert k(lib.OP_SCAN, n, n) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
+    assert k(lib.OP_SCAN, 8192, 8192) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "generic_thread_kernel"     # untuned lengths
     assert k(lib.OP_SEGMENTED_REDUCE, 3 << 20, 3 << 10) == "generic_wave_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, n, 3) == ""           # 3 does not divide n: the call reports an invalid argument
     assert k(lib.OP_SEGMENTED_SCAN, 0, 16) == ""
+
+
+def test_tuning_table_text_round_trip(lib):
+    assert lib.tuning_export() == ""
+    try:
+        lib.tuning_import("scan:14=8;reduce:20=1;scan:41=9;")
+        assert lib.tuning_export() == "scan:14=8;reduce:20=1;scan:41=9;"
+        # the dispatcher follows the table where the choice is valid for the segment length ...
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
+        lib.tuning_import("scan:14=4;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,nocarry>"
+        lib.tuning_import("reduce:20=1;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == "reduce_span_kernel<mfma,wave>"
+        # ... and ignores a shape whose share cannot hold the segment
+        lib.tuning_import("scan:16=0;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 16) == "scan_block_kernel<mfma,lookback>"
+        for bad in ("scan:14", "scan:99=1;", "scan:14=10;", "reduce:20=4;", "sort:3=1;", "scan:14=8"):
+            with pytest.raises(lib.TcrError):
+                lib.tuning_import(bad)
+        assert lib.tuning_export() == "scan:16=0;"       # a rejected text leaves the table untouched
+    finally:
+        lib.tuning_import("")
+    assert lib.tuning_export() == ""
