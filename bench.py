@@ -182,6 +182,9 @@ def main() -> int:
     if args.formulation == "mfma":
         variant_rows.append(("segmented_scan_ex seg_len=2^12 exclusive",
                              lambda: tcr.segmented_scan_ex(x, 1 << 12, tcr.SCAN_EXCLUSIVE, out=out_scan), n, (2 * n, 4 * n)))
+    out_r4 = torch.empty(n // 16, dtype=torch.float32, device="cuda")
+    variant_rows.append(("segmented_reduce seg_len=2^4 called back to back (in the step it follows a 1 GiB scan output "
+                         "whose write-back it overlaps)", lambda: tcr.segmented_reduce(x, 16, out=out_r4), n, (2 * n, n // 4)))
     for label, fn, nn, rd_wr in variant_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),

@@ -24,6 +24,9 @@
  *   The library keeps one small workspace per (device, stream), grown on demand by the first
  *   call that needs it; calls issued on one stream are ordered by the stream.  Calls that
  *   share a stream from several host threads must be serialised by the caller.
+ *   HIP graphs: calls that use no workspace (scans with seg_len <= 4096, reduces with seg_len <= 262144, the
+ *   untuned and irregular kernels; default variant and tuning) may be recorded into a graph; a call that needs
+ *   the workspace returns TCR_ERR_UNSUPPORTED while its stream is capturing and records nothing.
  *   There is no CPU fallback: without a usable HIP device every call returns TCR_ERR_HIP.
  */
 #ifndef TCR_H

@@ -99,7 +99,13 @@ tcr_status acquire_table(int device, uint64_t tiles, unsigned long long** ptr, u
     return TCR_OK;
 }
 
+// Every call that needs library-owned memory comes through here.  Such calls cannot be recorded into a
+// HIP graph: they may allocate, and the look-back epoch and ticket base are host-side counters passed as
+// kernel arguments, which a replayed graph would repeat.
 tcr_status get_workspace(hipStream_t stream, Workspace** out) {
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    TCR_HIP(hipStreamIsCapturing(stream, &capture));
+    if (capture != hipStreamCaptureStatusNone) return TCR_ERR_UNSUPPORTED;
     int dev = 0;
     TCR_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
