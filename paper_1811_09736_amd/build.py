@@ -13,6 +13,9 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-function", "-Wno-unknown-cuda-version",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # every atomic add here is a one-lane ticket draw; the wave-level atomic optimiser would wrap it in a
+    # cross-lane reduction whose read-back waits for the result at once instead of where it is used
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

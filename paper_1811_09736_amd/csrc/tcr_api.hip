@@ -357,15 +357,34 @@ void launch_scan_block(const _Float16* in, void* out, uint64_t n, uint64_t seg_m
 // measured 5-9 % faster for 1024-thread workgroups even without a carry) and chain workgroups
 // through the look-back when a segment is longer than the share.  One ticket costs about 12 ns of
 // a chip-wide serial resource, so ticketed shares start at 16384 elements.
-struct ScanShape { int u, w; bool ticket; };
-constexpr ScanShape kScanShapes[] = {{1, 2, false}, {1, 4, false}, {1, 8, false}, {1, 16, false}, {2, 16, false},
-                                     {4, 16, false}, {8, 16, false}, {2, 16, true}, {4, 16, true}, {8, 16, true}};
-constexpr int kScanShapeCount = 10;
+// Ids 10 and 11 are scan_chain_kernel: persistent workgroups (one per compute unit) that take
+// tiles by ticket in a loop and load the next tile while they look back for the current one; for
+// segments longer than the share (or the one-segment scan), matrix-core formulation only.
+struct ScanShape { int u, w; bool ticket; int persistent; };      // persistent: workgroups per compute unit (0: one per tile)
+constexpr ScanShape kScanShapes[] = {{1, 2, false, 0}, {1, 4, false, 0}, {1, 8, false, 0}, {1, 16, false, 0},
+                                     {2, 16, false, 0}, {4, 16, false, 0}, {8, 16, false, 0}, {2, 16, true, 0},
+                                     {4, 16, true, 0}, {8, 16, true, 0}, {4, 16, true, 1}, {8, 8, true, 1}};
+constexpr int kScanShapeCount = 12;
 uint64_t scan_shape_tile(int id) { return (uint64_t)kTile * kScanShapes[id].u * kScanShapes[id].w; }
 
-bool scan_shape_valid(int id, uint64_t len) {      // len: seg_len, or n for the one-segment scan
+bool scan_shape_valid(int id, uint64_t len, bool whole) {      // len: seg_len, or n for the one-segment scan
     if (id < 0 || id >= kScanShapeCount) return false;
+    if (kScanShapes[id].persistent)                             // (whole: len == n, which must be a multiple of 8)
+        return g_variant.formulation == kMfma && (whole ? len % 8 == 0 : len >= scan_shape_tile(id));
     return kScanShapes[id].ticket || scan_shape_tile(id) >= len;
+}
+
+// Compute units of the current device (cached per device id).
+int compute_units() {
+    static int cached[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int cu = 0;
+        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) cu = 256;
+        cached[dev] = cu;
+    }
+    return cached[dev];
 }
 
 int default_scan_shape(uint64_t len, bool whole) {
@@ -373,15 +392,16 @@ int default_scan_shape(uint64_t len, bool whole) {
     if (len <= 2048) return 1;
     if (len <= 4096) return 2;
     if (len < 8192 || (whole && len == 8192)) return 3;
-    if (whole || len >= (1u << 20)) return 9;      // 65536-element shares, chained
-    if (len >= 65536) return 8;                    // chained 32768-element shares
-    return len <= 16384 ? 7 : 8;                   // one ticketed share per segment (two segments of 8192)
+    if (!whole && len <= 16384) return 7;          // one ticketed share per segment (two segments of 8192)
+    if (scan_shape_valid(10, len, whole)) return 10;   // the pipelined chain: segments of 32768 and more, one segment
+    // another formulation, or n not a multiple of 8: scan_block_kernel shares of 65536 / 32768 elements
+    return (whole || len >= (1u << 20)) ? 9 : 8;
 }
 
 int pick_scan_shape(uint64_t len, bool whole) {
     init_tuning();
     const int tuned = g_tuned_scan[tuning_class(len, whole)];
-    return scan_shape_valid(tuned, len) ? tuned : default_scan_shape(len, whole);
+    return scan_shape_valid(tuned, len, whole) ? tuned : default_scan_shape(len, whole);
 }
 
 template <int FORM, int CARRY, int MODE>
@@ -440,13 +460,26 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
         if (st != TCR_OK) return st;
         st = begin_lookback(ws, s, tiles, &dev);
         if (st != TCR_OK) return st;
-        launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
+        uint64_t tickets = tiles;
+        if constexpr (FORM == kMfma) {
+            if (kScanShapes[shape].persistent) {
+                const uint64_t resident = (uint64_t)compute_units() * (uint64_t)kScanShapes[shape].persistent;
+                const uint64_t groups = tiles < resident ? tiles : resident;
+                const dim3 grid((unsigned)groups);
+                if (shape == 10)
+                    scan_chain_kernel<4, 16, MODE><<<grid, dim3(16 * kWave), 0, s>>>(in, out, n, seg_mask, dev, (uint32_t)tiles);
+                else
+                    scan_chain_kernel<8, 8, MODE><<<grid, dim3(8 * kWave), 0, s>>>(in, out, n, seg_mask, dev, (uint32_t)tiles);
+                tickets = tiles + 3 * groups;           // three drawn at the start of every workgroup, one per tile
+            }
+        }
+        if (tickets == tiles) launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
         st = check_launch("scan_block_kernel");
         if (st != TCR_OK) {
             ws->dirty = true;
             return st;
         }
-        ws->tickets_issued += (uint32_t)tiles;      // wraps modulo 2^32 like the device counter
+        ws->tickets_issued += (uint32_t)tickets;    // wraps modulo 2^32 like the device counter
         return TCR_OK;
     }
     if (g_variant.scan_carry == kStrategyScanThenPropagate) {
@@ -681,7 +714,7 @@ extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t 
     int best = -1;
     float best_us = 0.0f;
     for (int id = 0; id < count; ++id) {
-        if (is_scan && !scan_shape_valid(id, seg_len)) continue;
+        if (is_scan && !scan_shape_valid(id, seg_len, whole)) continue;
         if (is_scan && !kScanShapes[id].ticket && scan_shape_tile(id) > 8 * seg_len && !whole) continue;   // far oversized shares
         *slot = (signed char)id;
         const float us = time_calls([&]() -> tcr_status {
@@ -767,6 +800,7 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
                       : "scan_block_kernel<dpp,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel";
         if (!table) {
             const int shape = pick_scan_shape(seg_len, whole);
+            if (kScanShapes[shape].persistent) return "scan_chain_kernel<mfma>";
             if (!kScanShapes[shape].ticket) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
             if (scan_shape_tile(shape) >= seg_len) return mf ? "scan_block_kernel<mfma,ticket>" : "scan_block_kernel<dpp,ticket>";
             return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";

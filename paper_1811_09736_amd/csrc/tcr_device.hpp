@@ -182,6 +182,30 @@ __device__ __forceinline__ void store4(float* __restrict__ out, uint64_t off, fl
     *reinterpret_cast<float4v*>(out + off) = v;
 }
 
+// Raw buffer resource over [ptr, ptr + bytes).  The hardware range check makes loads beyond `bytes`
+// return zero and drops stores beyond it, so a ragged tile needs no branch around its memory
+// instructions (a branch there would also defeat the compiler's counting of outstanding loads and
+// stores, which the pipelined scan relies on).  Offsets are in bytes; `bytes` < 2^32.
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* ptr, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(ptr), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ half8 buffer_load8(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+    return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+}
+// Four consecutive results of one lane at element `elem` of the resource, binary32 or binary16.
+template <int F16>
+__device__ __forceinline__ void buffer_store4_t(__amdgpu_buffer_rsrc_t r, uint32_t elem, float4v v) {
+    if constexpr (F16) {
+        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+        const h4 h = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uint2v, h), r, (int)(elem * 2u), 0, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4v, v), r, (int)(elem * 4u), 0, 0);
+    }
+}
+
 // Output in binary32 (F16 = 0) or rounded to binary16 (F16 = 1, the paper's own output precision):
 // four consecutive results of one lane, `off` counted in elements.
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));

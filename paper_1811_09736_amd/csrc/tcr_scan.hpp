@@ -214,7 +214,7 @@ __device__ __forceinline__ unsigned long long load_descriptor(const unsigned lon
 // 64-wide read per tile adds ~6 ns per tile to the launch, and wider windows only add to it), so
 // the window is kept as narrow as the distance to the nearest finished prefix allows.
 template <int WIN>
-__device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint64_t pos,
+__device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint32_t pos,
                                                            float total, int lane) {
     static_assert(WIN >= 1 && WIN <= kWave, "");
     if (pos == 0) {
@@ -228,10 +228,10 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
                            __HIP_MEMORY_SCOPE_AGENT);
     constexpr int kNone = 1 << 30;
     float acc = 0.0f;
-    uint64_t base = 0;                           // this round inspects distances base+1 .. base+WIN
+    uint32_t base = 0;                           // this round inspects distances base+1 .. base+WIN
     while (true) {
         const bool in_window = lane < WIN;
-        const bool valid = in_window && base + 1 + (uint64_t)lane <= pos;    // not past the segment's first tile
+        const bool valid = in_window && base + 1u + (uint32_t)lane <= pos;   // not past the segment's first tile
         // slots past the segment start act as "prefix 0"; lanes outside the window as "aggregate 0"
         uint32_t status = in_window ? kStatusPrefix : kStatusAggregate;
         float value = 0.0f;
@@ -240,7 +240,7 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
         int polls = 0;
         while (true) {
             if (!ready) {
-                const uint32_t dist = (uint32_t)base + 1u + (uint32_t)lane;
+                const uint32_t dist = base + 1u + (uint32_t)lane;
                 const unsigned long long d = load_descriptor(&ws.desc[tile - dist]);
                 const uint32_t tag = (uint32_t)(d >> 32);
                 if ((tag >> 2) == ws.epoch && (tag & 3u) != 0u) {
@@ -261,7 +261,7 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
         }
         acc += wave_sum((ready && lane <= nearest) ? value : 0.0f);
         if (nearest != kNone) break;
-        base += (uint64_t)WIN;
+        base += (uint32_t)WIN;
     }
     if (lane == 0)
         __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, acc + total), __ATOMIC_RELAXED,
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
                     float total = 0.0f;
 #pragma unroll
                     for (int w = 0; w < WAVES; ++w) total += s_wave_total[w];
-                    const uint64_t pos = (block_base & seg_mask) / kBlockTile;
+                    const uint32_t pos = (uint32_t)((block_base & seg_mask) / kBlockTile);
                     const float pre = lookback_exclusive_prefix<LBK>(ws, tile, pos, total, id.lane);
                     if (id.lane == 0) s_prefix = pre;
                 }
@@ -395,6 +395,251 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
             store4_guarded_t<F16>(out, off_lo, n, lo);
             store4_guarded_t<F16>(out, off_hi, n, hi);
         }
+    }
+}
+
+// ------------------------------------------------------------------------------ long segments, pipelined
+// scan_chain_kernel: the single-pass chained scan as a persistent, software-pipelined loop (matrix
+// cores only).  One workgroup per compute unit draws tiles by ticket and holds three at a time, each in
+// registers of its own:
+//     C  just drawn: its loads are issued first thing in a step,
+//     B  loaded a step ago: its totals are computed and its aggregate PUBLISHED next,
+//     A  published a step ago: its carry is looked up, its results are computed and stored.
+// Why three stages.  scan_block_kernel leaves a compute unit with nothing in flight while a tile waits for
+// its carry (one descriptor round trip per tile).  Persistent workgroups move in step, one tile each per
+// "generation", so with two stages every tile would wait for the slowest aggregate of its whole
+// generation in every step.  Publishing a tile's aggregate a full step before its carry is looked up
+// removes the wait: by then the aggregates of all lower tiles have been visible for a step.
+// The carry of a tile is the inclusive prefix of the workgroup's OWN previous tile plus the aggregates of
+// the tiles in between (about one per workgroup, read in one round trip, see chain_sum_totals); no tile
+// waits for another tile's prefix, and only aggregates are published.
+// Loads are always issued before the stores of the same step: a wavefront's memory operations complete
+// in issue order, so data requested after stores could not be used before those stores have drained.
+// All bulk loads and stores go through range-checked buffer resources and are unconditional, which lets
+// the compiler count outstanding operations exactly instead of draining them at every branch.
+// Tickets: three draws at the start of a workgroup (spaced out, see the kernel) and one per finished
+// tile, so a launch of G workgroups over T tiles draws exactly T + 3G tickets.
+// Progress: a tile waits only for aggregates of lower tickets.  Each of those is held by a running
+// workgroup, which publishes it after finishing at most two tiles with still lower tickets; so the
+// lowest unfinished ticket can always complete.
+// seg_len >= one workgroup's share or seg_len == n; n % 8 == 0.
+
+// Executed by one whole wavefront: the sum of the published totals of tiles lo .. tile-1, read up to
+// four per lane per round trip.
+__device__ __forceinline__ float chain_sum_totals(const ScanWorkspace& ws, uint32_t lo, uint32_t tile, int lane) {
+    float acc = 0.0f;
+    uint32_t hi = tile;                                  // tiles lo .. hi-1 are still to be added
+    while (hi > lo) {
+        const uint32_t span = (hi - lo > 256u) ? 256u : hi - lo;
+        float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        bool need[4];
+        uint32_t idx[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            need[q] = (uint32_t)(lane + 64 * q) < span;
+            // slots beyond the span read this tile's own word, so all four reads are issued
+            // unconditionally, travel together and are waited for once
+            idx[q] = need[q] ? hi - 1u - (uint32_t)(lane + 64 * q) : tile;
+        }
+        const uint32_t want = ws.epoch * 4u + kStatusAggregate;
+        int polls = 0;
+        while (true) {
+            unsigned long long d[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) d[q] = load_descriptor(&ws.desc[idx[q]]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (need[q] && (uint32_t)(d[q] >> 32) == want) {
+                    v[q] = __builtin_bit_cast(float, (uint32_t)d[q]);
+                    need[q] = false;
+                }
+            }
+            if (__ballot(need[0] || need[1] || need[2] || need[3]) == 0ull) break;
+            if (++polls > kSpinLimit) {                  // should be unreachable: predecessors hold earlier tickets
+                if (lane == 0) __hip_atomic_store(ws.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        acc += wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+        hi -= span;
+    }
+    return acc;
+}
+
+struct ChainShared {
+    float wave_total[16];
+    float prefix;
+    uint32_t ticket;
+};
+
+// One held tile, as seen by one wavefront.
+template <int U>
+struct ChainTile {
+    half8 x[U];          // the wavefront's share of the tile
+    float pre[U];        // per lane: carry inside the wavefront's share in front of the lane's row of tile u
+    float ext;           // total of the lower wavefronts of the workgroup
+    float total;         // wavefront 0: total of the tile
+    uint32_t tile;       // ticket; >= tiles: nothing to do
+};
+
+// Stage C: request the data of ticket `tile`.
+template <int U, int WAVES>
+__device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const _Float16* __restrict__ in, uint64_t n,
+                                           uint32_t tiles, const LaneId& id, int wave) {
+    constexpr uint32_t kChunk = (uint32_t)kTile * U;
+    constexpr uint64_t kBlockTile = (uint64_t)kChunk * WAVES;
+    t.tile = tile;
+    // elements of the wavefront's share that lie inside the array (none for a ticket past the last tile)
+    const uint64_t base = (uint64_t)tile * kBlockTile + (uint64_t)wave * kChunk;
+    const uint64_t left = (tile < tiles && base < n) ? n - base : 0;
+    const uint32_t count = left < kChunk ? (uint32_t)left : kChunk;
+    const __amdgpu_buffer_rsrc_t src = make_rsrc(in + (count ? base : 0), count * 2u);
+#pragma unroll
+    for (int u = 0; u < U; ++u) t.x[u] = buffer_load8(src, (uint32_t)(kTile * u + kRow * id.j + 8 * id.g) * 2u);
+}
+
+// Stage B: totals of the tile, carries inside the workgroup, aggregate published.  Contains one barrier,
+// executed also for a ticket past the last tile.
+template <int U, int WAVES>
+__device__ __forceinline__ void chain_publish(ChainTile<U>& t, const ScanWorkspace& ws, uint32_t tiles, ChainShared& sh,
+                                              const LaneId& id, int wave) {
+    float run = 0.0f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float4v tot = mfma(const_ones(), t.x[u], splat(0.0f));
+        const float incl = row_scan_inclusive<16>(tot[0], id.j);
+        t.pre[u] = row_shr<1>(incl) + run;
+        asm volatile("" : "+v"(t.pre[u]));        // keep the sum here: sunk to its use it costs a second register per tile
+        run += read_lane(incl, 15);
+    }
+    if (id.lane == 0) sh.wave_total[wave] = run;
+    __syncthreads();
+    float ext = 0.0f;
+    for (int w = 0; w < wave; ++w) ext += sh.wave_total[w];
+    t.ext = ext;
+    if (wave == 0) {
+        float total = 0.0f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) total += sh.wave_total[w];
+        t.total = total;
+        if (id.lane == 0 && t.tile < tiles)
+            __hip_atomic_store(&ws.desc[t.tile], pack_desc(ws.epoch, kStatusAggregate, total), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Stage A: carry from the earlier tiles of the segment, results, stores.  Returns a freshly drawn ticket.
+// own_end / own_incl (wavefront 0): index after the tile this workgroup finished last (0: none yet) and
+// that tile's inclusive prefix.
+template <int U, int WAVES, int MODE>
+__device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restrict__ out, uint64_t n, uint64_t seg_mask,
+                                                 const ScanWorkspace& ws, ChainShared& sh, const LaneId& id, int wave,
+                                                 uint32_t& own_end, float& own_incl) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
+    constexpr uint32_t kChunk = (uint32_t)kTile * U;
+    constexpr uint64_t kBlockTile = (uint64_t)kChunk * WAVES;
+    const uint64_t block_base = (uint64_t)t.tile * kBlockTile;
+    const uint64_t base = block_base + (uint64_t)wave * kChunk;
+    if (wave == 0) {
+        uint32_t drawn = 0u;                      // used only after the reads below, so the draw rides along with them
+        if (id.lane == 0) drawn = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t seg_first = t.tile - (uint32_t)((block_base & seg_mask) / kBlockTile);   // first tile of the segment
+        const bool resume = own_end > seg_first;  // the workgroup's previous tile lies in the same segment
+        float before = chain_sum_totals(ws, resume ? own_end : seg_first, t.tile, id.lane);
+        if (resume) before += own_incl;
+        own_end = t.tile + 1u;
+        own_incl = before + t.total;
+        // The reads above have drained this wavefront's memory operations (or, with nothing to read, this
+        // does); saying so explicitly keeps the pending ticket draw from counting, after the branch
+        // rejoins, as a pending write to a register in all wavefronts.
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+        if (id.lane == 0) {
+            sh.prefix = before;
+            sh.ticket = drawn - ws.ticket_base;
+        }
+    }
+    __syncthreads();
+    const float ext = t.ext + sh.prefix;
+    const uint32_t fresh = __builtin_amdgcn_readfirstlane(sh.ticket);
+
+    const uint64_t left = base < n ? n - base : 0;
+    const uint32_t count = left < kChunk ? (uint32_t)left : kChunk;
+    const __amdgpu_buffer_rsrc_t dst =
+        make_rsrc(static_cast<char*>(out) + (count ? base : 0) * (F16 ? 2u : 4u), count * (F16 ? 2u : 4u));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float carry = t.pre[u] + ext;
+        const float4v lo = mfma(const_tri_lo<EXCL>(id), t.x[u], splat(carry));
+        const float4v hi = mfma(const_tri_hi<EXCL>(id), t.x[u], splat(carry));
+        const uint32_t elem = (uint32_t)(kTile * u + kRow * id.j + 4 * id.g);
+        buffer_store4_t<F16>(dst, elem, lo);
+        buffer_store4_t<F16>(dst, elem + 16u, hi);
+    }
+    return fresh;
+}
+
+template <int U, int WAVES, int MODE>
+__global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float16* __restrict__ in,
+                                                                   void* __restrict__ out, uint64_t n,
+                                                                   uint64_t seg_mask, ScanWorkspace ws,
+                                                                   uint32_t tiles) {
+    static_assert(WAVES <= 16, "");
+    __shared__ ChainShared sh;
+    __shared__ uint32_t s_draw;
+
+    const LaneId id;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // The three start-up draws are spaced out (each follows work on the previous ticket): drawn back to
+    // back, workgroup i would hold tiles 3i .. 3i+2 and every workgroup's first tile would wait for
+    // aggregates its neighbour publishes two steps later -- the launch would start as a chain of
+    // workgroups a step apart.  Spaced out, the first draws of all workgroups come before the second ones.
+    if (threadIdx.x == 0)
+        s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+    __syncthreads();
+    const uint32_t first = __builtin_amdgcn_readfirstlane(s_draw);
+    if (first >= tiles) {
+        // keeps the number of tickets drawn per launch fixed: three per workgroup plus one per tile
+        if (threadIdx.x == 0) {
+            __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        return;
+    }
+    ChainTile<U> a, b, c;
+    chain_load<U, WAVES>(a, first, in, n, tiles, id, wave);
+    __syncthreads();                              // s_draw has been read by everyone
+    if (threadIdx.x == 0)
+        s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+    __syncthreads();
+    const uint32_t second = __builtin_amdgcn_readfirstlane(s_draw);
+    chain_load<U, WAVES>(b, second, in, n, tiles, id, wave);
+    chain_publish<U, WAVES>(a, ws, tiles, sh, id, wave);          // (its barrier also orders the reads of s_draw)
+    if (threadIdx.x == 0)
+        s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+    __syncthreads();
+    uint32_t fresh = __builtin_amdgcn_readfirstlane(s_draw);
+    // Everything requested so far is waited for here, once: entering the loop with loads pending would make
+    // the compiler assume, on every trip, that nothing was issued after them and wait for the stores as well.
+    __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0), other counters untouched
+
+    uint32_t own_end = 0u;
+    float own_incl = 0.0f;
+    // three tiles per trip, the register sets rotating through the stages, so no tile is ever copied between
+    // registers (a copy would have to wait for the loads it copies, and with them for the stores before)
+    while (true) {
+        chain_load<U, WAVES>(c, fresh, in, n, tiles, id, wave);
+        chain_publish<U, WAVES>(b, ws, tiles, sh, id, wave);
+        fresh = chain_finish<U, WAVES, MODE>(a, out, n, seg_mask, ws, sh, id, wave, own_end, own_incl);
+        if (b.tile >= tiles) break;
+        chain_load<U, WAVES>(a, fresh, in, n, tiles, id, wave);
+        chain_publish<U, WAVES>(c, ws, tiles, sh, id, wave);
+        fresh = chain_finish<U, WAVES, MODE>(b, out, n, seg_mask, ws, sh, id, wave, own_end, own_incl);
+        if (c.tile >= tiles) break;
+        chain_load<U, WAVES>(b, fresh, in, n, tiles, id, wave);
+        chain_publish<U, WAVES>(a, ws, tiles, sh, id, wave);
+        fresh = chain_finish<U, WAVES, MODE>(c, out, n, seg_mask, ws, sh, id, wave, own_end, own_incl);
+        if (a.tile >= tiles) break;
     }
 }
 

@@ -86,7 +86,7 @@ def test_variant_switch(lib):
     finally:
         lib.set_variant("reset")
     assert "mfma" in lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 20, 256)
-    assert "lookback" in lib.kernel_name(lib.OP_SCAN, 1 << 28, 1 << 28)
+    assert lib.kernel_name(lib.OP_SCAN, 1 << 28, 1 << 28) == "scan_chain_kernel<mfma>"
 
 
 def test_dispatch_by_segment_length(lib):
@@ -101,16 +101,24 @@ def test_dispatch_by_segment_length(lib):
         assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << e) == "reduce_span_kernel<mfma,block>"
     for e in (10, 11, 12):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,nocarry>"
-    for e in (13, 14, 15):
+    for e in (13, 14):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,ticket>"
-    assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_block_kernel<mfma,lookback>"
+    for e in (15, 16, 20, 24):                             # the persistent, pipelined chain
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_chain_kernel<mfma>"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,block>"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20).endswith("block>+reduce_final_kernel")
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 24).endswith("+reduce_final_kernel")
-    assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 20) == "scan_block_kernel<mfma,lookback>"
     assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
     assert k(lib.OP_REDUCE, 1000, 1000) == "reduce_span_kernel<mfma,wave>"
-    assert k(lib.OP_SCAN, n, n) == "scan_block_kernel<mfma,lookback>"
+    assert k(lib.OP_SCAN, n, n) == "scan_chain_kernel<mfma>"
+    assert k(lib.OP_SCAN, n - 3, n - 3) == "scan_block_kernel<mfma,lookback>"      # n not a multiple of 8
+    lib.set_variant("formulation", "dpp")
+    try:
+        assert k(lib.OP_SCAN, n, n) == "scan_block_kernel<dpp,lookback>"
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_block_kernel<dpp,lookback>"
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 15) == "scan_block_kernel<dpp,ticket>"
+    finally:
+        lib.set_variant("reset")
     assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SCAN, 8192, 8192) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "generic_thread_kernel"     # untuned lengths
@@ -132,8 +140,12 @@ def test_tuning_table_text_round_trip(lib):
         assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == "reduce_span_kernel<mfma,wave>"
         # ... and ignores a shape whose share cannot hold the segment
         lib.tuning_import("scan:16=0;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 16) == "scan_chain_kernel<mfma>"
+        lib.tuning_import("scan:16=8;scan:14=10;")           # the pipelined shapes need a segment of a whole share at least
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 16) == "scan_block_kernel<mfma,lookback>"
-        for bad in ("scan:14", "scan:99=1;", "scan:14=10;", "reduce:20=4;", "sort:3=1;", "scan:14=8"):
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
+        lib.tuning_import("scan:16=0;")
+        for bad in ("scan:14", "scan:99=1;", "scan:14=12;", "reduce:20=4;", "sort:3=1;", "scan:14=8"):
             with pytest.raises(lib.TcrError):
                 lib.tuning_import(bad)
         assert lib.tuning_export() == "scan:16=0;"       # a rejected text leaves the table untouched

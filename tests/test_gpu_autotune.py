@@ -30,16 +30,19 @@ def data():
     return x, torch.from_numpy(x).cuda()
 
 
-SCAN_SHAPE_TILES = [1024, 2048, 4096, 8192, 16384, 32768, 65536, 16384, 32768, 65536]
-SCAN_SHAPE_TICKET = [False] * 7 + [True] * 3
+SCAN_SHAPE_TILES = [1024, 2048, 4096, 8192, 16384, 32768, 65536, 16384, 32768, 65536, 32768, 32768]
+SCAN_SHAPE_TICKET = [False] * 7 + [True] * 5
+SCAN_SHAPE_PERSISTENT = [False] * 10 + [True] * 2
 
 
-@pytest.mark.parametrize("log2_seg", [10, 12, 14, 16, 18])
-@pytest.mark.parametrize("shape", range(10))
+@pytest.mark.parametrize("log2_seg", [10, 12, 14, 15, 16, 18, 20])
+@pytest.mark.parametrize("shape", range(12))
 def test_every_scan_shape_matches_oracle(tcr, oracle, data, log2_seg, shape):
     seg = 1 << log2_seg
     if not SCAN_SHAPE_TICKET[shape] and SCAN_SHAPE_TILES[shape] < seg:
         pytest.skip("a share without carry must hold the whole segment")
+    if SCAN_SHAPE_PERSISTENT[shape] and SCAN_SHAPE_TILES[shape] > seg:
+        pytest.skip("the pipelined shapes are for segments longer than a share")
     x, xd = data
     tcr.tuning_import(f"scan:{log2_seg}={shape};")
     try:
@@ -50,12 +53,18 @@ def test_every_scan_shape_matches_oracle(tcr, oracle, data, log2_seg, shape):
     tcr.check_device_flags()
 
 
-@pytest.mark.parametrize("shape", [7, 8, 9])
-def test_every_full_scan_shape_matches_oracle(tcr, oracle, data, shape):
+@pytest.mark.parametrize("drop", [0, 5, 1549, 18949, 58949])
+@pytest.mark.parametrize("shape", [7, 8, 9, 10, 11])
+def test_every_full_scan_shape_matches_oracle(tcr, oracle, data, shape, drop):
+    # ragged n: not a multiple of 8 (the pipelined shapes then fall back), a multiple of 8 inside a
+    # wavefront's share, and a last tile that holds only a few wavefront shares
     x, xd = data
+    x, xd = x[:x.size - drop], xd[:xd.numel() - drop]
     tcr.tuning_import(f"scan:41={shape};")
     try:
-        got = tcr.scan(xd).cpu().numpy().astype(np.float64)              # ragged n
+        if shape >= 10:
+            assert (tcr.kernel_name(tcr.OP_SCAN, x.size, x.size) == "scan_chain_kernel<mfma>") == (x.size % 8 == 0)
+        got = tcr.scan(xd).cpu().numpy().astype(np.float64)
     finally:
         tcr.tuning_import("")
     ref = oracle.scan(x)
@@ -100,7 +109,7 @@ def test_autotune_picks_valid_shapes_and_results_stay_exact(tcr, oracle, data):
         table = dict(item.split("=") for item in tcr.tuning_export().split(";") if item)
         assert set(table) == {"scan:14", "reduce:14", "scan:41", "reduce:41"}
         assert int(table["scan:14"]) in range(4, 10)                     # shares that hold a 16384-element segment
-        assert int(table["scan:41"]) in (7, 8, 9)
+        assert int(table["scan:41"]) in (7, 8, 9, 10, 11)
         assert np.array_equal(tcr.segmented_scan(xd[:N], 1 << 14).cpu().numpy().astype(np.float64),
                               oracle.segmented_scan(x[:N], 1 << 14))
         assert np.array_equal(tcr.segmented_reduce(xd[:N], 1 << 14).cpu().numpy().astype(np.float64),

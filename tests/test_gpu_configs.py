@@ -113,10 +113,12 @@ def test_config(tcr, oracle, w):
     if nonneg and w.op.startswith("segmented"):
         # second, tighter gate for non-negative data, derived from the arithmetic: an output passes through at
         # most 32 (in-row adds of a product) + 15 (row carries) + 8 + 16 (tile and wavefront carries) binary32
-        # roundings, plus -- scan -- one per 65536-element workgroup share of its segment when the carry
-        # crosses workgroups, or -- reduce -- one per tile chained through the accumulator; every partial sum
-        # is bounded by the output itself, so the relative error is at most that count times 2^-24.
-        roundings = 71 + (w.seg_len // 65536 if w.op == "segmented_scan" else w.seg_len // 512)
+        # roundings, plus -- scan -- the cross-workgroup chain: per 32768-element workgroup share of its segment
+        # at most twelve (a ten-level tree over the up to 256 aggregates since the workgroup's previous share,
+        # adding that share's prefix, adding the own total), or -- reduce -- one per tile chained through the
+        # accumulator; every partial sum is bounded by the output itself, so the relative error is at most that
+        # count times 2^-24.
+        roundings = 71 + (12 * (w.seg_len // 32768) if w.op == "segmented_scan" else w.seg_len // 512)
         assert worst <= roundings * 2.0 ** -24, (w.name, worst)
     tcr.check_device_flags()
 
