@@ -245,6 +245,70 @@ def test_lookback_repeated_launches(tcr, oracle):
     tcr.check_device_flags()
 
 
+# tile counts of the persistent chain (32768-element tiles, one workgroup per compute unit, three tiles in
+# flight per workgroup): fewer tiles than pipeline stages, a ragged last tile that holds a few or nearly all
+# wavefront shares, exactly / one more than / far more tiles than workgroups
+CHAIN_NS = [8, 4096 + 8, 32768 - 8, 32768, 32768 + 8, 65536, 3 * 32768 + 40, 255 * 32768, 256 * 32768 + 8,
+            257 * 32768, 300 * 32768 - 32760, 700 * 32768 + 512 * 9]
+
+
+@pytest.mark.parametrize("n", CHAIN_NS)
+def test_pipelined_chain_tile_counts(tcr, oracle, n):
+    tcr.set_variant("reset")
+    assert tcr.kernel_name(tcr.OP_SCAN, n, n) in ("scan_chain_kernel<mfma>", "scan_block_kernel<mfma,nocarry>")
+    x = workloads.make_input(n, "int4", n % 997)
+    xd = dev(x)
+    ref = oracle.scan(x)
+    assert np.max(np.abs(ref)) < 2 ** 24
+    assert_exact(tcr.scan(xd), ref, f"scan n={n}")
+    assert_exact(tcr.scan_ex(xd, tcr.SCAN_EXCLUSIVE), ref - x.astype(np.float64), f"exclusive scan n={n}")
+    tcr.check_device_flags()
+
+
+@pytest.mark.parametrize("seg", [1 << 15, 1 << 16, 1 << 19])
+def test_pipelined_chain_segmented(tcr, oracle, seg):
+    # more tiles than workgroups, segments of 1, 2 and 16 tiles: the carry restarts at every segment
+    tcr.set_variant("reset")
+    n = max(300 * 32768 // seg, 3) * seg
+    assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, n, seg) == "scan_chain_kernel<mfma>"
+    x = workloads.make_input(n, "int8", seg % 991)
+    xd = dev(x)
+    assert_exact(tcr.segmented_scan(xd, seg), oracle.segmented_scan(x, seg), f"segmented scan L={seg}")
+    y = workloads.make_input(n, "uniform_pm1", 17)
+    assert_close_scan(tcr.segmented_scan(dev(y), seg), oracle.segmented_scan(y, seg), y, seg, f"scan L={seg} real")
+    tcr.check_device_flags()
+
+
+def test_pipelined_chain_repeated_launches(tcr, oracle):
+    # back-to-back launches share the aggregate table (epoch tag) and the running ticket counter, of which
+    # every launch draws tiles + 3 * workgroups; a lost or early carry shows up as a wrong integer
+    tcr.set_variant("reset")
+    n = (1 << 22) + 776
+    assert tcr.kernel_name(tcr.OP_SCAN, n, n) == "scan_chain_kernel<mfma>"
+    x = workloads.make_input(n, "int8", 5)
+    xd = dev(x)
+    ref = torch.from_numpy(oracle.scan(x).astype(np.float32)).cuda()
+    y = workloads.make_input(1 << 21, "int4", 6)
+    yd = dev(y)
+    yref = torch.from_numpy(oracle.segmented_scan(y, 1 << 17).astype(np.float32)).cuda()
+    outs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(4)]
+    youts = [torch.empty(1 << 21, dtype=torch.float32, device="cuda") for _ in range(4)]
+    for it in range(200):
+        tcr.scan(xd, out=outs[it % 4])
+        tcr.segmented_scan(yd, 1 << 17, out=youts[it % 4])
+        if it % 4 == 3:
+            for o in outs:
+                assert torch.equal(o, ref), f"iteration {it}"
+            for o in youts:
+                assert torch.equal(o, yref), f"iteration {it}"
+    # alternate with the look-back kernels on the same table (n not a multiple of 8)
+    for it in range(10):
+        a = tcr.scan(xd[: n - 3])
+        b = tcr.scan(xd)
+        assert torch.equal(a, ref[: n - 3]) and torch.equal(b, ref)
+    tcr.check_device_flags()
+
+
 def test_non_default_stream(tcr, oracle):
     x = workloads.make_input((1 << 20) + 24, "int8", 8)
     xd = dev(x)
