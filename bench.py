@@ -188,9 +188,9 @@ def main() -> int:
     for label, fn, nn, rd_wr in variant_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
-            ("segmented_reduce seg_len=3000 (untuned path)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
+            ("segmented_reduce seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
-            ("segmented_scan seg_len=3000 (untuned path)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
+            ("segmented_scan seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
              (2 * n3, 4 * n3))]:
         fn()
         torch.cuda.synchronize()

@@ -51,7 +51,8 @@ typedef enum {
  *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
- * seg_len == n, other lengths run untuned kernels (the paper pads such segments, Section 4).
+ * seg_len == n; other lengths run one wavefront per segment (from 256 elements on over zero-masked tiles of
+ * the array, the paper's padding of such segments, Section 4, applied in registers).
  */
 tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 
@@ -86,8 +87,9 @@ tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, vo
  *   tcr_irregular_reduce  out[s] = sum of segment s (0 for an empty one); out: nseg floats.
  *   tcr_irregular_scan    out[k] = sum of in[offsets[s] .. k] for k in segment s; out is indexed like `in`
  *                         (positions outside [offsets[0], offsets[nseg]) are not written).
- * in and out need only their natural alignment (2 and 4 bytes).  The offsets are not validated (they live on
- * the device); indices beyond the caller's arrays are the caller's error.  Untuned kernels, one wavefront per
+ * in and out need only their natural alignment (2 and 4 bytes); with 16-byte aligned pointers whole 8-element
+ * groups of the array are read and written at once.  The offsets are not validated (they live on the device);
+ * indices beyond the caller's arrays are the caller's error.  One wavefront per
  * segment.  nseg == 0 is a no-op.
  */
 tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *out, uint64_t nseg, void *stream);

@@ -527,7 +527,8 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
 }
 
 // Any other seg_len >= 1: the untuned kernels.
-constexpr uint64_t kGenericThreadMax = 96;      // up to here one thread walks a segment, beyond a wavefront does
+constexpr uint64_t kGenericThreadMax = 96;           // up to here one thread walks a segment, beyond a wavefront does
+constexpr uint64_t kMaskedMin = 256;                 // from here on the wavefront walks masked 512-element tiles of the array
 
 template <bool SCAN>
 tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
@@ -538,9 +539,25 @@ tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t se
             in, out, nseg, seg_len, excl, f16);
         return check_launch("generic_thread_kernel");
     }
-    generic_wave_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
-        in, out, nseg, seg_len, excl, f16);
-    return check_launch("generic_wave_kernel");
+    if (seg_len < kMaskedMin) {
+        generic_wave_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
+            in, out, nseg, seg_len, excl, f16);
+        return check_launch("generic_wave_kernel");
+    }
+    // masked 512-element tiles of the array, one wavefront per segment
+    const dim3 grid((unsigned)ceil_div(nseg, kMaskedWaves)), block(kMaskedWaves * kWave);
+    if constexpr (SCAN) {
+        switch (flags & 3u) {
+            case 0: masked_wave_scan_kernel<0><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
+            case 1: masked_wave_scan_kernel<1><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
+            case 2: masked_wave_scan_kernel<2><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
+            default: masked_wave_scan_kernel<3><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
+        }
+        return check_launch("masked_wave_scan_kernel");
+    } else {
+        masked_wave_reduce_kernel<<<grid, block, 0, s>>>(in, static_cast<float*>(out), nseg, seg_len);
+        return check_launch("masked_wave_reduce_kernel");
+    }
 }
 
 // The tuned scan paths for one (formulation, mode) pair.
@@ -618,6 +635,11 @@ extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offse
     if (in == nullptr || offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
     if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
     if (nseg > kMaxElements) return TCR_ERR_UNSUPPORTED;
+    if (aligned(in, 16)) {                   // 128-bit loads of whole 8-element groups of the array
+        masked_irregular_kernel<false><<<dim3((unsigned)ceil_div(nseg, kMaskedWaves)), dim3(kMaskedWaves * kWave), 0,
+                                         static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
+        return check_launch("masked_irregular_kernel");
+    }
     irregular_wave_kernel<false><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0,
                                    static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
     return check_launch("irregular_wave_kernel");
@@ -629,6 +651,11 @@ extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets
     if (in == nullptr || offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
     if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
     if (nseg > kMaxElements) return TCR_ERR_UNSUPPORTED;
+    if (aligned(in, 16) && aligned(out, 16)) {
+        masked_irregular_kernel<true><<<dim3((unsigned)ceil_div(nseg, kMaskedWaves)), dim3(kMaskedWaves * kWave), 0,
+                                        static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
+        return check_launch("masked_irregular_kernel");
+    }
     irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0,
                                   static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
     return check_launch("irregular_wave_kernel");
@@ -781,7 +808,9 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     const bool whole = seg_len == n;
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
         if (op != 0 && op != 1) return "";
-        return seg_len <= kGenericThreadMax ? "generic_thread_kernel" : "generic_wave_kernel";
+        if (seg_len <= kGenericThreadMax) return "generic_thread_kernel";
+        if (seg_len < kMaskedMin) return "generic_wave_kernel";
+        return op == 0 ? "masked_wave_reduce_kernel" : "masked_wave_scan_kernel";
     }
     if (op == 0 || op == 2) {
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";

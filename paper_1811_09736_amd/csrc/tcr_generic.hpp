@@ -1,10 +1,16 @@
-// Kernels for segment lengths without a tuned path (not a power of two, or shorter than 16).
-// The paper handles such sizes by zero padding or by masking the constant matrix (Section 4,
-// "Support for arbitrary segment sizes ..."); padding in place is not possible behind this
-// interface and segments that start at odd element offsets rule out 128-bit operand loads, so
-// these kernels read 16-bit elements and do the arithmetic with binary32 adds and the
-// wavefront scan primitive.  They are correct for every seg_len >= 1 and make no claim on
-// bandwidth.
+// Kernels for segment lengths without a tuned path (not a power of two, or shorter than 16) and for
+// irregular segments.  The paper handles such sizes by zero padding or by masking (Section 4, "Support
+// for arbitrary segment sizes ...").  Padding in place is not possible behind this interface, so:
+//   masked_wave_*   segments of 256 elements and more: one wavefront per segment walks the 512-element
+//                   tiles of the ARRAY (aligned to the array, not to the segment) that the segment
+//                   touches; elements of a tile outside the segment are read as zero -- the paper's
+//                   zero padding, applied to the operand registers -- and the matrix-core products,
+//                   the running carry through the accumulator and the 128-bit loads and stores of the
+//                   tuned kernels apply unchanged; only the 8-element groups cut by a segment end
+//                   are read and written element by element.
+//   generic_*       shorter segments (and irregular segments behind unaligned pointers): 16-bit
+//                   loads, binary32 adds, the wavefront scan primitive.
+// They are correct for every seg_len >= 1; none of them is tuned.
 #pragma once
 #include "tcr_device.hpp"
 #include "tcr_scan.hpp"
@@ -73,6 +79,122 @@ __global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Fl
     if (!SCAN) {
         const float total = wave_sum(acc);
         if (lane == 0) put(out, s, total, f16);
+    }
+}
+
+// ---------------------------------------------------------------------------------------- masked tiles
+// 8 inputs at element g (a multiple of 8), those outside [begin, end) read as zero.
+__device__ __forceinline__ half8 load8_masked(const _Float16* __restrict__ in, uint64_t g, uint64_t begin, uint64_t end) {
+    if (g >= begin && g + 8 <= end) return load8(in, g);
+    half8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (g + e >= begin && g + e < end) ? in[g + e] : (_Float16)0.0f;
+    return v;
+}
+
+// 4 results at element g (a multiple of 4), those outside [begin, end) are not written.
+template <int F16>
+__device__ __forceinline__ void store4_masked(void* __restrict__ out, uint64_t g, uint64_t begin, uint64_t end, float4v v) {
+    if (g >= begin && g + 4 <= end) {
+        store4_t<F16>(out, g, v);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (g + e >= begin && g + e < end) {
+                if constexpr (F16) static_cast<_Float16*>(out)[g + e] = (_Float16)v[e];
+                else static_cast<float*>(out)[g + e] = v[e];
+            }
+        }
+    }
+}
+
+// One wavefront scans the segment [begin, end) of the array (outputs indexed like inputs).
+// `in` and `out` are 16-byte aligned.  MODE bit 0: exclusive, bit 1: binary16 output.
+template <int MODE>
+__device__ __forceinline__ void masked_wave_scan(const _Float16* __restrict__ in, void* __restrict__ out,
+                                                 uint64_t begin, uint64_t end, const LaneId& id) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
+    constexpr int kSteps = 4;                            // tiles in flight
+    float carry = 0.0f;                                  // total of the tiles already done (the S matrix of Scan_256N)
+    for (uint64_t t0 = begin & ~(uint64_t)(kTile - 1); t0 < end; t0 += (uint64_t)(kTile * kSteps)) {
+        half8 x[kSteps];
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const uint64_t tile = t0 + (uint64_t)(kTile * i);
+            if (tile < end) x[i] = load8_masked(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end);
+        }
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const uint64_t tile = t0 + (uint64_t)(kTile * i);
+            if (tile >= end) break;                      // uniform over the wavefront
+            const float4v tot = mfma(const_ones(), x[i], splat(0.0f));
+            const float incl = row_scan_inclusive<16>(tot[0], id.j);
+            const float before = row_shr<1>(incl) + carry;
+            const float4v lo = mfma(const_tri_lo<EXCL>(id), x[i], splat(before));
+            const float4v hi = mfma(const_tri_hi<EXCL>(id), x[i], splat(before));
+            const uint64_t g = tile + (uint64_t)(kRow * id.j + 4 * id.g);
+            store4_masked<F16>(out, g, begin, end, lo);
+            store4_masked<F16>(out, g + 16, begin, end, hi);
+            carry += read_lane(incl, 15);
+        }
+    }
+}
+
+// One wavefront adds up the segment [begin, end); the result is uniform.  `in` is 16-byte aligned.
+__device__ __forceinline__ float masked_wave_reduce(const _Float16* __restrict__ in, uint64_t begin, uint64_t end,
+                                                    const LaneId& id) {
+    constexpr int kSteps = 4;
+    float4v acc = splat(0.0f);                           // running row sums (the accumulator matrix V of Reduction_256N)
+    for (uint64_t t0 = begin & ~(uint64_t)(kTile - 1); t0 < end; t0 += (uint64_t)(kTile * kSteps)) {
+        half8 x[kSteps];
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const uint64_t tile = t0 + (uint64_t)(kTile * i);
+            x[i] = (tile < end) ? load8_masked(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end)
+                                : __builtin_bit_cast(half8, splat(0.0f));
+        }
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) acc = mfma(const_ones(), x[i], acc);
+    }
+    return read_lane(row_sum_to_last<16>(acc[0]), 15);
+}
+
+constexpr int kMaskedWaves = 4;                          // wavefronts (segments) per workgroup
+
+template <int MODE>
+__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_wave_scan_kernel(const _Float16* __restrict__ in,
+                                                                                void* __restrict__ out, uint64_t nseg,
+                                                                                uint64_t seg_len) {
+    const LaneId id;
+    const uint64_t s = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (s >= nseg) return;
+    masked_wave_scan<MODE>(in, out, s * seg_len, (s + 1) * seg_len, id);
+}
+
+__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_wave_reduce_kernel(const _Float16* __restrict__ in,
+                                                                                  float* __restrict__ out, uint64_t nseg,
+                                                                                  uint64_t seg_len) {
+    const LaneId id;
+    const uint64_t s = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (s >= nseg) return;
+    const float total = masked_wave_reduce(in, s * seg_len, (s + 1) * seg_len, id);
+    if (id.lane == 0) out[s] = total;
+}
+
+// Irregular segments behind 16-byte aligned pointers: the same walk, boundaries read from `offsets`.
+template <bool SCAN>
+__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_irregular_kernel(const _Float16* __restrict__ in,
+                                                                                const uint64_t* __restrict__ offsets,
+                                                                                float* __restrict__ out, uint64_t nseg) {
+    const LaneId id;
+    const uint64_t s = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (s >= nseg) return;
+    const uint64_t begin = offsets[s], end = offsets[s + 1];
+    if constexpr (SCAN) {
+        masked_wave_scan<0>(in, out, begin, end, id);
+    } else {
+        const float total = masked_wave_reduce(in, begin, end, id);
+        if (id.lane == 0) out[s] = total;
     }
 }
 

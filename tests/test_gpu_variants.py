@@ -158,3 +158,32 @@ def test_irregular_partial_cover_and_uniform(tcr, oracle):
     reg = torch.arange(0, 4097, 256, dtype=torch.int64, device="cuda")
     assert torch.equal(tcr.irregular_reduce(xd, reg), tcr.segmented_reduce(xd[:4096].clone(), 256))
     assert tcr.irregular_reduce(xd, torch.zeros(1, dtype=torch.int64, device="cuda")).numel() == 0
+
+
+def test_irregular_behind_unaligned_pointers(tcr, oracle):
+    # a view that starts at element 1 is only 2-byte (input) / 4-byte (output) aligned: the element-wise
+    # kernels run instead of the ones that read whole 8-element groups
+    x = workloads.make_input(20001, "int8", 77)
+    xd = torch.from_numpy(x).cuda()[1:]
+    off = _random_offsets(20000, 40, 9)
+    od = torch.from_numpy(off).cuda()
+    out = torch.zeros(20001, dtype=torch.float32, device="cuda")[1:]
+    tcr.irregular_scan(xd, od, out=out)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), oracle.irregular_scan(x[1:].copy(), off))
+    red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
+    assert np.array_equal(red, oracle.irregular_reduce(x[1:].copy(), off))
+
+
+@pytest.mark.parametrize("seg", [256 + 8, 511, 513, 3000, 100003])
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+def test_masked_tile_kernels_take_every_flag(tcr, oracle, seg, flags):
+    nseg = max(3, (200000 // seg) | 1)
+    x = workloads.make_input(seg * nseg, "int4", seg % 89)
+    xd = torch.from_numpy(x).cuda()
+    assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, x.size, seg) == "masked_wave_scan_kernel"
+    ref = oracle.segmented_scan_exclusive(x, seg) if flags & 1 else oracle.segmented_scan(x, seg)
+    got = tcr.segmented_scan_ex(xd, seg, flags).cpu().numpy().astype(np.float64)
+    if flags & 2:
+        ref = ref.astype(np.float16).astype(np.float64)            # integer sums: one correct rounding
+    assert np.array_equal(got, ref)
+    assert np.array_equal(tcr.segmented_reduce(xd, seg).cpu().numpy().astype(np.float64), oracle.segmented_reduce(x, seg))
