@@ -38,6 +38,7 @@ def main() -> int:
     ap.add_argument("--formulation", default="mfma", choices=["mfma", "dpp"])
     ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan", "scan_then_propagate"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tuning", default="", help="launch-shape choices to import first (tcr_tuning_import text)")
     ap.add_argument("--autotune", action="store_true",
                     help="let tcr_autotune re-pick the launch shape of every timed call first (default: shipped shapes)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -109,6 +110,8 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.tuning:
+        tcr.tuning_import(args.tuning)
     if args.autotune:
         ids = {"segmented_reduce": tcr.OP_SEGMENTED_REDUCE, "segmented_scan": tcr.OP_SEGMENTED_SCAN}
         for op, e in calls:
