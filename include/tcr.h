@@ -42,7 +42,7 @@ typedef enum {
     TCR_OK = 0,
     TCR_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, seg_len == 0, n % seg_len != 0 */
     TCR_ERR_UNSUPPORTED = 2,   /* a size or variant this build has no kernel for */
-    TCR_ERR_WORKSPACE = 3,     /* workspace allocation failed */
+    TCR_ERR_WORKSPACE = 3,     /* workspace allocation failed, or the caller's workspace is too small */
     TCR_ERR_HIP = 4            /* a HIP runtime call failed (see tcr_last_hip_error) */
 } tcr_status;
 
@@ -148,6 +148,21 @@ const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);
  * expire).  Returns TCR_OK if none did, TCR_ERR_HIP otherwise.  Synchronises; for tests.
  */
 tcr_status tcr_check_device_flags(void *stream);
+
+/*
+ * Caller-supplied workspace, for callers that manage device memory themselves.
+ * tcr_workspace_bytes: an upper bound, over every variant and launch shape, of the workspace a call with
+ *   these arguments can need (op as for tcr_kernel_name; 0 for arguments no call accepts).
+ * tcr_set_workspace: from now on every call on the CURRENT device uses [dev_ptr, dev_ptr + bytes) instead of
+ *   library-owned memory, whatever its stream, and allocates nothing; a call that needs more returns
+ *   TCR_ERR_WORKSPACE.  dev_ptr: device memory, 256-byte aligned, at least 768 bytes, contents arbitrary (the
+ *   first call that chains tiles synchronises its stream once and clears it); it stays the caller's and must
+ *   outlive the calls that use it.  One buffer serves one stream at a time: calls that use it must be ordered
+ *   by their streams or by the caller.  dev_ptr == NULL returns the device to library-owned workspaces.
+ *   TCR_ERR_INVALID_ARG for a misaligned or too small buffer.
+ */
+uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len);
+tcr_status tcr_set_workspace(void *dev_ptr, uint64_t bytes);
 
 /* Releases every library-owned workspace.  The caller must have synchronised all streams.
  * The (small, uncached) look-back tables are kept for reuse until the process ends. */

@@ -23,6 +23,7 @@ SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
     "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
+    "tcr_workspace_bytes", "tcr_set_workspace",
     "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
 )
@@ -64,6 +65,10 @@ def _load() -> ctypes.CDLL:
     lib.tcr_tuning_export.restype = u64
     lib.tcr_tuning_import.argtypes = [ctypes.c_char_p]
     lib.tcr_tuning_import.restype = ctypes.c_int
+    lib.tcr_workspace_bytes.argtypes = [ctypes.c_int, u64, u64]
+    lib.tcr_workspace_bytes.restype = u64
+    lib.tcr_set_workspace.argtypes = [vp, u64]
+    lib.tcr_set_workspace.restype = ctypes.c_int
     lib.tcr_set_variant.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
     lib.tcr_set_variant.restype = ctypes.c_int
     lib.tcr_kernel_name.argtypes = [ctypes.c_int, u64, u64]
@@ -261,6 +266,24 @@ def tuning_import(text: str) -> None:
     st = _lib.tcr_tuning_import(text.encode())
     if st != OK:
         raise TcrError(st, "tcr_tuning_import")
+
+
+def workspace_bytes(op: int, n: int, seg_len: int) -> int:
+    return int(_lib.tcr_workspace_bytes(op, n, seg_len))
+
+
+def set_workspace(buffer: Optional[torch.Tensor]) -> None:
+    """tcr_set_workspace: use `buffer` (any contiguous CUDA tensor; the caller keeps it alive) on its device, or
+    return the current device to library-owned workspaces with None."""
+    if buffer is None:
+        st = _lib.tcr_set_workspace(None, 0)
+    else:
+        if not (buffer.is_cuda and buffer.is_contiguous()):
+            raise TypeError("workspace must be a contiguous CUDA tensor")
+        with torch.cuda.device(buffer.device):
+            st = _lib.tcr_set_workspace(buffer.data_ptr(), buffer.numel() * buffer.element_size())
+    if st != OK:
+        raise TcrError(st, "tcr_set_workspace")
 
 
 def set_variant(key: str, value: str = "") -> None:

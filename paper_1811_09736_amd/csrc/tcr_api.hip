@@ -63,10 +63,16 @@ struct Workspace {
     uint32_t tickets_issued = 0;    // host mirror of counters[0] once all enqueued launches finish
     uint32_t epoch = 0;
     bool dirty = true;              // counters / descriptors must be re-zeroed before use
+    bool caller_owned = false;      // memory supplied through tcr_set_workspace: never grown, never freed
+    bool flag_valid = true;         // false until the first clean-up has written the caller's (uninitialised) flag word
 };
 
 std::mutex g_mutex;
 std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
+// Caller-supplied workspaces, one per device: [256-byte header: ticket, flag | descriptors | partials],
+// the two areas of equal size.  While one is set, every call on that device uses it, whatever its stream.
+std::map<int, Workspace> g_caller_workspaces;
+constexpr uint64_t kWorkspaceHeader = 256;
 
 // Look-back descriptor tables are allocated uncached (polling them through the L2 path measured
 // ~5 % slower on the full scan).  Uncached allocations are never handed back to the runtime:
@@ -109,12 +115,14 @@ tcr_status get_workspace(hipStream_t stream, Workspace** out) {
     int dev = 0;
     TCR_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
-    *out = &g_workspaces[std::make_pair(dev, stream)];
+    auto own = g_caller_workspaces.find(dev);
+    *out = own != g_caller_workspaces.end() ? &own->second : &g_workspaces[std::make_pair(dev, stream)];
     return TCR_OK;
 }
 
 tcr_status ensure_partials(Workspace* ws, hipStream_t stream, uint64_t floats) {
     if (floats <= ws->partials_capacity) return TCR_OK;
+    if (ws->caller_owned) return TCR_ERR_WORKSPACE;
     TCR_HIP(hipStreamSynchronize(stream));
     if (ws->partials) TCR_HIP(hipFree(ws->partials));
     ws->partials = nullptr;
@@ -131,6 +139,7 @@ tcr_status ensure_partials(Workspace* ws, hipStream_t stream, uint64_t floats) {
 
 // Makes room for `tiles` look-back descriptors and starts a new epoch.
 tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, ScanWorkspace* dev) {
+    if (ws->caller_owned && tiles > ws->desc_capacity) return TCR_ERR_WORKSPACE;
     if (ws->counters == nullptr) {
         if (hipMalloc(&ws->counters, 2 * sizeof(uint32_t)) != hipSuccess) {
             (void)hipGetLastError();
@@ -157,7 +166,8 @@ tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, Sca
         TCR_HIP(hipStreamSynchronize(stream));
         TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
         uint32_t keep_flag = 0;
-        TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (ws->flag_valid) TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        ws->flag_valid = true;
         uint32_t init[2] = {0u, keep_flag};
         TCR_HIP(hipMemcpy(ws->counters, init, sizeof(init), hipMemcpyHostToDevice));
         ws->tickets_issued = 0;
@@ -858,6 +868,41 @@ extern "C" tcr_status tcr_check_device_flags(void* stream) {
     return TCR_OK;
 }
 
+extern "C" uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len) {
+    if (op < 0 || op > 3 || n == 0) return 0;
+    if (op >= 2) seg_len = n;
+    if (seg_len == 0 || n % seg_len != 0) return 0;
+    // Upper bounds over every variant and launch shape: one 8-byte descriptor per 16384-element share (the
+    // smallest share handed out by ticket), one binary32 partial per 16384 elements (the smallest span a
+    // reduction leaves a partial for is 65536, as is the share of the multi-kernel scans).
+    const uint64_t shares = ceil_div(n, 16384);
+    const uint64_t area = (shares * 8 + 255) / 256 * 256;
+    return kWorkspaceHeader + 2 * area;
+}
+
+extern "C" tcr_status tcr_set_workspace(void* dev_ptr, uint64_t bytes) {
+    int dev = 0;
+    TCR_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (dev_ptr == nullptr) {
+        g_caller_workspaces.erase(dev);
+        return TCR_OK;
+    }
+    if (!aligned(dev_ptr, 256) || bytes < kWorkspaceHeader + 512) return TCR_ERR_INVALID_ARG;
+    const uint64_t area = (bytes - kWorkspaceHeader) / 2 / 256 * 256;
+    Workspace w;
+    w.caller_owned = true;
+    w.counters = static_cast<uint32_t*>(dev_ptr);
+    w.desc = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_ptr) + kWorkspaceHeader);
+    w.desc_capacity = area / 8;
+    w.partials = reinterpret_cast<float*>(static_cast<char*>(dev_ptr) + kWorkspaceHeader + area);
+    w.partials_capacity = area / 4;
+    w.dirty = true;                                   // zeroed by the first call that chains tiles
+    w.flag_valid = false;
+    g_caller_workspaces[dev] = w;
+    return TCR_OK;
+}
+
 extern "C" void tcr_release(void) {
     std::lock_guard<std::mutex> lock(g_mutex);
     for (auto& kv : g_workspaces) {
@@ -874,7 +919,7 @@ extern "C" const char* tcr_status_string(tcr_status s) {
         case TCR_OK: return "ok";
         case TCR_ERR_INVALID_ARG: return "invalid argument";
         case TCR_ERR_UNSUPPORTED: return "unsupported size or variant";
-        case TCR_ERR_WORKSPACE: return "workspace allocation failed";
+        case TCR_ERR_WORKSPACE: return "workspace allocation failed or caller workspace too small";
         case TCR_ERR_HIP: return "HIP runtime error";
     }
     return "unknown status";

@@ -154,3 +154,15 @@ def test_tuning_table_text_round_trip(lib):
     finally:
         lib.tuning_import("")
     assert lib.tuning_export() == ""
+
+
+def test_workspace_bytes_is_a_host_side_bound(lib):
+    wb = lib.workspace_bytes
+    assert wb(lib.OP_SEGMENTED_SCAN, 0, 16) == 0
+    assert wb(lib.OP_SEGMENTED_SCAN, 48, 5) == 0            # 5 does not divide 48
+    assert wb(7, 1 << 20, 16) == 0
+    small, big = wb(lib.OP_SCAN, 1 << 20, 0), wb(lib.OP_SCAN, 1 << 28, 0)
+    assert 768 <= small < big
+    assert big == 256 + 2 * (1 << 28) // 16384 * 8          # header + descriptors + partials
+    assert big % 256 == 0
+    assert wb(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == big

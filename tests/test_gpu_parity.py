@@ -383,6 +383,53 @@ def test_workspace_grows_shrinks_and_survives_release(tcr, oracle):
     tcr.check_device_flags()
 
 
+def test_caller_supplied_workspace(tcr, oracle):
+    n = (1 << 22) + 4096
+    x = workloads.make_input(n, "int8", 31)
+    xd = dev(x)
+    ref_scan = oracle.scan(x)
+    need = tcr.workspace_bytes(tcr.OP_SCAN, n, n)
+    buf = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda")      # arbitrary contents
+    tcr.check_device_flags()
+    try:
+        tcr.set_workspace(buf)
+        for _ in range(3):
+            assert_exact(tcr.scan(xd), ref_scan, "chained scan, caller workspace")
+        tcr.tuning_import("scan:41=9;")                                     # the look-back kernel on the same buffer
+        assert_exact(tcr.scan(xd), ref_scan, "look-back scan, caller workspace")
+        tcr.tuning_import("")
+        assert float(tcr.reduce(xd).cpu()[0]) == oracle.reduce(x)
+        assert_exact(tcr.segmented_reduce(xd[: 1 << 22], 1 << 21), oracle.segmented_reduce(x[: 1 << 22], 1 << 21),
+                     "long-segment reduce, caller workspace")
+        for strategy in ("reduce_then_scan", "scan_then_propagate"):
+            tcr.set_variant("scan_carry", strategy)
+            assert_exact(tcr.scan(xd), ref_scan, f"{strategy}, caller workspace")
+        tcr.set_variant("reset")
+        s2 = torch.cuda.Stream()                                            # any stream uses the one buffer
+        torch.cuda.synchronize()
+        out = torch.empty(n, dtype=torch.float32, device="cuda")
+        tcr.scan(xd, out=out, stream=s2)
+        s2.synchronize()
+        assert_exact(out, ref_scan, "other stream, caller workspace")
+        tcr.check_device_flags()
+        # a buffer that is too small: calls that need more fail without allocating, others still run
+        tcr.set_workspace(buf[:1024])
+        with pytest.raises(tcr.TcrError) as e:
+            tcr.scan(xd)
+        assert e.value.status == tcr.ERR_WORKSPACE
+        assert_exact(tcr.segmented_scan(xd[: 1 << 20], 256), oracle.segmented_scan(x[: 1 << 20], 256), "no workspace needed")
+        with pytest.raises(tcr.TcrError):
+            tcr.set_workspace(buf[1:2049])                                  # misaligned
+        with pytest.raises(tcr.TcrError):
+            tcr.set_workspace(buf[:256])                                    # too small to hold anything
+    finally:
+        tcr.set_variant("reset")
+        tcr.tuning_import("")
+        tcr.set_workspace(None)
+    assert_exact(tcr.scan(xd), ref_scan, "library workspace again")
+    tcr.check_device_flags()
+
+
 def test_outputs_do_not_depend_on_previous_contents(tcr, oracle):
     x = workloads.make_input((1 << 20) + 24, "int8", 33)
     xd = dev(x)
