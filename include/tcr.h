@@ -113,6 +113,8 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
  *   "scan_carry"   "lookback" (default: single pass, decoupled look-back) | "reduce_then_scan" |
  *                  "scan_then_propagate" (the paper's three-kernel device-level scan, Section 5;
  *                  plain binary32 inclusive scan only)
+ *   "reduce_finish" "second_kernel" (default: the paper's two-kernel device-level reduction, Section 4) |
+ *                  "fused" (one kernel: the workgroup that finishes last adds up the partials)
  *   "reset"        any value: back to the defaults
  * Returns TCR_ERR_INVALID_ARG for an unknown key or value.  Process-wide; not thread safe.
  */

@@ -38,6 +38,7 @@ bool hip_failed(hipError_t e, const char* what) {
 struct Variant {
     int formulation = kMfma;
     int scan_carry = kStrategyLookback;
+    bool reduce_fused = false;      // long reductions: a second kernel adds the partials (true: the last workgroup does)
 };
 Variant g_variant;
 
@@ -52,6 +53,7 @@ constexpr int kReduceBlockW = 4;                     // reduce: wavefronts combi
 constexpr int kCarryU = 8, kCarryW = 16;             // scan with cross-workgroup carry: 65536 elements per workgroup
 constexpr uint64_t kCarryTile = (uint64_t)kTile * kCarryU * kCarryW;
 constexpr uint64_t kMaxElements = 1ull << 38;        // keeps every grid below 2^31 workgroups
+constexpr uint64_t kFusedPartialsMax = 4096;         // partials one workgroup adds up at the end of a fused long reduction
 
 // ---------------------------------------------------------------------------- workspace
 struct Workspace {
@@ -164,7 +166,7 @@ tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, Sca
     if (ws->dirty || ws->epoch >= (1u << 30) - 2u) {
         // first use, growth, a failed launch, or epoch wrap: start from a clean slate
         TCR_HIP(hipStreamSynchronize(stream));
-        TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
+        if (ws->desc_capacity) TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
         uint32_t keep_flag = 0;
         if (ws->flag_valid) TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
         ws->flag_valid = true;
@@ -223,18 +225,32 @@ tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n, int l
 
 template <int FORM>
 tcr_status launch_reduce_span(const _Float16* in, float* dst, uint64_t n, uint64_t span, uint64_t nspans,
-                              int combine_waves, hipStream_t s) {
+                              int combine_waves, hipStream_t s, const ReduceFinish* finish = nullptr) {
+    const ReduceFinish none = {};
+    if (finish != nullptr) {          // one partial per workgroup; the last workgroup adds them up
+        if (combine_waves == 4) {
+            reduce_span_kernel<FORM, 8, 4, true, true><<<dim3((unsigned)ceil_div(nspans, 4)), dim3(4 * kWave), 0, s>>>(
+                in, dst, n, span, nspans, *finish);
+        } else if (combine_waves == 2) {
+            reduce_span_kernel<FORM, 8, 2, true, true><<<dim3((unsigned)ceil_div(nspans, 2)), dim3(2 * kWave), 0, s>>>(
+                in, dst, n, span, nspans, *finish);
+        } else {
+            reduce_span_kernel<FORM, 8, 1, false, true><<<dim3((unsigned)nspans), dim3(kWave), 0, s>>>(in, dst, n, span, nspans,
+                                                                                                       *finish);
+        }
+        return check_launch("reduce_span_kernel");
+    }
     if (combine_waves == 4) {
         reduce_span_kernel<FORM, 8, 4, true><<<dim3((unsigned)ceil_div(nspans, 4)), dim3(4 * kWave), 0, s>>>(
-            in, dst, n, span, nspans);
+            in, dst, n, span, nspans, none);
     } else if (combine_waves == 2) {
         reduce_span_kernel<FORM, 8, 2, true><<<dim3((unsigned)ceil_div(nspans, 2)), dim3(2 * kWave), 0, s>>>(
-            in, dst, n, span, nspans);
+            in, dst, n, span, nspans, none);
     } else {
         const dim3 grid((unsigned)nspans), block(kWave);
-        if (span >= 8 * kTile) reduce_span_kernel<FORM, 8, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
-        else if (span >= 4 * kTile) reduce_span_kernel<FORM, 4, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
-        else reduce_span_kernel<FORM, 2, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans);
+        if (span >= 8 * kTile) reduce_span_kernel<FORM, 8, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans, none);
+        else if (span >= 4 * kTile) reduce_span_kernel<FORM, 4, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans, none);
+        else reduce_span_kernel<FORM, 2, 1, false><<<grid, block, 0, s>>>(in, dst, n, span, nspans, none);
     }
     return check_launch("reduce_span_kernel");
 }
@@ -323,6 +339,24 @@ tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_
         st = ensure_partials(ws, s, nseg * p.per);
         if (st != TCR_OK) return st;
         dst = ws->partials;
+    }
+    if (p.per > 1 && g_variant.reduce_fused && nseg * p.per <= kFusedPartialsMax) {
+        // one kernel: the workgroup that finishes last adds up the partials
+        Workspace* ws = nullptr;
+        tcr_status st = get_workspace(s, &ws);
+        if (st != TCR_OK) return st;
+        ScanWorkspace dev = {};
+        st = begin_lookback(ws, s, 0, &dev);              // the running counter that also hands out scan tiles
+        if (st != TCR_OK) return st;
+        const ReduceFinish fin = {out, dev.ticket, dev.ticket_base, (uint32_t)nseg, (uint32_t)p.per};
+        st = g_variant.formulation == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s, &fin)
+                                            : launch_reduce_span<kDpp>(in, dst, n, p.span, p.nspans, p.combine, s, &fin);
+        if (st != TCR_OK) {
+            ws->dirty = true;
+            return st;
+        }
+        ws->tickets_issued += (uint32_t)(nseg * p.per);   // one count per workgroup
+        return TCR_OK;
     }
     tcr_status st = g_variant.formulation == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s)
                                                    : launch_reduce_span<kDpp>(in, dst, n, p.span, p.nspans, p.combine, s);
@@ -706,6 +740,12 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
         else return TCR_ERR_INVALID_ARG;
         return TCR_OK;
     }
+    if (std::strcmp(key, "reduce_finish") == 0) {
+        if (std::strcmp(value, "fused") == 0) g_variant.reduce_fused = true;
+        else if (std::strcmp(value, "second_kernel") == 0) g_variant.reduce_fused = false;
+        else return TCR_ERR_INVALID_ARG;
+        return TCR_OK;
+    }
     return TCR_ERR_INVALID_ARG;
 }
 
@@ -827,6 +867,9 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         const ReducePlan p = plan_reduce(n, seg_len, whole);
         if (p.combine == 1) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
         if (p.per == 1) return mf ? "reduce_span_kernel<mfma,block>" : "reduce_span_kernel<dpp,block>";
+        const uint64_t nseg = whole ? 1 : n / seg_len;
+        if (g_variant.reduce_fused && nseg * p.per <= kFusedPartialsMax)
+            return mf ? "reduce_span_kernel<mfma,block,finish>" : "reduce_span_kernel<dpp,block,finish>";
         return mf ? "reduce_span_kernel<mfma,block>+reduce_final_kernel" : "reduce_span_kernel<dpp,block>+reduce_final_kernel";
     }
     if (op == 1 || op == 3) {

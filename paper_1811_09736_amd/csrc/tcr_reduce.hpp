@@ -111,11 +111,23 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Floa
 // partial).  COMBINE == true: the WAVES sums of a workgroup are added through LDS in wavefront
 // order and dst[blockIdx.x] receives the result (block-level Reduction_256N: one workgroup per
 // segment or per partial).
-template <int FORM, int U, int WAVES, bool COMBINE>
+// FINAL == true (device level, Section 4, as one kernel instead of the paper's two): dst holds `per`
+// partials per segment; every workgroup counts itself on a running counter after its partial is
+// visible, and the workgroup that counts last adds up the partials of every segment, in a fixed
+// order, into fin.out.  The counter is never reset: the host passes its value at launch.
+struct ReduceFinish {
+    float* out;            // [nseg]
+    uint32_t* counter;     // running count of finished workgroups
+    uint32_t base;         // value of *counter when this launch starts
+    uint32_t nseg, per;    // dst holds nseg * per partials
+};
+
+template <int FORM, int U, int WAVES, bool COMBINE, bool FINAL = false>
 __global__ __launch_bounds__(WAVES * kWave) void reduce_span_kernel(const _Float16* __restrict__ in,
                                                                     float* __restrict__ dst, uint64_t n,
-                                                                    uint64_t span, uint64_t nspans) {
+                                                                    uint64_t span, uint64_t nspans, ReduceFinish fin) {
     __shared__ float s_total[WAVES];
+    __shared__ uint32_t s_count;
     const LaneId id;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
     const uint64_t w = (uint64_t)blockIdx.x * WAVES + wave;
@@ -146,16 +158,46 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_span_kernel(const _Float
         if constexpr (FORM == kMfma) total = read_lane(row_sum_to_last<16>(acc[0]), 15);   // fold the 16 row sums
         else total = read_lane(lanes_sum_to_last<64>(s0 + s1), 63);
     }
-    if constexpr (!COMBINE) {
-        if (w < nspans && id.lane == 0) dst[w] = total;
+    if constexpr (!FINAL) {
+        if constexpr (!COMBINE) {
+            if (w < nspans && id.lane == 0) dst[w] = total;
+        } else {
+            if (id.lane == 0) s_total[wave] = total;
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int k = 0; k < WAVES; ++k) sum += s_total[k];
+                dst[blockIdx.x] = sum;
+            }
+        }
     } else {
+        static_assert(!FINAL || COMBINE || WAVES == 1, "one partial per workgroup");
         if (id.lane == 0) s_total[wave] = total;
         __syncthreads();
         if (threadIdx.x == 0) {
             float sum = 0.0f;
 #pragma unroll
             for (int k = 0; k < WAVES; ++k) sum += s_total[k];
-            dst[blockIdx.x] = sum;
+            // The partial is written through to device scope and its acknowledgement is waited for before the
+            // count is issued; the last workgroup reads the partials with device-scope loads that bypass its
+            // caches.  (A device-scope release / acquire pair instead would write back and invalidate the L2
+            // once per workgroup: measured, it costs a third of the bandwidth.)
+            __hip_atomic_store(&dst[blockIdx.x], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // compiler ordering
+            __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0): the store has been acknowledged
+            s_count = __hip_atomic_fetch_add(fin.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - fin.base;
+        }
+        __syncthreads();
+        if (s_count == gridDim.x - 1u) {
+            for (uint32_t seg = (uint32_t)wave; seg < fin.nseg; seg += WAVES) {
+                const float* p = dst + (uint64_t)seg * fin.per;
+                float a = 0.0f;
+                for (uint32_t i = (uint32_t)id.lane; i < fin.per; i += kWave)
+                    a += __hip_atomic_load(&p[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float t = wave_sum(a);
+                if (id.lane == 0) fin.out[seg] = t;
+            }
         }
     }
 }

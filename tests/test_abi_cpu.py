@@ -108,6 +108,10 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,block>"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20).endswith("block>+reduce_final_kernel")
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 24).endswith("+reduce_final_kernel")
+    lib.set_variant("reduce_finish", "fused")
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20) == "reduce_span_kernel<mfma,block,finish>"
+    assert k(lib.OP_SEGMENTED_REDUCE, 1 << 36, 1 << 24).endswith("+reduce_final_kernel")   # 2^18 partials: too many for one workgroup
+    lib.set_variant("reset")
     assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
     assert k(lib.OP_REDUCE, 1000, 1000) == "reduce_span_kernel<mfma,wave>"
     assert k(lib.OP_SCAN, n, n) == "scan_chain_kernel<mfma>"

@@ -383,6 +383,28 @@ def test_workspace_grows_shrinks_and_survives_release(tcr, oracle):
     tcr.check_device_flags()
 
 
+@pytest.mark.parametrize("finish", ["fused", "second_kernel"])
+def test_long_reductions_both_finishes(tcr, oracle, form, finish):
+    # device-level reduction: the last workgroup adds the partials (one kernel) or a second kernel does
+    tcr.set_variant("reduce_finish", finish)
+    x = workloads.make_input((1 << 23) + 12345, "int8", 41)
+    xd = dev(x)
+    for n in (100003, 1 << 20, (1 << 22) + 8, x.size):
+        assert float(tcr.reduce(xd[:n]).cpu()[0]) == oracle.reduce(x[:n]), f"reduce n={n}"
+    for seg in (1 << 19, 1 << 20, 1 << 22):
+        m = (1 << 23) // seg * seg
+        assert_exact(tcr.segmented_reduce(xd[:m], seg), oracle.segmented_reduce(x[:m], seg), f"reduce L={seg}")
+    # the running counter is shared with the scans' tile tickets on the same stream
+    ref = oracle.scan(x[: 1 << 22])
+    for it in range(20):
+        r = tcr.reduce(xd)
+        sc = tcr.scan(xd[: 1 << 22])
+        assert float(r.cpu()[0]) == oracle.reduce(x)
+        if it % 5 == 0:
+            assert_exact(sc, ref, "scan between fused reductions")
+    tcr.check_device_flags()
+
+
 def test_caller_supplied_workspace(tcr, oracle):
     n = (1 << 22) + 4096
     x = workloads.make_input(n, "int8", 31)
