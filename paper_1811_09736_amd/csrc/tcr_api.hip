@@ -44,13 +44,14 @@ Variant g_variant;
 
 // Launch shapes (U = tiles of 512 elements per wavefront, W = wavefronts per workgroup) come from
 // timing sweeps at n = 2^28 on MI355X: short-lived wavefronts with one tile each stream best, so
-// every shape is the smallest workgroup share that still contains a whole segment; only segments
-// longer than 65536 elements (and the full scan) take a cross-workgroup carry.
+// segments up to 16384 elements take the smallest workgroup share that still contains a whole
+// segment; longer ones (and the full scan) run the persistent chain, whose tiles pass carries
+// between workgroups.
 constexpr int kSmallScanW = 2;                       // scan_small: U = 1
 constexpr int kSmallReduceU = 2, kSmallReduceW = 4;  // reduce_small
 constexpr uint64_t kWaveSpanMax = 65536;             // reduce: longest span one wavefront folds
 constexpr int kReduceBlockW = 4;                     // reduce: wavefronts combined through LDS for longer segments
-constexpr int kCarryU = 8, kCarryW = 16;             // scan with cross-workgroup carry: 65536 elements per workgroup
+constexpr int kCarryU = 8, kCarryW = 16;             // the multi-kernel scan strategies: 65536 elements per workgroup
 constexpr uint64_t kCarryTile = (uint64_t)kTile * kCarryU * kCarryW;
 constexpr uint64_t kMaxElements = 1ull << 38;        // keeps every grid below 2^31 workgroups
 constexpr uint64_t kFusedPartialsMax = 4096;         // partials one workgroup adds up at the end of a fused long reduction
@@ -402,8 +403,9 @@ void launch_scan_block(const _Float16* in, void* out, uint64_t n, uint64_t seg_m
 // through the look-back when a segment is longer than the share.  One ticket costs about 12 ns of
 // a chip-wide serial resource, so ticketed shares start at 16384 elements.
 // Ids 10 and 11 are scan_chain_kernel: persistent workgroups (one per compute unit) that take
-// tiles by ticket in a loop and load the next tile while they look back for the current one; for
-// segments longer than the share (or the one-segment scan), matrix-core formulation only.
+// 32768-element tiles by ticket in a loop and keep three in flight (loading, aggregate published,
+// carry looked up and stored); for segments of at least one tile and the one-segment scan,
+// matrix-core formulation only, n a multiple of 8.
 struct ScanShape { int u, w; bool ticket; int persistent; };      // persistent: workgroups per compute unit (0: one per tile)
 constexpr ScanShape kScanShapes[] = {{1, 2, false, 0}, {1, 4, false, 0}, {1, 8, false, 0}, {1, 16, false, 0},
                                      {2, 16, false, 0}, {4, 16, false, 0}, {8, 16, false, 0}, {2, 16, true, 0},
@@ -504,7 +506,8 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
         if (st != TCR_OK) return st;
         st = begin_lookback(ws, s, tiles, &dev);
         if (st != TCR_OK) return st;
-        uint64_t tickets = tiles;
+        uint64_t tickets = tiles;                       // scan_block_kernel: one per workgroup
+        bool chain = false;
         if constexpr (FORM == kMfma) {
             if (kScanShapes[shape].persistent) {
                 const uint64_t resident = (uint64_t)compute_units() * (uint64_t)kScanShapes[shape].persistent;
@@ -515,10 +518,11 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
                 else
                     scan_chain_kernel<8, 8, MODE><<<grid, dim3(8 * kWave), 0, s>>>(in, out, n, seg_mask, dev, (uint32_t)tiles);
                 tickets = tiles + 3 * groups;           // three drawn at the start of every workgroup, one per tile
+                chain = true;
             }
         }
-        if (tickets == tiles) launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
-        st = check_launch("scan_block_kernel");
+        if (!chain) launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
+        st = check_launch(chain ? "scan_chain_kernel" : "scan_block_kernel");
         if (st != TCR_OK) {
             ws->dirty = true;
             return st;

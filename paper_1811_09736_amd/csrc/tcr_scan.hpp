@@ -12,13 +12,19 @@
 //
 //   scan_small_kernel     seg_len in {16, ..., 512}: segments never leave a tile (Scan_16 and
 //                         Scan_16N / Scan_256 territory).
-//   scan_block_kernel     seg_len >= 1024 and the full scan: a workgroup scans 4*U consecutive
+//   scan_block_kernel     seg_len >= 1024 and the full scan: a workgroup scans WAVES*U consecutive
 //                         tiles (Scan_256N per wavefront, the block-level combination through
 //                         LDS), and a segment longer than a workgroup's share gets its carry
 //                         from earlier workgroups either by single-pass decoupled look-back
 //                         (CARRY == kLookback) or from a precomputed table of exclusive prefixes
 //                         (CARRY == kTable, the reduce-then-scan alternative).
-//   scan_partials_kernel  exclusive scan of per-workgroup totals for kTable.
+//   scan_chain_kernel     the same single pass for segments of 32768 elements and more as a
+//                         persistent three-stage pipeline (the dispatched device-level scan,
+//                         Section 5, for the matrix-core formulation).
+//   scan_wave_kernel      one wavefront per segment, a measured dead end (not dispatched).
+//   scan_partials_kernel, gather_totals_kernel, uniform_add_kernel
+//                         the small kernels of the multi-kernel strategies (reduce-then-scan, and
+//                         the paper's scan-then-propagate).
 #pragma once
 #include "tcr_device.hpp"
 #include "tcr_reduce.hpp"
@@ -26,8 +32,8 @@
 namespace tcr {
 
 enum CarryMode { kNoCarry = 0, kLookback = 1, kTable = 2 };
-// Host-side choice of how a carry crosses workgroups: look-back (default), reduce-then-scan
-// (kTable kernels), or the paper's own three-kernel scan-then-propagate.
+// Host-side choice of how a carry crosses workgroups: a single pass (default: scan_chain_kernel or
+// look-back), reduce-then-scan (kTable kernels), or the paper's own three-kernel scan-then-propagate.
 enum CarryStrategy { kStrategyLookback = 0, kStrategyReduceThenScan = 1, kStrategyScanThenPropagate = 2 };
 
 // Inclusive scan over aligned groups of GROUP lanes (GROUP up to 64).
