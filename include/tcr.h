@@ -24,9 +24,14 @@
  *   The library keeps one small workspace per (device, stream), grown on demand by the first
  *   call that needs it; calls issued on one stream are ordered by the stream.  Calls that
  *   share a stream from several host threads must be serialised by the caller.
- *   HIP graphs: calls that use no workspace (scans with seg_len <= 4096, reduces with seg_len <= 262144, the
- *   untuned and irregular kernels; default variant and tuning) may be recorded into a graph; a call that needs
- *   the workspace returns TCR_ERR_UNSUPPORTED while its stream is capturing and records nothing.
+ *   HIP graphs: every call may be recorded into a graph, provided the workspace it needs exists already: a
+ *   call that would have to allocate, grow or initialise workspace while its stream is capturing returns
+ *   TCR_ERR_UNSUPPORTED and records nothing (run the same call once outside the capture, or supply a workspace
+ *   and run one chained scan on it first).  Calls that use no workspace (scans with seg_len <= 4096, reduces
+ *   with seg_len <= 262144, other segment lengths, irregular segments; default variant and tuning) never do.
+ *   From the first recorded chained scan on, the workspace keeps its launch counters on the device and every
+ *   chained scan on it, recorded or not, is preceded by one small bookkeeping kernel.  The "fused"
+ *   reduce_finish variant cannot be recorded.
  *   There is no CPU fallback: without a usable HIP device every call returns TCR_ERR_HIP.
  */
 #ifndef TCR_H

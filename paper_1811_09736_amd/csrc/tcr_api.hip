@@ -62,9 +62,13 @@ struct Workspace {
     uint64_t desc_capacity = 0;     // tiles
     float* partials = nullptr;
     uint64_t partials_capacity = 0; // floats
-    uint32_t* counters = nullptr;   // [0] = ticket, [1] = gave_up flag
+    uint32_t* counters = nullptr;   // [0] = ticket, [1] = gave_up flag, [2] = latest epoch, [3] = ticket base (device-managed)
     uint32_t tickets_issued = 0;    // host mirror of counters[0] once all enqueued launches finish
     uint32_t epoch = 0;
+    // Once a launch that chains tiles has been recorded into a HIP graph, epoch and ticket base live on the
+    // device (advanced by chain_begin_kernel in front of every launch) and the two host mirrors above are
+    // no longer used: a replayed graph repeats its kernel arguments.
+    bool device_managed = false;
     bool dirty = true;              // counters / descriptors must be re-zeroed before use
     bool caller_owned = false;      // memory supplied through tcr_set_workspace: never grown, never freed
     bool flag_valid = true;         // false until the first clean-up has written the caller's (uninitialised) flag word
@@ -108,13 +112,13 @@ tcr_status acquire_table(int device, uint64_t tiles, unsigned long long** ptr, u
     return TCR_OK;
 }
 
-// Every call that needs library-owned memory comes through here.  Such calls cannot be recorded into a
-// HIP graph: they may allocate, and the look-back epoch and ticket base are host-side counters passed as
-// kernel arguments, which a replayed graph would repeat.
-tcr_status get_workspace(hipStream_t stream, Workspace** out) {
+// Every call that needs workspace memory comes through here.  *capturing tells the caller that the stream
+// is recording a HIP graph: nothing may then be allocated, cleared or synchronised, so a workspace that is
+// too small or not yet initialised makes the call return TCR_ERR_UNSUPPORTED.
+tcr_status get_workspace(hipStream_t stream, Workspace** out, bool* capturing) {
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     TCR_HIP(hipStreamIsCapturing(stream, &capture));
-    if (capture != hipStreamCaptureStatusNone) return TCR_ERR_UNSUPPORTED;
+    *capturing = capture != hipStreamCaptureStatusNone;
     int dev = 0;
     TCR_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
@@ -123,9 +127,10 @@ tcr_status get_workspace(hipStream_t stream, Workspace** out) {
     return TCR_OK;
 }
 
-tcr_status ensure_partials(Workspace* ws, hipStream_t stream, uint64_t floats) {
+tcr_status ensure_partials(Workspace* ws, hipStream_t stream, uint64_t floats, bool capturing) {
     if (floats <= ws->partials_capacity) return TCR_OK;
     if (ws->caller_owned) return TCR_ERR_WORKSPACE;
+    if (capturing) return TCR_ERR_UNSUPPORTED;
     TCR_HIP(hipStreamSynchronize(stream));
     if (ws->partials) TCR_HIP(hipFree(ws->partials));
     ws->partials = nullptr;
@@ -140,15 +145,16 @@ tcr_status ensure_partials(Workspace* ws, hipStream_t stream, uint64_t floats) {
     return TCR_OK;
 }
 
-// Makes room for `tiles` look-back descriptors and starts a new epoch.
-tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, ScanWorkspace* dev) {
+// Makes room for `tiles` descriptors and starts a new epoch (tiles == 0: only the running counter is wanted).
+tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, ScanWorkspace* dev, bool capturing) {
     if (ws->caller_owned && tiles > ws->desc_capacity) return TCR_ERR_WORKSPACE;
+    if (capturing && (ws->counters == nullptr || tiles > ws->desc_capacity || ws->dirty)) return TCR_ERR_UNSUPPORTED;
     if (ws->counters == nullptr) {
-        if (hipMalloc(&ws->counters, 2 * sizeof(uint32_t)) != hipSuccess) {
+        if (hipMalloc(&ws->counters, 4 * sizeof(uint32_t)) != hipSuccess) {
             (void)hipGetLastError();
             return TCR_ERR_WORKSPACE;
         }
-        TCR_HIP(hipMemset(ws->counters, 0, 2 * sizeof(uint32_t)));
+        TCR_HIP(hipMemset(ws->counters, 0, 4 * sizeof(uint32_t)));
         ws->tickets_issued = 0;
         ws->dirty = true;
     }
@@ -164,23 +170,33 @@ tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t tiles, Sca
         if (st != TCR_OK) return st;
         ws->dirty = true;
     }
-    if (ws->dirty || ws->epoch >= (1u << 30) - 2u) {
+    if (ws->dirty || (!ws->device_managed && ws->epoch >= (1u << 30) - 2u)) {
         // first use, growth, a failed launch, or epoch wrap: start from a clean slate
         TCR_HIP(hipStreamSynchronize(stream));
         if (ws->desc_capacity) TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
         uint32_t keep_flag = 0;
         if (ws->flag_valid) TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
         ws->flag_valid = true;
-        uint32_t init[2] = {0u, keep_flag};
+        uint32_t init[4] = {0u, keep_flag, 0u, 0u};
         TCR_HIP(hipMemcpy(ws->counters, init, sizeof(init), hipMemcpyHostToDevice));
         ws->tickets_issued = 0;
         ws->epoch = 0;
         ws->dirty = false;
     }
-    ws->epoch += 1;
+    if (capturing) ws->device_managed = true;         // for good: the host can no longer follow the counters
     dev->desc = ws->desc;
     dev->ticket = ws->counters;
     dev->gave_up = ws->counters + 1;
+    dev->state = ws->counters + 2;
+    dev->device_managed = ws->device_managed ? 1u : 0u;
+    if (ws->device_managed) {
+        chain_begin_kernel<<<dim3(1), dim3(kBeginThreads), 0, stream>>>(ws->counters, ws->desc, ws->desc_capacity);
+        if (hip_failed(hipGetLastError(), "chain_begin_kernel")) return TCR_ERR_HIP;
+        dev->ticket_base = 0;
+        dev->epoch = 0;
+        return TCR_OK;
+    }
+    ws->epoch += 1;
     dev->ticket_base = ws->tickets_issued;
     dev->epoch = ws->epoch;
     return TCR_OK;
@@ -333,21 +349,20 @@ tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_
     const ReducePlan p = plan_reduce(n, seg_len, whole);
     const uint64_t nseg = whole ? 1 : n / seg_len;
     float* dst = out;
+    Workspace* ws = nullptr;
+    bool capturing = false;
     if (p.per > 1) {
-        Workspace* ws = nullptr;
-        tcr_status st = get_workspace(s, &ws);
+        tcr_status st = get_workspace(s, &ws, &capturing);
         if (st != TCR_OK) return st;
-        st = ensure_partials(ws, s, nseg * p.per);
+        st = ensure_partials(ws, s, nseg * p.per, capturing);
         if (st != TCR_OK) return st;
         dst = ws->partials;
     }
     if (p.per > 1 && g_variant.reduce_fused && nseg * p.per <= kFusedPartialsMax) {
         // one kernel: the workgroup that finishes last adds up the partials
-        Workspace* ws = nullptr;
-        tcr_status st = get_workspace(s, &ws);
-        if (st != TCR_OK) return st;
+        if (capturing || ws->device_managed) return TCR_ERR_UNSUPPORTED;     // its count base is a kernel argument
         ScanWorkspace dev = {};
-        st = begin_lookback(ws, s, 0, &dev);              // the running counter that also hands out scan tiles
+        tcr_status st = begin_lookback(ws, s, 0, &dev, false);   // the running counter that also hands out scan tiles
         if (st != TCR_OK) return st;
         const ReduceFinish fin = {out, dev.ticket, dev.ticket_base, (uint32_t)nseg, (uint32_t)p.per};
         st = g_variant.formulation == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s, &fin)
@@ -502,9 +517,10 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
         const uint64_t tiles = ceil_div(n, scan_shape_tile(shape));
         ScanWorkspace dev = {};
         Workspace* ws = nullptr;
-        tcr_status st = get_workspace(s, &ws);
+        bool capturing = false;
+        tcr_status st = get_workspace(s, &ws, &capturing);
         if (st != TCR_OK) return st;
-        st = begin_lookback(ws, s, tiles, &dev);
+        st = begin_lookback(ws, s, tiles, &dev, capturing);
         if (st != TCR_OK) return st;
         uint64_t tickets = tiles;                       // scan_block_kernel: one per workgroup
         bool chain = false;
@@ -535,9 +551,10 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
         if (MODE != 0) return TCR_ERR_UNSUPPORTED;
         const uint64_t shares = ceil_div(n, kCarryTile);
         Workspace* w = nullptr;
-        tcr_status st = get_workspace(s, &w);
+        bool capturing = false;
+        tcr_status st = get_workspace(s, &w, &capturing);
         if (st != TCR_OK) return st;
-        st = ensure_partials(w, s, shares);
+        st = ensure_partials(w, s, shares, capturing);
         if (st != TCR_OK) return st;
         const ScanWorkspace none = {};
         float* o = static_cast<float*>(out);
@@ -557,10 +574,11 @@ tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len
     const uint64_t tiles = ceil_div(n, kCarryTile);
     ScanWorkspace dev = {};
     Workspace* ws = nullptr;
-    tcr_status st = get_workspace(s, &ws);
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
     if (st != TCR_OK) return st;
     // reduce-then-scan: workgroup totals, their exclusive scan per segment, then the scan proper
-    st = ensure_partials(ws, s, tiles);
+    st = ensure_partials(ws, s, tiles, capturing);
     if (st != TCR_OK) return st;
     // one wavefront span per workgroup tile; spans are uniform because seg_len is a multiple of the tile (or one segment)
     st = launch_reduce_span<FORM>(in, ws->partials, n, kCarryTile, tiles, 1, s);

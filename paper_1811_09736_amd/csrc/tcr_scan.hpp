@@ -199,7 +199,40 @@ struct ScanWorkspace {
     uint32_t* gave_up;          // set to 1 if a bounded wait expired
     uint32_t ticket_base;       // value of *ticket when this launch starts
     uint32_t epoch;
+    // state[0]: epoch of the latest launch, state[1]: *ticket at its start.  Host-managed workspaces
+    // (device_managed == 0) pass epoch and ticket_base above and the launch only records its epoch in
+    // state[0]; device-managed ones (launches recorded into HIP graphs, whose arguments are frozen)
+    // take both from state[], which chain_begin_kernel advances in front of every launch.
+    uint32_t* state;
+    uint32_t device_managed;
 };
+
+__device__ __forceinline__ ScanWorkspace resolve_workspace(ScanWorkspace w) {
+    if (w.state != nullptr && w.device_managed) {
+        w.epoch = w.state[0];
+        w.ticket_base = w.state[1];
+    }
+    return w;
+}
+
+// Device-managed workspaces: one workgroup, enqueued in front of every launch that chains tiles.  Starts a
+// new epoch (clearing the descriptor table when the 30-bit epoch wraps) and records the ticket count the
+// launch starts from -- every earlier launch on the stream has finished drawing by now.
+constexpr int kBeginThreads = 256;
+__global__ __launch_bounds__(kBeginThreads) void chain_begin_kernel(uint32_t* __restrict__ counters,
+                                                                    unsigned long long* __restrict__ desc,
+                                                                    uint64_t desc_capacity) {
+    uint32_t epoch = counters[2] + 1u;
+    if (epoch >= (1u << 30) - 2u) {
+        for (uint64_t i = threadIdx.x; i < desc_capacity; i += kBeginThreads) desc[i] = 0ull;
+        epoch = 1u;
+    }
+    __syncthreads();                                  // every thread has read the old epoch
+    if (threadIdx.x == 0) {
+        counters[2] = epoch;
+        counters[3] = counters[0];
+    }
+}
 
 __device__ __forceinline__ unsigned long long pack_desc(uint32_t epoch, uint32_t status, float v) {
     return ((unsigned long long)(epoch * 4u + status) << 32) | (unsigned long long)__builtin_bit_cast(uint32_t, v);
@@ -284,9 +317,10 @@ template <int FORM, int U, int WAVES, int CARRY, int LBK = 64, bool TICKET = tru
 __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float16* __restrict__ in,
                                                                    void* __restrict__ out, uint64_t n,
                                                                    uint64_t seg_mask, uint64_t seg_len,
-                                                                   ScanWorkspace ws,
+                                                                   ScanWorkspace ws_arg,
                                                                    const float* __restrict__ tile_prefix) {
     constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
+    const ScanWorkspace ws = resolve_workspace(ws_arg);
     constexpr uint64_t kChunk = (uint64_t)kTile * U;             // one wavefront's share
     constexpr uint64_t kBlockTile = kChunk * WAVES;              // one workgroup's share
     __shared__ float s_wave_total[WAVES];
@@ -309,6 +343,9 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
             s_tile = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
         __syncthreads();
         tile = s_tile;
+    }
+    if constexpr (CARRY == kLookback) {
+        if (tile == 0 && threadIdx.x == 0 && ws.state != nullptr && !ws.device_managed) ws.state[0] = ws.epoch;
     }
     const uint64_t block_base = (uint64_t)tile * kBlockTile;
     const uint64_t base = block_base + (uint64_t)wave * kChunk;
@@ -588,9 +625,10 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
 template <int U, int WAVES, int MODE>
 __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float16* __restrict__ in,
                                                                    void* __restrict__ out, uint64_t n,
-                                                                   uint64_t seg_mask, ScanWorkspace ws,
+                                                                   uint64_t seg_mask, ScanWorkspace ws_arg,
                                                                    uint32_t tiles) {
     static_assert(WAVES <= 16, "");
+    const ScanWorkspace ws = resolve_workspace(ws_arg);
     __shared__ ChainShared sh;
     __shared__ uint32_t s_draw;
 
@@ -604,6 +642,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
     __syncthreads();
     const uint32_t first = __builtin_amdgcn_readfirstlane(s_draw);
+    if (first == 0 && threadIdx.x == 0 && ws.state != nullptr && !ws.device_managed) ws.state[0] = ws.epoch;
     if (first >= tiles) {
         // keeps the number of tickets drawn per launch fixed: three per workgroup plus one per tile
         if (threadIdx.x == 0) {

@@ -1,5 +1,6 @@
-"""HIP graph capture: calls that need no library workspace can be recorded and replayed; calls that need it
-refuse while the stream is capturing (their epoch and ticket arguments would be frozen into the graph)."""
+"""HIP graph capture: calls that need no workspace can always be recorded and replayed; calls that need one can
+once it exists (a recorded launch takes its epoch and ticket base from the device, not from frozen kernel
+arguments), and refuse while it would have to be created during the capture."""
 import numpy as np
 import pytest
 import torch
@@ -41,11 +42,6 @@ def test_capture_and_replay_of_workspace_free_calls(tcr, oracle):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         calls()
-        with pytest.raises(tcr.TcrError) as err:         # needs the look-back workspace: refused, nothing recorded
-            tcr.segmented_scan(x, 1 << 16, out=scan4096)
-        assert err.value.status == tcr.ERR_UNSUPPORTED
-        with pytest.raises(tcr.TcrError):
-            tcr.scan(x, out=scan4096)
     for k in (1, 2, 0, 1):                               # several replays, eager work and synchronisation in between
         x.copy_(torch.from_numpy(inputs[k]).cuda())
         for t in (scan256, scan4096, red16, red64k):
@@ -61,3 +57,57 @@ def test_capture_and_replay_of_workspace_free_calls(tcr, oracle):
         # the eager long scan still works between replays
         got = tcr.scan(x).cpu().numpy().astype(np.float64)
         assert np.array_equal(got, oracle.scan(h))
+
+
+def test_chained_scans_in_a_graph(tcr, oracle):
+    n = (1 << 22) + 4096
+    inputs = [workloads.make_input(n, "int8", (23, k)) for k in range(3)]
+    x = torch.from_numpy(inputs[0]).cuda()
+    full = torch.empty(n, dtype=torch.float32, device="cuda")
+    seg = torch.empty(1 << 22, dtype=torch.float32, device="cuda")
+    look = torch.empty(n - 8, dtype=torch.float32, device="cuda")
+    total = torch.empty(1, dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+
+    def calls():
+        tcr.scan(x, out=full)                                  # the pipelined chain
+        tcr.segmented_scan(x[: 1 << 22], 1 << 17, out=seg)     # chained segments
+        tcr.tuning_import("scan:41=9;")
+        tcr.scan(x[: n - 8], out=look)                         # decoupled look-back on the same table
+        tcr.tuning_import("")
+        tcr.reduce(x, out=total)                               # partials + second kernel
+
+    # a workspace that does not exist yet cannot be created while capturing
+    tcr.release()
+    torch.cuda.synchronize()
+    fresh = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(fresh, stream=side):
+        with pytest.raises(tcr.TcrError) as err:
+            tcr.scan(x, out=full)
+        assert err.value.status == tcr.ERR_UNSUPPORTED
+        tcr.segmented_scan(x, 256, out=full)                   # something to record, so the capture is not empty
+    with torch.cuda.stream(side):
+        calls()                                                # eager once on the capture stream: its workspace exists now
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    for k in (1, 2, 0, 1, 2):
+        x.copy_(torch.from_numpy(inputs[k]).cuda())
+        for t in (full, seg, look, total):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        h = inputs[k]
+        ref = oracle.scan(h)
+        assert np.array_equal(full.cpu().numpy().astype(np.float64), ref)
+        assert np.array_equal(look.cpu().numpy().astype(np.float64), ref[: n - 8])
+        assert np.array_equal(seg.cpu().numpy().astype(np.float64), oracle.segmented_scan(h[: 1 << 22], 1 << 17))
+        assert float(total.cpu()[0]) == oracle.reduce(h)
+        # eager calls on the same stream share the device-managed counters with the graph
+        with torch.cuda.stream(side):
+            got = tcr.scan(x)
+        side.synchronize()
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), ref)
+    tcr.check_device_flags(side)
