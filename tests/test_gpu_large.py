@@ -1,0 +1,105 @@
+"""Beyond 2^31 elements: byte offsets no longer fit 32 bits, the pipelined chain runs 65568 tiles and rebases
+its range-checked buffer resources per tile.  The input is a period-7 integer pattern whose periods sum to
+zero, so every prefix is a small integer with a closed form; every output is compared with that closed form
+(computed with integer index arithmetic on the device, in chunks) and sampled outputs with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+N = (1 << 31) + (1 << 20)
+PATTERN = np.array([3, -1, -2, 2, -3, 0, 1], dtype=np.float16)           # sums to zero
+CHUNK = 1 << 27
+
+
+@pytest.fixture(scope="module")
+def tcr():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    if torch.cuda.get_device_properties(0).total_memory < 40 * (1 << 30):
+        pytest.skip("needs 40 GiB of device memory")
+    from paper_1811_09736_amd import binding
+    binding.set_variant("reset")
+    binding.tuning_import("")
+    yield binding
+    binding.release()
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(scope="module")
+def data():
+    x = np.tile(PATTERN, N // 7 + 1)[:N].copy()
+    return x, torch.from_numpy(x).cuda()
+
+
+def _prefix_table(device):
+    return torch.tensor(np.concatenate([[0.0], np.cumsum(PATTERN.astype(np.float64))[:-1], [0.0]])[:8],
+                        dtype=torch.float32, device=device)
+
+
+def _expected_scan_chunk(lo, hi, seg, device):
+    """Inclusive scan restarted every `seg` elements, positions lo .. hi-1: P(k) - P(start - 1) with
+    P(k) = sum of the pattern's first (k mod 7) + 1 entries (whole periods add nothing)."""
+    incl = torch.tensor(np.cumsum(PATTERN.astype(np.float64)), dtype=torch.float32, device=device)
+    k = torch.arange(lo, hi, dtype=torch.int64, device=device)
+    start = k - k % seg
+    before = torch.where(start % 7 == 0, torch.zeros((), device=device), incl[(start - 1) % 7])
+    return incl[k % 7] - before
+
+
+@pytest.mark.parametrize("seg", [1 << 20, N])
+def test_scan_beyond_2_31_elements(tcr, oracle, data, seg):
+    x, xd = data
+    print(f"  scan n={N} seg={seg} kernel={tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, N, seg)}", flush=True)
+    out = tcr.segmented_scan(xd, seg)
+    for lo in range(0, N, CHUNK):
+        hi = min(lo + CHUNK, N)
+        want = _expected_scan_chunk(lo, hi, seg, xd.device)
+        if not torch.equal(out[lo:hi], want):
+            bad = lo + int(torch.nonzero(out[lo:hi] != want)[0])
+            raise AssertionError(f"first mismatch at {bad}: got {float(out[bad])} want {float(want[bad - lo])}")
+    # sampled outputs against the oracle (each sample walks its segment from the start)
+    rng = np.random.default_rng(5)
+    idx = np.concatenate([rng.integers(0, N, 6), [N - 1, (1 << 31) + 12345]]).astype(np.uint64)
+    if seg == N:
+        idx = idx[-2:]                                       # two long walks are enough
+    ref = oracle.segmented_scan_at(x, seg, idx)
+    got = out[torch.from_numpy(idx.astype(np.int64)).cuda()].cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, ref)
+    tcr.check_device_flags()
+    del out
+
+
+def test_scan_variants_and_reduce_beyond_2_31_elements(tcr, oracle, data):
+    x, xd = data
+    seg = 1 << 20
+    # small segments (one tile per wavefront kernels) and the binary16 / exclusive outputs
+    out = tcr.segmented_scan(xd, 256)
+    for lo in range(0, N, CHUNK):
+        hi = min(lo + CHUNK, N)
+        assert torch.equal(out[lo:hi], _expected_scan_chunk(lo, hi, 256, xd.device)), f"seg 256, chunk at {lo}"
+    del out
+    out16 = tcr.segmented_scan_ex(xd, seg, tcr.OUT_F16 | tcr.SCAN_EXCLUSIVE)
+    for lo in range(0, N, CHUNK):
+        hi = min(lo + CHUNK, N)
+        want = _expected_scan_chunk(lo, hi, seg, xd.device) - xd[lo:hi].float()
+        assert torch.equal(out16[lo:hi].float(), want), f"exclusive binary16, chunk at {lo}"
+    del out16
+    # reductions: a segment's total is the last entry of its scan
+    last = torch.arange(seg - 1, N, seg, dtype=torch.int64, device=xd.device)
+    want = torch.cat([_expected_scan_chunk(int(k), int(k) + 1, seg, xd.device) for k in last[:4]] +
+                     [_expected_scan_chunk(int(k), int(k) + 1, seg, xd.device) for k in last[-4:]])
+    red = tcr.segmented_reduce(xd, seg)
+    assert torch.equal(torch.cat([red[:4], red[-4:]]), want)
+    ref = oracle.segmented_scan_at(x, seg, (last.cpu().numpy()[[0, 1000, 2048]]).astype(np.uint64))
+    assert np.array_equal(red[[0, 1000, 2048]].cpu().numpy().astype(np.float64), ref)
+    total = float(tcr.reduce(xd).cpu()[0])
+    assert total == float(np.sum(PATTERN[: N % 7].astype(np.float64)))
+    red16 = tcr.segmented_reduce(xd, 16)
+    k = torch.arange(0, N // 16, dtype=torch.int64, device=xd.device) * 16 + 15
+    incl = torch.tensor(np.cumsum(PATTERN.astype(np.float64)), dtype=torch.float32, device=xd.device)
+    start = k - 15
+    before = torch.where(start % 7 == 0, torch.zeros((), device=xd.device), incl[(start - 1) % 7])
+    assert torch.equal(red16, incl[k % 7] - before)
+    tcr.check_device_flags()
