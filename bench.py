@@ -243,6 +243,9 @@ def main() -> int:
                "sample": f"the same 16 calls on the first 2^{sample_log2} elements of the input (seg_len capped at the sample), "
                          f"sequential binary64 C loops, {dt:.1f} s"}
 
+    props = torch.cuda.get_device_properties(0)
+    device = {"name": props.name, "compute_units": props.multi_processor_count,
+              "memory_GiB": round(props.total_memory / 2 ** 30, 1)}
     line = {
         "metric": "effective input GB/s (% of HBM peak) for seg-reduce/scan at N=2^" + str(args.log2n),
         "pct_of_hbm_peak": round(sum(sum(workloads.algorithmic_bytes(op, n, 1 << e)) for op, e in calls)
@@ -254,7 +257,7 @@ def main() -> int:
                                "seg_len=2^{%s}; fp32 accumulate and output" % (args.log2n, ",".join(map(str, sweep))),
                    "formulation": args.formulation, "scan_carry": args.scan_carry,
                    "input_sha256": workloads.sha256(x_host)[:16]},
-        "roofline": roofline, "cpu_baseline": cpu, "measured_copy_GBps": copy_gbps, "tuning": tcr.tuning_export(), "rows": rows, "context_rows": extra,
+        "roofline": roofline, "cpu_baseline": cpu, "measured_copy_GBps": copy_gbps, "device": device, "tuning": tcr.tuning_export(), "rows": rows, "context_rows": extra,
     }
     print(json.dumps(line))
     return 0
