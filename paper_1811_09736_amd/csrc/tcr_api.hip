@@ -407,7 +407,7 @@ template <int FORM, int U, int W, int CARRY, int MODE>
 void launch_scan_block(const _Float16* in, void* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
                        const ScanWorkspace& dev, const float* prefix, hipStream_t s) {
     const unsigned blocks = (unsigned)ceil_div(n, (uint64_t)kTile * U * W);
-    scan_block_kernel<FORM, U, W, CARRY, 64, true, false, MODE><<<dim3(blocks), dim3(W * kWave), 0, s>>>(
+    scan_block_kernel<FORM, U, W, CARRY, MODE><<<dim3(blocks), dim3(W * kWave), 0, s>>>(
         in, out, n, seg_mask, seg_len, dev, prefix);
 }
 

@@ -21,7 +21,6 @@
 //   scan_chain_kernel     the same single pass for segments of 32768 elements and more as a
 //                         persistent three-stage pipeline (the dispatched device-level scan,
 //                         Section 5, for the matrix-core formulation).
-//   scan_wave_kernel      one wavefront per segment, a measured dead end (not dispatched).
 //   scan_partials_kernel, gather_totals_kernel, uniform_add_kernel
 //                         the small kernels of the multi-kernel strategies (reduce-then-scan, and
 //                         the paper's scan-then-propagate).
@@ -130,57 +129,6 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
         } else {
             store4_guarded_t<F16>(out, off_lo, n, lo);
             store4_guarded_t<F16>(out, off_hi, n, hi);
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------ one wavefront per segment
-// Scan_256N as a stream: wavefront w walks segment w tile by tile, U tiles in flight, and the
-// running total of the tiles already done (the paper's S matrix) enters each tile's products
-// through the accumulator.  No LDS, no barrier, no dependence between wavefronts.
-// n is a multiple of seg_len; seg_len is a multiple of the tile size.
-template <int FORM, int U, int WAVES>
-__global__ __launch_bounds__(WAVES * kWave) void scan_wave_kernel(const _Float16* __restrict__ in,
-                                                                  float* __restrict__ out, uint64_t n,
-                                                                  uint64_t seg_len) {
-    const LaneId id;
-    const uint64_t seg = (uint64_t)blockIdx.x * WAVES + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint64_t begin = seg * seg_len;
-    if (begin >= n) return;
-    const uint64_t end = begin + seg_len;
-    const int lane_off = (FORM == kMfma) ? (kRow * id.j + 8 * id.g) : (8 * id.lane);
-    const int store_off = (FORM == kMfma) ? (kRow * id.j + 4 * id.g) : (8 * id.lane);
-    constexpr int kHi = (FORM == kMfma) ? 16 : 4;      // distance between a lane's two 4-element outputs
-    float run = 0.0f;                                  // total of the tiles of this segment already done
-    for (uint64_t t = begin; t < end; t += (uint64_t)(kTile * U)) {
-        half8 x[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (t + (uint64_t)(kTile * u) < end) x[u] = load8(in, t + (uint64_t)(kTile * u + lane_off));
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint64_t tbase = t + (uint64_t)(kTile * u);
-            if (tbase < end) {
-                float4v lo, hi;
-                if constexpr (FORM == kMfma) {
-                    const float4v tot = mfma(const_ones(), x[u], splat(0.0f));
-                    const float incl = row_scan_inclusive<16>(tot[0], id.j);
-                    const float carry = row_shr<1>(incl) + run;
-                    lo = mfma(const_tri_lo(id), x[u], splat(carry));
-                    hi = mfma(const_tri_hi(id), x[u], splat(carry));
-                    run += read_lane(incl, 15);
-                } else {
-                    float p[8];
-                    const float lane_total = scan8(x[u], p);
-                    const float incl = wave_scan_inclusive(lane_total);
-                    const float carry = wave_shr1(incl) + run;
-                    lo = (float4v){p[0] + carry, p[1] + carry, p[2] + carry, p[3] + carry};
-                    hi = (float4v){p[4] + carry, p[5] + carry, p[6] + carry, p[7] + carry};
-                    run += read_lane(incl, 63);
-                }
-                store4(out, tbase + (uint64_t)store_off, lo);
-                store4(out, tbase + (uint64_t)(store_off + kHi), hi);
-            }
         }
     }
 }
@@ -313,7 +261,7 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
 // seg_len   only compared against the wavefront / workgroup share (saturated for the full scan).
 // Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.
 // MODE bit 0: exclusive scan; bit 1: binary16 output.
-template <int FORM, int U, int WAVES, int CARRY, int LBK = 64, bool TICKET = true, bool XCDPART = false, int MODE = 0>
+template <int FORM, int U, int WAVES, int CARRY, int MODE = 0>
 __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float16* __restrict__ in,
                                                                    void* __restrict__ out, uint64_t n,
                                                                    uint64_t seg_mask, uint64_t seg_len,
@@ -330,13 +278,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
     const LaneId id;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: keeps per-wave branches and addresses scalar
     uint32_t tile = blockIdx.x;
-    if constexpr (XCDPART) {
-        // workgroups go round-robin to the 8 XCDs: give each XCD one contiguous eighth of the tiles
-        const uint32_t per_xcd = (gridDim.x + 7u) >> 3;
-        tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-        if ((uint64_t)tile * ((uint64_t)kTile * U * WAVES) >= n) return;
-    }
-    if constexpr (CARRY == kLookback && TICKET) {
+    if constexpr (CARRY == kLookback) {
         // tiles are handed out in launch order, so every predecessor of a waiting tile is
         // already running or finished
         if (threadIdx.x == 0)
@@ -402,7 +344,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
 #pragma unroll
                     for (int w = 0; w < WAVES; ++w) total += s_wave_total[w];
                     const uint32_t pos = (uint32_t)((block_base & seg_mask) / kBlockTile);
-                    const float pre = lookback_exclusive_prefix<LBK>(ws, tile, pos, total, id.lane);
+                    const float pre = lookback_exclusive_prefix<64>(ws, tile, pos, total, id.lane);
                     if (id.lane == 0) s_prefix = pre;
                 }
                 __syncthreads();
