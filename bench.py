@@ -175,6 +175,8 @@ def main() -> int:
     # length without a tuned path
     extra = []
     out_one = torch.empty(1, dtype=torch.float32, device="cuda")
+    big = 3 << 20
+    nb = (n // big) * big
     n3 = (n // 3000) * 3000
     out_g = torch.empty(n3 // 3000, dtype=torch.float32, device="cuda")
     out_h = torch.empty(n, dtype=torch.float16, device="cuda")
@@ -202,6 +204,10 @@ def main() -> int:
     for label, fn, nn, rd_wr in variant_rows + library_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
+            ("segmented_reduce seg_len=3*2^20 (no power of two: masked pieces + second kernel)",
+             lambda: tcr.segmented_reduce(x[:nb], big, out=out_g[: nb // big]), nb, (2 * nb, 4 * (nb // big))),
+            ("segmented_scan seg_len=3*2^20 (no power of two: chain on a per-segment tile grid)",
+             lambda: tcr.segmented_scan(x[:nb], big, out=out_scan[:nb]), nb, (2 * nb, 4 * nb)),
             ("segmented_reduce seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
             ("segmented_scan seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,

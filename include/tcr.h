@@ -57,7 +57,8 @@ typedef enum {
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
  * seg_len == n; other lengths run one wavefront per segment (from 256 elements on over zero-masked tiles of
- * the array, the paper's padding of such segments, Section 4, applied in registers).
+ * the array, the paper's padding of such segments, Section 4, applied in registers), long ones (from 65536
+ * elements for scans with seg_len % 8 == 0, from 131072 for reductions) the device-level algorithms.
  */
 tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 

@@ -303,6 +303,34 @@ inline int nocarry_shape_for(uint64_t fit) {
     return 6;
 }
 
+// The persistent chain (shape 10 or 11) over segments of `seg_len` elements: any multiple of 8 that is at
+// least one tile, or one segment of n elements (n a multiple of 8).  Matrix-core formulation.
+template <int MODE>
+tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    const uint64_t tile = scan_shape_tile(shape);
+    const uint64_t per_segment = ceil_div(seg_len, tile);
+    const uint64_t tiles = (n / seg_len) * per_segment;
+    ScanWorkspace dev = {};
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    st = begin_lookback(ws, s, tiles, &dev, capturing);
+    if (st != TCR_OK) return st;
+    const uint64_t resident = (uint64_t)compute_units() * (uint64_t)kScanShapes[shape].persistent;
+    const uint64_t groups = tiles < resident ? tiles : resident;
+    const ChainGrid grid = {seg_len, (uint32_t)per_segment, (uint32_t)tiles};
+    if (shape == 10) scan_chain_kernel<4, 16, MODE><<<dim3((unsigned)groups), dim3(16 * kWave), 0, s>>>(in, out, grid, dev);
+    else scan_chain_kernel<8, 8, MODE><<<dim3((unsigned)groups), dim3(8 * kWave), 0, s>>>(in, out, grid, dev);
+    st = check_launch("scan_chain_kernel");
+    if (st != TCR_OK) {
+        ws->dirty = true;
+        return st;
+    }
+    ws->tickets_issued += (uint32_t)(tiles + 3 * groups);   // three drawn at the start of every workgroup, one per tile
+    return TCR_OK;
+}
+
 // seg_len >= 1024 (power of two), or the full scan (seg_len == n, any n).
 template <int FORM, int MODE>
 inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, bool whole, hipStream_t s) {
@@ -322,6 +350,9 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
             launch_scan_shape<FORM, kNoCarry, MODE>(shape, in, out, n, seg_mask, seg_len, none, nullptr, s);
             return check_launch("scan_block_kernel");
         }
+        if constexpr (FORM == kMfma) {
+            if (kScanShapes[shape].persistent) return launch_chain<MODE>(shape, in, out, n, host_seg_len, s);
+        }
         const uint64_t tiles = ceil_div(n, scan_shape_tile(shape));
         ScanWorkspace dev = {};
         Workspace* ws = nullptr;
@@ -330,28 +361,13 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
         if (st != TCR_OK) return st;
         st = begin_lookback(ws, s, tiles, &dev, capturing);
         if (st != TCR_OK) return st;
-        uint64_t tickets = tiles;                       // scan_block_kernel: one per workgroup
-        bool chain = false;
-        if constexpr (FORM == kMfma) {
-            if (kScanShapes[shape].persistent) {
-                const uint64_t resident = (uint64_t)compute_units() * (uint64_t)kScanShapes[shape].persistent;
-                const uint64_t groups = tiles < resident ? tiles : resident;
-                const dim3 grid((unsigned)groups);
-                if (shape == 10)
-                    scan_chain_kernel<4, 16, MODE><<<grid, dim3(16 * kWave), 0, s>>>(in, out, n, seg_mask, dev, (uint32_t)tiles);
-                else
-                    scan_chain_kernel<8, 8, MODE><<<grid, dim3(8 * kWave), 0, s>>>(in, out, n, seg_mask, dev, (uint32_t)tiles);
-                tickets = tiles + 3 * groups;           // three drawn at the start of every workgroup, one per tile
-                chain = true;
-            }
-        }
-        if (!chain) launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
-        st = check_launch(chain ? "scan_chain_kernel" : "scan_block_kernel");
+        launch_scan_shape<FORM, kLookback, MODE>(shape, in, out, n, seg_mask, seg_len, dev, nullptr, s);
+        st = check_launch("scan_block_kernel");
         if (st != TCR_OK) {
             ws->dirty = true;
             return st;
         }
-        ws->tickets_issued += (uint32_t)tickets;    // wraps modulo 2^32 like the device counter
+        ws->tickets_issued += (uint32_t)tiles;      // one per workgroup; wraps modulo 2^32 like the device counter
         return TCR_OK;
     }
     if (g_variant.scan_carry == kStrategyScanThenPropagate) {
@@ -429,8 +445,24 @@ inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint
         }
         return check_launch("masked_wave_scan_kernel");
     } else {
-        masked_wave_reduce_kernel<<<grid, block, 0, s>>>(in, static_cast<float*>(out), nseg, seg_len);
-        return check_launch("masked_wave_reduce_kernel");
+        if (seg_len <= 2 * kWaveSpanMax) {
+            masked_wave_reduce_kernel<<<grid, block, 0, s>>>(in, static_cast<float*>(out), nseg, seg_len);
+            return check_launch("masked_wave_reduce_kernel");
+        }
+        // long segments: pieces of 65536 elements per wavefront, then the paper's second kernel over the pieces
+        const uint64_t per = ceil_div(seg_len, kWaveSpanMax);
+        Workspace* ws = nullptr;
+        bool capturing = false;
+        tcr_status st = get_workspace(s, &ws, &capturing);
+        if (st != TCR_OK) return st;
+        st = ensure_partials(ws, s, nseg * per, capturing);
+        if (st != TCR_OK) return st;
+        masked_span_reduce_kernel<<<dim3((unsigned)ceil_div(nseg * per, kMaskedWaves)), block, 0, s>>>(
+            in, ws->partials, nseg, seg_len, kWaveSpanMax, per);
+        st = check_launch("masked_span_reduce_kernel");
+        if (st != TCR_OK) return st;
+        reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kFinalThreads), 0, s>>>(ws->partials, static_cast<float*>(out), per);
+        return check_launch("reduce_final_kernel");
     }
 }
 
@@ -442,10 +474,28 @@ inline tcr_status scan_tuned(const _Float16* x, void* out, uint64_t n, uint64_t 
     return scan_long<FORM, MODE>(x, out, n, seg_len, false, s);
 }
 
+// Segment lengths that are no power of two but long enough for the persistent chain (its ragged last tile per
+// segment is cut off by the buffer range check, which works on whole 8-element groups).
+inline bool chain_takes_any_length(uint64_t seg_len) {
+    return g_variant.formulation == kMfma && g_variant.scan_carry == kStrategyLookback && seg_len % 8 == 0 &&
+           seg_len >= 2 * scan_shape_tile(10);
+}
+
 inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
     const _Float16* x = static_cast<const _Float16*>(in);
-    if (seg_len != n && (!is_pow2(seg_len) || seg_len < 16)) return launch_generic<true>(x, out, n, seg_len, flags, s);
     const int mode = (int)(flags & 3u);
+    if (seg_len != n && (!is_pow2(seg_len) || seg_len < 16)) {
+        if (chain_takes_any_length(seg_len)) {
+            // long segments of any length that keeps 8-element groups whole: the chain on a per-segment tile grid
+            switch (mode) {
+                case 0: return launch_chain<0>(10, x, out, n, seg_len, s);
+                case 1: return launch_chain<1>(10, x, out, n, seg_len, s);
+                case 2: return launch_chain<2>(10, x, out, n, seg_len, s);
+                default: return launch_chain<3>(10, x, out, n, seg_len, s);
+            }
+        }
+        return launch_generic<true>(x, out, n, seg_len, flags, s);
+    }
     if (g_variant.formulation == kDpp) {
         // the wavefront-primitive alternative is kept for the default mode only
         if (mode != 0) return TCR_ERR_UNSUPPORTED;

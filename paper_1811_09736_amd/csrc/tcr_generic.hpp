@@ -181,6 +181,23 @@ __global__ __launch_bounds__(kMaskedWaves * kWave) void masked_wave_reduce_kerne
     if (id.lane == 0) out[s] = total;
 }
 
+// Long segments of any length: wavefront w adds up piece w % per of segment w / per (pieces of `span` elements
+// counted from the segment's start, the last one shorter) into dst[w]; reduce_final_kernel adds the pieces.
+__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_span_reduce_kernel(const _Float16* __restrict__ in,
+                                                                                  float* __restrict__ dst, uint64_t nseg,
+                                                                                  uint64_t seg_len, uint64_t span,
+                                                                                  uint64_t per) {
+    const LaneId id;
+    const uint64_t w = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (w >= nseg * per) return;
+    const uint64_t s = w / per, piece = w - s * per;
+    const uint64_t begin = s * seg_len + piece * span;
+    const uint64_t seg_end = (s + 1) * seg_len;
+    const uint64_t end = begin + span < seg_end ? begin + span : seg_end;
+    const float total = masked_wave_reduce(in, begin, end, id);
+    if (id.lane == 0) dst[w] = total;
+}
+
 // Irregular segments behind 16-byte aligned pointers: the same walk, boundaries read from `offsets`.
 template <bool SCAN>
 __global__ __launch_bounds__(kMaskedWaves * kWave) void masked_irregular_kernel(const _Float16* __restrict__ in,

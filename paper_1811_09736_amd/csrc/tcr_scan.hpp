@@ -407,7 +407,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
 // Progress: a tile waits only for aggregates of lower tickets.  Each of those is held by a running
 // workgroup, which publishes it after finishing at most two tiles with still lower tickets; so the
 // lowest unfinished ticket can always complete.
-// seg_len >= one workgroup's share or seg_len == n; n % 8 == 0.
+// seg_len: any multiple of 8 that is at least one workgroup's share, or seg_len == n with n % 8 == 0.
 
 // Executed by one whole wavefront: the sum of the published totals of tiles lo .. tile-1, read up to
 // four per lane per round trip.
@@ -466,20 +466,36 @@ struct ChainTile {
     float ext;           // total of the lower wavefronts of the workgroup
     float total;         // wavefront 0: total of the tile
     uint32_t tile;       // ticket; >= tiles: nothing to do
+    uint32_t pos;        // index of the tile inside its segment
+    uint32_t count;      // elements of the wavefront's share that exist (the last tile of a segment is ragged)
+    uint64_t base;       // first element of the wavefront's share
+};
+
+// Tiles are laid out per segment: segment s owns tiles s * per_segment .. (s + 1) * per_segment - 1, which
+// start at s * seg_len and may overhang its end (the overhang is cut off by the buffer range check).  seg_len
+// is any multiple of 8 that is at least one tile; the one-segment scan has seg_len = n and per_segment = tiles.
+struct ChainGrid {
+    uint64_t seg_len;
+    uint32_t per_segment;
+    uint32_t tiles;
 };
 
 // Stage C: request the data of ticket `tile`.
 template <int U, int WAVES>
-__device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const _Float16* __restrict__ in, uint64_t n,
-                                           uint32_t tiles, const LaneId& id, int wave) {
+__device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const _Float16* __restrict__ in,
+                                           const ChainGrid& grid, const LaneId& id, int wave) {
     constexpr uint32_t kChunk = (uint32_t)kTile * U;
     constexpr uint64_t kBlockTile = (uint64_t)kChunk * WAVES;
+    const uint32_t seg = tile / grid.per_segment;
     t.tile = tile;
-    // elements of the wavefront's share that lie inside the array (none for a ticket past the last tile)
-    const uint64_t base = (uint64_t)tile * kBlockTile + (uint64_t)wave * kChunk;
-    const uint64_t left = (tile < tiles && base < n) ? n - base : 0;
-    const uint32_t count = left < kChunk ? (uint32_t)left : kChunk;
-    const __amdgpu_buffer_rsrc_t src = make_rsrc(in + (count ? base : 0), count * 2u);
+    t.pos = tile - seg * grid.per_segment;
+    const uint64_t seg_begin = (uint64_t)seg * grid.seg_len;
+    t.base = seg_begin + (uint64_t)t.pos * kBlockTile + (uint64_t)wave * kChunk;
+    // elements of the wavefront's share inside the segment (none for a ticket past the last tile)
+    const uint64_t seg_end = seg_begin + grid.seg_len;
+    const uint64_t left = (tile < grid.tiles && t.base < seg_end) ? seg_end - t.base : 0;
+    t.count = left < kChunk ? (uint32_t)left : kChunk;
+    const __amdgpu_buffer_rsrc_t src = make_rsrc(in + (t.count ? t.base : 0), t.count * 2u);
 #pragma unroll
     for (int u = 0; u < U; ++u) t.x[u] = buffer_load8(src, (uint32_t)(kTile * u + kRow * id.j + 8 * id.g) * 2u);
 }
@@ -518,18 +534,14 @@ __device__ __forceinline__ void chain_publish(ChainTile<U>& t, const ScanWorkspa
 // own_end / own_incl (wavefront 0): index after the tile this workgroup finished last (0: none yet) and
 // that tile's inclusive prefix.
 template <int U, int WAVES, int MODE>
-__device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restrict__ out, uint64_t n, uint64_t seg_mask,
+__device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restrict__ out,
                                                  const ScanWorkspace& ws, ChainShared& sh, const LaneId& id, int wave,
                                                  uint32_t& own_end, float& own_incl) {
     constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
-    constexpr uint32_t kChunk = (uint32_t)kTile * U;
-    constexpr uint64_t kBlockTile = (uint64_t)kChunk * WAVES;
-    const uint64_t block_base = (uint64_t)t.tile * kBlockTile;
-    const uint64_t base = block_base + (uint64_t)wave * kChunk;
     if (wave == 0) {
         uint32_t drawn = 0u;                      // used only after the reads below, so the draw rides along with them
         if (id.lane == 0) drawn = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t seg_first = t.tile - (uint32_t)((block_base & seg_mask) / kBlockTile);   // first tile of the segment
+        const uint32_t seg_first = t.tile - t.pos;                  // first tile of the segment
         const bool resume = own_end > seg_first;  // the workgroup's previous tile lies in the same segment
         float before = chain_sum_totals(ws, resume ? own_end : seg_first, t.tile, id.lane);
         if (resume) before += own_incl;
@@ -548,10 +560,8 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
     const float ext = t.ext + sh.prefix;
     const uint32_t fresh = __builtin_amdgcn_readfirstlane(sh.ticket);
 
-    const uint64_t left = base < n ? n - base : 0;
-    const uint32_t count = left < kChunk ? (uint32_t)left : kChunk;
     const __amdgpu_buffer_rsrc_t dst =
-        make_rsrc(static_cast<char*>(out) + (count ? base : 0) * (F16 ? 2u : 4u), count * (F16 ? 2u : 4u));
+        make_rsrc(static_cast<char*>(out) + (t.count ? t.base : 0) * (F16 ? 2u : 4u), t.count * (F16 ? 2u : 4u));
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const float carry = t.pre[u] + ext;
@@ -566,10 +576,10 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
 
 template <int U, int WAVES, int MODE>
 __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float16* __restrict__ in,
-                                                                   void* __restrict__ out, uint64_t n,
-                                                                   uint64_t seg_mask, ScanWorkspace ws_arg,
-                                                                   uint32_t tiles) {
+                                                                   void* __restrict__ out, ChainGrid grid,
+                                                                   ScanWorkspace ws_arg) {
     static_assert(WAVES <= 16, "");
+    const uint32_t tiles = grid.tiles;
     const ScanWorkspace ws = resolve_workspace(ws_arg);
     __shared__ ChainShared sh;
     __shared__ uint32_t s_draw;
@@ -594,13 +604,13 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
         return;
     }
     ChainTile<U> a, b, c;
-    chain_load<U, WAVES>(a, first, in, n, tiles, id, wave);
+    chain_load<U, WAVES>(a, first, in, grid, id, wave);
     __syncthreads();                              // s_draw has been read by everyone
     if (threadIdx.x == 0)
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
     __syncthreads();
     const uint32_t second = __builtin_amdgcn_readfirstlane(s_draw);
-    chain_load<U, WAVES>(b, second, in, n, tiles, id, wave);
+    chain_load<U, WAVES>(b, second, in, grid, id, wave);
     chain_publish<U, WAVES>(a, ws, tiles, sh, id, wave);          // (its barrier also orders the reads of s_draw)
     if (threadIdx.x == 0)
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
@@ -615,17 +625,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
     // three tiles per trip, the register sets rotating through the stages, so no tile is ever copied between
     // registers (a copy would have to wait for the loads it copies, and with them for the stores before)
     while (true) {
-        chain_load<U, WAVES>(c, fresh, in, n, tiles, id, wave);
+        chain_load<U, WAVES>(c, fresh, in, grid, id, wave);
         chain_publish<U, WAVES>(b, ws, tiles, sh, id, wave);
-        fresh = chain_finish<U, WAVES, MODE>(a, out, n, seg_mask, ws, sh, id, wave, own_end, own_incl);
+        fresh = chain_finish<U, WAVES, MODE>(a, out, ws, sh, id, wave, own_end, own_incl);
         if (b.tile >= tiles) break;
-        chain_load<U, WAVES>(a, fresh, in, n, tiles, id, wave);
+        chain_load<U, WAVES>(a, fresh, in, grid, id, wave);
         chain_publish<U, WAVES>(c, ws, tiles, sh, id, wave);
-        fresh = chain_finish<U, WAVES, MODE>(b, out, n, seg_mask, ws, sh, id, wave, own_end, own_incl);
+        fresh = chain_finish<U, WAVES, MODE>(b, out, ws, sh, id, wave, own_end, own_incl);
         if (c.tile >= tiles) break;
-        chain_load<U, WAVES>(b, fresh, in, n, tiles, id, wave);
+        chain_load<U, WAVES>(b, fresh, in, grid, id, wave);
         chain_publish<U, WAVES>(a, ws, tiles, sh, id, wave);
-        fresh = chain_finish<U, WAVES, MODE>(c, out, n, seg_mask, ws, sh, id, wave, own_end, own_incl);
+        fresh = chain_finish<U, WAVES, MODE>(c, out, ws, sh, id, wave, own_end, own_incl);
         if (a.tile >= tiles) break;
     }
 }

@@ -280,6 +280,29 @@ def test_pipelined_chain_segmented(tcr, oracle, seg):
     tcr.check_device_flags()
 
 
+@pytest.mark.parametrize("seg", [65536 + 8, 100000, 3 << 16, (3 << 20) + 4096, 1000000])
+def test_long_segments_of_any_length(tcr, oracle, seg):
+    # no power of two: the chain runs on a per-segment tile grid whose last tile overhangs the segment's end;
+    # reductions add 65536-element pieces of every segment
+    tcr.set_variant("reset")
+    nseg = max(3, (9 << 20) // seg)
+    n = seg * nseg
+    assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, n, seg) == "scan_chain_kernel<mfma>"
+    x = workloads.make_input(n, "int8", seg % 983)
+    xd = dev(x)
+    ref = oracle.segmented_scan(x, seg)
+    assert_exact(tcr.segmented_scan(xd, seg), ref, f"scan L={seg}")
+    assert_exact(tcr.segmented_scan_ex(xd, seg, tcr.SCAN_EXCLUSIVE), ref - x.astype(np.float64), f"exclusive scan L={seg}")
+    got16 = tcr.segmented_scan_ex(xd, seg, tcr.OUT_F16).cpu().numpy().astype(np.float64)
+    assert np.array_equal(got16, ref.astype(np.float16).astype(np.float64))
+    assert_exact(tcr.segmented_reduce(xd, seg), oracle.segmented_reduce(x, seg), f"reduce L={seg}")
+    y = workloads.make_input(n, "uniform_pm1", 19)
+    yd = dev(y)
+    assert_close_scan(tcr.segmented_scan(yd, seg), oracle.segmented_scan(y, seg), y, seg, f"scan L={seg} real")
+    assert_close_reduce(tcr.segmented_reduce(yd, seg), oracle.segmented_reduce(y, seg), y, seg, f"reduce L={seg} real")
+    tcr.check_device_flags()
+
+
 def test_pipelined_chain_repeated_launches(tcr, oracle):
     # back-to-back launches share the aggregate table (epoch tag) and the running ticket counter, of which
     # every launch draws tiles + 3 * workgroups; a lost or early carry shows up as a wrong integer
