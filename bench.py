@@ -210,7 +210,7 @@ def main() -> int:
              lambda: tcr.segmented_scan(x[:nb], big, out=out_scan[:nb]), nb, (2 * nb, 4 * nb)),
             ("segmented_reduce seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
-            ("segmented_scan seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
+            ("segmented_scan seg_len=3000 (no power of two: one workgroup per segment)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
              (2 * n3, 4 * n3))]:
         fn()
         torch.cuda.synchronize()

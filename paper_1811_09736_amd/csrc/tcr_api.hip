@@ -226,7 +226,8 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         if (seg_len <= kGenericThreadMax) return "generic_thread_kernel";
         if (seg_len < kMaskedMin) return "generic_wave_kernel";
         if (op == 0) return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";
-        return chain_takes_any_length(seg_len) ? "scan_chain_kernel<mfma>" : "masked_wave_scan_kernel";
+        if (chain_takes_any_length(seg_len)) return "scan_chain_kernel<mfma>";
+        return segment_kernel_takes(seg_len) ? "scan_segment_kernel" : "masked_wave_scan_kernel";
     }
     if (op == 0 || op == 2) {
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";

@@ -474,6 +474,37 @@ inline tcr_status scan_tuned(const _Float16* x, void* out, uint64_t n, uint64_t 
     return scan_long<FORM, MODE>(x, out, n, seg_len, false, s);
 }
 
+// Segment lengths that are no power of two, a multiple of 8, and fit one workgroup: scan_segment_kernel with the
+// smallest share that holds a segment.
+inline bool segment_kernel_takes(uint64_t seg_len) {
+    return g_variant.formulation == kMfma && seg_len % 8 == 0 && seg_len > kTile && seg_len < 2 * scan_shape_tile(10);
+}
+
+template <int U, int W, int MODE>
+void launch_scan_segment_shape(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    scan_segment_kernel<U, W, MODE><<<dim3((unsigned)(n / seg_len)), dim3(W * kWave), 0, s>>>(in, out, seg_len);
+}
+
+// Shares in steps of at most a third, so that few wavefronts of a workgroup lie beyond the segment's end.
+template <int MODE>
+tcr_status launch_scan_segment(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    const uint64_t t = ceil_div(seg_len, kTile);           // tiles per segment
+    if (t <= 2) launch_scan_segment_shape<1, 2, MODE>(in, out, n, seg_len, s);
+    else if (t <= 3) launch_scan_segment_shape<1, 3, MODE>(in, out, n, seg_len, s);
+    else if (t <= 4) launch_scan_segment_shape<1, 4, MODE>(in, out, n, seg_len, s);
+    else if (t <= 6) launch_scan_segment_shape<1, 6, MODE>(in, out, n, seg_len, s);
+    else if (t <= 8) launch_scan_segment_shape<1, 8, MODE>(in, out, n, seg_len, s);
+    else if (t <= 12) launch_scan_segment_shape<1, 12, MODE>(in, out, n, seg_len, s);
+    else if (t <= 16) launch_scan_segment_shape<1, 16, MODE>(in, out, n, seg_len, s);
+    else if (t <= 24) launch_scan_segment_shape<2, 12, MODE>(in, out, n, seg_len, s);
+    else if (t <= 32) launch_scan_segment_shape<2, 16, MODE>(in, out, n, seg_len, s);
+    else if (t <= 48) launch_scan_segment_shape<4, 12, MODE>(in, out, n, seg_len, s);
+    else if (t <= 64) launch_scan_segment_shape<4, 16, MODE>(in, out, n, seg_len, s);
+    else if (t <= 96) launch_scan_segment_shape<8, 12, MODE>(in, out, n, seg_len, s);
+    else launch_scan_segment_shape<8, 16, MODE>(in, out, n, seg_len, s);
+    return check_launch("scan_segment_kernel");
+}
+
 // Segment lengths that are no power of two but long enough for the persistent chain (its ragged last tile per
 // segment is cut off by the buffer range check, which works on whole 8-element groups).
 inline bool chain_takes_any_length(uint64_t seg_len) {
@@ -492,6 +523,14 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
                 case 1: return launch_chain<1>(10, x, out, n, seg_len, s);
                 case 2: return launch_chain<2>(10, x, out, n, seg_len, s);
                 default: return launch_chain<3>(10, x, out, n, seg_len, s);
+            }
+        }
+        if (segment_kernel_takes(seg_len)) {
+            switch (mode) {
+                case 0: return launch_scan_segment<0>(x, out, n, seg_len, s);
+                case 1: return launch_scan_segment<1>(x, out, n, seg_len, s);
+                case 2: return launch_scan_segment<2>(x, out, n, seg_len, s);
+                default: return launch_scan_segment<3>(x, out, n, seg_len, s);
             }
         }
         return launch_generic<true>(x, out, n, seg_len, flags, s);

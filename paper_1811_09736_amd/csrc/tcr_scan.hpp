@@ -640,6 +640,54 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
     }
 }
 
+// ------------------------------------------------------------------------------ one workgroup per segment, any length
+// Segment lengths that are no power of two (the paper pads such segments, Section 4): workgroup s scans
+// segment s, whose length is a multiple of 8 and at most WAVES * U tiles.  The tiles are laid out from the
+// segment's start, so no tile holds two segments; the part of the workgroup's share beyond the segment's end
+// is cut off by the buffer range check -- zero padding that costs no memory traffic.  Matrix cores only.
+template <int U, int WAVES, int MODE>
+__global__ __launch_bounds__(WAVES * kWave) void scan_segment_kernel(const _Float16* __restrict__ in,
+                                                                     void* __restrict__ out, uint64_t seg_len) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
+    constexpr uint32_t kChunk = (uint32_t)kTile * U;
+    __shared__ float s_wave_total[WAVES];
+    const LaneId id;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t offset = (uint64_t)wave * kChunk;                      // of the wavefront's share inside the segment
+    const uint64_t left = offset < seg_len ? seg_len - offset : 0;
+    const uint32_t count = left < kChunk ? (uint32_t)left : kChunk;
+    const uint64_t base = (uint64_t)blockIdx.x * seg_len + (count ? offset : 0);
+    const __amdgpu_buffer_rsrc_t src = make_rsrc(in + base, count * 2u);
+    half8 x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) x[u] = buffer_load8(src, (uint32_t)(kTile * u + kRow * id.j + 8 * id.g) * 2u);
+    float pre[U];
+    float run = 0.0f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float4v tot = mfma(const_ones(), x[u], splat(0.0f));
+        const float incl = row_scan_inclusive<16>(tot[0], id.j);
+        pre[u] = row_shr<1>(incl) + run;
+        run += read_lane(incl, 15);
+    }
+    float ext = 0.0f;
+    if constexpr (WAVES > 1) {
+        if (id.lane == 0) s_wave_total[wave] = run;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) ext += s_wave_total[w];
+    }
+    const __amdgpu_buffer_rsrc_t dst = make_rsrc(static_cast<char*>(out) + base * (F16 ? 2u : 4u), count * (F16 ? 2u : 4u));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float carry = pre[u] + ext;
+        const float4v lo = mfma(const_tri_lo<EXCL>(id), x[u], splat(carry));
+        const float4v hi = mfma(const_tri_hi<EXCL>(id), x[u], splat(carry));
+        const uint32_t elem = (uint32_t)(kTile * u + kRow * id.j + 4 * id.g);
+        buffer_store4_t<F16>(dst, elem, lo);
+        buffer_store4_t<F16>(dst, elem + 16u, hi);
+    }
+}
+
 // ------------------------------------------------------------------------------ reduce-then-scan helper
 // Workgroup s turns the `per` workgroup totals of segment s into exclusive prefixes, in place.
 constexpr int kPartialsThreads = 256;

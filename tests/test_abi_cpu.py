@@ -130,8 +130,9 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_REDUCE, 3 << 24, 3 << 20) == "masked_span_reduce_kernel+reduce_final_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "scan_chain_kernel<mfma>"        # long, a multiple of 8
     assert k(lib.OP_SEGMENTED_SCAN, 100003 * 5, 100003) == "masked_wave_scan_kernel"       # long, odd
-    assert k(lib.OP_SEGMENTED_SCAN, 40000 * 5, 40000) == "masked_wave_scan_kernel"         # under two chain tiles
-    assert k(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "masked_wave_scan_kernel"
+    assert k(lib.OP_SEGMENTED_SCAN, 40000 * 5, 40000) == "scan_segment_kernel"             # under two chain tiles
+    assert k(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "scan_segment_kernel"             # a multiple of 8: one workgroup each
+    assert k(lib.OP_SEGMENTED_SCAN, 3001 * 7, 3001) == "masked_wave_scan_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 200 * 7, 200) == "generic_wave_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, n, 3) == ""           # 3 does not divide n: the call reports an invalid argument
     assert k(lib.OP_SEGMENTED_SCAN, 0, 16) == ""
