@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--tuning", default="", help="launch-shape choices to import first (tcr_tuning_import text)")
     ap.add_argument("--autotune", action="store_true",
                     help="let tcr_autotune re-pick the launch shape of every timed call first (default: shipped shapes)")
+    ap.add_argument("--no-context", action="store_true", help="skip the context rows (variants, library calls, full operations)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (read 1 GiB, write 1 GiB) three times before the timed "
                          "region, as the known-size reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE")
@@ -201,7 +202,7 @@ def main() -> int:
                      lambda: torch.sum(x, dtype=torch.float32), n, (2 * n, 4)),
                     ("context: torch.cumsum(x, 0, dtype=float32) (library full scan)",
                      lambda: torch.cumsum(x, 0, dtype=torch.float32, out=copy_dst), n, (2 * n, 4 * n))]
-    for label, fn, nn, rd_wr in variant_rows + library_rows + [
+    for label, fn, nn, rd_wr in [] if args.no_context else variant_rows + library_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
             ("segmented_reduce seg_len=3*2^20 (no power of two: masked pieces + second kernel)",
@@ -226,9 +227,10 @@ def main() -> int:
                       "pct_of_hbm_peak": round(sum(rd_wr) / us * 1e-3 / HBM_PEAK_GBS * 100, 1)})
     tcr.check_device_flags()
     del copy_dst
-    copy_gbps = extra[len(variant_rows)]["total_GBps"]
+    copy_gbps = None if args.no_context else extra[len(variant_rows)]["total_GBps"]
     for r in rows:
-        r["pct_of_measured_copy"] = round(r["total_GBps"] / copy_gbps * 100, 1)
+        if copy_gbps:
+            r["pct_of_measured_copy"] = round(r["total_GBps"] / copy_gbps * 100, 1)
 
     cpu = None
     if not args.no_cpu_baseline:
