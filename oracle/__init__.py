@@ -44,6 +44,7 @@ def _bind(path: str):
         ("oracle_segmented_reduce", [u16p, f64p, u64, u64]),
         ("oracle_segmented_scan", [u16p, f64p, u64, u64]),
         ("oracle_segmented_scan_exclusive", [u16p, f64p, u64, u64]),
+        ("oracle_segmented_moments", [u16p, f64p, f64p, u64, u64]),
         ("oracle_irregular_reduce", [u16p, u64p, f64p, u64]),
         ("oracle_irregular_scan", [u16p, u64p, f64p, u64]),
         ("oracle_reduce", [u16p, f64p, u64]),
@@ -103,6 +104,17 @@ class Oracle:
         if self._lib.oracle_segmented_scan_exclusive(_in_ptr(x), _out_ptr(out), n, seg_len):
             raise ValueError("oracle_segmented_scan_exclusive rejected its arguments")
         return out
+
+    def segmented_moments(self, x: np.ndarray, seg_len: int):
+        """(sum, sum of squares) of every segment."""
+        n = x.shape[0]
+        if seg_len <= 0 or n % seg_len:
+            raise ValueError("seg_len must be positive and divide n")
+        a = np.empty(n // seg_len, dtype=np.float64)
+        q = np.empty(n // seg_len, dtype=np.float64)
+        if self._lib.oracle_segmented_moments(_in_ptr(x), _out_ptr(a), _out_ptr(q), n, seg_len):
+            raise ValueError("oracle_segmented_moments rejected its arguments")
+        return a, q
 
     def irregular_reduce(self, x: np.ndarray, offsets) -> np.ndarray:
         off = np.ascontiguousarray(offsets, dtype=np.uint64)
@@ -191,3 +203,7 @@ def scan(x):
 
 def segmented_scan_at(x, seg_len, idx):
     return _get().segmented_scan_at(x, seg_len, idx)
+
+
+def segmented_moments(x, seg_len):
+    return _get().segmented_moments(x, seg_len)

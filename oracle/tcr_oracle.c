@@ -13,7 +13,8 @@
  *     scan is inclusive;
  *   - the regular segmented forms apply the same operation independently to
  *     consecutive, equally sized pieces of the input;
- * plus the exclusive variant of the scan (each output leaves out its own element).
+ * plus the exclusive variant of the scan (each output leaves out its own element), irregular segments
+ * given by an offsets array, and the first two moments of every segment.
  * The matrix-product algorithms of Sections 4 and 5 reach exactly these results (up
  * to the order of floating-point additions), so the oracle is the definition written
  * out: one left-to-right loop per segment, accumulating in binary64.  Each binary16
@@ -132,6 +133,31 @@ int oracle_irregular_scan(const uint16_t *in, const uint64_t *offsets, double *o
             acc += oracle_half_to_double(in[k]);
             out[k] = acc;
         }
+    }
+    return 0;
+}
+
+/*
+ * First two moments of every segment -- the reduction the paper's conclusion points at as the next use of
+ * the method (mean and variance for batch normalisation):
+ *   sum[s]   = sum_{k < seg_len} x[s*seg_len + k]
+ *   sumsq[s] = sum_{k < seg_len} x[s*seg_len + k]^2
+ * The square of a binary16 value has at most 22 significant bits, so every product is exact in binary64.
+ */
+int oracle_segmented_moments(const uint16_t *in, double *sum, double *sumsq, uint64_t n, uint64_t seg_len)
+{
+    if (bad_args(in, sum, n, seg_len)) return 1;
+    if (n > 0 && sumsq == NULL) return 1;
+    const uint64_t segs = n / seg_len;
+    for (uint64_t s = 0; s < segs; ++s) {
+        double a = 0.0, q = 0.0;
+        for (uint64_t k = 0; k < seg_len; ++k) {
+            const double v = oracle_half_to_double(in[s * seg_len + k]);
+            a += v;
+            q += v * v;
+        }
+        sum[s] = a;
+        sumsq[s] = q;
     }
     return 0;
 }

@@ -278,3 +278,49 @@ def test_argument_errors(oracle):
     assert oracle.scan(np.empty(0, dtype=np.float16)).size == 0
     with pytest.raises(ValueError):
         oracle.segmented_scan_at(x, 4, [12])
+
+
+# ------------------------------------------------------------------ first two moments
+
+def test_moments_hand_values_and_closed_forms(oracle):
+    x = np.array([1, 2, 3, 4, -5, 6, -7, 8], dtype=np.float16)
+    a, q = oracle.segmented_moments(x, 4)
+    assert a.tolist() == [10, 2] and q.tolist() == [30, 174]               # 1+4+9+16, 25+36+49+64
+    a, q = oracle.segmented_moments(x, 8)
+    assert a.tolist() == [12] and q.tolist() == [204]
+    a, q = oracle.segmented_moments(np.array([0.5, -0.25], dtype=np.float16), 1)
+    assert a.tolist() == [0.5, -0.25] and q.tolist() == [0.25, 0.0625]
+    for m in (1, 7, 16, 300, 2048):                                         # 1..m: m(m+1)/2 and m(m+1)(2m+1)/6
+        ramp = np.arange(1, m + 1, dtype=np.float16)
+        a, q = oracle.segmented_moments(ramp, m)
+        assert a[0] == m * (m + 1) // 2 and q[0] == m * (m + 1) * (2 * m + 1) // 6
+    ones = workloads.make_input(4096, "ones", 0)
+    a, q = oracle.segmented_moments(ones, 256)
+    assert np.all(a == 256) and np.all(q == 256)
+
+
+def test_moments_exact_rational_and_invariants(oracle):
+    from fractions import Fraction
+    x = workloads.make_input(60, "uniform_pm1", 12)
+    fx = [Fraction(float(v)) for v in x]
+    for seg in (1, 2, 3, 4, 5, 6, 10, 12, 15, 20, 30, 60):
+        a, q = oracle.segmented_moments(x, seg)
+        for s in range(60 // seg):
+            piece = fx[s * seg:(s + 1) * seg]
+            assert Fraction(a[s]) == sum(piece)
+            assert Fraction(q[s]) == sum(v * v for v in piece)          # < 2^53 of 2^-48 units: exact in binary64
+    y = workloads.make_input(1 << 14, "normal", 3)
+    for seg in (16, 1000 if (1 << 14) % 1000 == 0 else 1024, 1 << 14):
+        a, q = oracle.segmented_moments(y, seg)
+        assert np.array_equal(a, oracle.segmented_reduce(y, seg))           # the first moment is the reduction
+        a2, q2 = oracle.segmented_moments(-y, seg)
+        assert np.array_equal(a2, -a) and np.array_equal(q2, q)             # squares do not see the sign
+        assert np.all(q * seg >= a * a * (1 - 1e-12))                       # Cauchy-Schwarz: variance >= 0
+        yd = y.astype(np.float64).reshape(-1, seg)
+        assert np.allclose(q, (yd * yd).sum(axis=1), rtol=1e-12, atol=0)    # numpy float64 cross-check
+    z = workloads.make_input(1 << 12, "int8", 2)                            # integers: numpy must agree exactly
+    a, q = oracle.segmented_moments(z, 64)
+    zd = z.astype(np.float64).reshape(-1, 64)
+    assert np.array_equal(q, (zd * zd).sum(axis=1))
+    with pytest.raises(ValueError):
+        oracle.segmented_moments(z, 7)

@@ -31,6 +31,9 @@ MUTANTS = {
                                       "for (uint64_t k = offsets[s]; k <= offsets[s + 1]; ++k)\n            acc += "),
     "irregular_scan_carry_not_reset": ("        double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {",
                                        "        static double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {"),
+    "moments_square_of_sum": ("            q += v * v;", "            q += v;"),
+    "moments_sum_of_abs": ("            a += v;\n            q += v * v;", "            a += v < 0 ? -v : v;\n            q += v * v;"),
+    "moments_carry_not_reset": ("        double a = 0.0, q = 0.0;", "        double a = 0.0; static double q = 0.0;"),
     "sampled_scan_starts_at_zero": ("const uint64_t first = idx[q] - idx[q] % seg_len;", "const uint64_t first = 0;"),
     "sampled_scan_exclusive": ("k <= idx[q]; ++k)", "k < idx[q]; ++k)"),
 }
@@ -50,6 +53,8 @@ def _pins(o) -> None:
     assert o.irregular_reduce(x, [0, 3, 3, 4, 7]).tolist() == [6, 0, 4, 18]
     assert o.irregular_scan(x, [0, 3, 3, 4, 8]).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
     assert o.reduce(x) == 36.0
+    a, q = o.segmented_moments(np.array([1, -2, 3, 4, -5, 6], dtype=np.float16), 3)
+    assert a.tolist() == [2, 5] and q.tolist() == [14, 77]
     for dist, seed in (("uniform_pm1", 0), ("subnormal", 9)):
         y = workloads.make_input(1 << 12, dist, seed)
         q = np.rint(y.astype(np.float64) * 2.0 ** 24).astype(np.int64)
