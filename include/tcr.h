@@ -102,6 +102,17 @@ tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *
 tcr_status tcr_irregular_scan(const void *in, const uint64_t *offsets, float *out, uint64_t nseg, void *stream);
 
 /*
+ * First two moments of every segment: the statistics of a normalisation layer, which the paper's conclusion
+ * (Section 7) names as the next use of reductions on matrix cores.
+ *   sum[s] = sum_{k < seg_len} x,   sumsq[s] = sum_{k < seg_len} x^2,   x = in[s*seg_len + k].
+ * sum, sumsq: n/seg_len floats each, 4-byte aligned, distinct.  Every seg_len >= 1 that divides n, including
+ * seg_len == n.  The sums of squares come from products of the data with itself on the matrix cores (exact
+ * products, binary32 accumulation); both are exact for integer-valued inputs while the sums stay below 2^24.
+ * One wavefront per segment (per 65536-element piece of a long one); segments under 256 elements are slow.
+ */
+tcr_status tcr_segmented_moments(const void *in, float *sum, float *sumsq, uint64_t n, uint64_t seg_len, void *stream);
+
+/*
  * Full reduction (device level, Section 4): out[0] = sum of all n inputs (0 for n == 0).
  * Any n is accepted.  out: 1 float.
  */

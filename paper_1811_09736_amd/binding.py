@@ -23,7 +23,7 @@ SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
     "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
-    "tcr_workspace_bytes", "tcr_set_workspace",
+    "tcr_workspace_bytes", "tcr_set_workspace", "tcr_segmented_moments",
     "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
 )
@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_tuning_export.restype = u64
     lib.tcr_tuning_import.argtypes = [ctypes.c_char_p]
     lib.tcr_tuning_import.restype = ctypes.c_int
+    lib.tcr_segmented_moments.argtypes = [vp, fp, fp, u64, u64, vp]
+    lib.tcr_segmented_moments.restype = ctypes.c_int
     lib.tcr_workspace_bytes.argtypes = [ctypes.c_int, u64, u64]
     lib.tcr_workspace_bytes.restype = u64
     lib.tcr_set_workspace.argtypes = [vp, u64]
@@ -266,6 +268,20 @@ def tuning_import(text: str) -> None:
     st = _lib.tcr_tuning_import(text.encode())
     if st != OK:
         raise TcrError(st, "tcr_tuning_import")
+
+
+def segmented_moments(x: torch.Tensor, seg_len: int, stream: Optional[torch.cuda.Stream] = None):
+    """tcr_segmented_moments: (sum, sum of squares) of every segment, two float32 tensors."""
+    _check_input(x)
+    n = x.numel()
+    count = n // seg_len if seg_len > 0 else 0
+    a = torch.empty(count, dtype=torch.float32, device=x.device)
+    q = torch.empty(count, dtype=torch.float32, device=x.device)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_segmented_moments(x.data_ptr(), a.data_ptr(), q.data_ptr(), n, seg_len, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_segmented_moments")
+    return a, q
 
 
 def workspace_bytes(op: int, n: int, seg_len: int) -> int:

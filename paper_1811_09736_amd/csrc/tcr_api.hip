@@ -70,6 +70,14 @@ extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets
     return check_launch("irregular_wave_kernel");
 }
 
+extern "C" tcr_status tcr_segmented_moments(const void* in, float* sum, float* sumsq, uint64_t n, uint64_t seg_len,
+                                             void* stream) {
+    tcr_status st = validate(in, sum, n, seg_len, 4);
+    if (st != TCR_OK || n == 0) return st;
+    if (sumsq == nullptr || !aligned(sumsq, 4)) return TCR_ERR_INVALID_ARG;
+    return launch_moments(static_cast<const _Float16*>(in), sum, sumsq, n, seg_len, static_cast<hipStream_t>(stream));
+}
+
 extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* stream) {
     if (out == nullptr) return TCR_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -474,6 +474,37 @@ inline tcr_status scan_tuned(const _Float16* x, void* out, uint64_t n, uint64_t 
     return scan_long<FORM, MODE>(x, out, n, seg_len, false, s);
 }
 
+// First two moments of every segment, any seg_len >= 1 that divides n.
+inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    const uint64_t nseg = n / seg_len;
+    if (seg_len <= kGenericThreadMax) {
+        generic_moments_kernel<<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
+            in, sum, sumsq, nseg, seg_len);
+        return check_launch("generic_moments_kernel");
+    }
+    const dim3 block(kMaskedWaves * kWave);
+    if (seg_len <= 2 * kWaveSpanMax) {
+        masked_moments_kernel<<<dim3((unsigned)ceil_div(nseg, kMaskedWaves)), block, 0, s>>>(in, sum, sumsq, nseg, seg_len,
+                                                                                             seg_len, 1);
+        return check_launch("masked_moments_kernel");
+    }
+    // long segments: 65536-element pieces, then the second kernel of the device-level reduction for each moment
+    const uint64_t per = ceil_div(seg_len, kWaveSpanMax), pieces = nseg * per;
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    st = ensure_partials(ws, s, 2 * pieces, capturing);
+    if (st != TCR_OK) return st;
+    masked_moments_kernel<<<dim3((unsigned)ceil_div(pieces, kMaskedWaves)), block, 0, s>>>(
+        in, ws->partials, ws->partials + pieces, nseg, seg_len, kWaveSpanMax, per);
+    st = check_launch("masked_moments_kernel");
+    if (st != TCR_OK) return st;
+    reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kFinalThreads), 0, s>>>(ws->partials, sum, per);
+    reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kFinalThreads), 0, s>>>(ws->partials + pieces, sumsq, per);
+    return check_launch("reduce_final_kernel");
+}
+
 // Segment lengths that are no power of two, a multiple of 8, and fit one workgroup: scan_segment_kernel with the
 // smallest share that holds a segment.
 inline bool segment_kernel_takes(uint64_t seg_len) {

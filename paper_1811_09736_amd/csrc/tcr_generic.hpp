@@ -198,6 +198,77 @@ __global__ __launch_bounds__(kMaskedWaves * kWave) void masked_span_reduce_kerne
     if (id.lane == 0) dst[w] = total;
 }
 
+// ---------------------------------------------------------------------------------------- first two moments
+// Sum and sum of squares of a segment -- the statistics of a normalisation layer, which the paper's conclusion
+// names as the next use of reductions on matrix cores.  The sum is Reduction_256N (V <- ones . X^T + V).  The
+// sum of squares takes the data as BOTH operands: entry (i, j) of X . X^T is the inner product of data rows i
+// and j, so the DIAGONAL of W <- X . X^T + W accumulates the sums of squares of the 16 rows (the other entries
+// are not used).  A product of two binary16 values is exact in the binary32 accumulator.
+// One wavefront, segment [begin, end) over zero-masked tiles of the array; both results are uniform.
+__device__ __forceinline__ void masked_wave_moments(const _Float16* __restrict__ in, uint64_t begin, uint64_t end,
+                                                    const LaneId& id, float& sum, float& sumsq) {
+    constexpr int kSteps = 4;
+    float4v acc = splat(0.0f), sq = splat(0.0f);
+    for (uint64_t t0 = begin & ~(uint64_t)(kTile - 1); t0 < end; t0 += (uint64_t)(kTile * kSteps)) {
+        half8 x[kSteps];
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const uint64_t tile = t0 + (uint64_t)(kTile * i);
+            x[i] = (tile < end) ? load8_masked(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end)
+                                : __builtin_bit_cast(half8, splat(0.0f));
+        }
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            acc = mfma(const_ones(), x[i], acc);
+            sq = __builtin_amdgcn_mfma_f32_16x16x32_f16(x[i], x[i], sq, 0, 0, 0);
+        }
+    }
+    sum = read_lane(row_sum_to_last<16>(acc[0]), 15);
+    // lane (j, g) holds rows 4g .. 4g+3 of column j: the diagonal entry of column j sits in lane (j, j / 4), register j % 4
+    const int r = id.j & 3;
+    const float d = r == 0 ? sq[0] : (r == 1 ? sq[1] : (r == 2 ? sq[2] : sq[3]));
+    sumsq = wave_sum(id.g == (id.j >> 2) ? d : 0.0f);
+}
+
+// One wavefront per piece: piece w % per of segment w / per (pieces of `span` elements from the segment's
+// start; per == 1: whole segments).  sum[w], sumsq[w] receive the piece's moments.
+__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_moments_kernel(const _Float16* __restrict__ in,
+                                                                              float* __restrict__ sum,
+                                                                              float* __restrict__ sumsq, uint64_t nseg,
+                                                                              uint64_t seg_len, uint64_t span, uint64_t per) {
+    const LaneId id;
+    const uint64_t w = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (w >= nseg * per) return;
+    const uint64_t s = w / per, piece = w - s * per;
+    const uint64_t begin = s * seg_len + piece * span;
+    const uint64_t seg_end = (s + 1) * seg_len;
+    const uint64_t end = begin + span < seg_end ? begin + span : seg_end;
+    float a, q;
+    masked_wave_moments(in, begin, end, id, a, q);
+    if (id.lane == 0) {
+        sum[w] = a;
+        sumsq[w] = q;
+    }
+}
+
+// Short segments: one thread per segment, binary32 adds and fused multiply-adds.
+__global__ __launch_bounds__(kGenericThreads) void generic_moments_kernel(const _Float16* __restrict__ in,
+                                                                          float* __restrict__ sum,
+                                                                          float* __restrict__ sumsq, uint64_t nseg,
+                                                                          uint64_t seg_len) {
+    const uint64_t s = (uint64_t)blockIdx.x * kGenericThreads + threadIdx.x;
+    if (s >= nseg) return;
+    const _Float16* p = in + s * seg_len;
+    float a = 0.0f, q = 0.0f;
+    for (uint64_t k = 0; k < seg_len; ++k) {
+        const float v = (float)p[k];
+        a += v;
+        q = __builtin_fmaf(v, v, q);
+    }
+    sum[s] = a;
+    sumsq[s] = q;
+}
+
 // Irregular segments behind 16-byte aligned pointers: the same walk, boundaries read from `offsets`.
 template <bool SCAN>
 __global__ __launch_bounds__(kMaskedWaves * kWave) void masked_irregular_kernel(const _Float16* __restrict__ in,

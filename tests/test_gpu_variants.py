@@ -190,3 +190,39 @@ def test_other_segment_lengths_take_every_flag(tcr, oracle, seg, flags):
         ref = ref.astype(np.float16).astype(np.float64)            # integer sums: one correct rounding
     assert np.array_equal(got, ref)
     assert np.array_equal(tcr.segmented_reduce(xd, seg).cpu().numpy().astype(np.float64), oracle.segmented_reduce(x, seg))
+
+
+# ------------------------------------------------------------------ first two moments
+
+@pytest.mark.parametrize("seg", [1, 5, 16, 96, 97, 256, 1000, 4096, 3001, 1 << 16, (1 << 17) + 8, 3 << 18, 1 << 21])
+def test_segmented_moments(tcr, oracle, seg):
+    nseg = max(2, (1 << 21) // seg) | 1 if seg < (1 << 20) else 2
+    n = seg * nseg
+    x = workloads.make_input(n, "int4", seg % 97)                      # |x| <= 4: sums of squares stay below 2^24
+    xd = torch.from_numpy(x).cuda()
+    a, q = tcr.segmented_moments(xd, seg)
+    ra, rq = oracle.segmented_moments(x, seg)
+    assert np.max(rq) < 2 ** 24
+    assert np.array_equal(a.cpu().numpy().astype(np.float64), ra)
+    assert np.array_equal(q.cpu().numpy().astype(np.float64), rq)
+    assert torch.equal(a, tcr.segmented_reduce(xd, seg))              # the first moment is the reduction
+    y = workloads.make_input(n, "normal", 7)
+    a, q = tcr.segmented_moments(torch.from_numpy(y).cuda(), seg)
+    ra, rq = oracle.segmented_moments(y, seg)
+    got_q = q.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got_q - rq) <= 1e-3 * rq)                     # all terms positive: plain relative error
+    rho = np.sqrt(rq)
+    assert np.all(np.abs(a.cpu().numpy().astype(np.float64) - ra) <= 1e-3 * np.maximum(np.abs(ra), rho))
+
+
+def test_full_moments_and_errors(tcr, oracle):
+    x = workloads.make_input((1 << 22) + 8, "int4", 5)
+    xd = torch.from_numpy(x).cuda()
+    a, q = tcr.segmented_moments(xd, x.size)                           # one segment: pieces + second kernel
+    ra, rq = oracle.segmented_moments(x, x.size)
+    assert float(a.cpu()[0]) == ra[0] and float(q.cpu()[0]) == rq[0]
+    with pytest.raises(tcr.TcrError):
+        tcr.segmented_moments(xd, 7)                                   # 7 does not divide n
+    with pytest.raises(tcr.TcrError):
+        tcr.segmented_moments(xd, 0)
+    tcr.check_device_flags()
