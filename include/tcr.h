@@ -28,7 +28,8 @@
  *   call that would have to allocate, grow or initialise workspace while its stream is capturing returns
  *   TCR_ERR_UNSUPPORTED and records nothing (run the same call once outside the capture, or supply a workspace
  *   and run one chained scan on it first).  Calls that use no workspace (scans with seg_len <= 4096, reduces
- *   with seg_len <= 262144, other segment lengths, irregular segments; default variant and tuning) never do.
+ *   with seg_len <= 262144 -- powers of two; other segment lengths below 65536; irregular segments; default
+ *   variant and tuning) never do.
  *   From the first recorded chained scan on, the workspace keeps its launch counters on the device and every
  *   chained scan on it, recorded or not, is preceded by one small bookkeeping kernel.  The "fused"
  *   reduce_finish variant cannot be recorded.
