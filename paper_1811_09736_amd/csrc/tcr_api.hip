@@ -257,7 +257,7 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
                       : "scan_block_kernel<dpp,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel";
         if (!table) {
             const int shape = pick_scan_shape(seg_len, whole);
-            if (kScanShapes[shape].persistent) return "scan_chain_kernel<mfma>";
+            if (kScanShapes[shape].persistent) return mf ? "scan_chain_kernel<mfma>" : "scan_chain_kernel<dpp>";
             if (!kScanShapes[shape].ticket) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
             if (scan_shape_tile(shape) >= seg_len) return mf ? "scan_block_kernel<mfma,ticket>" : "scan_block_kernel<dpp,ticket>";
             return mf ? "scan_block_kernel<mfma,lookback>" : "scan_block_kernel<dpp,lookback>";

@@ -239,7 +239,7 @@ inline uint64_t scan_shape_tile(int id) { return (uint64_t)kTile * kScanShapes[i
 inline bool scan_shape_valid(int id, uint64_t len, bool whole) {      // len: seg_len, or n for the one-segment scan
     if (id < 0 || id >= kScanShapeCount) return false;
     if (kScanShapes[id].persistent)                             // (whole: len == n, which must be a multiple of 8)
-        return g_variant.formulation == kMfma && (whole ? len % 8 == 0 : len >= scan_shape_tile(id));
+        return whole ? len % 8 == 0 : len >= scan_shape_tile(id);
     return kScanShapes[id].ticket || scan_shape_tile(id) >= len;
 }
 
@@ -262,12 +262,14 @@ inline int default_scan_shape(uint64_t len, bool whole) {
     if (len <= 4096) return 2;
     if (len < 8192 || (whole && len == 8192)) return 3;
     if (!whole && len <= 16384) return 7;          // one ticketed share per segment (two segments of 8192)
-    if (scan_shape_valid(10, len, whole)) return 10;   // the pipelined chain: segments of 32768 and more, one segment
-    // another formulation, or n not a multiple of 8: scan_block_kernel shares of 65536 / 32768 elements
+    // the pipelined chain: segments of 32768 and more, one segment with n % 8 == 0.  (16 wavefronts of 4 tiles
+    // for the matrix cores; the DPP arithmetic needs more registers and takes 8 wavefronts of 8 tiles.)
+    if (scan_shape_valid(10, len, whole)) return g_variant.formulation == kMfma ? 10 : 11;
+    // n not a multiple of 8: scan_block_kernel shares of 65536 / 32768 elements with decoupled look-back
     return (whole || len >= (1u << 20)) ? 9 : 8;
 }
 
-inline int pick_scan_shape(uint64_t len, bool whole) {
+int pick_scan_shape(uint64_t len, bool whole) {
     init_tuning();
     const int tuned = g_tuned_scan[tuning_class(len, whole)];
     return scan_shape_valid(tuned, len, whole) ? tuned : default_scan_shape(len, whole);
@@ -304,8 +306,8 @@ inline int nocarry_shape_for(uint64_t fit) {
 }
 
 // The persistent chain (shape 10 or 11) over segments of `seg_len` elements: any multiple of 8 that is at
-// least one tile, or one segment of n elements (n a multiple of 8).  Matrix-core formulation.
-template <int MODE>
+// least one tile, or one segment of n elements (n a multiple of 8).
+template <int FORM, int MODE>
 tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
     const uint64_t tile = scan_shape_tile(shape);
     const uint64_t per_segment = ceil_div(seg_len, tile);
@@ -320,8 +322,8 @@ tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, ui
     const uint64_t resident = (uint64_t)compute_units() * (uint64_t)kScanShapes[shape].persistent;
     const uint64_t groups = tiles < resident ? tiles : resident;
     const ChainGrid grid = {seg_len, (uint32_t)per_segment, (uint32_t)tiles};
-    if (shape == 10) scan_chain_kernel<4, 16, MODE><<<dim3((unsigned)groups), dim3(16 * kWave), 0, s>>>(in, out, grid, dev);
-    else scan_chain_kernel<8, 8, MODE><<<dim3((unsigned)groups), dim3(8 * kWave), 0, s>>>(in, out, grid, dev);
+    if (shape == 10) scan_chain_kernel<FORM, 4, 16, MODE><<<dim3((unsigned)groups), dim3(16 * kWave), 0, s>>>(in, out, grid, dev);
+    else scan_chain_kernel<FORM, 8, 8, MODE><<<dim3((unsigned)groups), dim3(8 * kWave), 0, s>>>(in, out, grid, dev);
     st = check_launch("scan_chain_kernel");
     if (st != TCR_OK) {
         ws->dirty = true;
@@ -350,9 +352,7 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
             launch_scan_shape<FORM, kNoCarry, MODE>(shape, in, out, n, seg_mask, seg_len, none, nullptr, s);
             return check_launch("scan_block_kernel");
         }
-        if constexpr (FORM == kMfma) {
-            if (kScanShapes[shape].persistent) return launch_chain<MODE>(shape, in, out, n, host_seg_len, s);
-        }
+        if (kScanShapes[shape].persistent) return launch_chain<FORM, MODE>(shape, in, out, n, host_seg_len, s);
         const uint64_t tiles = ceil_div(n, scan_shape_tile(shape));
         ScanWorkspace dev = {};
         Workspace* ws = nullptr;
@@ -550,10 +550,10 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
         if (chain_takes_any_length(seg_len)) {
             // long segments of any length that keeps 8-element groups whole: the chain on a per-segment tile grid
             switch (mode) {
-                case 0: return launch_chain<0>(10, x, out, n, seg_len, s);
-                case 1: return launch_chain<1>(10, x, out, n, seg_len, s);
-                case 2: return launch_chain<2>(10, x, out, n, seg_len, s);
-                default: return launch_chain<3>(10, x, out, n, seg_len, s);
+                case 0: return launch_chain<kMfma, 0>(10, x, out, n, seg_len, s);
+                case 1: return launch_chain<kMfma, 1>(10, x, out, n, seg_len, s);
+                case 2: return launch_chain<kMfma, 2>(10, x, out, n, seg_len, s);
+                default: return launch_chain<kMfma, 3>(10, x, out, n, seg_len, s);
             }
         }
         if (segment_kernel_takes(seg_len)) {

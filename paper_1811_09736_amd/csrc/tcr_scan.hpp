@@ -384,8 +384,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
 }
 
 // ------------------------------------------------------------------------------ long segments, pipelined
-// scan_chain_kernel: the single-pass chained scan as a persistent, software-pipelined loop (matrix
-// cores only).  One workgroup per compute unit draws tiles by ticket and holds three at a time, each in
+// scan_chain_kernel: the single-pass chained scan as a persistent, software-pipelined loop (either
+// formulation of the tile arithmetic).  One workgroup per compute unit draws tiles by ticket and holds three at a time, each in
 // registers of its own:
 //     C  just drawn: its loads are issued first thing in a step,
 //     B  loaded a step ago: its totals are computed and its aggregate PUBLISHED next,
@@ -481,7 +481,7 @@ struct ChainGrid {
 };
 
 // Stage C: request the data of ticket `tile`.
-template <int U, int WAVES>
+template <int FORM, int U, int WAVES>
 __device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const _Float16* __restrict__ in,
                                            const ChainGrid& grid, const LaneId& id, int wave) {
     constexpr uint32_t kChunk = (uint32_t)kTile * U;
@@ -497,22 +497,29 @@ __device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const
     t.count = left < kChunk ? (uint32_t)left : kChunk;
     const __amdgpu_buffer_rsrc_t src = make_rsrc(in + (t.count ? t.base : 0), t.count * 2u);
 #pragma unroll
-    for (int u = 0; u < U; ++u) t.x[u] = buffer_load8(src, (uint32_t)(kTile * u + kRow * id.j + 8 * id.g) * 2u);
+    for (int u = 0; u < U; ++u)
+        t.x[u] = buffer_load8(src, (uint32_t)(kTile * u + (FORM == kMfma ? kRow * id.j + 8 * id.g : 8 * id.lane)) * 2u);
 }
 
 // Stage B: totals of the tile, carries inside the workgroup, aggregate published.  Contains one barrier,
 // executed also for a ticket past the last tile.
-template <int U, int WAVES>
+template <int FORM, int U, int WAVES>
 __device__ __forceinline__ void chain_publish(ChainTile<U>& t, const ScanWorkspace& ws, uint32_t tiles, ChainShared& sh,
                                               const LaneId& id, int wave) {
     float run = 0.0f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float4v tot = mfma(const_ones(), t.x[u], splat(0.0f));
-        const float incl = row_scan_inclusive<16>(tot[0], id.j);
-        t.pre[u] = row_shr<1>(incl) + run;
+        if constexpr (FORM == kMfma) {
+            const float4v tot = mfma(const_ones(), t.x[u], splat(0.0f));
+            const float incl = row_scan_inclusive<16>(tot[0], id.j);
+            t.pre[u] = row_shr<1>(incl) + run;
+            run += read_lane(incl, 15);
+        } else {
+            const float incl = wave_scan_inclusive(sum8(t.x[u]));
+            t.pre[u] = wave_shr1(incl) + run;
+            run += read_lane(incl, 63);
+        }
         asm volatile("" : "+v"(t.pre[u]));        // keep the sum here: sunk to its use it costs a second register per tile
-        run += read_lane(incl, 15);
     }
     if (id.lane == 0) sh.wave_total[wave] = run;
     __syncthreads();
@@ -533,7 +540,7 @@ __device__ __forceinline__ void chain_publish(ChainTile<U>& t, const ScanWorkspa
 // Stage A: carry from the earlier tiles of the segment, results, stores.  Returns a freshly drawn ticket.
 // own_end / own_incl (wavefront 0): index after the tile this workgroup finished last (0: none yet) and
 // that tile's inclusive prefix.
-template <int U, int WAVES, int MODE>
+template <int FORM, int U, int WAVES, int MODE>
 __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restrict__ out,
                                                  const ScanWorkspace& ws, ChainShared& sh, const LaneId& id, int wave,
                                                  uint32_t& own_end, float& own_incl) {
@@ -565,16 +572,24 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const float carry = t.pre[u] + ext;
-        const float4v lo = mfma(const_tri_lo<EXCL>(id), t.x[u], splat(carry));
-        const float4v hi = mfma(const_tri_hi<EXCL>(id), t.x[u], splat(carry));
-        const uint32_t elem = (uint32_t)(kTile * u + kRow * id.j + 4 * id.g);
-        buffer_store4_t<F16>(dst, elem, lo);
-        buffer_store4_t<F16>(dst, elem + 16u, hi);
+        if constexpr (FORM == kMfma) {
+            const float4v lo = mfma(const_tri_lo<EXCL>(id), t.x[u], splat(carry));
+            const float4v hi = mfma(const_tri_hi<EXCL>(id), t.x[u], splat(carry));
+            const uint32_t elem = (uint32_t)(kTile * u + kRow * id.j + 4 * id.g);
+            buffer_store4_t<F16>(dst, elem, lo);
+            buffer_store4_t<F16>(dst, elem + 16u, hi);
+        } else {
+            float p[8];                           // the in-lane scan is recomputed here rather than kept for a step
+            scan8<EXCL>(t.x[u], p);
+            const uint32_t elem = (uint32_t)(kTile * u + 8 * id.lane);
+            buffer_store4_t<F16>(dst, elem, (float4v){p[0] + carry, p[1] + carry, p[2] + carry, p[3] + carry});
+            buffer_store4_t<F16>(dst, elem + 4u, (float4v){p[4] + carry, p[5] + carry, p[6] + carry, p[7] + carry});
+        }
     }
     return fresh;
 }
 
-template <int U, int WAVES, int MODE>
+template <int FORM, int U, int WAVES, int MODE>
 __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float16* __restrict__ in,
                                                                    void* __restrict__ out, ChainGrid grid,
                                                                    ScanWorkspace ws_arg) {
@@ -604,14 +619,14 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
         return;
     }
     ChainTile<U> a, b, c;
-    chain_load<U, WAVES>(a, first, in, grid, id, wave);
+    chain_load<FORM, U, WAVES>(a, first, in, grid, id, wave);
     __syncthreads();                              // s_draw has been read by everyone
     if (threadIdx.x == 0)
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
     __syncthreads();
     const uint32_t second = __builtin_amdgcn_readfirstlane(s_draw);
-    chain_load<U, WAVES>(b, second, in, grid, id, wave);
-    chain_publish<U, WAVES>(a, ws, tiles, sh, id, wave);          // (its barrier also orders the reads of s_draw)
+    chain_load<FORM, U, WAVES>(b, second, in, grid, id, wave);
+    chain_publish<FORM, U, WAVES>(a, ws, tiles, sh, id, wave);          // (its barrier also orders the reads of s_draw)
     if (threadIdx.x == 0)
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
     __syncthreads();
@@ -625,17 +640,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
     // three tiles per trip, the register sets rotating through the stages, so no tile is ever copied between
     // registers (a copy would have to wait for the loads it copies, and with them for the stores before)
     while (true) {
-        chain_load<U, WAVES>(c, fresh, in, grid, id, wave);
-        chain_publish<U, WAVES>(b, ws, tiles, sh, id, wave);
-        fresh = chain_finish<U, WAVES, MODE>(a, out, ws, sh, id, wave, own_end, own_incl);
+        chain_load<FORM, U, WAVES>(c, fresh, in, grid, id, wave);
+        chain_publish<FORM, U, WAVES>(b, ws, tiles, sh, id, wave);
+        fresh = chain_finish<FORM, U, WAVES, MODE>(a, out, ws, sh, id, wave, own_end, own_incl);
         if (b.tile >= tiles) break;
-        chain_load<U, WAVES>(a, fresh, in, grid, id, wave);
-        chain_publish<U, WAVES>(c, ws, tiles, sh, id, wave);
-        fresh = chain_finish<U, WAVES, MODE>(b, out, ws, sh, id, wave, own_end, own_incl);
+        chain_load<FORM, U, WAVES>(a, fresh, in, grid, id, wave);
+        chain_publish<FORM, U, WAVES>(c, ws, tiles, sh, id, wave);
+        fresh = chain_finish<FORM, U, WAVES, MODE>(b, out, ws, sh, id, wave, own_end, own_incl);
         if (c.tile >= tiles) break;
-        chain_load<U, WAVES>(b, fresh, in, grid, id, wave);
-        chain_publish<U, WAVES>(a, ws, tiles, sh, id, wave);
-        fresh = chain_finish<U, WAVES, MODE>(c, out, ws, sh, id, wave, own_end, own_incl);
+        chain_load<FORM, U, WAVES>(b, fresh, in, grid, id, wave);
+        chain_publish<FORM, U, WAVES>(a, ws, tiles, sh, id, wave);
+        fresh = chain_finish<FORM, U, WAVES, MODE>(c, out, ws, sh, id, wave, own_end, own_incl);
         if (a.tile >= tiles) break;
     }
 }

@@ -118,9 +118,10 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SCAN, n - 3, n - 3) == "scan_block_kernel<mfma,lookback>"      # n not a multiple of 8
     lib.set_variant("formulation", "dpp")
     try:
-        assert k(lib.OP_SCAN, n, n) == "scan_block_kernel<dpp,lookback>"
-        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_block_kernel<dpp,lookback>"
-        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 15) == "scan_block_kernel<dpp,ticket>"
+        assert k(lib.OP_SCAN, n, n) == "scan_chain_kernel<dpp>"
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_chain_kernel<dpp>"
+        assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 14) == "scan_block_kernel<dpp,ticket>"
+        assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "masked_wave_scan_kernel"   # other lengths: matrix cores only
     finally:
         lib.set_variant("reset")
     assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
