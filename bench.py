@@ -192,8 +192,11 @@ def main() -> int:
         variant_rows.append(("segmented_scan_ex seg_len=2^12 exclusive",
                              lambda: tcr.segmented_scan_ex(x, 1 << 12, tcr.SCAN_EXCLUSIVE, out=out_scan), n, (2 * n, 4 * n)))
     out_r4 = torch.empty(n // 16, dtype=torch.float32, device="cuda")
-    variant_rows.append(("segmented_reduce seg_len=2^4 called back to back (in the step it follows a 1 GiB scan output "
-                         "whose write-back it overlaps)", lambda: tcr.segmented_reduce(x, 16, out=out_r4), n, (2 * n, n // 4)))
+    variant_rows.append(("segmented_reduce seg_len=2^4 called back to back", lambda: tcr.segmented_reduce(x, 16, out=out_r4), n,
+                         (2 * n, n // 4)))
+    variant_rows.append(("segmented_scan seg_len=2^4 called back to back (in the step it follows the reductions, whose "
+                         "streaming loads leave the last scan's 256 MiB of dirty cache lines for it to write back)",
+                         lambda: tcr.segmented_scan(x, 16, out=out_scan), n, (2 * n, 4 * n)))
     # library context (neither oracle nor target): the device copy this machine sustains -- the paper quotes its
     # results against the measured copy rate -- and torch's own sum / cumsum (rocPRIM) on the same input
     copy_src = out_scan

@@ -84,8 +84,9 @@ __global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Fl
 
 // ---------------------------------------------------------------------------------------- masked tiles
 // 8 inputs at element g (a multiple of 8), those outside [begin, end) read as zero.
+template <bool STREAM = false>
 __device__ __forceinline__ half8 load8_masked(const _Float16* __restrict__ in, uint64_t g, uint64_t begin, uint64_t end) {
-    if (g >= begin && g + 8 <= end) return load8(in, g);
+    if (g >= begin && g + 8 <= end) return load8<STREAM>(in, g);
     half8 v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (g + e >= begin && g + e < end) ? in[g + e] : (_Float16)0.0f;
@@ -150,7 +151,7 @@ __device__ __forceinline__ float masked_wave_reduce(const _Float16* __restrict__
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
             const uint64_t tile = t0 + (uint64_t)(kTile * i);
-            x[i] = (tile < end) ? load8_masked(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end)
+            x[i] = (tile < end) ? load8_masked<true>(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end)
                                 : __builtin_bit_cast(half8, splat(0.0f));
         }
 #pragma unroll
@@ -214,7 +215,7 @@ __device__ __forceinline__ void masked_wave_moments(const _Float16* __restrict__
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
             const uint64_t tile = t0 + (uint64_t)(kTile * i);
-            x[i] = (tile < end) ? load8_masked(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end)
+            x[i] = (tile < end) ? load8_masked<true>(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end)
                                 : __builtin_bit_cast(half8, splat(0.0f));
         }
 #pragma unroll

@@ -58,10 +58,10 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Floa
     half8 x[U];
     if (base + (uint64_t)(kTile * U) <= n) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = load8(in, base + (uint64_t)(kTile * u + lane_off));
+        for (int u = 0; u < U; ++u) x[u] = load8<true>(in, base + (uint64_t)(kTile * u + lane_off));
     } else {
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + lane_off), n);
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded<true>(in, base + (uint64_t)(kTile * u + lane_off), n);
     }
 
     // Per tile, the segment sums sit in scattered lanes (the last lane of each row group).  They are
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_span_kernel(const _Float
         for (; t + (uint64_t)(kTile * U) <= end; t += (uint64_t)(kTile * U)) {
             half8 x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) x[u] = load8(in, t + (uint64_t)(kTile * u + lane_off));
+            for (int u = 0; u < U; ++u) x[u] = load8<true>(in, t + (uint64_t)(kTile * u + lane_off));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if constexpr (FORM == kMfma) acc = mfma(const_ones(), x[u], acc);
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_span_kernel(const _Float
             }
         }
         for (; t < end; t += kTile) {
-            const half8 x = load8_guarded(in, t + (uint64_t)lane_off, end);
+            const half8 x = load8_guarded<true>(in, t + (uint64_t)lane_off, end);
             if constexpr (FORM == kMfma) acc = mfma(const_ones(), x, acc);
             else s0 += sum8(x);
         }
