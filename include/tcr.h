@@ -28,8 +28,8 @@
  *   call that would have to allocate, grow or initialise workspace while its stream is capturing returns
  *   TCR_ERR_UNSUPPORTED and records nothing (run the same call once outside the capture, or supply a workspace
  *   and run one chained scan on it first).  Calls that use no workspace (scans with seg_len <= 4096, reduces
- *   with seg_len <= 262144 -- powers of two; other segment lengths below 65536; irregular segments; default
- *   variant and tuning) never do.
+ *   with seg_len <= 262144 -- powers of two; other segment lengths below 65536; default variant and tuning)
+ *   never do.
  *   From the first recorded chained scan on, the workspace keeps its launch counters on the device and every
  *   chained scan on it, recorded or not, is preceded by one small bookkeeping kernel.  The "fused"
  *   reduce_finish variant cannot be recorded.
@@ -90,17 +90,22 @@ tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, vo
 /*
  * Irregular segments (the paper pads them to regular ones, footnote in Section 3; here the segment
  * boundaries are read directly).  Segment s is in[offsets[s] .. offsets[s+1]); offsets is a DEVICE pointer to
- * nseg + 1 non-decreasing element indices, 8-byte aligned; empty segments are allowed.
+ * nseg + 1 non-decreasing element indices, 8-byte aligned, none larger than n; empty segments are allowed.
+ * n is the number of elements of `in` (and of `out` for the scan): the launch is sized by it, the segments
+ * may cover any part [offsets[0], offsets[nseg]) of it.
  *   tcr_irregular_reduce  out[s] = sum of segment s (0 for an empty one); out: nseg floats.
  *   tcr_irregular_scan    out[k] = sum of in[offsets[s] .. k] for k in segment s; out is indexed like `in`
  *                         (positions outside [offsets[0], offsets[nseg]) are not written).
- * in and out need only their natural alignment (2 and 4 bytes); with 16-byte aligned pointers whole 8-element
- * groups of the array are read and written at once.  The offsets are not validated (they live on the device);
- * indices beyond the caller's arrays are the caller's error.  One wavefront per
- * segment.  nseg == 0 is a no-op.
+ * With 16-byte aligned in (and out, for the scan) the work is divided by elements, not by segments: fixed
+ * tiles of the array, chained through the workspace like the long regular scans (tcr_workspace_bytes for a
+ * full scan of n elements covers it), at a speed that does not depend on the mix of segment lengths.
+ * Otherwise in and out need only their natural alignment (2 and 4 bytes) and one wavefront walks each
+ * segment.  The offsets are not validated (they live on the device): entries that decrease or exceed n
+ * give wrong results for the segments they bound, never an access outside in[0 .. n) and the outputs.
+ * nseg == 0 is a no-op.
  */
-tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *out, uint64_t nseg, void *stream);
-tcr_status tcr_irregular_scan(const void *in, const uint64_t *offsets, float *out, uint64_t nseg, void *stream);
+tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg, void *stream);
+tcr_status tcr_irregular_scan(const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg, void *stream);
 
 /*
  * First two moments of every segment: the statistics of a normalisation layer, which the paper's conclusion

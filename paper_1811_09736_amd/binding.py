@@ -51,8 +51,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_scan_ex.argtypes = [vp, vp, u64, ctypes.c_uint32, vp]
     lib.tcr_segmented_scan_ex.restype = ctypes.c_int
     lib.tcr_scan_ex.restype = ctypes.c_int
-    lib.tcr_irregular_reduce.argtypes = [vp, vp, fp, u64, vp]
-    lib.tcr_irregular_scan.argtypes = [vp, vp, fp, u64, vp]
+    lib.tcr_irregular_reduce.argtypes = [vp, vp, fp, u64, u64, vp]
+    lib.tcr_irregular_scan.argtypes = [vp, vp, fp, u64, u64, vp]
     lib.tcr_irregular_reduce.restype = ctypes.c_int
     lib.tcr_irregular_scan.restype = ctypes.c_int
     lib.tcr_reduce.argtypes = [vp, fp, u64, vp]
@@ -192,7 +192,7 @@ def irregular_reduce(x: torch.Tensor, offsets: torch.Tensor, out: Optional[torch
         out = torch.empty(nseg, dtype=torch.float32, device=x.device)
     _check_output(out, nseg, x)
     with torch.cuda.device(x.device):
-        st = _lib.tcr_irregular_reduce(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), nseg, _stream_handle(stream))
+        st = _lib.tcr_irregular_reduce(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), x.numel(), nseg, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_irregular_reduce")
     return out
@@ -208,7 +208,7 @@ def irregular_scan(x: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.T
         out = torch.zeros(x.numel(), dtype=torch.float32, device=x.device)
     _check_output(out, x.numel(), x)
     with torch.cuda.device(x.device):
-        st = _lib.tcr_irregular_scan(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), nseg, _stream_handle(stream))
+        st = _lib.tcr_irregular_scan(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), x.numel(), nseg, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_irregular_scan")
     return out

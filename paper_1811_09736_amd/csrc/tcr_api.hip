@@ -38,35 +38,39 @@ extern "C" tcr_status tcr_scan_ex(const void* in, void* out, uint64_t n, uint32_
     return tcr_segmented_scan_ex(in, out, n, n, flags, stream);
 }
 
-extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offsets, float* out, uint64_t nseg,
+static tcr_status validate_irregular(const void* in, const uint64_t* offsets, const float* out, uint64_t n, uint64_t nseg) {
+    if (in == nullptr && n != 0) return TCR_ERR_INVALID_ARG;
+    if (offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
+    if (nseg > kMaxElements || n > kMaxElements) return TCR_ERR_UNSUPPORTED;
+    return TCR_OK;
+}
+
+extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
                                            void* stream) {
     if (nseg == 0) return TCR_OK;
-    if (in == nullptr || offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
-    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
-    if (nseg > kMaxElements) return TCR_ERR_UNSUPPORTED;
-    if (aligned(in, 16)) {                   // 128-bit loads of whole 8-element groups of the array
-        masked_irregular_kernel<false><<<dim3((unsigned)ceil_div(nseg, kMaskedWaves)), dim3(kMaskedWaves * kWave), 0,
-                                         static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
-        return check_launch("masked_irregular_kernel");
+    const tcr_status st = validate_irregular(in, offsets, out, n, nseg);
+    if (st != TCR_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) {                            // every segment is empty
+        fill_zero_kernel<<<dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, s>>>(out, nseg);
+        return check_launch("fill_zero_kernel");
     }
-    irregular_wave_kernel<false><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0,
-                                   static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
+    if (aligned(in, 16)) return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, out, n, nseg, s);
+    irregular_wave_kernel<false><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
+        static_cast<const _Float16*>(in), offsets, out, nseg);
     return check_launch("irregular_wave_kernel");
 }
 
-extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets, float* out, uint64_t nseg,
+extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
                                          void* stream) {
-    if (nseg == 0) return TCR_OK;
-    if (in == nullptr || offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
-    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
-    if (nseg > kMaxElements) return TCR_ERR_UNSUPPORTED;
-    if (aligned(in, 16) && aligned(out, 16)) {
-        masked_irregular_kernel<true><<<dim3((unsigned)ceil_div(nseg, kMaskedWaves)), dim3(kMaskedWaves * kWave), 0,
-                                        static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
-        return check_launch("masked_irregular_kernel");
-    }
-    irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0,
-                                  static_cast<hipStream_t>(stream)>>>(static_cast<const _Float16*>(in), offsets, out, nseg);
+    if (nseg == 0 || n == 0) return TCR_OK;
+    const tcr_status st = validate_irregular(in, offsets, out, n, nseg);
+    if (st != TCR_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (aligned(in, 16) && aligned(out, 16)) return launch_irregular_scan(static_cast<const _Float16*>(in), offsets, out, n, nseg, s);
+    irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
+        static_cast<const _Float16*>(in), offsets, out, nseg);
     return check_launch("irregular_wave_kernel");
 }
 

@@ -579,6 +579,80 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
     }
 }
 
+// Irregular segments over 16-byte aligned arrays: fixed tiles of the flat array, whatever the segments.
+constexpr int kIrregularScanU = 4, kIrregularScanW = 16;        // 32768-element tiles, chained
+constexpr int kIrregularReduceU = 4, kIrregularReduceW = 8;     // 16384-element tiles, independent
+inline uint64_t irregular_tiles(bool scan, uint64_t n) {
+    return ceil_div(n, (uint64_t)kTile * (scan ? kIrregularScanU * kIrregularScanW : kIrregularReduceU * kIrregularReduceW));
+}
+// 8-byte words of the partials area: the look-up table(s) of the tile boundaries, and for the reduction one
+// carried-segment index and one pair per tile and one pair per group of 64 tiles.
+inline uint64_t irregular_words(bool scan, uint64_t n) {
+    const uint64_t tiles = irregular_tiles(scan, n);
+    return scan ? tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
+}
+
+inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
+                                        hipStream_t s) {
+    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularScanU * kIrregularScanW;
+    const uint64_t tiles = irregular_tiles(true, n);
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    st = ensure_partials(ws, s, 2 * irregular_words(true, n), capturing);
+    if (st != TCR_OK) return st;
+    ScanWorkspace dev = {};
+    st = begin_lookback(ws, s, tiles, &dev, capturing);
+    if (st != TCR_OK) return st;
+    uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
+    irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+        offsets, nseg + 1, kElems, tiles + 1, starts, nullptr);
+    st = check_launch("irregular_bounds_kernel");
+    if (st != TCR_OK) return st;
+    irregular_scan_kernel<kIrregularScanU, kIrregularScanW><<<dim3((unsigned)tiles), dim3(kIrregularScanW * kWave), 0, s>>>(
+        in, offsets, out, n, nseg, starts, dev);
+    st = check_launch("irregular_scan_kernel");
+    if (st != TCR_OK) {
+        ws->dirty = true;
+        return st;
+    }
+    ws->tickets_issued += (uint32_t)tiles;
+    return TCR_OK;
+}
+
+inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
+                                          hipStream_t s) {
+    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
+    const uint64_t tiles = irregular_tiles(false, n);
+    const uint64_t groups = ceil_div(tiles, kWave);
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    st = ensure_partials(ws, s, 2 * irregular_words(false, n), capturing);
+    if (st != TCR_OK) return st;
+    uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
+    uint64_t* ends = starts + (tiles + 1);
+    uint64_t* carried = ends + (tiles + 1);
+    TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);
+    TilePair* group_pairs = pairs + tiles;
+    irregular_bounds_kernel<<<dim3((unsigned)ceil_div(2 * (tiles + 1), kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+        offsets, nseg + 1, kElems, tiles + 1, starts, ends);
+    st = check_launch("irregular_bounds_kernel");
+    if (st != TCR_OK) return st;
+    irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW><<<dim3((unsigned)tiles), dim3(kIrregularReduceW * kWave), 0, s>>>(
+        in, offsets, out, n, starts, ends, pairs, carried);
+    st = check_launch("irregular_reduce_kernel");
+    if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it
+    irregular_groups_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, tiles, group_pairs);
+    st = check_launch("irregular_groups_kernel");
+    if (st != TCR_OK) return st;
+    irregular_carry_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, group_pairs, carried,
+                                                                                                            tiles, out);
+    return check_launch("irregular_carry_kernel");
+}
+
 inline tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {
     if (seg_len == 0) return TCR_ERR_INVALID_ARG;
     if (n % seg_len != 0) return TCR_ERR_INVALID_ARG;

@@ -1,0 +1,426 @@
+// Irregular segments given by an offsets array, load-balanced: the work is cut by ELEMENTS, not by
+// segments.  A workgroup owns a fixed tile of the flat array whatever the segments look like, so sixteen
+// million segments of a few elements, a handful of segments of a hundred million elements and any mix
+// of the two all run as the same stream of aligned 128-bit loads and stores.
+//
+// The paper treats the irregular case by padding the input to regular segments (Section 3, footnote);
+// reading the offsets needs no padded copy.  Segment starts inside a tile make the scan operator
+// "restart here", which no constant operand matrix expresses (the triangular matrix would have to differ
+// from tile row to tile row), so the tile arithmetic is the cross-lane formulation throughout: a lane
+// scans its 8 consecutive elements, (flag, value) pairs are combined across lanes with DPP under
+//     (fl, vl) . (fr, vr) = (fl | fr,  fr ? vr : vl + vr),
+// across a wavefront's sub-tiles in registers and across wavefronts through LDS.  Across tiles the scan
+// uses the descriptor chain of the regular scans -- a tile that contains a segment start publishes the
+// sum since its last start as a finished prefix at once, because no later tile can need more of it --
+// while the reduction, where at most one result per tile depends on earlier tiles, leaves the tiles
+// independent and adds that one carry afterwards (two small kernels over the per-tile sums).
+//
+// What a tile needs from the offsets is found before it starts: irregular_bounds_kernel writes, per
+// tile boundary, how many offsets lie below it, so a tile reads its range of entries with one look-up
+// instead of searching while its data waits in registers.
+#pragma once
+#include "tcr_scan.hpp"
+
+namespace tcr {
+
+// Number of entries of the sorted array a[0 .. count) that are smaller than key, found by one whole
+// wavefront probing 64 places per round.  Returned uniformly.
+__device__ __forceinline__ uint64_t wave_lower_bound(const uint64_t* __restrict__ a, uint64_t count, uint64_t key,
+                                                      int lane) {
+    uint64_t lo = 0, hi = count;             // a[i] < key for i < lo;  a[i] >= key for i >= hi
+    while (lo < hi) {
+        const uint64_t step = (hi - lo + (uint64_t)(kWave - 1)) / (uint64_t)kWave;
+        const uint64_t idx = lo + step * (uint64_t)(lane + 1) - 1;
+        const bool below = idx < hi && a[idx] < key;
+        const uint64_t c = (uint64_t)__builtin_popcountll(__ballot(below));        // a sorted: the first c lanes
+        const uint64_t first_not_below = lo + step * (c + 1) - 1;                  // lane c's probe, if it made one
+        hi = first_not_below < hi ? first_not_below : hi;
+        lo = lo + step * c;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ uint32_t wave_shr1_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x138, 0xf, 0xf, true);
+}
+
+// One step of the segmented scan: the pair CTRL places to the left (or the identity (0, 0) where the
+// DPP pattern delivers nothing) is combined in front of this lane's pair.
+template <int CTRL, int ROW_MASK, bool BOUND>
+__device__ __forceinline__ void seg_combine_left(uint32_t& f, float& v) {
+    const uint32_t fl = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)f, CTRL, ROW_MASK, 0xf, BOUND);
+    const float vl = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
+    v = f ? v : v + vl;
+    f |= fl;
+}
+
+// Inclusive segmented scan over the 64 lanes: on return (f, v) of lane l is the combination of the
+// pairs of lanes 0 .. l.
+__device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float& v) {
+    seg_combine_left<0x111, 0xf, true>(f, v);
+    seg_combine_left<0x112, 0xf, true>(f, v);
+    seg_combine_left<0x114, 0xf, true>(f, v);
+    seg_combine_left<0x118, 0xf, true>(f, v);
+    seg_combine_left<0x142, 0xa, false>(f, v);     // lane 15 of rows 0 and 2 -> rows 1 and 3
+    seg_combine_left<0x143, 0xc, false>(f, v);     // lane 31 -> rows 2 and 3
+}
+
+// Sum of a lane's 8 elements behind its last segment start (all 8 if it has none).
+__device__ __forceinline__ float lane_tail_sum(half8 x, uint32_t heads) {
+    float q = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q = ((heads >> e) & 1u ? 0.0f : q) + (float)x[e];
+    return q;
+}
+
+// table[i] = number of entries of offsets[0 .. count) below i * tile_elems (+ 1 for the second table, which
+// turns "segment starts in [begin, end)" into "segment ends in (begin, end]"), i = 0 .. boundaries - 1.
+// One wavefront per look-up.
+constexpr int kBoundsWaves = 4;
+__global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(const uint64_t* __restrict__ offsets,
+                                                                                uint64_t count, uint64_t tile_elems,
+                                                                                uint64_t boundaries,
+                                                                                uint64_t* __restrict__ starts_below,
+                                                                                uint64_t* __restrict__ ends_below) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t w = (uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool second = w >= boundaries;
+    const uint64_t i = second ? w - boundaries : w;
+    if (i >= boundaries || (second && ends_below == nullptr)) return;
+    const uint64_t r = wave_lower_bound(offsets, count, i * tile_elems + (second ? 1u : 0u), lane);
+    if (lane == 0) (second ? ends_below : starts_below)[i] = r;
+}
+
+// Per sub-tile: the pair of every lane's predecessors and the sub-tile's own pair, chained over the
+// wavefront's U sub-tiles.  `run` / `chunk_flag` leave as the pair of the wavefront's whole share.
+template <int U>
+struct WaveShare {
+    uint32_t heads[U], lane_flag[U], seen_before[U];
+    float lane_value[U], before[U];
+    float run;
+    uint32_t chunk_flag;
+};
+
+template <int U>
+__device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x)[U], const uint8_t* head_bytes, bool has_heads,
+                                                int lane) {
+    w.run = 0.0f;
+    w.chunk_flag = 0u;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        w.heads[u] = has_heads ? (uint32_t)head_bytes[(kTile / 8) * u + lane] : 0u;
+        uint32_t f = w.heads[u] != 0u ? 1u : 0u;
+        float v = lane_tail_sum(x[u], w.heads[u]);
+        wave_seg_scan_inclusive(f, v);
+        w.lane_flag[u] = wave_shr1_u32(f);
+        w.lane_value[u] = wave_shr1(v);
+        const uint32_t sub_flag = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
+        const float sub_value = read_lane(v, 63);
+        w.before[u] = w.run;
+        w.seen_before[u] = w.chunk_flag;
+        w.run = sub_flag ? sub_value : w.run + sub_value;
+        w.chunk_flag |= sub_flag;
+    }
+}
+
+// Running sums of a lane's 8 elements of sub-tile u, given the sum `ext` that reaches the wavefront's share
+// from in front of it.
+template <int U>
+__device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const half8 (&x)[U], int u, float ext, float (&p)[8]) {
+    const float into_sub = w.seen_before[u] ? w.before[u] : w.before[u] + ext;
+    float q = w.lane_flag[u] ? w.lane_value[u] : w.lane_value[u] + into_sub;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        q = ((w.heads[u] >> e) & 1u ? 0.0f : q) + (float)x[u][e];
+        p[e] = q;
+    }
+}
+
+// Tile geometry of both kernels: WAVES wavefronts, each with U consecutive 512-element sub-tiles; a lane holds
+// elements 8 lane .. 8 lane + 7 of a sub-tile.  Heads are the positions offsets[0 .. nseg]; a bit per head in
+// an LDS bitmap tells every lane where its running sums restart.  offsets must be non-decreasing and at
+// most n.
+//
+// Scan: out[k] = inclusive running sum of the segment that contains k, offsets[0] <= k < offsets[nseg].
+template <int U, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, float* __restrict__ out,
+                           uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, ScanWorkspace ws_arg) {
+    constexpr uint32_t kChunk = (uint32_t)kTile * U;          // one wavefront's share
+    constexpr uint32_t kBlockTile = kChunk * WAVES;           // one workgroup's share
+    __shared__ uint32_t s_heads[kBlockTile / 32];
+    __shared__ float s_wave_value[WAVES];
+    __shared__ uint32_t s_wave_flag[WAVES];
+    __shared__ float s_prefix;
+    __shared__ uint32_t s_tile;
+
+    const ScanWorkspace ws = resolve_workspace(ws_arg);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // tiles are handed out in launch order, so every predecessor of a waiting tile is running or finished
+    if (threadIdx.x == 0)
+        s_tile = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+    for (uint32_t i = threadIdx.x; i < kBlockTile / 32; i += WAVES * kWave) s_heads[i] = 0u;
+    __syncthreads();
+    const uint32_t tile = s_tile;
+    if (tile == 0 && threadIdx.x == 0 && ws.state != nullptr && !ws.device_managed) ws.state[0] = ws.epoch;
+
+    const uint64_t tb = (uint64_t)tile * kBlockTile;
+    const uint64_t base = tb + (uint64_t)wave * kChunk;
+    const bool full = base + kChunk <= n;
+    half8 x[U];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8(in, base + (uint64_t)(kTile * u + 8 * lane));
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + 8 * lane), n);
+    }
+
+    const uint64_t head_lo = starts_below[tile], head_hi = starts_below[tile + 1];     // heads in [tb, tb + tile)
+    const bool has_heads = head_lo < head_hi;
+    if (has_heads) {
+        for (uint64_t s = head_lo + threadIdx.x; s < head_hi; s += (uint64_t)(WAVES * kWave)) {
+            const uint64_t pos = offsets[s] - tb;
+            if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
+        }
+        __syncthreads();
+    }
+
+    WaveShare<U> w;
+    wave_share_scan<U>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
+    if (lane == 0) {
+        s_wave_value[wave] = w.run;
+        s_wave_flag[wave] = w.chunk_flag;
+    }
+    __syncthreads();
+
+    // carry from the wavefronts in front, back to the nearest one that holds a head
+    float ext = 0.0f;
+    bool open = true;                         // no head between the tile's start and this wavefront's share
+    for (int v = wave - 1; v >= 0; --v) {
+        ext += s_wave_value[v];
+        if (s_wave_flag[v]) {
+            open = false;
+            break;
+        }
+    }
+    if (wave == 0) {
+        float total = 0.0f;
+        bool closed = false;
+        for (int v = WAVES - 1; v >= 0; --v) {
+            total += s_wave_value[v];
+            if (s_wave_flag[v]) {
+                closed = true;
+                break;
+            }
+        }
+        // nothing in front of the tile can reach into it if it starts with a head (or is the first)
+        const uint32_t reach = (has_heads && (s_heads[0] & 1u)) ? 0u : tile;
+        const float pre = lookback_carry<64>(ws, tile, reach, closed, total, lane);
+        if (lane == 0) s_prefix = pre;
+    }
+    __syncthreads();
+    if (open) ext += s_prefix;
+
+    const uint64_t first = offsets[0], last = offsets[nseg];
+    const bool inside = first <= tb && tb + kBlockTile <= last;       // every element of the tile is in a segment
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float p[8];
+        wave_share_finish<U>(w, x, u, ext, p);
+        const uint64_t k = base + (uint64_t)(kTile * u + 8 * lane);
+        if (inside) {
+            store4(out, k, (float4v){p[0], p[1], p[2], p[3]});
+            store4(out, k + 4, (float4v){p[4], p[5], p[6], p[7]});
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (k + e >= first && k + e < last) out[k + e] = p[e];
+        }
+    }
+}
+
+// Sum of one tile since its last head (all of it if it has none) and whether it has one: the pair that later
+// tiles may need of it.
+struct TilePair {
+    float value;
+    uint32_t flag;
+};
+constexpr uint64_t kNoSegment = ~0ull;
+
+__device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);
+    return x;
+}
+
+// Reduction: out[s] = sum of segment s.  Tiles are independent.  A wavefront stages the running sums of a
+// sub-tile in its own 2 KiB of LDS and the lanes then walk the entries of offsets that end a segment
+// inside that sub-tile, so consecutive lanes write consecutive results.  The one result per tile that
+// belongs to a segment begun in an earlier tile is written without that earlier part; the tile records
+// which segment it is (carried[tile], or none) and its own pair (pairs[tile]) for the carry kernels.
+template <int U, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _Float16* __restrict__ in,
+                                                                         const uint64_t* __restrict__ offsets,
+                                                                         float* __restrict__ out, uint64_t n,
+                                                                         const uint64_t* __restrict__ starts_below,
+                                                                         const uint64_t* __restrict__ ends_below,
+                                                                         TilePair* __restrict__ pairs,
+                                                                         uint64_t* __restrict__ carried) {
+    constexpr uint32_t kChunk = (uint32_t)kTile * U;
+    constexpr uint32_t kBlockTile = kChunk * WAVES;
+    constexpr int kSubs = U * WAVES;
+    static_assert(kSubs <= kWave, "one lane per sub-tile count");
+    __shared__ uint32_t s_heads[kBlockTile / 32];
+    __shared__ uint32_t s_ends[kSubs];            // segment ends per sub-tile
+    __shared__ float s_wave_value[WAVES];
+    __shared__ uint32_t s_wave_flag[WAVES];
+    __shared__ __attribute__((aligned(16))) float s_stage[WAVES][kTile];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t tile = blockIdx.x;
+    const uint64_t tb = (uint64_t)tile * kBlockTile;
+    const uint64_t base = tb + (uint64_t)wave * kChunk;
+    const bool full = base + kChunk <= n;
+    half8 x[U];
+    if (full) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8<true>(in, base + (uint64_t)(kTile * u + 8 * lane));
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded<true>(in, base + (uint64_t)(kTile * u + 8 * lane), n);
+    }
+    for (uint32_t i = threadIdx.x; i < kBlockTile / 32; i += WAVES * kWave) s_heads[i] = 0u;
+    if (threadIdx.x < kSubs) s_ends[threadIdx.x] = 0u;
+
+    // entries [head_lo, head_hi) lie in [tb, tb + tile): heads; entries [end_lo, end_hi) lie in
+    // (tb, tb + tile]: each closes the segment in front of it.  head_lo <= end_lo, head_hi <= end_hi.
+    const uint64_t head_lo = starts_below[tile], head_hi = starts_below[tile + 1];
+    // (the first tile also takes the entries on position 0, which close empty segments in front of everything)
+    const uint64_t end_lo = tile == 0 ? 0 : ends_below[tile], end_hi = ends_below[tile + 1];
+    const bool has_entries = head_lo < end_hi;
+    __syncthreads();
+    if (has_entries) {
+        for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
+            const uint64_t pos = offsets[s] - tb;
+            if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
+            if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
+            else if (pos == 0 && tile == 0) atomicAdd(&s_ends[0], 1u);
+        }
+        __syncthreads();
+    }
+    const bool has_heads = head_lo < head_hi;
+
+    WaveShare<U> w;
+    wave_share_scan<U>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
+    if (lane == 0) {
+        s_wave_value[wave] = w.run;
+        s_wave_flag[wave] = w.chunk_flag;
+    }
+    __syncthreads();
+
+    if (wave == 0 && lane == 0) {
+        float total = 0.0f;
+        uint32_t closed = 0u;
+        for (int v = WAVES - 1; v >= 0; --v) {
+            total += s_wave_value[v];
+            if (s_wave_flag[v]) {
+                closed = 1u;
+                break;
+            }
+        }
+        pairs[tile] = TilePair{total, closed};
+        // the first segment end of the tile closes a segment begun earlier unless an entry sits on tb itself
+        carried[tile] = (end_lo < end_hi && end_lo == head_lo && end_lo >= 1) ? end_lo - 1 : kNoSegment;
+    }
+    if (end_lo == end_hi) return;             // no segment ends here: nothing to write
+
+    float ext = 0.0f;                         // carry from the wavefronts in front, inside this tile only
+    for (int v = wave - 1; v >= 0; --v) {
+        ext += s_wave_value[v];
+        if (s_wave_flag[v]) break;
+    }
+    // entries that end a segment in each of this wavefront's sub-tiles
+    const uint32_t mine = lane < kSubs ? s_ends[lane] : 0u;
+    const uint32_t upto = wave_scan_inclusive_u32(mine);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int sub = wave * U + u;
+        const uint32_t count = (uint32_t)__builtin_amdgcn_readlane((int)mine, sub);
+        if (count == 0u) continue;
+        const uint64_t entry0 = end_lo + (uint64_t)((uint32_t)__builtin_amdgcn_readlane((int)upto, sub) - count);
+        float p[8];
+        wave_share_finish<U>(w, x, u, ext, p);
+        float4v* dst = reinterpret_cast<float4v*>(&s_stage[wave][8 * lane]);
+        dst[0] = (float4v){p[0], p[1], p[2], p[3]};
+        dst[1] = (float4v){p[4], p[5], p[6], p[7]};
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint64_t sub_base = tb + (uint64_t)sub * kTile;
+        for (uint32_t r = (uint32_t)lane; r < count; r += (uint32_t)kWave) {
+            const uint64_t s = entry0 + r;
+            if (s == 0) continue;                                  // offsets[0] closes nothing
+            const uint64_t end = offsets[s], begin = offsets[s - 1];
+            const uint64_t at = end - 1 - sub_base;                // the segment's last element
+            out[s - 1] = (end > begin && at < (uint64_t)kTile) ? s_stage[wave][at] : 0.0f;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
+// The pairs of 64 consecutive tiles combined into one (one wavefront per group).
+constexpr int kCarryWaves = 4;
+__global__ __launch_bounds__(kCarryWaves * kWave) void irregular_groups_kernel(const TilePair* __restrict__ pairs,
+                                                                               uint64_t tiles,
+                                                                               TilePair* __restrict__ groups) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t g = (uint64_t)blockIdx.x * kCarryWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (g * kWave >= tiles) return;
+    const uint64_t t = g * kWave + (uint64_t)lane;
+    TilePair mine = {0.0f, 0u};
+    if (t < tiles) mine = pairs[t];
+    wave_seg_scan_inclusive(mine.flag, mine.value);
+    if (lane == kWave - 1) groups[g] = mine;
+}
+
+// Adds to the one carried result of every tile the sum that reaches the tile from the tiles in front of
+// it: the groups back to the nearest one with a head, then the tiles of its own group.  Plain loads, fixed
+// order: the results do not vary from run to run.
+__global__ __launch_bounds__(kCarryWaves * kWave) void irregular_carry_kernel(const TilePair* __restrict__ pairs,
+                                                                              const TilePair* __restrict__ groups,
+                                                                              const uint64_t* __restrict__ carried,
+                                                                              uint64_t tiles, float* __restrict__ out) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t g = (uint64_t)blockIdx.x * kCarryWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (g * kWave >= tiles) return;
+    const uint64_t t = g * kWave + (uint64_t)lane;
+    const uint64_t seg = t < tiles ? carried[t] : kNoSegment;
+    if (__ballot(seg != kNoSegment) == 0ull) return;
+    float into_group = 0.0f;
+    for (uint64_t reach = g; reach > 0; reach = reach > (uint64_t)kWave ? reach - kWave : 0) {
+        const bool valid = (uint64_t)lane < reach;
+        TilePair q = {0.0f, 0u};
+        if (valid) q = groups[reach - 1 - (uint64_t)lane];          // lane 0 reads the nearest group
+        const unsigned long long closed = __ballot(valid && q.flag != 0u);
+        const int nearest = closed != 0ull ? __builtin_ctzll(closed) : kWave;
+        into_group += wave_sum((valid && lane <= nearest) ? q.value : 0.0f);
+        if (closed != 0ull) break;
+    }
+    TilePair mine = {0.0f, 0u};
+    if (t < tiles) mine = pairs[t];
+    wave_seg_scan_inclusive(mine.flag, mine.value);
+    const uint32_t flag_before = wave_shr1_u32(mine.flag);
+    const float value_before = wave_shr1(mine.value);
+    if (seg != kNoSegment) out[seg] += flag_before ? value_before : value_before + into_group;
+}
+
+}  // namespace tcr

@@ -195,24 +195,23 @@ __device__ __forceinline__ unsigned long long load_descriptor(const unsigned lon
 
 // Executed by one whole wavefront.  Returns (uniformly) the sum of the totals of all earlier
 // tiles of this tile's segment and publishes this tile's own state.
-//   pos   index of this tile inside its segment (0 = first tile of the segment)
-//   WIN   descriptors inspected per round (the WIN nearest predecessors, one per lane).
+//   pos     number of earlier tiles that may belong to this tile's segment (0 = none: nothing to look up)
+//   closed  a segment starts inside this tile: `total` is then the sum since the last such start, which is
+//           all a later tile can need of this one, so it is published as a finished prefix at once and
+//           the carry found here (for the elements in front of the first start) is not added to it
+//   WIN     descriptors inspected per round (the WIN nearest predecessors, one per lane).
 // Every agent-scope read costs a slice of a resource shared by the whole chip (measured: one
 // 64-wide read per tile adds ~6 ns per tile to the launch, and wider windows only add to it), so
 // the window is kept as narrow as the distance to the nearest finished prefix allows.
 template <int WIN>
-__device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint32_t pos,
-                                                           float total, int lane) {
+__device__ __forceinline__ float lookback_carry(const ScanWorkspace& ws, uint32_t tile, uint32_t pos, bool closed,
+                                                float total, int lane) {
     static_assert(WIN >= 1 && WIN <= kWave, "");
-    if (pos == 0) {
-        if (lane == 0)
-            __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, total), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        return 0.0f;
-    }
+    const bool final_now = closed || pos == 0;
     if (lane == 0)
-        __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusAggregate, total), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, final_now ? kStatusPrefix : kStatusAggregate, total),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (pos == 0) return 0.0f;
     constexpr int kNone = 1 << 30;
     float acc = 0.0f;
     uint32_t base = 0;                           // this round inspects distances base+1 .. base+WIN
@@ -250,10 +249,17 @@ __device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& 
         if (nearest != kNone) break;
         base += (uint32_t)WIN;
     }
-    if (lane == 0)
+    if (lane == 0 && !final_now)
         __hip_atomic_store(&ws.desc[tile], pack_desc(ws.epoch, kStatusPrefix, acc + total), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     return acc;
+}
+
+// Regular segments: tile number `pos` of its segment has exactly `pos` predecessors and no start inside.
+template <int WIN>
+__device__ __forceinline__ float lookback_exclusive_prefix(const ScanWorkspace& ws, uint32_t tile, uint32_t pos,
+                                                           float total, int lane) {
+    return lookback_carry<WIN>(ws, tile, pos, false, total, lane);
 }
 
 // ------------------------------------------------------------------------------ long segments

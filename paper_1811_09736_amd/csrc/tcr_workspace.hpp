@@ -16,6 +16,7 @@
 #include "tcr_reduce.hpp"
 #include "tcr_scan.hpp"
 #include "tcr_generic.hpp"
+#include "tcr_irregular.hpp"
 
 namespace tcr {
 namespace host {

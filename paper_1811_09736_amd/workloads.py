@@ -51,6 +51,38 @@ def make_input(n: int, dist: str, seed) -> np.ndarray:
     return out
 
 
+def make_offsets(n: int, recipe: str, seed) -> np.ndarray:
+    """Return uint64 offsets[nseg + 1] (offsets[0] = 0, offsets[-1] = n, non-decreasing) cutting n elements
+    into irregular segments.  The paper evaluates regular segments only; these recipes give the
+    irregular entry points length mixes of the same scale as its sweep:
+
+    * ``"uniform<M>"``   lengths i.i.d. uniform on {0..2M} (mean M, empty segments included);
+    * ``"lognormal<M>"`` lengths i.i.d. log-normal with median M and sigma 2 (heavy tail: most segments are
+      short, most elements lie in a few long ones);
+    * ``"few<K>"``       K - 1 cut points i.i.d. uniform on {0..n} (K very long segments).
+    """
+    rng = np.random.default_rng(seed)
+    if recipe.startswith("few"):
+        cuts = np.sort(rng.integers(0, n, int(recipe[3:]) - 1, endpoint=True).astype(np.uint64))
+        return np.concatenate(([0], cuts, [n])).astype(np.uint64)
+    if recipe.startswith("uniform"):
+        m = int(recipe[7:])
+        draw = lambda k: rng.integers(0, 2 * m, k, endpoint=True)
+    elif recipe.startswith("lognormal"):
+        m = int(recipe[9:])
+        draw = lambda k: np.floor(rng.lognormal(np.log(m), 2.0, k)).astype(np.int64)
+    else:
+        raise ValueError(f"unknown offsets recipe {recipe!r}")
+    parts, total = [], 0
+    while total < n:
+        lens = draw(max(1024, n // max(m, 1) // 4 + 1))
+        parts.append(lens)
+        total += int(lens.sum())
+    ends = np.cumsum(np.concatenate(parts))
+    ends = ends[: int(np.searchsorted(ends, n, side="left"))]      # cut points strictly below n
+    return np.concatenate(([0], ends, [n])).astype(np.uint64)
+
+
 def sha256(x: np.ndarray) -> str:
     return hashlib.sha256(np.ascontiguousarray(x).view(np.uint8)).hexdigest()
 
