@@ -207,7 +207,22 @@ def main() -> int:
                      lambda: torch.sum(x, dtype=torch.float32), n, (2 * n, 4)),
                     ("context: torch.cumsum(x, 0, dtype=float32) (library full scan)",
                      lambda: torch.cumsum(x, 0, dtype=torch.float32, out=copy_dst), n, (2 * n, 4 * n))]
-    for label, fn, nn, rd_wr in [] if args.no_context else variant_rows + library_rows + [
+    # irregular segments (offsets array): three length mixes over the same input; the offsets are part of the
+    # bytes the call must read
+    irregular_rows = []
+    if not args.no_context:
+        import numpy as np
+        for recipe, what in (("uniform16", "lengths uniform on 0..32"), ("lognormal256", "log-normal lengths, median 256, sigma 2"),
+                             ("few7", "7 segments cut at random")):
+            off = torch.from_numpy(workloads.make_offsets(n, recipe, 5).view(np.int64)).cuda()
+            nseg = off.numel() - 1
+            out_i = torch.empty(nseg, dtype=torch.float32, device="cuda")
+            irregular_rows.append((f"irregular_reduce, {nseg} segments ({what})",
+                                   (lambda off=off, out_i=out_i: tcr.irregular_reduce(x, off, out=out_i)), n,
+                                   (2 * n + 8 * (nseg + 1), 4 * nseg)))
+            irregular_rows.append((f"irregular_scan, {nseg} segments ({what})",
+                                   (lambda off=off: tcr.irregular_scan(x, off, out=out_scan)), n, (2 * n + 8 * (nseg + 1), 4 * n)))
+    for label, fn, nn, rd_wr in [] if args.no_context else variant_rows + library_rows + irregular_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
             ("segmented_reduce seg_len=3*2^20 (no power of two: masked pieces + second kernel)",

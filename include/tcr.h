@@ -97,8 +97,11 @@ tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, vo
  *   tcr_irregular_scan    out[k] = sum of in[offsets[s] .. k] for k in segment s; out is indexed like `in`
  *                         (positions outside [offsets[0], offsets[nseg]) are not written).
  * With 16-byte aligned in (and out, for the scan) the work is divided by elements, not by segments: fixed
- * tiles of the array, chained through the workspace like the long regular scans (tcr_workspace_bytes for a
- * full scan of n elements covers it), at a speed that does not depend on the mix of segment lengths.
+ * tiles of the array at a speed that hardly depends on the mix of segment lengths.  Both use the workspace
+ * (tcr_workspace_bytes, op 4 and 5): one small kernel looks up where the tile boundaries fall among the
+ * offsets; the scan chains its tiles like the long regular scans; the reduction keeps its tiles independent
+ * and two small kernels add the one sum per tile that reaches in from earlier tiles -- plain loads in a fixed
+ * order, so the reduction's results are the same from run to run.
  * Otherwise in and out need only their natural alignment (2 and 4 bytes) and one wavefront walks each
  * segment.  The offsets are not validated (they live on the device): entries that decrease or exceed n
  * give wrong results for the segments they bound, never an access outside in[0 .. n) and the outputs.
@@ -162,7 +165,8 @@ tcr_status tcr_tuning_import(const char *text);
 
 /*
  * Name of the kernel the dispatcher would launch for (op, n, seg_len) under the current
- * variant settings; op is 0 = segmented_reduce, 1 = segmented_scan, 2 = reduce, 3 = scan.
+ * variant settings; op is 0 = segmented_reduce, 1 = segmented_scan, 2 = reduce, 3 = scan,
+ * 4 = irregular_reduce, 5 = irregular_scan (16-byte aligned arrays; seg_len is ignored).
  * Returns a static string ("" when nothing would be launched); never NULL.
  */
 const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);

@@ -16,7 +16,7 @@ import torch
 from .build import LIB_PATH
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
-OP_SEGMENTED_REDUCE, OP_SEGMENTED_SCAN, OP_REDUCE, OP_SCAN = range(4)
+OP_SEGMENTED_REDUCE, OP_SEGMENTED_SCAN, OP_REDUCE, OP_SCAN, OP_IRREGULAR_REDUCE, OP_IRREGULAR_SCAN = range(6)
 
 SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 

@@ -229,6 +229,8 @@ extern "C" tcr_status tcr_tuning_import(const char* text) {
 }
 
 extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
+    if (op == 4) return n ? "irregular_bounds_kernel+irregular_reduce_kernel+irregular_groups_kernel+irregular_carry_kernel" : "fill_zero_kernel";
+    if (op == 5) return n ? "irregular_bounds_kernel+irregular_scan_kernel" : "";
     if (op == 2 || op == 3) seg_len = n;
     if (n == 0 || seg_len == 0 || n % seg_len != 0) return "";
     const bool mf = g_variant.formulation == kMfma;
@@ -291,7 +293,14 @@ extern "C" tcr_status tcr_check_device_flags(void* stream) {
 }
 
 extern "C" uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len) {
-    if (op < 0 || op > 3 || n == 0) return 0;
+    if (op < 0 || op > 5 || n == 0) return 0;
+    if (op >= 4) {
+        // the irregular kernels keep 8-byte words in the partials area (look-up tables, pairs) and the scan one
+        // descriptor per tile; the two areas of a workspace are of equal size
+        const uint64_t bytes = 8 * (irregular_words(op == 5, n) > irregular_tiles(true, n) ? irregular_words(op == 5, n)
+                                                                                         : irregular_tiles(true, n));
+        return kWorkspaceHeader + 2 * ((bytes + 255) / 256 * 256);
+    }
     if (op >= 2) seg_len = n;
     if (seg_len == 0 || n % seg_len != 0) return 0;
     // Upper bounds over every variant and launch shape: one 8-byte descriptor per 16384-element share (the

@@ -637,7 +637,7 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     uint64_t* carried = ends + (tiles + 1);
     TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);
     TilePair* group_pairs = pairs + tiles;
-    irregular_bounds_kernel<<<dim3((unsigned)ceil_div(2 * (tiles + 1), kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+    irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
         offsets, nseg + 1, kElems, tiles + 1, starts, ends);
     st = check_launch("irregular_bounds_kernel");
     if (st != TCR_OK) return st;

@@ -270,23 +270,6 @@ __global__ __launch_bounds__(kGenericThreads) void generic_moments_kernel(const 
     sumsq[s] = q;
 }
 
-// Irregular segments behind 16-byte aligned pointers: the same walk, boundaries read from `offsets`.
-template <bool SCAN>
-__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_irregular_kernel(const _Float16* __restrict__ in,
-                                                                                const uint64_t* __restrict__ offsets,
-                                                                                float* __restrict__ out, uint64_t nseg) {
-    const LaneId id;
-    const uint64_t s = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (s >= nseg) return;
-    const uint64_t begin = offsets[s], end = offsets[s + 1];
-    if constexpr (SCAN) {
-        masked_wave_scan<0>(in, out, begin, end, id);
-    } else {
-        const float total = masked_wave_reduce(in, begin, end, id);
-        if (id.lane == 0) out[s] = total;
-    }
-}
-
 // Irregular segments: segment s is [offsets[s], offsets[s+1]).  One wavefront per segment, same
 // arithmetic as generic_wave_kernel.  (The paper reduces the irregular case to the regular one by
 // padding the input, Section 3 footnote; reading the offsets directly needs no padded copy.)

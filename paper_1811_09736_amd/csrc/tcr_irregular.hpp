@@ -73,9 +73,9 @@ __device__ __forceinline__ float lane_tail_sum(half8 x, uint32_t heads) {
     return q;
 }
 
-// table[i] = number of entries of offsets[0 .. count) below i * tile_elems (+ 1 for the second table, which
-// turns "segment starts in [begin, end)" into "segment ends in (begin, end]"), i = 0 .. boundaries - 1.
-// One wavefront per look-up.
+// starts_below[i] = number of entries of offsets[0 .. count) below i * tile_elems, i = 0 .. boundaries - 1;
+// ends_below[i] (optional) = the same for i * tile_elems + 1, i.e. with the entries ON the boundary added,
+// which turns "segment starts in [begin, end)" into "segment ends in (begin, end]".  One wavefront per boundary.
 constexpr int kBoundsWaves = 4;
 __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(const uint64_t* __restrict__ offsets,
                                                                                 uint64_t count, uint64_t tile_elems,
@@ -83,12 +83,20 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
                                                                                 uint64_t* __restrict__ starts_below,
                                                                                 uint64_t* __restrict__ ends_below) {
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t w = (uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const bool second = w >= boundaries;
-    const uint64_t i = second ? w - boundaries : w;
-    if (i >= boundaries || (second && ends_below == nullptr)) return;
-    const uint64_t r = wave_lower_bound(offsets, count, i * tile_elems + (second ? 1u : 0u), lane);
-    if (lane == 0) (second ? ends_below : starts_below)[i] = r;
+    const uint64_t i = (uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (i >= boundaries) return;
+    const uint64_t key = i * tile_elems;
+    const uint64_t below = wave_lower_bound(offsets, count, key, lane);
+    if (lane == 0) starts_below[i] = below;
+    if (ends_below == nullptr) return;
+    uint64_t on = 0;                          // entries equal to key follow directly
+    while (true) {
+        const uint64_t idx = below + on + (uint64_t)lane;
+        const int c = __builtin_popcountll(__ballot(idx < count && offsets[idx] == key));
+        on += (uint64_t)c;
+        if (c < kWave) break;
+    }
+    if (lane == 0) ends_below[i] = below + on;
 }
 
 // Per sub-tile: the pair of every lane's predecessors and the sub-tile's own pair, chained over the
@@ -259,11 +267,14 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
     return x;
 }
 
-// Reduction: out[s] = sum of segment s.  Tiles are independent.  A wavefront stages the running sums of a
-// sub-tile in its own 2 KiB of LDS and the lanes then walk the entries of offsets that end a segment
-// inside that sub-tile, so consecutive lanes write consecutive results.  The one result per tile that
+// Reduction: out[s] = sum of segment s.  Tiles are independent.  While the heads are marked, the position of
+// every entry of offsets that falls into the tile is kept in LDS (the first kPositions of them; a tile with
+// more -- segments under four elements on average -- reads the rest from memory again).  A wavefront then
+// stages the running sums of a sub-tile in its own 2 KiB of LDS and its lanes walk the entries that end a
+// segment inside that sub-tile, so consecutive lanes write consecutive results.  The one result per tile that
 // belongs to a segment begun in an earlier tile is written without that earlier part; the tile records
 // which segment it is (carried[tile], or none) and its own pair (pairs[tile]) for the carry kernels.
+constexpr uint32_t kPositions = 4096;
 template <int U, int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _Float16* __restrict__ in,
                                                                          const uint64_t* __restrict__ offsets,
@@ -278,6 +289,8 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     static_assert(kSubs <= kWave, "one lane per sub-tile count");
     __shared__ uint32_t s_heads[kBlockTile / 32];
     __shared__ uint32_t s_ends[kSubs];            // segment ends per sub-tile
+    __shared__ uint16_t s_position[kPositions];   // entry head_lo + i lies on element tb + s_position[i]
+    static_assert(kBlockTile <= 65535u, "positions are kept in 16 bits");
     __shared__ float s_wave_value[WAVES];
     __shared__ uint32_t s_wave_flag[WAVES];
     __shared__ __attribute__((aligned(16))) float s_stage[WAVES][kTile];
@@ -309,6 +322,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     if (has_entries) {
         for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
             const uint64_t pos = offsets[s] - tb;
+            if (s - head_lo < (uint64_t)kPositions) s_position[s - head_lo] = (uint16_t)pos;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
             if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
             else if (pos == 0 && tile == 0) atomicAdd(&s_ends[0], 1u);
@@ -363,13 +377,22 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const uint64_t sub_base = tb + (uint64_t)sub * kTile;
         for (uint32_t r = (uint32_t)lane; r < count; r += (uint32_t)kWave) {
             const uint64_t s = entry0 + r;
             if (s == 0) continue;                                  // offsets[0] closes nothing
-            const uint64_t end = offsets[s], begin = offsets[s - 1];
-            const uint64_t at = end - 1 - sub_base;                // the segment's last element
-            out[s - 1] = (end > begin && at < (uint64_t)kTile) ? s_stage[wave][at] : 0.0f;
+            const uint64_t i = s - head_lo;
+            // positions of this entry and the one before it (which lies in front of the tile if i == 0)
+            uint32_t end, begin;
+            if (i < (uint64_t)kPositions) {
+                end = s_position[i];
+                begin = i > 0 ? (uint32_t)s_position[i - 1] : 0u;
+            } else {
+                end = (uint32_t)(offsets[s] - tb);
+                begin = (uint32_t)(offsets[s - 1] - tb);
+            }
+            const uint32_t at = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
+            const bool empty = i > 0 && end == begin;
+            out[s - 1] = (!empty && at < (uint32_t)kTile) ? s_stage[wave][at] : 0.0f;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();

@@ -176,3 +176,9 @@ def test_workspace_bytes_is_a_host_side_bound(lib):
     assert big == 256 + 2 * (1 << 28) // 16384 * 8          # header + descriptors + partials
     assert big % 256 == 0
     assert wb(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == big
+    # irregular segments: look-up tables and per-tile pairs (reduce), one descriptor per 32768-element tile (scan)
+    ired, iscan = wb(lib.OP_IRREGULAR_REDUCE, 1 << 28, 0), wb(lib.OP_IRREGULAR_SCAN, 1 << 28, 0)
+    assert ired % 256 == 0 and iscan % 256 == 0
+    assert ired >= 256 + 2 * 8 * (4 * (1 << 14) + 2) and iscan >= 256 + 2 * 8 * ((1 << 13) + 1)
+    assert ired < 4 << 20 and iscan < 1 << 20
+    assert wb(lib.OP_IRREGULAR_SCAN, 0, 0) == 0

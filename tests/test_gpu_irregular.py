@@ -158,3 +158,72 @@ def test_repeated_launches_share_the_workspace(tcr, oracle):
         assert np.array_equal(scan.cpu().numpy().astype(np.float64), oracle.irregular_scan(x, off))
         assert np.array_equal(full.cpu().numpy().astype(np.float64), oracle.scan(x))
     tcr.check_device_flags()
+
+
+def test_caller_supplied_workspace(tcr, oracle):
+    n = 40 * SCAN_TILE + 16
+    x = workloads.make_input(n, "int8", 41)
+    off = workloads.make_offsets(n, "lognormal256", 3).view(np.int64)
+    xd, od = torch.from_numpy(x).cuda(), torch.from_numpy(off).cuda()
+    need = max(tcr.workspace_bytes(tcr.OP_IRREGULAR_REDUCE, n, 0), tcr.workspace_bytes(tcr.OP_IRREGULAR_SCAN, n, 0))
+    buf = torch.empty(need, dtype=torch.uint8, device="cuda")
+    try:
+        tcr.set_workspace(buf)
+        for _ in range(2):
+            assert np.array_equal(tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64), oracle.irregular_reduce(x, off))
+            assert np.array_equal(tcr.irregular_scan(xd, od).cpu().numpy().astype(np.float64), oracle.irregular_scan(x, off))
+        tcr.set_workspace(buf[:1024])                                # room for 32 tiles: too small for either
+        with pytest.raises(tcr.TcrError) as err:
+            tcr.irregular_reduce(xd, od)
+        assert err.value.status == tcr.ERR_WORKSPACE
+        with pytest.raises(tcr.TcrError) as err:
+            tcr.irregular_scan(xd, od)
+        assert err.value.status == tcr.ERR_WORKSPACE
+    finally:
+        tcr.set_workspace(None)
+    assert np.array_equal(tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64), oracle.irregular_reduce(x, off))
+
+
+def test_capture_and_replay(tcr, oracle):
+    # recorded once the workspace exists; offsets and data change between replays (same number of segments)
+    n = 5 * SCAN_TILE + 8
+    nseg = 3000
+    side = torch.cuda.Stream()
+    xd = torch.empty(n, dtype=torch.float16, device="cuda")
+    od = torch.empty(nseg + 1, dtype=torch.int64, device="cuda")
+    red = torch.empty(nseg, dtype=torch.float32, device="cuda")
+    scan = torch.empty(n, dtype=torch.float32, device="cuda")
+
+    def cuts(k):
+        c = np.sort(np.random.default_rng(k).integers(0, n, nseg - 1, endpoint=True))
+        return np.concatenate([[0], c, [n]]).astype(np.int64)
+
+    def calls():
+        tcr.irregular_reduce(xd, od, out=red)
+        tcr.irregular_scan(xd, od, out=scan)
+
+    xd.copy_(torch.from_numpy(workloads.make_input(n, "int8", 50)).cuda())
+    od.copy_(torch.from_numpy(cuts(0)).cuda())
+    with torch.cuda.stream(side):
+        calls()                                                      # eager once: the stream's workspace exists now
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    for k in (1, 2, 3):
+        x = workloads.make_input(n, "int8", 50 + k)
+        off = cuts(k)
+        xd.copy_(torch.from_numpy(x).cuda())
+        od.copy_(torch.from_numpy(off).cuda())
+        red.fill_(float("nan"))
+        scan.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(red.cpu().numpy().astype(np.float64), oracle.irregular_reduce(x, off))
+        assert np.array_equal(scan.cpu().numpy().astype(np.float64), oracle.irregular_scan(x, off))
+        with torch.cuda.stream(side):                                # eager calls share the device-managed counters
+            got = tcr.irregular_scan(xd, od)
+        side.synchronize()
+        assert np.array_equal(got.cpu().numpy().astype(np.float64), oracle.irregular_scan(x, off))
+    tcr.check_device_flags(side)
