@@ -103,7 +103,8 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
 // wavefront's U sub-tiles.  `run` / `chunk_flag` leave as the pair of the wavefront's whole share.
 template <int U>
 struct WaveShare {
-    uint32_t heads[U], lane_flag[U], seen_before[U];
+    uint32_t heads[U];            // bits 0..7: heads among the lane's 8 elements; bit 8: a head in a lane in front
+    uint32_t seen_before[U];
     float lane_value[U], before[U];
     float run;
     uint32_t chunk_flag;
@@ -120,7 +121,7 @@ __device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x
         uint32_t f = w.heads[u] != 0u ? 1u : 0u;
         float v = lane_tail_sum(x[u], w.heads[u]);
         wave_seg_scan_inclusive(f, v);
-        w.lane_flag[u] = wave_shr1_u32(f);
+        w.heads[u] |= wave_shr1_u32(f) << 8;
         w.lane_value[u] = wave_shr1(v);
         const uint32_t sub_flag = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
         const float sub_value = read_lane(v, 63);
@@ -136,7 +137,7 @@ __device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x
 template <int U>
 __device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const half8 (&x)[U], int u, float ext, float (&p)[8]) {
     const float into_sub = w.seen_before[u] ? w.before[u] : w.before[u] + ext;
-    float q = w.lane_flag[u] ? w.lane_value[u] : w.lane_value[u] + into_sub;
+    float q = (w.heads[u] >> 8) ? w.lane_value[u] : w.lane_value[u] + into_sub;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         q = ((w.heads[u] >> e) & 1u ? 0.0f : q) + (float)x[u][e];
@@ -213,38 +214,46 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
             break;
         }
     }
-    if (wave == 0) {
-        float total = 0.0f;
-        bool closed = false;
-        for (int v = WAVES - 1; v >= 0; --v) {
-            total += s_wave_value[v];
-            if (s_wave_flag[v]) {
-                closed = true;
-                break;
-            }
-        }
-        // nothing in front of the tile can reach into it if it starts with a head (or is the first)
-        const uint32_t reach = (has_heads && (s_heads[0] & 1u)) ? 0u : tile;
-        const float pre = lookback_carry<64>(ws, tile, reach, closed, total, lane);
-        if (lane == 0) s_prefix = pre;
-    }
-    __syncthreads();
-    if (open) ext += s_prefix;
-
+    // the part [valid_lo, valid_hi) of this wavefront's share lies in a segment (all of it, nearly always)
     const uint64_t first = offsets[0], last = offsets[nseg];
-    const bool inside = first <= tb && tb + kBlockTile <= last;       // every element of the tile is in a segment
+    const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
+    const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
+    const bool inside = valid_lo == 0u && valid_hi == kChunk;
+    // A wavefront behind a head needs nothing from earlier tiles and goes straight to its stores instead of
+    // waiting for the look-up (the barrier only counts the wavefronts that are still running, so it opens
+    // for the others once these have finished).  Wavefront 0 is always open.
+    if (open) {
+        if (wave == 0) {
+            float total = 0.0f;
+            bool closed = false;
+            for (int v = WAVES - 1; v >= 0; --v) {
+                total += s_wave_value[v];
+                if (s_wave_flag[v]) {
+                    closed = true;
+                    break;
+                }
+            }
+            // nothing in front of the tile can reach into it if it starts with a head (or is the first)
+            const uint32_t reach = (has_heads && (s_heads[0] & 1u)) ? 0u : tile;
+            const float pre = lookback_carry<64>(ws, tile, reach, closed, total, lane);
+            if (lane == 0) s_prefix = pre;
+        }
+        __syncthreads();
+        ext += s_prefix;
+    }
+    float* const dst = out + base;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         float p[8];
         wave_share_finish<U>(w, x, u, ext, p);
-        const uint64_t k = base + (uint64_t)(kTile * u + 8 * lane);
+        const uint32_t k = (uint32_t)(kTile * u + 8 * lane);
         if (inside) {
-            store4(out, k, (float4v){p[0], p[1], p[2], p[3]});
-            store4(out, k + 4, (float4v){p[4], p[5], p[6], p[7]});
+            store4(dst, k, (float4v){p[0], p[1], p[2], p[3]});
+            store4(dst, k + 4, (float4v){p[4], p[5], p[6], p[7]});
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                if (k + e >= first && k + e < last) out[k + e] = p[e];
+                if (k + e >= valid_lo && k + e < valid_hi) dst[k + e] = p[e];
         }
     }
 }
