@@ -103,3 +103,43 @@ def test_scan_variants_and_reduce_beyond_2_31_elements(tcr, oracle, data):
     before = torch.where(start % 7 == 0, torch.zeros((), device=xd.device), incl[(start - 1) % 7])
     assert torch.equal(red16, incl[k % 7] - before)
     tcr.check_device_flags()
+
+
+def test_irregular_segments_beyond_2_31_elements(tcr, oracle, data):
+    # 200 000 random cuts, a dense stretch of short segments across element 2^31 and a run of empty segments;
+    # closed form as above with every element's own segment start
+    x, xd = data
+    rng = np.random.default_rng(17)
+    cuts = np.concatenate([rng.integers(0, N, 200000, endpoint=True), (1 << 31) - 5000 + np.arange(0, 10000, 7),
+                           np.full(300, (1 << 31) + 77), [5, N - 3]])
+    off = np.concatenate([[5], np.sort(cuts[(cuts >= 5) & (cuts <= N - 3)]), [N - 3]]).astype(np.int64)   # x[:5], x[N-3:]: no segment
+    od = torch.from_numpy(off).cuda()
+    incl = torch.tensor(np.cumsum(PATTERN.astype(np.float64)), dtype=torch.float32, device=xd.device)
+
+    def before(start):                                       # sum of x[0 .. start)
+        return torch.where(start % 7 == 0, torch.zeros((), device=xd.device), incl[(start - 1) % 7])
+
+    out = torch.full((N,), -5.0, dtype=torch.float32, device="cuda")
+    tcr.irregular_scan(xd, od, out=out)
+    assert torch.all(out[:5] == -5.0) and torch.all(out[N - 3:] == -5.0)
+    for lo in range(0, N, CHUNK):
+        hi = min(lo + CHUNK, N)
+        k = torch.arange(max(lo, 5), min(hi, N - 3), dtype=torch.int64, device=xd.device)
+        start = od[torch.searchsorted(od, k, right=True) - 1]
+        want = incl[k % 7] - before(start)
+        got = out[max(lo, 5):min(hi, N - 3)]
+        if not torch.equal(got, want):
+            bad = int(torch.nonzero(got != want)[0])
+            raise AssertionError(f"first mismatch at {int(k[bad])}: got {float(got[bad])} want {float(want[bad])}")
+    del out
+    red = tcr.irregular_reduce(xd, od)
+    want = torch.where(od[1:] > od[:-1], before(od[1:]) - before(od[:-1]), torch.zeros((), device=xd.device))
+    if not torch.equal(red, want):
+        bad = int(torch.nonzero(red != want)[0])
+        raise AssertionError(f"segment {bad} [{off[bad]}, {off[bad + 1]}): got {float(red[bad])} want {float(want[bad])}")
+    # sampled segments against the oracle: the short ones around 2^31 and a few of the long ones
+    around = int(np.searchsorted(off, 1 << 31))
+    for s in list(range(around - 3, around + 3)) + [0, 1000, off.size - 2]:
+        piece = x[off[s]:off[s + 1]]
+        assert float(red[s].cpu()) == oracle.reduce(piece) if piece.size else float(red[s].cpu()) == 0.0
+    tcr.check_device_flags()

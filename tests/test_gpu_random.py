@@ -81,3 +81,46 @@ def test_random_dispatch(tcr, oracle, block):
         assert np.max(np.abs(ref)) < 2 ** 24 or flags & 2
         assert np.array_equal(got, ref), what
     tcr.check_device_flags()
+
+
+def _draw_offsets(rng, n):
+    """Random cover of part of [0, n): pieces drawn from several length scales, with empty segments and cuts placed
+    on and around multiples of the 16384- and 32768-element tiles."""
+    lo = int(rng.integers(0, max(1, min(n, 40000)))) if rng.integers(0, 3) == 0 else 0
+    hi = n - int(rng.integers(0, max(1, min(n - lo, 40000)))) if rng.integers(0, 3) == 0 else n
+    cuts = [np.array([lo, hi], dtype=np.int64)]
+    for _ in range(int(rng.integers(0, 4))):
+        scale = int((1, 8, 100, 5000, 200000)[int(rng.integers(0, 5))])
+        start = int(rng.integers(lo, hi + 1))
+        lens = rng.integers(0, 2 * scale + 1, int(rng.integers(1, 3000)))
+        cuts.append(start + np.cumsum(lens))
+    if rng.integers(0, 2):
+        tiles = 16384 * rng.integers(0, n // 16384 + 1, int(rng.integers(1, 30)))
+        cuts.append(tiles + rng.integers(-2, 3, tiles.size))
+    if rng.integers(0, 2):
+        cuts.append(np.full(int(rng.integers(1, 600)), int(rng.integers(lo, hi + 1))))      # a run of empty segments
+    c = np.concatenate(cuts)
+    return np.sort(c[(c >= lo) & (c <= hi)]).astype(np.int64)
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_irregular_segments(tcr, oracle, block):
+    rng = np.random.default_rng(5000 + block)
+    for case in range(20):
+        n = int(rng.integers(1, MAX_N)) if rng.integers(0, 4) else int(rng.integers(1, 70000))
+        off = _draw_offsets(rng, n)
+        x = workloads.make_input(n, "int4", int(rng.integers(0, 1 << 30)))
+        what = f"block {block} case {case}: n={n} nseg={off.size - 1} cover=[{off[0]}, {off[-1]})"
+        print("  " + what, flush=True)
+        xd, od = torch.from_numpy(x).cuda(), torch.from_numpy(off).cuda()
+        out = torch.full((n,), -7.0, dtype=torch.float32, device="cuda")
+        tcr.irregular_scan(xd, od, out=out)
+        red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
+        scan = out.cpu().numpy().astype(np.float64)
+        ref = oracle.irregular_scan(x, off)
+        assert np.max(np.abs(ref)) < 2 ** 24
+        lo, hi = int(off[0]), int(off[-1])
+        assert np.array_equal(scan[lo:hi], ref[lo:hi]), what + " (scan)"
+        assert np.all(scan[:lo] == -7.0) and np.all(scan[hi:] == -7.0), what + " (outside)"
+        assert np.array_equal(red, oracle.irregular_reduce(x, off)), what + " (reduce)"
+    tcr.check_device_flags()
