@@ -28,8 +28,7 @@
  *   call that would have to allocate, grow or initialise workspace while its stream is capturing returns
  *   TCR_ERR_UNSUPPORTED and records nothing (run the same call once outside the capture, or supply a workspace
  *   and run one chained scan on it first).  Calls that use no workspace (scans with seg_len <= 4096, reduces
- *   with seg_len <= 262144 -- powers of two; other segment lengths below 65536; default variant and tuning)
- *   never do.
+ *   with seg_len <= 262144 -- powers of two from 16 on; default variant and tuning) never do.
  *   From the first recorded chained scan on, the workspace keeps its launch counters on the device and every
  *   chained scan on it, recorded or not, is preceded by one small bookkeeping kernel.  The "fused"
  *   reduce_finish variant cannot be recorded.
@@ -57,9 +56,12 @@ typedef enum {
  *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
- * seg_len == n; other lengths run one wavefront per segment (from 256 elements on over zero-masked tiles of
- * the array, the paper's padding of such segments, Section 4, applied in registers), long ones (from 65536
- * elements for scans with seg_len % 8 == 0, from 131072 for reductions) the device-level algorithms.
+ * seg_len == n.  Other lengths: reductions of 8 to 999 elements and all scans run on fixed tiles of the array
+ * with the segment starts marked (the kernels of the irregular calls below; they use the workspace), except
+ * scans of a multiple of 8 elements above 512, which have one workgroup per segment or, from 65536 elements,
+ * the chained scan; longer reductions run one wavefront per segment (per 65536-element piece of one, from
+ * 131072 elements) over zero-masked tiles of the array, the paper's padding of such segments (Section 4)
+ * applied in registers.
  */
 tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 

@@ -56,7 +56,7 @@ extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offse
         fill_zero_kernel<<<dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, s>>>(out, nseg);
         return check_launch("fill_zero_kernel");
     }
-    if (aligned(in, 16)) return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, out, n, nseg, s);
+    if (aligned(in, 16)) return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, out, n, nseg, 0, s);
     irregular_wave_kernel<false><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
         static_cast<const _Float16*>(in), offsets, out, nseg);
     return check_launch("irregular_wave_kernel");
@@ -68,7 +68,7 @@ extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets
     const tcr_status st = validate_irregular(in, offsets, out, n, nseg);
     if (st != TCR_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (aligned(in, 16) && aligned(out, 16)) return launch_irregular_scan(static_cast<const _Float16*>(in), offsets, out, n, nseg, s);
+    if (aligned(in, 16) && aligned(out, 16)) return launch_irregular_scan<0>(static_cast<const _Float16*>(in), offsets, out, n, nseg, 0, s);
     irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
         static_cast<const _Float16*>(in), offsets, out, nseg);
     return check_launch("irregular_wave_kernel");
@@ -237,11 +237,14 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     const bool whole = seg_len == n;
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
         if (op != 0 && op != 1) return "";
-        if (seg_len <= kGenericThreadMax) return "generic_thread_kernel";
-        if (seg_len < kMaskedMin) return "generic_wave_kernel";
-        if (op == 0) return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";
+        if (op == 0) {
+            if (seg_len < kTiledReduceMin) return "generic_thread_kernel";
+            if (seg_len < kTiledReduceMax) return "irregular_reduce_kernel<regular>+irregular_groups_kernel+irregular_carry_kernel";
+            return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";
+        }
+        if (seg_len < kTiledScanMin) return "generic_thread_kernel";
         if (chain_takes_any_length(seg_len)) return "scan_chain_kernel<mfma>";
-        return segment_kernel_takes(seg_len) ? "scan_segment_kernel" : "masked_wave_scan_kernel";
+        return segment_kernel_takes(seg_len) ? "scan_segment_kernel" : "irregular_scan_kernel<regular>";
     }
     if (op == 0 || op == 2) {
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";

@@ -416,54 +416,153 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
     return check_launch("scan_block_kernel");
 }
 
-// Any other seg_len >= 1: the untuned kernels.
-constexpr uint64_t kGenericThreadMax = 96;           // up to here one thread walks a segment, beyond a wavefront does
-constexpr uint64_t kMaskedMin = 256;                 // from here on the wavefront walks masked 512-element tiles of the array
+// Irregular segments over 16-byte aligned arrays: fixed tiles of the flat array, whatever the segments.
+constexpr int kIrregularScanU = 4, kIrregularScanW = 16;        // 32768-element tiles, chained
+constexpr int kIrregularReduceU = 4, kIrregularReduceW = 8;     // 16384-element tiles, independent
+inline uint64_t irregular_tiles(bool scan, uint64_t n) {
+    return ceil_div(n, (uint64_t)kTile * (scan ? kIrregularScanU * kIrregularScanW : kIrregularReduceU * kIrregularReduceW));
+}
+// 8-byte words of the partials area: the look-up table(s) of the tile boundaries, and for the reduction one
+// carried-segment index and one pair per tile and one pair per group of 64 tiles.
+inline uint64_t irregular_words(bool scan, uint64_t n) {
+    const uint64_t tiles = irregular_tiles(scan, n);
+    return scan ? tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
+}
+
+// offsets == nullptr: regular segments of seg_len elements (no look-up table; MODE as for the other scans).
+template <int MODE>
+inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
+                                        uint64_t seg_len, hipStream_t s) {
+    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularScanU * kIrregularScanW;
+    const uint64_t tiles = irregular_tiles(true, n);
+    const bool regular = offsets == nullptr;
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    if (!regular) {
+        st = ensure_partials(ws, s, 2 * irregular_words(true, n), capturing);
+        if (st != TCR_OK) return st;
+    }
+    ScanWorkspace dev = {};
+    st = begin_lookback(ws, s, tiles, &dev, capturing);
+    if (st != TCR_OK) return st;
+    uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
+    const dim3 grid((unsigned)tiles), block(kIrregularScanW * kWave);
+    if (regular) {
+        irregular_scan_kernel<kIrregularScanU, kIrregularScanW, true, MODE><<<grid, block, 0, s>>>(in, nullptr, out, n, nseg, nullptr,
+                                                                                                 seg_len, dev);
+    } else {
+        irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+            offsets, nseg + 1, kElems, tiles + 1, starts, nullptr);
+        st = check_launch("irregular_bounds_kernel");
+        if (st != TCR_OK) return st;
+        irregular_scan_kernel<kIrregularScanU, kIrregularScanW, false, MODE><<<grid, block, 0, s>>>(in, offsets, out, n, nseg, starts,
+                                                                                                  0, dev);
+    }
+    st = check_launch("irregular_scan_kernel");
+    if (st != TCR_OK) {
+        ws->dirty = true;
+        return st;
+    }
+    ws->tickets_issued += (uint32_t)tiles;
+    return TCR_OK;
+}
+
+// offsets == nullptr: regular segments of seg_len elements (no look-up tables).
+inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
+                                          uint64_t seg_len, hipStream_t s) {
+    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
+    const uint64_t tiles = irregular_tiles(false, n);
+    const uint64_t groups = ceil_div(tiles, kWave);
+    const bool regular = offsets == nullptr;
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    st = ensure_partials(ws, s, 2 * irregular_words(false, n), capturing);
+    if (st != TCR_OK) return st;
+    uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
+    uint64_t* ends = starts + (tiles + 1);
+    uint64_t* carried = ends + (tiles + 1);
+    TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);
+    TilePair* group_pairs = pairs + tiles;
+    const dim3 grid((unsigned)tiles), block(kIrregularReduceW * kWave);
+    if (regular) {
+        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr, nullptr,
+                                                                                                 seg_len, nseg, pairs, carried);
+    } else {
+        irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+            offsets, nseg + 1, kElems, tiles + 1, starts, ends);
+        st = check_launch("irregular_bounds_kernel");
+        if (st != TCR_OK) return st;
+        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(in, offsets, out, n, starts, ends, 0,
+                                                                                                  nseg, pairs, carried);
+    }
+    st = check_launch("irregular_reduce_kernel");
+    if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it
+    irregular_groups_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, tiles, group_pairs);
+    st = check_launch("irregular_groups_kernel");
+    if (st != TCR_OK) return st;
+    irregular_carry_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, group_pairs, carried,
+                                                                                                            tiles, out);
+    return check_launch("irregular_carry_kernel");
+}
+
+// Any other seg_len >= 1 (no power of two, or below 16): no kernel is tuned for it.
+// Scans from 2 elements on and reductions of 8 to 999 elements run on the fixed tiles of the irregular
+// kernels with the multiples of seg_len as segment starts.  Measured at n = 2^28: scans 300-325 us
+// whatever the length (one thread or one wavefront per segment took 440-5600 us below 256 elements,
+// 350-400 us above, and 13 ms for 15 segments of 2^24 + 1 elements); reductions 146-231 us (against
+// 230-1060 us).  Longer reductions keep one wavefront per segment over zero-masked tiles (116 us at
+// 1000 elements, 85 us at 3001), the shortest segments one thread each.
+constexpr uint64_t kGenericThreadMax = 96;           // moments: up to here one thread walks a segment
+constexpr uint64_t kTiledScanMin = 2;
+constexpr uint64_t kTiledReduceMin = 8, kTiledReduceMax = 1000;
+constexpr uint64_t kMaskedMin = 256;                 // moments: from here on a wavefront walks masked 512-element tiles
 
 template <bool SCAN>
 inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
     const uint64_t nseg = n / seg_len;
     const bool excl = (flags & TCR_SCAN_EXCLUSIVE) != 0, f16 = (flags & TCR_OUT_F16) != 0;
-    if (seg_len <= kGenericThreadMax) {
+    if constexpr (SCAN) {
+        if (seg_len >= kTiledScanMin) {
+            switch (flags & 3u) {
+                case 0: return launch_irregular_scan<0>(in, nullptr, out, n, nseg, seg_len, s);
+                case 1: return launch_irregular_scan<1>(in, nullptr, out, n, nseg, seg_len, s);
+                case 2: return launch_irregular_scan<2>(in, nullptr, out, n, nseg, seg_len, s);
+                default: return launch_irregular_scan<3>(in, nullptr, out, n, nseg, seg_len, s);
+            }
+        }
+    } else {
+        if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax)
+            return launch_irregular_reduce(in, nullptr, static_cast<float*>(out), n, nseg, seg_len, s);
+    }
+    if (SCAN || seg_len < kTiledReduceMin) {
         generic_thread_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
             in, out, nseg, seg_len, excl, f16);
         return check_launch("generic_thread_kernel");
     }
-    if (seg_len < kMaskedMin) {
-        generic_wave_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
-            in, out, nseg, seg_len, excl, f16);
-        return check_launch("generic_wave_kernel");
-    }
-    // masked 512-element tiles of the array, one wavefront per segment
+    // reductions from 1000 elements on: masked 512-element tiles of the array, one wavefront per segment
     const dim3 grid((unsigned)ceil_div(nseg, kMaskedWaves)), block(kMaskedWaves * kWave);
-    if constexpr (SCAN) {
-        switch (flags & 3u) {
-            case 0: masked_wave_scan_kernel<0><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
-            case 1: masked_wave_scan_kernel<1><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
-            case 2: masked_wave_scan_kernel<2><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
-            default: masked_wave_scan_kernel<3><<<grid, block, 0, s>>>(in, out, nseg, seg_len); break;
-        }
-        return check_launch("masked_wave_scan_kernel");
-    } else {
-        if (seg_len <= 2 * kWaveSpanMax) {
-            masked_wave_reduce_kernel<<<grid, block, 0, s>>>(in, static_cast<float*>(out), nseg, seg_len);
-            return check_launch("masked_wave_reduce_kernel");
-        }
-        // long segments: pieces of 65536 elements per wavefront, then the paper's second kernel over the pieces
-        const uint64_t per = ceil_div(seg_len, kWaveSpanMax);
-        Workspace* ws = nullptr;
-        bool capturing = false;
-        tcr_status st = get_workspace(s, &ws, &capturing);
-        if (st != TCR_OK) return st;
-        st = ensure_partials(ws, s, nseg * per, capturing);
-        if (st != TCR_OK) return st;
-        masked_span_reduce_kernel<<<dim3((unsigned)ceil_div(nseg * per, kMaskedWaves)), block, 0, s>>>(
-            in, ws->partials, nseg, seg_len, kWaveSpanMax, per);
-        st = check_launch("masked_span_reduce_kernel");
-        if (st != TCR_OK) return st;
-        reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kFinalThreads), 0, s>>>(ws->partials, static_cast<float*>(out), per);
-        return check_launch("reduce_final_kernel");
+    if (seg_len <= 2 * kWaveSpanMax) {
+        masked_wave_reduce_kernel<<<grid, block, 0, s>>>(in, static_cast<float*>(out), nseg, seg_len);
+        return check_launch("masked_wave_reduce_kernel");
     }
+    // long segments: pieces of 65536 elements per wavefront, then the paper's second kernel over the pieces
+    const uint64_t per = ceil_div(seg_len, kWaveSpanMax);
+    Workspace* ws = nullptr;
+    bool capturing = false;
+    tcr_status st = get_workspace(s, &ws, &capturing);
+    if (st != TCR_OK) return st;
+    st = ensure_partials(ws, s, nseg * per, capturing);
+    if (st != TCR_OK) return st;
+    masked_span_reduce_kernel<<<dim3((unsigned)ceil_div(nseg * per, kMaskedWaves)), block, 0, s>>>(
+        in, ws->partials, nseg, seg_len, kWaveSpanMax, per);
+    st = check_launch("masked_span_reduce_kernel");
+    if (st != TCR_OK) return st;
+    reduce_final_kernel<<<dim3((unsigned)nseg), dim3(kFinalThreads), 0, s>>>(ws->partials, static_cast<float*>(out), per);
+    return check_launch("reduce_final_kernel");
 }
 
 // The tuned scan paths for one (formulation, mode) pair.
@@ -577,80 +676,6 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
         case 2: return scan_tuned<kMfma, 2>(x, out, n, seg_len, s);
         default: return scan_tuned<kMfma, 3>(x, out, n, seg_len, s);
     }
-}
-
-// Irregular segments over 16-byte aligned arrays: fixed tiles of the flat array, whatever the segments.
-constexpr int kIrregularScanU = 4, kIrregularScanW = 16;        // 32768-element tiles, chained
-constexpr int kIrregularReduceU = 4, kIrregularReduceW = 8;     // 16384-element tiles, independent
-inline uint64_t irregular_tiles(bool scan, uint64_t n) {
-    return ceil_div(n, (uint64_t)kTile * (scan ? kIrregularScanU * kIrregularScanW : kIrregularReduceU * kIrregularReduceW));
-}
-// 8-byte words of the partials area: the look-up table(s) of the tile boundaries, and for the reduction one
-// carried-segment index and one pair per tile and one pair per group of 64 tiles.
-inline uint64_t irregular_words(bool scan, uint64_t n) {
-    const uint64_t tiles = irregular_tiles(scan, n);
-    return scan ? tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
-}
-
-inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
-                                        hipStream_t s) {
-    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularScanU * kIrregularScanW;
-    const uint64_t tiles = irregular_tiles(true, n);
-    Workspace* ws = nullptr;
-    bool capturing = false;
-    tcr_status st = get_workspace(s, &ws, &capturing);
-    if (st != TCR_OK) return st;
-    st = ensure_partials(ws, s, 2 * irregular_words(true, n), capturing);
-    if (st != TCR_OK) return st;
-    ScanWorkspace dev = {};
-    st = begin_lookback(ws, s, tiles, &dev, capturing);
-    if (st != TCR_OK) return st;
-    uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
-    irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-        offsets, nseg + 1, kElems, tiles + 1, starts, nullptr);
-    st = check_launch("irregular_bounds_kernel");
-    if (st != TCR_OK) return st;
-    irregular_scan_kernel<kIrregularScanU, kIrregularScanW><<<dim3((unsigned)tiles), dim3(kIrregularScanW * kWave), 0, s>>>(
-        in, offsets, out, n, nseg, starts, dev);
-    st = check_launch("irregular_scan_kernel");
-    if (st != TCR_OK) {
-        ws->dirty = true;
-        return st;
-    }
-    ws->tickets_issued += (uint32_t)tiles;
-    return TCR_OK;
-}
-
-inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
-                                          hipStream_t s) {
-    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
-    const uint64_t tiles = irregular_tiles(false, n);
-    const uint64_t groups = ceil_div(tiles, kWave);
-    Workspace* ws = nullptr;
-    bool capturing = false;
-    tcr_status st = get_workspace(s, &ws, &capturing);
-    if (st != TCR_OK) return st;
-    st = ensure_partials(ws, s, 2 * irregular_words(false, n), capturing);
-    if (st != TCR_OK) return st;
-    uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
-    uint64_t* ends = starts + (tiles + 1);
-    uint64_t* carried = ends + (tiles + 1);
-    TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);
-    TilePair* group_pairs = pairs + tiles;
-    irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-        offsets, nseg + 1, kElems, tiles + 1, starts, ends);
-    st = check_launch("irregular_bounds_kernel");
-    if (st != TCR_OK) return st;
-    irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW><<<dim3((unsigned)tiles), dim3(kIrregularReduceW * kWave), 0, s>>>(
-        in, offsets, out, n, starts, ends, pairs, carried);
-    st = check_launch("irregular_reduce_kernel");
-    if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it
-    irregular_groups_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, tiles, group_pairs);
-    st = check_launch("irregular_groups_kernel");
-    if (st != TCR_OK) return st;
-    irregular_carry_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, group_pairs, carried,
-                                                                                                            tiles, out);
-    return check_launch("irregular_carry_kernel");
 }
 
 inline tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {

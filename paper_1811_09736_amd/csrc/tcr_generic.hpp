@@ -1,15 +1,16 @@
-// Kernels for segment lengths without a tuned path (not a power of two, or shorter than 16) and for
-// irregular segments.  The paper handles such sizes by zero padding or by masking (Section 4, "Support
-// for arbitrary segment sizes ...").  Padding in place is not possible behind this interface, so:
-//   masked_wave_*   segments of 256 elements and more: one wavefront per segment walks the 512-element
+// Kernels for what the tiled kernels do not take: reductions of regular segments whose length is no power
+// of two (long ones; short ones run on the fixed tiles of tcr_irregular.hpp), the shortest segments, the
+// moments, and irregular segments behind unaligned pointers.  The paper handles such sizes by zero padding
+// or by masking (Section 4, "Support for arbitrary segment sizes ...").  Padding in place is not possible
+// behind this interface, so:
+//   masked_*        one wavefront per segment (or per 65536-element piece of one) walks the 512-element
 //                   tiles of the ARRAY (aligned to the array, not to the segment) that the segment
 //                   touches; elements of a tile outside the segment are read as zero -- the paper's
 //                   zero padding, applied to the operand registers -- and the matrix-core products,
-//                   the running carry through the accumulator and the 128-bit loads and stores of the
-//                   tuned kernels apply unchanged; only the 8-element groups cut by a segment end
-//                   are read and written element by element.
-//   generic_*       shorter segments (and irregular segments behind unaligned pointers): 16-bit
-//                   loads, binary32 adds, the wavefront scan primitive.
+//                   the running sums through the accumulator and the 128-bit loads of the tuned
+//                   kernels apply unchanged; only the 8-element groups cut by a segment end are read
+//                   element by element.
+//   generic_*       one thread per segment: 16-bit loads, binary32 adds.
 // They are correct for every seg_len >= 1; none of them is tuned.
 #pragma once
 #include "tcr_device.hpp"
@@ -42,46 +43,6 @@ __global__ __launch_bounds__(kGenericThreads) void generic_thread_kernel(const _
     if (!SCAN) put(out, s, acc, f16);
 }
 
-// One wavefront per segment: 64 elements per step, four steps in flight.
-template <bool SCAN>
-__global__ __launch_bounds__(kGenericThreads) void generic_wave_kernel(const _Float16* __restrict__ in,
-                                                                       void* __restrict__ out, uint64_t nseg,
-                                                                       uint64_t seg_len, bool exclusive, bool f16) {
-    constexpr int kSteps = 4;
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t s = (uint64_t)blockIdx.x * (kGenericThreads / kWave) +
-                       (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (s >= nseg) return;
-    const _Float16* p = in + s * seg_len;
-    const uint64_t q = s * seg_len;
-    float carry = 0.0f;      // SCAN: total of the steps already done (uniform)
-    float acc = 0.0f;        // REDUCE: this lane's running sum
-    for (uint64_t k0 = 0; k0 < seg_len; k0 += (uint64_t)(kWave * kSteps)) {
-        float v[kSteps];
-#pragma unroll
-        for (int i = 0; i < kSteps; ++i) {
-            const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
-            v[i] = (k < seg_len) ? (float)p[k] : 0.0f;
-        }
-#pragma unroll
-        for (int i = 0; i < kSteps; ++i) {
-            if (SCAN) {
-                const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
-                const float incl = wave_scan_inclusive(v[i]);
-                const float excl = wave_shr1(incl);          // sum of the lower lanes only (no subtraction)
-                if (k < seg_len) put(out, q + k, (exclusive ? excl : incl) + carry, f16);
-                carry += read_lane(incl, 63);
-            } else {
-                acc += v[i];
-            }
-        }
-    }
-    if (!SCAN) {
-        const float total = wave_sum(acc);
-        if (lane == 0) put(out, s, total, f16);
-    }
-}
-
 // ---------------------------------------------------------------------------------------- masked tiles
 // 8 inputs at element g (a multiple of 8), those outside [begin, end) read as zero.
 template <bool STREAM = false>
@@ -91,54 +52,6 @@ __device__ __forceinline__ half8 load8_masked(const _Float16* __restrict__ in, u
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (g + e >= begin && g + e < end) ? in[g + e] : (_Float16)0.0f;
     return v;
-}
-
-// 4 results at element g (a multiple of 4), those outside [begin, end) are not written.
-template <int F16>
-__device__ __forceinline__ void store4_masked(void* __restrict__ out, uint64_t g, uint64_t begin, uint64_t end, float4v v) {
-    if (g >= begin && g + 4 <= end) {
-        store4_t<F16>(out, g, v);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (g + e >= begin && g + e < end) {
-                if constexpr (F16) static_cast<_Float16*>(out)[g + e] = (_Float16)v[e];
-                else static_cast<float*>(out)[g + e] = v[e];
-            }
-        }
-    }
-}
-
-// One wavefront scans the segment [begin, end) of the array (outputs indexed like inputs).
-// `in` and `out` are 16-byte aligned.  MODE bit 0: exclusive, bit 1: binary16 output.
-template <int MODE>
-__device__ __forceinline__ void masked_wave_scan(const _Float16* __restrict__ in, void* __restrict__ out,
-                                                 uint64_t begin, uint64_t end, const LaneId& id) {
-    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
-    constexpr int kSteps = 4;                            // tiles in flight
-    float carry = 0.0f;                                  // total of the tiles already done (the S matrix of Scan_256N)
-    for (uint64_t t0 = begin & ~(uint64_t)(kTile - 1); t0 < end; t0 += (uint64_t)(kTile * kSteps)) {
-        half8 x[kSteps];
-#pragma unroll
-        for (int i = 0; i < kSteps; ++i) {
-            const uint64_t tile = t0 + (uint64_t)(kTile * i);
-            if (tile < end) x[i] = load8_masked(in, tile + (uint64_t)(kRow * id.j + 8 * id.g), begin, end);
-        }
-#pragma unroll
-        for (int i = 0; i < kSteps; ++i) {
-            const uint64_t tile = t0 + (uint64_t)(kTile * i);
-            if (tile >= end) break;                      // uniform over the wavefront
-            const float4v tot = mfma(const_ones(), x[i], splat(0.0f));
-            const float incl = row_scan_inclusive<16>(tot[0], id.j);
-            const float before = row_shr<1>(incl) + carry;
-            const float4v lo = mfma(const_tri_lo<EXCL>(id), x[i], splat(before));
-            const float4v hi = mfma(const_tri_hi<EXCL>(id), x[i], splat(before));
-            const uint64_t g = tile + (uint64_t)(kRow * id.j + 4 * id.g);
-            store4_masked<F16>(out, g, begin, end, lo);
-            store4_masked<F16>(out, g + 16, begin, end, hi);
-            carry += read_lane(incl, 15);
-        }
-    }
 }
 
 // One wavefront adds up the segment [begin, end); the result is uniform.  `in` is 16-byte aligned.
@@ -161,16 +74,6 @@ __device__ __forceinline__ float masked_wave_reduce(const _Float16* __restrict__
 }
 
 constexpr int kMaskedWaves = 4;                          // wavefronts (segments) per workgroup
-
-template <int MODE>
-__global__ __launch_bounds__(kMaskedWaves * kWave) void masked_wave_scan_kernel(const _Float16* __restrict__ in,
-                                                                                void* __restrict__ out, uint64_t nseg,
-                                                                                uint64_t seg_len) {
-    const LaneId id;
-    const uint64_t s = (uint64_t)blockIdx.x * kMaskedWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (s >= nseg) return;
-    masked_wave_scan<MODE>(in, out, s * seg_len, (s + 1) * seg_len, id);
-}
 
 __global__ __launch_bounds__(kMaskedWaves * kWave) void masked_wave_reduce_kernel(const _Float16* __restrict__ in,
                                                                                   float* __restrict__ out, uint64_t nseg,
@@ -270,8 +173,8 @@ __global__ __launch_bounds__(kGenericThreads) void generic_moments_kernel(const 
     sumsq[s] = q;
 }
 
-// Irregular segments: segment s is [offsets[s], offsets[s+1]).  One wavefront per segment, same
-// arithmetic as generic_wave_kernel.  (The paper reduces the irregular case to the regular one by
+// Irregular segments behind unaligned pointers: segment s is [offsets[s], offsets[s+1]).  One wavefront per
+// segment, 64 elements per step, the wavefront scan primitive.  (The paper reduces the irregular case to the regular one by
 // padding the input, Section 3 footnote; reading the offsets directly needs no padded copy.)
 template <bool SCAN>
 __global__ __launch_bounds__(kGenericThreads) void irregular_wave_kernel(const _Float16* __restrict__ in,

@@ -134,14 +134,16 @@ __device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x
 
 // Running sums of a lane's 8 elements of sub-tile u, given the sum `ext` that reaches the wavefront's share
 // from in front of it.
-template <int U>
+template <int U, int EXCL = 0>
 __device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const half8 (&x)[U], int u, float ext, float (&p)[8]) {
     const float into_sub = w.seen_before[u] ? w.before[u] : w.before[u] + ext;
     float q = (w.heads[u] >> 8) ? w.lane_value[u] : w.lane_value[u] + into_sub;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        q = ((w.heads[u] >> e) & 1u ? 0.0f : q) + (float)x[u][e];
-        p[e] = q;
+        q = (w.heads[u] >> e) & 1u ? 0.0f : q;
+        if constexpr (EXCL) p[e] = q;
+        q += (float)x[u][e];
+        if constexpr (!EXCL) p[e] = q;
     }
 }
 
@@ -150,11 +152,16 @@ __device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const h
 // an LDS bitmap tells every lane where its running sums restart.  offsets must be non-decreasing and at
 // most n.
 //
-// Scan: out[k] = inclusive running sum of the segment that contains k, offsets[0] <= k < offsets[nseg].
-template <int U, int WAVES>
+// Scan: out[k] = running sum of the segment that contains k, offsets[0] <= k < offsets[nseg].
+// REGULAR: the heads are the multiples of seg_len instead (offsets and starts_below are not read): regular
+// segments of a length no other kernel is tuned for -- odd lengths above all, which leave no 8-element group
+// aligned with the segments.  MODE bit 0: exclusive scan; bit 1: binary16 output.
+template <int U, int WAVES, bool REGULAR, int MODE>
 __global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, float* __restrict__ out,
-                           uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, ScanWorkspace ws_arg) {
+void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, void* __restrict__ out,
+                           uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, uint64_t seg_len,
+                           ScanWorkspace ws_arg) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
     constexpr uint32_t kChunk = (uint32_t)kTile * U;          // one wavefront's share
     constexpr uint32_t kBlockTile = kChunk * WAVES;           // one workgroup's share
     __shared__ uint32_t s_heads[kBlockTile / 32];
@@ -186,11 +193,13 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + 8 * lane), n);
     }
 
-    const uint64_t head_lo = starts_below[tile], head_hi = starts_below[tile + 1];     // heads in [tb, tb + tile)
+    // heads in [tb, tb + tile): entries head_lo .. head_hi - 1
+    const uint64_t head_lo = REGULAR ? (tb + seg_len - 1) / seg_len : starts_below[tile];
+    const uint64_t head_hi = REGULAR ? (tb + kBlockTile + seg_len - 1) / seg_len : starts_below[tile + 1];
     const bool has_heads = head_lo < head_hi;
     if (has_heads) {
         for (uint64_t s = head_lo + threadIdx.x; s < head_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = offsets[s] - tb;
+            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) - tb;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
         }
         __syncthreads();
@@ -215,7 +224,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         }
     }
     // the part [valid_lo, valid_hi) of this wavefront's share lies in a segment (all of it, nearly always)
-    const uint64_t first = offsets[0], last = offsets[nseg];
+    const uint64_t first = REGULAR ? 0 : offsets[0], last = REGULAR ? n : offsets[nseg];
     const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
     const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
     const bool inside = valid_lo == 0u && valid_hi == kChunk;
@@ -241,19 +250,23 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         __syncthreads();
         ext += s_prefix;
     }
-    float* const dst = out + base;
+    void* const dst = F16 ? static_cast<void*>(static_cast<_Float16*>(out) + base) : static_cast<void*>(static_cast<float*>(out) + base);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         float p[8];
-        wave_share_finish<U>(w, x, u, ext, p);
+        wave_share_finish<U, EXCL>(w, x, u, ext, p);
         const uint32_t k = (uint32_t)(kTile * u + 8 * lane);
         if (inside) {
-            store4(dst, k, (float4v){p[0], p[1], p[2], p[3]});
-            store4(dst, k + 4, (float4v){p[4], p[5], p[6], p[7]});
+            store4_t<F16>(dst, k, (float4v){p[0], p[1], p[2], p[3]});
+            store4_t<F16>(dst, k + 4, (float4v){p[4], p[5], p[6], p[7]});
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (k + e >= valid_lo && k + e < valid_hi) dst[k + e] = p[e];
+            for (int e = 0; e < 8; ++e) {
+                if (k + e >= valid_lo && k + e < valid_hi) {
+                    if constexpr (F16) static_cast<_Float16*>(dst)[k + e] = (_Float16)p[e];
+                    else static_cast<float*>(dst)[k + e] = p[e];
+                }
+            }
         }
     }
 }
@@ -284,12 +297,14 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
 // belongs to a segment begun in an earlier tile is written without that earlier part; the tile records
 // which segment it is (carried[tile], or none) and its own pair (pairs[tile]) for the carry kernels.
 constexpr uint32_t kPositions = 4096;
-template <int U, int WAVES>
+// REGULAR: entry s is s * seg_len, s = 0 .. nseg, instead of offsets[s] (offsets and the tables are not read).
+template <int U, int WAVES, bool REGULAR>
 __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _Float16* __restrict__ in,
                                                                          const uint64_t* __restrict__ offsets,
                                                                          float* __restrict__ out, uint64_t n,
                                                                          const uint64_t* __restrict__ starts_below,
                                                                          const uint64_t* __restrict__ ends_below,
+                                                                         uint64_t seg_len, uint64_t nseg,
                                                                          TilePair* __restrict__ pairs,
                                                                          uint64_t* __restrict__ carried) {
     constexpr uint32_t kChunk = (uint32_t)kTile * U;
@@ -323,14 +338,26 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
 
     // entries [head_lo, head_hi) lie in [tb, tb + tile): heads; entries [end_lo, end_hi) lie in
     // (tb, tb + tile]: each closes the segment in front of it.  head_lo <= end_lo, head_hi <= end_hi.
-    const uint64_t head_lo = starts_below[tile], head_hi = starts_below[tile + 1];
+    uint64_t head_lo, head_hi, end_lo, end_hi;
+    if constexpr (REGULAR) {
+        const uint64_t te = tb + kBlockTile, entries = nseg + 1;
+        head_lo = (tb + seg_len - 1) / seg_len;
+        head_hi = (te + seg_len - 1) / seg_len < entries ? (te + seg_len - 1) / seg_len : entries;
+        end_lo = tb / seg_len + 1;
+        end_hi = te / seg_len + 1 < entries ? te / seg_len + 1 : entries;
+    } else {
+        head_lo = starts_below[tile];
+        head_hi = starts_below[tile + 1];
+        end_lo = ends_below[tile];
+        end_hi = ends_below[tile + 1];
+    }
     // (the first tile also takes the entries on position 0, which close empty segments in front of everything)
-    const uint64_t end_lo = tile == 0 ? 0 : ends_below[tile], end_hi = ends_below[tile + 1];
+    if (tile == 0) end_lo = 0;
     const bool has_entries = head_lo < end_hi;
     __syncthreads();
     if (has_entries) {
         for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = offsets[s] - tb;
+            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) - tb;
             if (s - head_lo < (uint64_t)kPositions) s_position[s - head_lo] = (uint16_t)pos;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
             if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
@@ -396,8 +423,8 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
                 end = s_position[i];
                 begin = i > 0 ? (uint32_t)s_position[i - 1] : 0u;
             } else {
-                end = (uint32_t)(offsets[s] - tb);
-                begin = (uint32_t)(offsets[s - 1] - tb);
+                end = (uint32_t)((REGULAR ? s * seg_len : offsets[s]) - tb);
+                begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1]) - tb);
             }
             const uint32_t at = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
             const bool empty = i > 0 && end == begin;

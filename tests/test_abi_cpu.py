@@ -121,20 +121,27 @@ def test_dispatch_by_segment_length(lib):
         assert k(lib.OP_SCAN, n, n) == "scan_chain_kernel<dpp>"
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 16) == "scan_chain_kernel<dpp>"
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << 14) == "scan_block_kernel<dpp,ticket>"
-        assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "masked_wave_scan_kernel"   # other lengths: matrix cores only
+        assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "irregular_scan_kernel<regular>"   # other lengths: fixed tiles
     finally:
         lib.set_variant("reset")
     assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SCAN, 8192, 8192) == "scan_block_kernel<mfma,nocarry>"
-    assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "generic_thread_kernel"     # untuned lengths
+    assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "irregular_scan_kernel<regular>"     # untuned lengths: fixed tiles
+    assert k(lib.OP_SEGMENTED_SCAN, 48000, 1) == "generic_thread_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6) == "generic_thread_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 48).startswith("irregular_reduce_kernel<regular>+")
+    assert k(lib.OP_SEGMENTED_REDUCE, 999 * 5, 999).startswith("irregular_reduce_kernel<regular>+")
+    assert k(lib.OP_SEGMENTED_REDUCE, 1001 * 5, 1001) == "masked_wave_reduce_kernel"
+    assert k(lib.OP_IRREGULAR_REDUCE, 1 << 20, 0).startswith("irregular_bounds_kernel+irregular_reduce_kernel")
+    assert k(lib.OP_IRREGULAR_SCAN, 1 << 20, 0) == "irregular_bounds_kernel+irregular_scan_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 3 << 20, 3 << 10) == "masked_wave_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 3 << 24, 3 << 20) == "masked_span_reduce_kernel+reduce_final_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "scan_chain_kernel<mfma>"        # long, a multiple of 8
-    assert k(lib.OP_SEGMENTED_SCAN, 100003 * 5, 100003) == "masked_wave_scan_kernel"       # long, odd
+    assert k(lib.OP_SEGMENTED_SCAN, 100003 * 5, 100003) == "irregular_scan_kernel<regular>"   # long, odd
     assert k(lib.OP_SEGMENTED_SCAN, 40000 * 5, 40000) == "scan_segment_kernel"             # under two chain tiles
     assert k(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "scan_segment_kernel"             # a multiple of 8: one workgroup each
-    assert k(lib.OP_SEGMENTED_SCAN, 3001 * 7, 3001) == "masked_wave_scan_kernel"
-    assert k(lib.OP_SEGMENTED_SCAN, 200 * 7, 200) == "generic_wave_kernel"
+    assert k(lib.OP_SEGMENTED_SCAN, 3001 * 7, 3001) == "irregular_scan_kernel<regular>"
+    assert k(lib.OP_SEGMENTED_SCAN, 200 * 7, 200) == "irregular_scan_kernel<regular>"
     assert k(lib.OP_SEGMENTED_SCAN, n, 3) == ""           # 3 does not divide n: the call reports an invalid argument
     assert k(lib.OP_SEGMENTED_SCAN, 0, 16) == ""
 

@@ -177,12 +177,12 @@ def test_irregular_behind_unaligned_pointers(tcr, oracle):
 @pytest.mark.parametrize("seg", [256 + 8, 511, 513, 520, 1000, 3000, 8200, 3001, 40000, 65528, 100003])
 @pytest.mark.parametrize("flags", [0, 1, 2, 3])
 def test_other_segment_lengths_take_every_flag(tcr, oracle, seg, flags):
-    # multiples of 8 above one tile: one workgroup per segment; everything else: one wavefront per segment over
-    # zero-masked tiles
+    # multiples of 8 above one tile: one workgroup per segment; everything else: fixed tiles of the array with
+    # the segment starts marked
     nseg = max(3, (200000 // seg) | 1)
     x = workloads.make_input(seg * nseg, "int4", seg % 89)
     xd = torch.from_numpy(x).cuda()
-    want = "scan_segment_kernel" if seg % 8 == 0 and seg > 512 else "masked_wave_scan_kernel"
+    want = "scan_segment_kernel" if seg % 8 == 0 and seg > 512 else "irregular_scan_kernel<regular>"
     assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, x.size, seg) == want
     ref = oracle.segmented_scan_exclusive(x, seg) if flags & 1 else oracle.segmented_scan(x, seg)
     got = tcr.segmented_scan_ex(xd, seg, flags).cpu().numpy().astype(np.float64)
