@@ -179,7 +179,9 @@ def main() -> int:
     big = 3 << 20
     nb = (n // big) * big
     n3 = (n // 3000) * 3000
+    n1, n100 = (n // 3001) * 3001, (n // 100) * 100
     out_g = torch.empty(n3 // 3000, dtype=torch.float32, device="cuda")
+    out_h100 = torch.empty(n100 // 100, dtype=torch.float32, device="cuda")
     out_h = torch.empty(n, dtype=torch.float16, device="cuda")
     variant_rows = []
     for e in (8, 12, 16, 20):
@@ -232,7 +234,13 @@ def main() -> int:
             ("segmented_reduce seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
             ("segmented_scan seg_len=3000 (no power of two: one workgroup per segment)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
-             (2 * n3, 4 * n3))]:
+             (2 * n3, 4 * n3)),
+            ("segmented_scan seg_len=3001 (odd: fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n1], 3001, out=out_scan[:n1]), n1,
+             (2 * n1, 4 * n1)),
+            ("segmented_scan seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n100], 100, out=out_scan[:n100]), n100,
+             (2 * n100, 4 * n100)),
+            ("segmented_reduce seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_reduce(x[:n100], 100, out=out_h100), n100,
+             (2 * n100, 4 * (n100 // 100)))]:
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
