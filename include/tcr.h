@@ -111,6 +111,10 @@ tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, vo
  */
 tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg, void *stream);
 tcr_status tcr_irregular_scan(const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg, void *stream);
+/* The scan with the flags of tcr_segmented_scan_ex (exclusive, binary16 output; out: n elements).  flags != 0
+ * needs 16-byte aligned in and out (TCR_ERR_UNSUPPORTED otherwise). */
+tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *out, uint64_t n, uint64_t nseg, uint32_t flags,
+                                 void *stream);
 
 /*
  * First two moments of every segment: the statistics of a normalisation layer, which the paper's conclusion

@@ -47,6 +47,7 @@ def _bind(path: str):
         ("oracle_segmented_moments", [u16p, f64p, f64p, u64, u64]),
         ("oracle_irregular_reduce", [u16p, u64p, f64p, u64]),
         ("oracle_irregular_scan", [u16p, u64p, f64p, u64]),
+        ("oracle_irregular_scan_exclusive", [u16p, u64p, f64p, u64]),
         ("oracle_reduce", [u16p, f64p, u64]),
         ("oracle_scan", [u16p, f64p, u64]),
         ("oracle_segmented_scan_at", [u16p, u64, u64, u64p, u64, f64p]),
@@ -136,6 +137,16 @@ class Oracle:
             raise ValueError("oracle_irregular_scan rejected its arguments")
         return out
 
+    def irregular_scan_exclusive(self, x: np.ndarray, offsets) -> np.ndarray:
+        off = np.ascontiguousarray(offsets, dtype=np.uint64)
+        if off.ndim != 1 or off.size < 1 or (off.size > 1 and int(off.max()) > x.shape[0]):
+            raise ValueError("offsets must hold nseg + 1 indices into x")
+        out = np.zeros(x.shape[0], dtype=np.float64)
+        if self._lib.oracle_irregular_scan_exclusive(_in_ptr(x), off.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+                                                     _out_ptr(out), off.size - 1):
+            raise ValueError("oracle_irregular_scan_exclusive rejected its arguments")
+        return out
+
     def reduce(self, x: np.ndarray) -> float:
         out = np.zeros(1, dtype=np.float64)
         if self._lib.oracle_reduce(_in_ptr(x), _out_ptr(out), x.shape[0]):
@@ -191,6 +202,10 @@ def irregular_reduce(x, offsets):
 
 def irregular_scan(x, offsets):
     return _get().irregular_scan(x, offsets)
+
+
+def irregular_scan_exclusive(x, offsets):
+    return _get().irregular_scan_exclusive(x, offsets)
 
 
 def reduce(x):

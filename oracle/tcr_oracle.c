@@ -137,6 +137,21 @@ int oracle_irregular_scan(const uint16_t *in, const uint64_t *offsets, double *o
     return 0;
 }
 
+/* Exclusive form of the irregular scan: out[k] = sum of the elements of k's segment in front of k. */
+int oracle_irregular_scan_exclusive(const uint16_t *in, const uint64_t *offsets, double *out, uint64_t nseg)
+{
+    if (nseg > 0 && (in == NULL || offsets == NULL || out == NULL)) return 1;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        if (offsets[s + 1] < offsets[s]) return 1;
+        double acc = 0.0;
+        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {
+            out[k] = acc;
+            acc += oracle_half_to_double(in[k]);
+        }
+    }
+    return 0;
+}
+
 /*
  * First two moments of every segment -- the reduction the paper's conclusion points at as the next use of
  * the method (mean and variance for batch normalisation):

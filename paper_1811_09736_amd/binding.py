@@ -22,7 +22,7 @@ SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
-    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
+    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
     "tcr_workspace_bytes", "tcr_set_workspace", "tcr_segmented_moments",
     "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
@@ -53,6 +53,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_scan_ex.restype = ctypes.c_int
     lib.tcr_irregular_reduce.argtypes = [vp, vp, fp, u64, u64, vp]
     lib.tcr_irregular_scan.argtypes = [vp, vp, fp, u64, u64, vp]
+    lib.tcr_irregular_scan_ex.argtypes = [vp, vp, vp, u64, u64, ctypes.c_uint32, vp]
+    lib.tcr_irregular_scan_ex.restype = ctypes.c_int
     lib.tcr_irregular_reduce.restype = ctypes.c_int
     lib.tcr_irregular_scan.restype = ctypes.c_int
     lib.tcr_reduce.argtypes = [vp, fp, u64, vp]
@@ -211,6 +213,25 @@ def irregular_scan(x: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.T
         st = _lib.tcr_irregular_scan(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), x.numel(), nseg, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_irregular_scan")
+    return out
+
+
+def irregular_scan_ex(x: torch.Tensor, offsets: torch.Tensor, flags: int, out: Optional[torch.Tensor] = None,
+                      stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_irregular_scan_ex: the irregular scan with SCAN_EXCLUSIVE / OUT_F16 flags."""
+    if not (x.is_cuda and x.dtype == torch.float16 and x.dim() == 1 and x.is_contiguous()):
+        raise TypeError("input must be a contiguous 1-D float16 CUDA tensor")
+    nseg = _check_offsets(x, offsets)
+    dtype = torch.float16 if flags & OUT_F16 else torch.float32
+    if out is None:
+        out = torch.zeros(x.numel(), dtype=dtype, device=x.device)
+    if not (out.is_cuda and out.dtype == dtype and out.is_contiguous() and out.numel() == x.numel() and out.device == x.device):
+        raise TypeError(f"out must be a contiguous {dtype} CUDA tensor of {x.numel()} elements on the input's device")
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_irregular_scan_ex(x.data_ptr(), offsets.data_ptr(), out.data_ptr(), x.numel(), nseg, flags,
+                                        _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_irregular_scan_ex")
     return out
 
 

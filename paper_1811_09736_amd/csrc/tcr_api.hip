@@ -38,10 +38,11 @@ extern "C" tcr_status tcr_scan_ex(const void* in, void* out, uint64_t n, uint32_
     return tcr_segmented_scan_ex(in, out, n, n, flags, stream);
 }
 
-static tcr_status validate_irregular(const void* in, const uint64_t* offsets, const float* out, uint64_t n, uint64_t nseg) {
+static tcr_status validate_irregular(const void* in, const uint64_t* offsets, const void* out, uint64_t n, uint64_t nseg,
+                                     uintptr_t out_align = 4) {
     if (in == nullptr && n != 0) return TCR_ERR_INVALID_ARG;
     if (offsets == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
-    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, 4)) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 2) || !aligned(offsets, 8) || !aligned(out, out_align)) return TCR_ERR_INVALID_ARG;
     if (nseg > kMaxElements || n > kMaxElements) return TCR_ERR_UNSUPPORTED;
     return TCR_OK;
 }
@@ -62,16 +63,31 @@ extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offse
     return check_launch("irregular_wave_kernel");
 }
 
-extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
-                                         void* stream) {
+extern "C" tcr_status tcr_irregular_scan_ex(const void* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
+                                            uint32_t flags, void* stream) {
+    if ((flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) != 0) return TCR_ERR_INVALID_ARG;
     if (nseg == 0 || n == 0) return TCR_OK;
-    const tcr_status st = validate_irregular(in, offsets, out, n, nseg);
+    const tcr_status st = validate_irregular(in, offsets, out, n, nseg, (flags & TCR_OUT_F16) ? 2 : 4);
     if (st != TCR_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (aligned(in, 16) && aligned(out, 16)) return launch_irregular_scan<0>(static_cast<const _Float16*>(in), offsets, out, n, nseg, 0, s);
+    const _Float16* x = static_cast<const _Float16*>(in);
+    if (aligned(in, 16) && aligned(out, 16)) {
+        switch (flags & 3u) {
+            case 0: return launch_irregular_scan<0>(x, offsets, out, n, nseg, 0, s);
+            case 1: return launch_irregular_scan<1>(x, offsets, out, n, nseg, 0, s);
+            case 2: return launch_irregular_scan<2>(x, offsets, out, n, nseg, 0, s);
+            default: return launch_irregular_scan<3>(x, offsets, out, n, nseg, 0, s);
+        }
+    }
+    if (flags != 0) return TCR_ERR_UNSUPPORTED;        // the element-wise kernel writes inclusive binary32 sums only
     irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
-        static_cast<const _Float16*>(in), offsets, out, nseg);
+        x, offsets, static_cast<float*>(out), nseg);
     return check_launch("irregular_wave_kernel");
+}
+
+extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
+                                         void* stream) {
+    return tcr_irregular_scan_ex(in, offsets, out, n, nseg, 0u, stream);
 }
 
 extern "C" tcr_status tcr_segmented_moments(const void* in, float* sum, float* sumsq, uint64_t n, uint64_t seg_len,

@@ -227,3 +227,23 @@ def test_capture_and_replay(tcr, oracle):
         side.synchronize()
         assert np.array_equal(got.cpu().numpy().astype(np.float64), oracle.irregular_scan(x, off))
     tcr.check_device_flags(side)
+
+
+@pytest.mark.parametrize("flags", [1, 2, 3])
+@pytest.mark.parametrize("recipe", ["uniform16", "lognormal256", "few5"])
+def test_scan_flags(tcr, oracle, recipe, flags):
+    # exclusive and binary16 output (integer sums: one correct rounding), partial cover
+    n = 5 * SCAN_TILE + 24
+    x = workloads.make_input(n, "int4", 60)
+    off = workloads.make_offsets(n - 40, recipe, flags).view(np.int64) + 16
+    xd, od = torch.from_numpy(x).cuda(), torch.from_numpy(off).cuda()
+    out = torch.full((n,), -3.0, dtype=torch.float16 if flags & 2 else torch.float32, device="cuda")
+    tcr.irregular_scan_ex(xd, od, flags, out=out)
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.irregular_scan_exclusive(x, off) if flags & 1 else oracle.irregular_scan(x, off)
+    if flags & 2:
+        ref = ref.astype(np.float16).astype(np.float64)
+    lo, hi = int(off[0]), int(off[-1])
+    assert np.array_equal(got[lo:hi], ref[lo:hi])
+    assert np.all(got[:lo] == -3.0) and np.all(got[hi:] == -3.0)
+    assert torch.equal(tcr.irregular_scan_ex(xd, od, 0), tcr.irregular_scan(xd, od))

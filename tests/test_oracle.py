@@ -206,6 +206,7 @@ def test_irregular_hand_values(oracle):
     off = [0, 3, 3, 4, 8]                                    # lengths 3, 0, 1, 4 -- worked by hand
     assert oracle.irregular_reduce(x, off).tolist() == [6, 0, 4, 26]
     assert oracle.irregular_scan(x, off).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
+    assert oracle.irregular_scan_exclusive(x, off).tolist() == [0, 1, 3, 0, 0, 5, 11, 18]
     # segments need not cover the input: untouched outputs stay zero
     assert oracle.irregular_scan(x, [2, 5]).tolist() == [0, 0, 3, 7, 12, 0, 0, 0]
     assert oracle.irregular_reduce(x, [2, 5]).tolist() == [12]
@@ -236,6 +237,10 @@ def test_irregular_equals_per_piece_definition(oracle):
     reg = np.arange(0, 5001, 125)
     assert np.array_equal(oracle.irregular_reduce(x, reg), oracle.segmented_reduce(x, 125))
     assert np.array_equal(oracle.irregular_scan(x, reg), oracle.segmented_scan(x, 125))
+    assert np.array_equal(oracle.irregular_scan_exclusive(x, reg), oracle.segmented_scan_exclusive(x, 125))
+    # exclusive + own element = inclusive (exact: every term is a multiple of 2^-24 far below 2^53)
+    covered = slice(int(off[0]), int(off[-1]))
+    assert np.array_equal((oracle.irregular_scan_exclusive(x, off) + xd)[covered], scan[covered])
 
 
 def test_reduce_is_permutation_invariant_on_integers(oracle):

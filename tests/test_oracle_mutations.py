@@ -31,6 +31,10 @@ MUTANTS = {
                                       "for (uint64_t k = offsets[s]; k <= offsets[s + 1]; ++k)\n            acc += "),
     "irregular_scan_carry_not_reset": ("        double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {",
                                        "        static double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {"),
+    "irregular_exclusive_includes_own_element": ("            out[k] = acc;\n            acc += oracle_half_to_double(in[k]);",
+                                                 "            acc += oracle_half_to_double(in[k]);\n            out[k] = acc;"),
+    "irregular_exclusive_carry_not_reset": ("        double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {\n            out[k] = acc;",
+                                            "        static double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {\n            out[k] = acc;"),
     "moments_square_of_sum": ("            q += v * v;", "            q += v;"),
     "moments_sum_of_abs": ("            a += v;\n            q += v * v;", "            a += v < 0 ? -v : v;\n            q += v * v;"),
     "moments_carry_not_reset": ("        double a = 0.0, q = 0.0;", "        double a = 0.0; static double q = 0.0;"),
@@ -52,6 +56,7 @@ def _pins(o) -> None:
     assert o.segmented_scan_exclusive(x, 4).tolist() == [0, 1, 3, 6, 0, 5, 11, 18]
     assert o.irregular_reduce(x, [0, 3, 3, 4, 7]).tolist() == [6, 0, 4, 18]
     assert o.irregular_scan(x, [0, 3, 3, 4, 8]).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
+    assert o.irregular_scan_exclusive(x, [0, 3, 3, 4, 8]).tolist() == [0, 1, 3, 0, 0, 5, 11, 18]
     assert o.reduce(x) == 36.0
     a, q = o.segmented_moments(np.array([1, -2, 3, 4, -5, 6], dtype=np.float16), 3)
     assert a.tolist() == [2, 5] and q.tolist() == [14, 77]
