@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--tuning", default="", help="launch-shape choices to import first (tcr_tuning_import text)")
     ap.add_argument("--autotune", action="store_true",
                     help="let tcr_autotune re-pick the launch shape of every timed call first (default: shipped shapes)")
+    ap.add_argument("--context-filter", default="", help="run only the context rows whose label contains this text")
     ap.add_argument("--no-context", action="store_true", help="skip the context rows (variants, library calls, full operations)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (read 1 GiB, write 1 GiB) three times before the timed "
@@ -224,7 +225,7 @@ def main() -> int:
                                    (2 * n + 8 * (nseg + 1), 4 * nseg)))
             irregular_rows.append((f"irregular_scan, {nseg} segments ({what})",
                                    (lambda off=off: tcr.irregular_scan(x, off, out=out_scan)), n, (2 * n + 8 * (nseg + 1), 4 * n)))
-    for label, fn, nn, rd_wr in [] if args.no_context else variant_rows + library_rows + irregular_rows + [
+    for label, fn, nn, rd_wr in [] if args.no_context else [row for row in variant_rows + library_rows + irregular_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
             ("segmented_reduce seg_len=3*2^20 (no power of two: masked pieces + second kernel)",
@@ -240,7 +241,7 @@ def main() -> int:
             ("segmented_scan seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n100], 100, out=out_scan[:n100]), n100,
              (2 * n100, 4 * n100)),
             ("segmented_reduce seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_reduce(x[:n100], 100, out=out_h100), n100,
-             (2 * n100, 4 * (n100 // 100)))]:
+             (2 * n100, 4 * (n100 // 100)))] if args.context_filter in row[0]]:
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -255,7 +256,7 @@ def main() -> int:
                       "pct_of_hbm_peak": round(sum(rd_wr) / us * 1e-3 / HBM_PEAK_GBS * 100, 1)})
     tcr.check_device_flags()
     del copy_dst
-    copy_gbps = None if args.no_context else extra[len(variant_rows)]["total_GBps"]
+    copy_gbps = next((r["total_GBps"] for r in extra if r["call"].startswith("context: device copy")), None)
     for r in rows:
         if copy_gbps:
             r["pct_of_measured_copy"] = round(r["total_GBps"] / copy_gbps * 100, 1)

@@ -169,13 +169,24 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     __shared__ uint32_t s_wave_flag[WAVES];
     __shared__ float s_prefix;
     __shared__ uint32_t s_tile;
+    __shared__ uint64_t s_bound[2];
 
     const ScanWorkspace ws = resolve_workspace(ws_arg);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // tiles are handed out in launch order, so every predecessor of a waiting tile is running or finished
-    if (threadIdx.x == 0)
-        s_tile = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+    if (threadIdx.x == 0) {
+        const uint32_t t = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+        s_tile = t;
+        if constexpr (REGULAR) {
+            // heads in [tb, tb + tile) are the multiples head_lo .. head_hi - 1 of seg_len; one thread divides for
+            // the whole workgroup (64-bit divisions are long instruction sequences)
+            const uint64_t b = (uint64_t)t * kBlockTile, e = b + kBlockTile;
+            const uint64_t q0 = b / seg_len, q1 = e / seg_len;
+            s_bound[0] = q0 + (q0 * seg_len != b ? 1u : 0u);
+            s_bound[1] = q1 + (q1 * seg_len != e ? 1u : 0u);
+        }
+    }
     for (uint32_t i = threadIdx.x; i < kBlockTile / 32; i += WAVES * kWave) s_heads[i] = 0u;
     __syncthreads();
     const uint32_t tile = s_tile;
@@ -194,8 +205,8 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     }
 
     // heads in [tb, tb + tile): entries head_lo .. head_hi - 1
-    const uint64_t head_lo = REGULAR ? (tb + seg_len - 1) / seg_len : starts_below[tile];
-    const uint64_t head_hi = REGULAR ? (tb + kBlockTile + seg_len - 1) / seg_len : starts_below[tile + 1];
+    const uint64_t head_lo = REGULAR ? s_bound[0] : starts_below[tile];
+    const uint64_t head_hi = REGULAR ? s_bound[1] : starts_below[tile + 1];
     const bool has_heads = head_lo < head_hi;
     if (has_heads) {
         for (uint64_t s = head_lo + threadIdx.x; s < head_hi; s += (uint64_t)(WAVES * kWave)) {
@@ -317,6 +328,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     __shared__ uint32_t s_heads[kBlockTile / 32];
     __shared__ uint32_t s_ends[kSubs];            // segment ends per sub-tile
     __shared__ uint16_t s_position[kPositions];   // entry head_lo + i lies on element tb + s_position[i]
+    __shared__ uint64_t s_bound[4];
     static_assert(kBlockTile <= 65535u, "positions are kept in 16 bits");
     __shared__ float s_wave_value[WAVES];
     __shared__ uint32_t s_wave_flag[WAVES];
@@ -341,13 +353,25 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
 
     // entries [head_lo, head_hi) lie in [tb, tb + tile): heads; entries [end_lo, end_hi) lie in
     // (tb, tb + tile]: each closes the segment in front of it.  head_lo <= end_lo, head_hi <= end_hi.
+    if constexpr (REGULAR) {
+        // one thread divides for the whole workgroup (64-bit divisions are long instruction sequences)
+        if (threadIdx.x == 0) {
+            const uint64_t te = tb + kBlockTile, entries = nseg + 1;
+            const uint64_t q0 = tb / seg_len, q1 = te / seg_len;
+            const uint64_t h0 = q0 + (q0 * seg_len != tb ? 1u : 0u), h1 = q1 + (q1 * seg_len != te ? 1u : 0u);
+            s_bound[0] = h0;
+            s_bound[1] = h1 < entries ? h1 : entries;
+            s_bound[2] = q0 + 1;
+            s_bound[3] = q1 + 1 < entries ? q1 + 1 : entries;
+        }
+    }
+    __syncthreads();
     uint64_t head_lo, head_hi, end_lo, end_hi;
     if constexpr (REGULAR) {
-        const uint64_t te = tb + kBlockTile, entries = nseg + 1;
-        head_lo = (tb + seg_len - 1) / seg_len;
-        head_hi = (te + seg_len - 1) / seg_len < entries ? (te + seg_len - 1) / seg_len : entries;
-        end_lo = tb / seg_len + 1;
-        end_hi = te / seg_len + 1 < entries ? te / seg_len + 1 : entries;
+        head_lo = s_bound[0];
+        head_hi = s_bound[1];
+        end_lo = s_bound[2];
+        end_hi = s_bound[3];
     } else {
         head_lo = starts_below[tile];
         head_hi = starts_below[tile + 1];
@@ -357,7 +381,6 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     // (the first tile also takes the entries on position 0, which close empty segments in front of everything)
     if (tile == 0) end_lo = 0;
     const bool has_entries = head_lo < end_hi;
-    __syncthreads();
     if (has_entries) {
         for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
             const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) - tb;
