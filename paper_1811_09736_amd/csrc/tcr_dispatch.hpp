@@ -470,8 +470,9 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
 }
 
 // offsets == nullptr: regular segments of seg_len elements (no look-up tables).
+// square (regular segments only): sums of squares.
 inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
-                                          uint64_t seg_len, hipStream_t s) {
+                                          uint64_t seg_len, hipStream_t s, bool square = false) {
     constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
     const uint64_t tiles = irregular_tiles(false, n);
     const uint64_t groups = ceil_div(tiles, kWave);
@@ -488,7 +489,11 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);
     TilePair* group_pairs = pairs + tiles;
     const dim3 grid((unsigned)tiles), block(kIrregularReduceW * kWave);
-    if (regular) {
+    if (regular && square) {
+        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr,
+                                                                                                       nullptr, seg_len, nseg, pairs,
+                                                                                                       carried);
+    } else if (regular) {
         irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr, nullptr,
                                                                                                  seg_len, nseg, pairs, carried);
     } else {
@@ -574,8 +579,32 @@ inline tcr_status scan_tuned(const _Float16* x, void* out, uint64_t n, uint64_t 
 }
 
 // First two moments of every segment, any seg_len >= 1 that divides n.
+template <int LOG2L>
+inline void launch_moments_small(const _Float16* in, float* sum, float* sumsq, uint64_t n, hipStream_t s) {
+    const uint64_t per_group = (uint64_t)kTile * kSmallReduceU * kSmallReduceW;
+    moments_small_kernel<LOG2L, kSmallReduceU, kSmallReduceW><<<dim3((unsigned)ceil_div(n, per_group)), dim3(kSmallReduceW * kWave), 0, s>>>(
+        in, sum, sumsq, n);
+}
+
 inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, uint64_t n, uint64_t seg_len, hipStream_t s) {
     const uint64_t nseg = n / seg_len;
+    if (is_pow2(seg_len) && seg_len >= 16 && seg_len <= kTile) {
+        switch (log2u(seg_len)) {
+            case 4: launch_moments_small<4>(in, sum, sumsq, n, s); break;
+            case 5: launch_moments_small<5>(in, sum, sumsq, n, s); break;
+            case 6: launch_moments_small<6>(in, sum, sumsq, n, s); break;
+            case 7: launch_moments_small<7>(in, sum, sumsq, n, s); break;
+            case 8: launch_moments_small<8>(in, sum, sumsq, n, s); break;
+            default: launch_moments_small<9>(in, sum, sumsq, n, s); break;
+        }
+        return check_launch("moments_small_kernel");
+    }
+    if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax) {
+        // fixed tiles with the segment starts marked, once for each moment
+        const tcr_status st = launch_irregular_reduce(in, nullptr, sum, n, nseg, seg_len, s, false);
+        if (st != TCR_OK) return st;
+        return launch_irregular_reduce(in, nullptr, sumsq, n, nseg, seg_len, s, true);
+    }
     if (seg_len <= kGenericThreadMax) {
         generic_moments_kernel<<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
             in, sum, sumsq, nseg, seg_len);

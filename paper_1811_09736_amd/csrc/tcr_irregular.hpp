@@ -65,11 +65,19 @@ __device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float& v) {
     seg_combine_left<0x143, 0xc, false>(f, v);     // lane 31 -> rows 2 and 3
 }
 
+// The value an element contributes: itself, or its square (exact in binary32) for the second moment.
+template <bool SQUARE>
+__device__ __forceinline__ float term(_Float16 h) {
+    const float v = (float)h;
+    return SQUARE ? v * v : v;
+}
+
 // Sum of a lane's 8 elements behind its last segment start (all 8 if it has none).
+template <bool SQUARE>
 __device__ __forceinline__ float lane_tail_sum(half8 x, uint32_t heads) {
     float q = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q = ((heads >> e) & 1u ? 0.0f : q) + (float)x[e];
+    for (int e = 0; e < 8; ++e) q = ((heads >> e) & 1u ? 0.0f : q) + term<SQUARE>(x[e]);
     return q;
 }
 
@@ -110,7 +118,7 @@ struct WaveShare {
     uint32_t chunk_flag;
 };
 
-template <int U>
+template <int U, bool SQUARE = false>
 __device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x)[U], const uint8_t* head_bytes, bool has_heads,
                                                 int lane) {
     w.run = 0.0f;
@@ -119,7 +127,7 @@ __device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x
     for (int u = 0; u < U; ++u) {
         w.heads[u] = has_heads ? (uint32_t)head_bytes[(kTile / 8) * u + lane] : 0u;
         uint32_t f = w.heads[u] != 0u ? 1u : 0u;
-        float v = lane_tail_sum(x[u], w.heads[u]);
+        float v = lane_tail_sum<SQUARE>(x[u], w.heads[u]);
         wave_seg_scan_inclusive(f, v);
         w.heads[u] |= wave_shr1_u32(f) << 8;
         w.lane_value[u] = wave_shr1(v);
@@ -134,7 +142,7 @@ __device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x
 
 // Running sums of a lane's 8 elements of sub-tile u, given the sum `ext` that reaches the wavefront's share
 // from in front of it.
-template <int U, int EXCL = 0>
+template <int U, int EXCL = 0, bool SQUARE = false>
 __device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const half8 (&x)[U], int u, float ext, float (&p)[8]) {
     const float into_sub = w.seen_before[u] ? w.before[u] : w.before[u] + ext;
     float q = (w.heads[u] >> 8) ? w.lane_value[u] : w.lane_value[u] + into_sub;
@@ -142,7 +150,7 @@ __device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const h
     for (int e = 0; e < 8; ++e) {
         q = (w.heads[u] >> e) & 1u ? 0.0f : q;
         if constexpr (EXCL) p[e] = q;
-        q += (float)x[u][e];
+        q += term<SQUARE>(x[u][e]);
         if constexpr (!EXCL) p[e] = q;
     }
 }
@@ -312,7 +320,8 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
 // which segment it is (carried[tile], or none) and its own pair (pairs[tile]) for the carry kernels.
 constexpr uint32_t kPositions = 4096;
 // REGULAR: entry s is s * seg_len, s = 0 .. nseg, instead of offsets[s] (offsets and the tables are not read).
-template <int U, int WAVES, bool REGULAR>
+// SQUARE: the sums are of the squares of the elements (second moments).
+template <int U, int WAVES, bool REGULAR, bool SQUARE = false>
 __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _Float16* __restrict__ in,
                                                                          const uint64_t* __restrict__ offsets,
                                                                          float* __restrict__ out, uint64_t n,
@@ -394,7 +403,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     const bool has_heads = head_lo < head_hi;
 
     WaveShare<U> w;
-    wave_share_scan<U>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
+    wave_share_scan<U, SQUARE>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
     if (lane == 0) {
         s_wave_value[wave] = w.run;
         s_wave_flag[wave] = w.chunk_flag;
@@ -432,7 +441,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
         if (count == 0u) continue;
         const uint64_t entry0 = end_lo + (uint64_t)((uint32_t)__builtin_amdgcn_readlane((int)upto, sub) - count);
         float p[8];
-        wave_share_finish<U>(w, x, u, ext, p);
+        wave_share_finish<U, 0, SQUARE>(w, x, u, ext, p);
         float4v* dst = reinterpret_cast<float4v*>(&s_stage[wave][8 * lane]);
         dst[0] = (float4v){p[0], p[1], p[2], p[3]};
         dst[1] = (float4v){p[4], p[5], p[6], p[7]};

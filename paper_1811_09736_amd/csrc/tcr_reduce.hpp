@@ -105,6 +105,76 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Floa
     if (slot < RT * U && s < nseg) out[s] = v;
 }
 
+// First two moments of small segments (seg_len in {16, ..., 512}): reduce_small_kernel's sums, and the sums of
+// squares from the diagonal of X . X^T -- the tile multiplied with itself on the matrix cores, whose entry
+// (j, j) is the sum of the squares of tile row j (products of two binary16 values are exact in the binary32
+// accumulator).  Lane (j, g) holds rows 4g .. 4g+3 of column j of the product, so the diagonal entry of row j
+// sits in lane (j, j / 4), register j % 4, and one cross-lane read brings it to every lane of column j.
+__device__ __forceinline__ float row_squares(half8 a, const LaneId& id) {
+    const float4v d = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, a, splat(0.0f), 0, 0, 0);
+    const int r = id.j & 3;
+    const float c = r == 0 ? d[0] : (r == 1 ? d[1] : (r == 2 ? d[2] : d[3]));
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((id.j + 16 * (id.j >> 2)) << 2, __builtin_bit_cast(int, c)));
+}
+
+template <int LOG2L, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void moments_small_kernel(const _Float16* __restrict__ in,
+                                                                      float* __restrict__ sum, float* __restrict__ sumsq,
+                                                                      uint64_t n) {
+    static_assert(LOG2L >= 4 && LOG2L <= 9, "");
+    const LaneId id;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint64_t base = ((uint64_t)blockIdx.x * WAVES + wave) * (uint64_t)(kTile * U);
+    if (base >= n) return;
+    const uint64_t nseg = n >> LOG2L;
+    const int lane_off = kRow * id.j + 8 * id.g;
+    half8 x[U];
+    if (base + (uint64_t)(kTile * U) <= n) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8<true>(in, base + (uint64_t)(kTile * u + lane_off));
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = load8_guarded<true>(in, base + (uint64_t)(kTile * u + lane_off), n);
+    }
+    constexpr int RT = kTile >> LOG2L;                   // results per tile
+    static_assert(RT * U <= kWave, "one result per lane at most");
+    float t[U], q[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (LOG2L == 4) {
+            // two segments per row, as in reduce_small_kernel: segment 2j + h of the tile in lane (j, g = 2h);
+            // the squares of each half row come from the tile with the other half's columns zeroed
+            t[u] = mfma(const_half_rows(id), x[u], splat(0.0f))[0];
+            const half8 zero = __builtin_bit_cast(half8, splat(0.0f));
+            const float first = row_squares(id.g < 2 ? x[u] : zero, id);
+            const float second = row_squares(id.g < 2 ? zero : x[u], id);
+            q[u] = id.g < 2 ? first : second;
+        } else {
+            constexpr int ROWS = 1 << (LOG2L - 5);       // tile rows per segment; sums valid in the group's last row
+            t[u] = row_sum_to_last<ROWS>(mfma(const_ones(), x[u], splat(0.0f))[0]);
+            q[u] = row_sum_to_last<ROWS>(row_squares(x[u], id));
+        }
+    }
+    const int slot = id.lane;                            // this lane stores results `slot` of the wavefront
+    const int slot_tile = slot / RT, slot_seg = slot % RT;
+    const int src = LOG2L == 4 ? (slot_seg >> 1) + 32 * (slot_seg & 1) : ((slot_seg + 1) << (LOG2L - 5)) - 1;
+    float a = 0.0f, b = 0.0f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float ga = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, t[u])));
+        const float gb = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, q[u])));
+        if (u == slot_tile) {
+            a = ga;
+            b = gb;
+        }
+    }
+    const uint64_t s = (base >> LOG2L) + (uint64_t)slot;
+    if (slot < RT * U && s < nseg) {
+        sum[s] = a;
+        sumsq[s] = b;
+    }
+}
+
 // ------------------------------------------------------------------------------ long spans
 // Wavefront w (global index) reduces elements [w*span, min((w+1)*span, n)); span is a multiple
 // of the tile size.  COMBINE == false: dst[w] receives that sum (one wavefront per segment or per
