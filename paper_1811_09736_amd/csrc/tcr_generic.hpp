@@ -43,6 +43,42 @@ __global__ __launch_bounds__(kGenericThreads) void generic_thread_kernel(const _
     if (!SCAN) put(out, s, acc, f16);
 }
 
+// Segments of 1, 2, 4 or 8 elements: a lane adds up the whole segments inside its 8 consecutive elements and
+// stores the 8 >> LOG2L results side by side (seg_len 1 is the conversion to binary32, also the inclusive scan).
+template <int LOG2L>
+__global__ __launch_bounds__(kGenericThreads) void tiny_reduce_kernel(const _Float16* __restrict__ in,
+                                                                      float* __restrict__ out, uint64_t n) {
+    static_assert(LOG2L >= 0 && LOG2L <= 3, "");
+    constexpr int kResults = 8 >> LOG2L;
+    const uint64_t g = ((uint64_t)blockIdx.x * kGenericThreads + threadIdx.x) * 8;
+    if (g >= n) return;
+    const half8 x = load8_guarded<true>(in, g, n);
+    float r[kResults];
+#pragma unroll
+    for (int i = 0; i < kResults; ++i) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int e = 0; e < (1 << LOG2L); ++e) acc += (float)x[(i << LOG2L) + e];
+        r[i] = acc;
+    }
+    float* dst = out + (g >> LOG2L);
+    if (g + 8 <= n) {
+        if constexpr (kResults == 8) {
+            store4(dst, 0, (float4v){r[0], r[1], r[2], r[3]});
+            store4(dst, 4, (float4v){r[4], r[5], r[6], r[7]});
+        } else if constexpr (kResults == 4) {
+            store4(dst, 0, (float4v){r[0], r[1], r[2], r[3]});
+        } else {
+#pragma unroll
+            for (int i = 0; i < kResults; ++i) dst[i] = r[i];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kResults; ++i)
+            if (g + (uint64_t)((i + 1) << LOG2L) <= n) dst[i] = r[i];
+    }
+}
+
 // ---------------------------------------------------------------------------------------- masked tiles
 // 8 inputs at element g (a multiple of 8), those outside [begin, end) read as zero.
 template <bool STREAM = false>

@@ -112,7 +112,7 @@ def test_single_segment_and_tiny_inputs(tcr, oracle, form, seg):
 
 # ------------------------------------------------------------------ segment lengths without a tuned path
 
-GENERIC_SEGS = [1, 2, 3, 5, 7, 8, 12, 15, 17, 24, 48, 96, 97, 100, 127, 129, 255, 257, 264, 511, 513, 520, 1000, 1536,
+GENERIC_SEGS = [1, 2, 3, 4, 5, 7, 8, 12, 15, 17, 24, 48, 96, 97, 100, 127, 129, 255, 257, 264, 511, 513, 520, 1000, 1536,
                 3000, 4097, 10000, 3 << 15]
 
 
