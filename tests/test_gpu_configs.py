@@ -135,3 +135,33 @@ def test_config4_integer_variants_both_carry_strategies(tcr, oracle):
             _compare(tcr.scan(xd), ref, x, w.n, True, True, False, f"cfg4 {key}={val}")
     finally:
         tcr.set_variant("reset")
+
+
+@pytest.mark.parametrize("recipe", ["uniform16", "lognormal256", "few7"])
+def test_irregular_mixes_at_bench_size(tcr, oracle, recipe):
+    # the three offset arrays bench.py times, over the input of configuration 5 (non-negative: plain relative
+    # error), every output element against the oracle
+    n = 1 << 28
+    x, xd = _input(n, "uniform_01", 4)
+    off = workloads.make_offsets(n, recipe, 5).view(np.int64)
+    od = torch.from_numpy(off).cuda()
+    nseg = off.size - 1
+    red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
+    ref = oracle.irregular_reduce(x, off)
+    err = np.abs(red - ref)
+    assert np.all(err <= REL_TOL * np.abs(ref)), f"{recipe}: reduce, worst segment {int(np.argmax(err - REL_TOL * np.abs(ref)))}"
+    print(f"  {recipe}: {nseg} segments, reduce max relative error {np.max(err[ref > 0] / ref[ref > 0]):.3e}", flush=True)
+    del red, ref, err
+    got = tcr.irregular_scan(xd, od).cpu().numpy()
+    ref = oracle.irregular_scan(x, off)
+    worst = 0.0
+    for lo in range(0, n, CHUNK):
+        r = ref[lo:lo + CHUNK]
+        e = np.abs(got[lo:lo + CHUNK].astype(np.float64) - r)
+        if not np.all(e <= REL_TOL * np.abs(r)):
+            bad = lo + int(np.argmax(e - REL_TOL * np.abs(r)))
+            raise AssertionError(f"{recipe}: scan, worst at {bad}: got {got[bad]!r} want {ref[bad]!r}")
+        nz = r > 0
+        worst = max(worst, float(np.max(e[nz] / r[nz])))
+    print(f"  {recipe}: scan max relative error {worst:.3e}", flush=True)
+    tcr.check_device_flags()
