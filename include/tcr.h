@@ -98,21 +98,22 @@ tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, vo
  *   tcr_irregular_reduce  out[s] = sum of segment s (0 for an empty one); out: nseg floats.
  *   tcr_irregular_scan    out[k] = sum of in[offsets[s] .. k] for k in segment s; out is indexed like `in`
  *                         (positions outside [offsets[0], offsets[nseg]) are not written).
- * With 16-byte aligned in (and out, for the scan) the work is divided by elements, not by segments: fixed
- * tiles of the array at a speed that hardly depends on the mix of segment lengths.  Both use the workspace
- * (tcr_workspace_bytes, op 4 and 5): one small kernel looks up where the tile boundaries fall among the
- * offsets; the scan chains its tiles like the long regular scans; the reduction keeps its tiles independent
- * and two small kernels add the one sum per tile that reaches in from earlier tiles -- plain loads in a fixed
- * order, so the reduction's results are the same from run to run.
- * Otherwise in and out need only their natural alignment (2 and 4 bytes) and one wavefront walks each
- * segment.  The offsets are not validated (they live on the device): entries that decrease or exceed n
- * give wrong results for the segments they bound, never an access outside in[0 .. n) and the outputs.
- * nseg == 0 is a no-op.
+ * The work is divided by elements, not by segments: fixed tiles of the array at a speed that hardly depends on
+ * the mix of segment lengths.  Both use the workspace (tcr_workspace_bytes, op 4 and 5): one small kernel looks
+ * up where the tile boundaries fall among the offsets; the scan chains its tiles like the long regular scans;
+ * the reduction keeps its tiles independent and two small kernels add the one sum per tile that reaches in
+ * from earlier tiles -- plain loads in a fixed order, so the reduction's results are the same from run to run.
+ * in and out need only their natural alignment (2 and 4 bytes): the tiles start at the 16-byte boundary at or
+ * below `in` (up to 7 elements in front of it are read and ignored), and a scan whose `out` does not sit at the
+ * same distance from a 16-byte boundary stores its results one by one (slower).
+ * The offsets are not validated (they live on the device): entries that decrease or exceed n give wrong
+ * results for the segments they bound, never an access outside in[0 .. n), beyond those leading elements,
+ * and the outputs.  nseg == 0 is a no-op.
  */
 tcr_status tcr_irregular_reduce(const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg, void *stream);
 tcr_status tcr_irregular_scan(const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg, void *stream);
-/* The scan with the flags of tcr_segmented_scan_ex (exclusive, binary16 output; out: n elements).  flags != 0
- * needs 16-byte aligned in and out (TCR_ERR_UNSUPPORTED otherwise). */
+/* The scan with the flags of tcr_segmented_scan_ex (exclusive, binary16 output; out: n elements, aligned to
+ * their size). */
 tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *out, uint64_t n, uint64_t nseg, uint32_t flags,
                                  void *stream);
 

@@ -57,10 +57,7 @@ extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offse
         fill_zero_kernel<<<dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, s>>>(out, nseg);
         return check_launch("fill_zero_kernel");
     }
-    if (aligned(in, 16)) return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, out, n, nseg, 0, s);
-    irregular_wave_kernel<false><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
-        static_cast<const _Float16*>(in), offsets, out, nseg);
-    return check_launch("irregular_wave_kernel");
+    return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, out, n, nseg, 0, s);
 }
 
 extern "C" tcr_status tcr_irregular_scan_ex(const void* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
@@ -71,18 +68,12 @@ extern "C" tcr_status tcr_irregular_scan_ex(const void* in, const uint64_t* offs
     if (st != TCR_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const _Float16* x = static_cast<const _Float16*>(in);
-    if (aligned(in, 16) && aligned(out, 16)) {
-        switch (flags & 3u) {
-            case 0: return launch_irregular_scan<0>(x, offsets, out, n, nseg, 0, s);
-            case 1: return launch_irregular_scan<1>(x, offsets, out, n, nseg, 0, s);
-            case 2: return launch_irregular_scan<2>(x, offsets, out, n, nseg, 0, s);
-            default: return launch_irregular_scan<3>(x, offsets, out, n, nseg, 0, s);
-        }
+    switch (flags & 3u) {
+        case 0: return launch_irregular_scan<0>(x, offsets, out, n, nseg, 0, s);
+        case 1: return launch_irregular_scan<1>(x, offsets, out, n, nseg, 0, s);
+        case 2: return launch_irregular_scan<2>(x, offsets, out, n, nseg, 0, s);
+        default: return launch_irregular_scan<3>(x, offsets, out, n, nseg, 0, s);
     }
-    if (flags != 0) return TCR_ERR_UNSUPPORTED;        // the element-wise kernel writes inclusive binary32 sums only
-    irregular_wave_kernel<true><<<dim3((unsigned)ceil_div(nseg, kGenericThreads / kWave)), dim3(kGenericThreads), 0, s>>>(
-        x, offsets, static_cast<float*>(out), nseg);
-    return check_launch("irregular_wave_kernel");
 }
 
 extern "C" tcr_status tcr_irregular_scan(const void* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,

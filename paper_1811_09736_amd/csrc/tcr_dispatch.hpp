@@ -429,11 +429,20 @@ inline uint64_t irregular_words(bool scan, uint64_t n) {
     return scan ? tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
 }
 
+// The tiles start at the 16-byte boundary at or below `in`: `shift` elements in front of it (0 for aligned arrays).
+inline uint32_t alignment_shift(const _Float16* in) { return (uint32_t)((reinterpret_cast<uintptr_t>(in) & 15u) / 2u); }
+
 // offsets == nullptr: regular segments of seg_len elements (no look-up table; MODE as for the other scans).
+// in: 2-byte aligned; out: aligned to its element size.
 template <int MODE>
 inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
                                         uint64_t seg_len, hipStream_t s) {
     constexpr uint64_t kElems = (uint64_t)kTile * kIrregularScanU * kIrregularScanW;
+    const uint32_t shift = alignment_shift(in);
+    in -= shift;
+    out = static_cast<char*>(out) - (size_t)shift * ((MODE & 2) ? 2 : 4);
+    n += shift;
+    const uint32_t vector_stores = aligned(out, 16) ? 1u : 0u;
     const uint64_t tiles = irregular_tiles(true, n);
     const bool regular = offsets == nullptr;
     Workspace* ws = nullptr;
@@ -451,14 +460,14 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
     const dim3 grid((unsigned)tiles), block(kIrregularScanW * kWave);
     if (regular) {
         irregular_scan_kernel<kIrregularScanU, kIrregularScanW, true, MODE><<<grid, block, 0, s>>>(in, nullptr, out, n, nseg, nullptr,
-                                                                                                 seg_len, dev);
+                                                                                                 seg_len, 0u, vector_stores, dev);
     } else {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-            offsets, nseg + 1, kElems, tiles + 1, starts, nullptr);
+            offsets, nseg + 1, kElems, tiles + 1, shift, starts, nullptr);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
         irregular_scan_kernel<kIrregularScanU, kIrregularScanW, false, MODE><<<grid, block, 0, s>>>(in, offsets, out, n, nseg, starts,
-                                                                                                  0, dev);
+                                                                                                  0, shift, vector_stores, dev);
     }
     st = check_launch("irregular_scan_kernel");
     if (st != TCR_OK) {
@@ -474,6 +483,9 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
 inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
                                           uint64_t seg_len, hipStream_t s, bool square = false) {
     constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
+    const uint32_t shift = alignment_shift(in);
+    in -= shift;
+    n += shift;
     const uint64_t tiles = irregular_tiles(false, n);
     const uint64_t groups = ceil_div(tiles, kWave);
     const bool regular = offsets == nullptr;
@@ -491,18 +503,18 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     const dim3 grid((unsigned)tiles), block(kIrregularReduceW * kWave);
     if (regular && square) {
         irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr,
-                                                                                                       nullptr, seg_len, nseg, pairs,
+                                                                                                       nullptr, seg_len, nseg, 0u, pairs,
                                                                                                        carried);
     } else if (regular) {
         irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr, nullptr,
-                                                                                                 seg_len, nseg, pairs, carried);
+                                                                                                 seg_len, nseg, 0u, pairs, carried);
     } else {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-            offsets, nseg + 1, kElems, tiles + 1, starts, ends);
+            offsets, nseg + 1, kElems, tiles + 1, shift, starts, ends);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
         irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(in, offsets, out, n, starts, ends, 0,
-                                                                                                  nseg, pairs, carried);
+                                                                                                  nseg, shift, pairs, carried);
     }
     st = check_launch("irregular_reduce_kernel");
     if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it

@@ -1,6 +1,6 @@
 // Kernels for what the tiled kernels do not take: reductions of regular segments whose length is no power
-// of two (long ones; short ones run on the fixed tiles of tcr_irregular.hpp), the shortest segments, the
-// moments, and irregular segments behind unaligned pointers.  The paper handles such sizes by zero padding
+// of two (long ones; short ones run on the fixed tiles of tcr_irregular.hpp), the shortest segments and the
+// moments.  The paper handles such sizes by zero padding
 // or by masking (Section 4, "Support for arbitrary segment sizes ...").  Padding in place is not possible
 // behind this interface, so:
 //   masked_*        one wavefront per segment (or per 65536-element piece of one) walks the 512-element
@@ -207,45 +207,6 @@ __global__ __launch_bounds__(kGenericThreads) void generic_moments_kernel(const 
     }
     sum[s] = a;
     sumsq[s] = q;
-}
-
-// Irregular segments behind unaligned pointers: segment s is [offsets[s], offsets[s+1]).  One wavefront per
-// segment, 64 elements per step, the wavefront scan primitive.  (The paper reduces the irregular case to the regular one by
-// padding the input, Section 3 footnote; reading the offsets directly needs no padded copy.)
-template <bool SCAN>
-__global__ __launch_bounds__(kGenericThreads) void irregular_wave_kernel(const _Float16* __restrict__ in,
-                                                                         const uint64_t* __restrict__ offsets,
-                                                                         float* __restrict__ out, uint64_t nseg) {
-    constexpr int kSteps = 4;
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t s = (uint64_t)blockIdx.x * (kGenericThreads / kWave) +
-                       (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (s >= nseg) return;
-    const uint64_t begin = offsets[s], end = offsets[s + 1];
-    float carry = 0.0f, acc = 0.0f;
-    for (uint64_t k0 = begin; k0 < end; k0 += (uint64_t)(kWave * kSteps)) {
-        float v[kSteps];
-#pragma unroll
-        for (int i = 0; i < kSteps; ++i) {
-            const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
-            v[i] = (k < end) ? (float)in[k] : 0.0f;
-        }
-#pragma unroll
-        for (int i = 0; i < kSteps; ++i) {
-            if (SCAN) {
-                const uint64_t k = k0 + (uint64_t)(kWave * i + lane);
-                const float incl = wave_scan_inclusive(v[i]);
-                if (k < end) out[k] = incl + carry;
-                carry += read_lane(incl, 63);
-            } else {
-                acc += v[i];
-            }
-        }
-    }
-    if (!SCAN) {
-        const float total = wave_sum(acc);
-        if (lane == 0) out[s] = total;
-    }
 }
 
 }  // namespace tcr

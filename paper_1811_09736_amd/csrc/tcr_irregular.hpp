@@ -85,20 +85,23 @@ __device__ __forceinline__ float lane_tail_sum(half8 x, uint32_t heads) {
 // ends_below[i] (optional) = the same for i * tile_elems + 1, i.e. with the entries ON the boundary added,
 // which turns "segment starts in [begin, end)" into "segment ends in (begin, end]".  One wavefront per boundary.
 constexpr int kBoundsWaves = 4;
+// shift: the tiles are laid out from `shift` elements in front of the array (see irregular_scan_kernel), so
+// entry s lies on tile position offsets[s] + shift.
 __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(const uint64_t* __restrict__ offsets,
                                                                                 uint64_t count, uint64_t tile_elems,
-                                                                                uint64_t boundaries,
+                                                                                uint64_t boundaries, uint32_t shift,
                                                                                 uint64_t* __restrict__ starts_below,
                                                                                 uint64_t* __restrict__ ends_below) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t i = (uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (i >= boundaries) return;
-    const uint64_t key = i * tile_elems;
+    const bool reachable = i * tile_elems >= (uint64_t)shift;       // no entry lies in front of position `shift`
+    const uint64_t key = reachable ? i * tile_elems - shift : 0;
     const uint64_t below = wave_lower_bound(offsets, count, key, lane);
     if (lane == 0) starts_below[i] = below;
     if (ends_below == nullptr) return;
     uint64_t on = 0;                          // entries equal to key follow directly
-    while (true) {
+    while (reachable) {
         const uint64_t idx = below + on + (uint64_t)lane;
         const int c = __builtin_popcountll(__ballot(idx < count && offsets[idx] == key));
         on += (uint64_t)c;
@@ -164,11 +167,15 @@ __device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const h
 // REGULAR: the heads are the multiples of seg_len instead (offsets and starts_below are not read): regular
 // segments of a length no other kernel is tuned for -- odd lengths above all, which leave no 8-element group
 // aligned with the segments.  MODE bit 0: exclusive scan; bit 1: binary16 output.
+// Arrays that are not 16-byte aligned: `in` and `out` point `shift` (0..7) elements in front of the caller's
+// arrays, where `in` is 16-byte aligned, n counts from there and entry s lies on position offsets[s] + shift;
+// the elements in front of offsets[0] + shift belong to no segment like any others outside the segments.
+// vector_stores == 0: `out` is not 16-byte aligned there and every result is stored on its own.
 template <int U, int WAVES, bool REGULAR, int MODE>
 __global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(8, 8)))
 void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, void* __restrict__ out,
                            uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, uint64_t seg_len,
-                           ScanWorkspace ws_arg) {
+                           uint32_t shift, uint32_t vector_stores, ScanWorkspace ws_arg) {
     constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
     constexpr uint32_t kChunk = (uint32_t)kTile * U;          // one wavefront's share
     constexpr uint32_t kBlockTile = kChunk * WAVES;           // one workgroup's share
@@ -218,7 +225,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     const bool has_heads = head_lo < head_hi;
     if (has_heads) {
         for (uint64_t s = head_lo + threadIdx.x; s < head_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) - tb;
+            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s] + shift) - tb;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
         }
         __syncthreads();
@@ -243,10 +250,10 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         }
     }
     // the part [valid_lo, valid_hi) of this wavefront's share lies in a segment (all of it, nearly always)
-    const uint64_t first = REGULAR ? 0 : offsets[0], last = REGULAR ? n : offsets[nseg];
+    const uint64_t first = REGULAR ? 0 : offsets[0] + shift, last = REGULAR ? n : offsets[nseg] + shift;
     const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
     const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
-    const bool inside = valid_lo == 0u && valid_hi == kChunk;
+    const bool inside = valid_lo == 0u && valid_hi == kChunk && vector_stores != 0u;
     // A wavefront behind a head needs nothing from earlier tiles and goes straight to its stores instead of
     // waiting for the look-up (the barrier only counts the wavefronts that are still running, so it opens
     // for the others once these have finished).  Wavefront 0 is always open.
@@ -320,6 +327,7 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
 // which segment it is (carried[tile], or none) and its own pair (pairs[tile]) for the carry kernels.
 constexpr uint32_t kPositions = 4096;
 // REGULAR: entry s is s * seg_len, s = 0 .. nseg, instead of offsets[s] (offsets and the tables are not read).
+// shift: as for irregular_scan_kernel (`in` points that many elements in front of the caller's array).
 // SQUARE: the sums are of the squares of the elements (second moments).
 template <int U, int WAVES, bool REGULAR, bool SQUARE = false>
 __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _Float16* __restrict__ in,
@@ -327,7 +335,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
                                                                          float* __restrict__ out, uint64_t n,
                                                                          const uint64_t* __restrict__ starts_below,
                                                                          const uint64_t* __restrict__ ends_below,
-                                                                         uint64_t seg_len, uint64_t nseg,
+                                                                         uint64_t seg_len, uint64_t nseg, uint32_t shift,
                                                                          TilePair* __restrict__ pairs,
                                                                          uint64_t* __restrict__ carried) {
     constexpr uint32_t kChunk = (uint32_t)kTile * U;
@@ -392,7 +400,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     const bool has_entries = head_lo < end_hi;
     if (has_entries) {
         for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) - tb;
+            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s] + shift) - tb;
             if (s - head_lo < (uint64_t)kPositions) s_position[s - head_lo] = (uint16_t)pos;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
             if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
@@ -458,8 +466,8 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
                 end = s_position[i];
                 begin = i > 0 ? (uint32_t)s_position[i - 1] : 0u;
             } else {
-                end = (uint32_t)((REGULAR ? s * seg_len : offsets[s]) - tb);
-                begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1]) - tb);
+                end = (uint32_t)((REGULAR ? s * seg_len : offsets[s] + shift) - tb);
+                begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1] + shift) - tb);
             }
             const uint32_t at = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
             const bool empty = i > 0 && end == begin;

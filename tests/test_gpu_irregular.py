@@ -247,3 +247,39 @@ def test_scan_flags(tcr, oracle, recipe, flags):
     assert np.array_equal(got[lo:hi], ref[lo:hi])
     assert np.all(got[:lo] == -3.0) and np.all(got[hi:] == -3.0)
     assert torch.equal(tcr.irregular_scan_ex(xd, od, 0), tcr.irregular_scan(xd, od))
+
+
+@pytest.mark.parametrize("in_shift,out_shift", [(1, 1), (3, 3), (7, 7), (5, 1), (0, 2), (4, 0), (6, 6)])
+def test_unaligned_arrays(tcr, oracle, in_shift, out_shift):
+    # views that start in_shift / out_shift elements into 16-byte aligned buffers: the tiles start at the aligned
+    # boundary below `in`; equal shifts keep 128-bit stores, different ones store results one by one
+    n = 3 * SCAN_TILE + 100
+    base = workloads.make_input(n + 8, "int8", 70 + in_shift)
+    x = base[in_shift:in_shift + n].copy()
+    xd = torch.from_numpy(base).cuda()[in_shift:in_shift + n]
+    assert xd.data_ptr() % 16 == (2 * in_shift) % 16
+    for recipe in ("uniform16", "lognormal256", "few3"):
+        off = workloads.make_offsets(n, recipe, in_shift).view(np.int64)
+        od = torch.from_numpy(off).cuda()
+        red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
+        assert np.array_equal(red, oracle.irregular_reduce(x, off)), recipe
+        for flags in (0, 1, 2):
+            dtype = torch.float16 if flags & 2 else torch.float32
+            buf = torch.full((n + 16,), -3.0, dtype=dtype, device="cuda")
+            out = buf[out_shift:out_shift + n]
+            tcr.irregular_scan_ex(xd, od, flags, out=out)
+            ref = oracle.irregular_scan_exclusive(x, off) if flags & 1 else oracle.irregular_scan(x, off)
+            if flags & 2:
+                ref = ref.astype(np.float16).astype(np.float64)
+            got = buf.cpu().numpy().astype(np.float64)
+            assert np.array_equal(got[out_shift:out_shift + n], ref), f"{recipe} flags={flags}"
+            assert np.all(got[:out_shift] == -3.0) and np.all(got[out_shift + n:] == -3.0), f"{recipe} flags={flags}: wrote outside"
+    # a partial cover behind an unaligned pointer
+    off = np.array([3, 3, 40, SCAN_TILE + 5, n - 9], dtype=np.int64)
+    od = torch.from_numpy(off).cuda()
+    assert np.array_equal(tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64), oracle.irregular_reduce(x, off))
+    buf = torch.full((n + 16,), -3.0, dtype=torch.float32, device="cuda")
+    tcr.irregular_scan(xd, od, out=buf[out_shift:out_shift + n])
+    got = buf.cpu().numpy().astype(np.float64)[out_shift:out_shift + n]
+    assert np.array_equal(got[3:n - 9], oracle.irregular_scan(x, off)[3:n - 9])
+    assert np.all(got[:3] == -3.0) and np.all(got[n - 9:] == -3.0)
