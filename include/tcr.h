@@ -10,8 +10,11 @@
  * constant ones / triangular matrices on the matrix cores -- re-derived for CDNA4 MFMA.
  *
  * Conventions common to every call
- *   in      DEVICE pointer to n binary16 values, contiguous, 16-byte aligned, read only.
- *   out     DEVICE pointer, caller owned, must not overlap `in`; alignment stated per call.
+ *   in      DEVICE pointer to n binary16 values, contiguous, read only.  16-byte aligned for the tuned kernels;
+ *           with less (2 bytes at least) the call runs on the fixed tiles of the irregular calls, laid out from
+ *           the 16-byte boundary below `in`: up to 7 elements in front of `in` are read and ignored.
+ *   out     DEVICE pointer, caller owned, must not overlap `in`.  Scans: 16-byte aligned for the tuned kernels,
+ *           at least the alignment of an element otherwise; reductions: 4-byte aligned.
  *   stream  a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *           and return; they never synchronise with the host.
  *   Inputs must be finite.  (A zero entry of a constant matrix times an infinity is NaN, so
@@ -68,7 +71,7 @@ tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t
 /*
  * Regular segmented inclusive scan (Section 3; algorithms of Section 5).
  *   out[s*seg_len + k] = sum_{j <= k} in[s*seg_len + j].
- * out: n floats, 16-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
+ * out: n floats.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted, as for tcr_segmented_reduce.
  */
 tcr_status tcr_segmented_scan(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
@@ -80,7 +83,7 @@ tcr_status tcr_segmented_scan(const void *in, float *out, uint64_t n, uint64_t s
  *   TCR_OUT_F16         results are rounded (to nearest even) to binary16 and `out` points to n binary16
  *                       values -- the paper's own output precision (Section 6 counts 4 bytes per scanned
  *                       element).  Accumulation stays binary32; sums beyond 65504 become infinities.
- * flags == 0 is tcr_segmented_scan / tcr_scan.  out: n elements, 16-byte aligned.  Unknown flag bits
+ * flags == 0 is tcr_segmented_scan / tcr_scan.  out: n elements.  Unknown flag bits
  * return TCR_ERR_INVALID_ARG.  Under the "dpp" formulation only flags == 0 has tuned kernels
  * (TCR_ERR_UNSUPPORTED otherwise); segment lengths without a tuned path accept every flag.
  */
@@ -138,7 +141,7 @@ tcr_status tcr_reduce(const void *in, float *out, uint64_t n, void *stream);
 
 /*
  * Full inclusive scan (device level, Section 5): out[k] = sum_{j <= k} in[j].
- * Any n is accepted.  out: n floats, 16-byte aligned.
+ * Any n is accepted.  out: n floats.
  */
 tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
 
@@ -175,7 +178,7 @@ tcr_status tcr_tuning_import(const char *text);
 /*
  * Name of the kernel the dispatcher would launch for (op, n, seg_len) under the current
  * variant settings; op is 0 = segmented_reduce, 1 = segmented_scan, 2 = reduce, 3 = scan,
- * 4 = irregular_reduce, 5 = irregular_scan (16-byte aligned arrays; seg_len is ignored).
+ * 4 = irregular_reduce, 5 = irregular_scan (seg_len is ignored).  Arrays are taken to be 16-byte aligned.
  * Returns a static string ("" when nothing would be launched); never NULL.
  */
 const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);

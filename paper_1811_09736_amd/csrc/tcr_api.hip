@@ -13,6 +13,9 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     if (st != TCR_OK || n == 0) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const _Float16* x = static_cast<const _Float16*>(in);
+    // the tuned kernels load 128 bits at a time; an input that is not aligned for that takes the fixed tiles laid
+    // out from the 16-byte boundary below it
+    if (!aligned(in, 16)) return launch_irregular_reduce(x, nullptr, out, n, n / seg_len, seg_len, s);
     if (seg_len == n) return reduce_long(x, out, n, n, true, s);
     if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<false>(x, out, n, seg_len, 0u, s);
     if (seg_len <= kTile)
@@ -24,9 +27,20 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
 extern "C" tcr_status tcr_segmented_scan_ex(const void* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags,
                                             void* stream) {
     if ((flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) != 0) return TCR_ERR_INVALID_ARG;
-    tcr_status st = validate(in, out, n, seg_len, 16);
+    tcr_status st = validate(in, out, n, seg_len, (flags & TCR_OUT_F16) ? 2 : 4);
     if (st != TCR_OK || n == 0) return st;
-    return scan_any(in, out, n, seg_len, flags, static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!aligned(in, 16) || !aligned(out, 16)) {
+        // arrays that are not aligned for 128-bit accesses: the fixed tiles, laid out from the boundary below `in`
+        const _Float16* x = static_cast<const _Float16*>(in);
+        switch (flags & 3u) {
+            case 0: return launch_irregular_scan<0>(x, nullptr, out, n, n / seg_len, seg_len, s);
+            case 1: return launch_irregular_scan<1>(x, nullptr, out, n, n / seg_len, seg_len, s);
+            case 2: return launch_irregular_scan<2>(x, nullptr, out, n, n / seg_len, seg_len, s);
+            default: return launch_irregular_scan<3>(x, nullptr, out, n, n / seg_len, seg_len, s);
+        }
+    }
+    return scan_any(in, out, n, seg_len, flags, s);
 }
 
 extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
@@ -86,6 +100,13 @@ extern "C" tcr_status tcr_segmented_moments(const void* in, float* sum, float* s
     tcr_status st = validate(in, sum, n, seg_len, 4);
     if (st != TCR_OK || n == 0) return st;
     if (sumsq == nullptr || !aligned(sumsq, 4)) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 16)) {                  // the tiled reduction, once per moment
+        const _Float16* x = static_cast<const _Float16*>(in);
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        st = launch_irregular_reduce(x, nullptr, sum, n, n / seg_len, seg_len, s, false);
+        if (st != TCR_OK) return st;
+        return launch_irregular_reduce(x, nullptr, sumsq, n, n / seg_len, seg_len, s, true);
+    }
     return launch_moments(static_cast<const _Float16*>(in), sum, sumsq, n, seg_len, static_cast<hipStream_t>(stream));
 }
 
@@ -98,6 +119,7 @@ extern "C" tcr_status tcr_reduce(const void* in, float* out, uint64_t n, void* s
     }
     tcr_status st = validate(in, out, n, n, 4);
     if (st != TCR_OK) return st;
+    if (!aligned(in, 16)) return launch_irregular_reduce(static_cast<const _Float16*>(in), nullptr, out, n, 1, n, s);
     return reduce_long(static_cast<const _Float16*>(in), out, n, n, true, s);
 }
 
@@ -160,9 +182,10 @@ extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t 
     if (op < 0 || op > 3) return TCR_ERR_INVALID_ARG;
     if (op >= 2) seg_len = n;
     const bool is_scan = (op == 1 || op == 3);
-    tcr_status st = validate(in, out, n, seg_len, is_scan ? 16 : 4);
+    tcr_status st = validate(in, out, n, seg_len, 4);
     if (st != TCR_OK) return st;
     if (n == 0) return TCR_OK;
+    if (!aligned(in, 16) || (is_scan && !aligned(out, 16))) return TCR_ERR_INVALID_ARG;     // the tuned kernels' alignment
     const bool whole = seg_len == n;
     if (!whole && (!is_pow2(seg_len) || seg_len < 1024)) return TCR_OK;       // a single shape: nothing to choose
     if (whole && n < 1024) return TCR_OK;

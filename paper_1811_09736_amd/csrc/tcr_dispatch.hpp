@@ -460,7 +460,7 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
     const dim3 grid((unsigned)tiles), block(kIrregularScanW * kWave);
     if (regular) {
         irregular_scan_kernel<kIrregularScanU, kIrregularScanW, true, MODE><<<grid, block, 0, s>>>(in, nullptr, out, n, nseg, nullptr,
-                                                                                                 seg_len, 0u, vector_stores, dev);
+                                                                                                 seg_len, shift, vector_stores, dev);
     } else {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
             offsets, nseg + 1, kElems, tiles + 1, shift, starts, nullptr);
@@ -503,11 +503,11 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     const dim3 grid((unsigned)tiles), block(kIrregularReduceW * kWave);
     if (regular && square) {
         irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr,
-                                                                                                       nullptr, seg_len, nseg, 0u, pairs,
+                                                                                                       nullptr, seg_len, nseg, shift, pairs,
                                                                                                        carried);
     } else if (regular) {
         irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr, nullptr,
-                                                                                                 seg_len, nseg, 0u, pairs, carried);
+                                                                                                 seg_len, nseg, shift, pairs, carried);
     } else {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
             offsets, nseg + 1, kElems, tiles + 1, shift, starts, ends);
@@ -732,12 +732,13 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
     }
 }
 
+// out_align: the natural alignment of the output's elements.
 inline tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {
     if (seg_len == 0) return TCR_ERR_INVALID_ARG;
     if (n % seg_len != 0) return TCR_ERR_INVALID_ARG;
     if (n == 0) return TCR_OK;
     if (in == nullptr || out == nullptr) return TCR_ERR_INVALID_ARG;
-    if (!aligned(in, 16) || !aligned(out, out_align)) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 2) || !aligned(out, out_align)) return TCR_ERR_INVALID_ARG;
     if (n > kMaxElements) return TCR_ERR_UNSUPPORTED;
     return TCR_OK;
 }

@@ -196,7 +196,9 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         if constexpr (REGULAR) {
             // heads in [tb, tb + tile) are the multiples head_lo .. head_hi - 1 of seg_len; one thread divides for
             // the whole workgroup (64-bit divisions are long instruction sequences)
-            const uint64_t b = (uint64_t)t * kBlockTile, e = b + kBlockTile;
+            // (entry s lies on position s * seg_len + shift; the tile's range is taken relative to `shift`)
+            const uint64_t tile_b = (uint64_t)t * kBlockTile, tile_e = tile_b + kBlockTile;
+            const uint64_t b = tile_b > shift ? tile_b - shift : 0, e = tile_e - shift;
             const uint64_t q0 = b / seg_len, q1 = e / seg_len;
             s_bound[0] = q0 + (q0 * seg_len != b ? 1u : 0u);
             s_bound[1] = q1 + (q1 * seg_len != e ? 1u : 0u);
@@ -225,7 +227,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     const bool has_heads = head_lo < head_hi;
     if (has_heads) {
         for (uint64_t s = head_lo + threadIdx.x; s < head_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s] + shift) - tb;
+            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) + shift - tb;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
         }
         __syncthreads();
@@ -250,7 +252,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         }
     }
     // the part [valid_lo, valid_hi) of this wavefront's share lies in a segment (all of it, nearly always)
-    const uint64_t first = REGULAR ? 0 : offsets[0] + shift, last = REGULAR ? n : offsets[nseg] + shift;
+    const uint64_t first = (REGULAR ? 0 : offsets[0]) + shift, last = REGULAR ? n : offsets[nseg] + shift;
     const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
     const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
     const bool inside = valid_lo == 0u && valid_hi == kChunk && vector_stores != 0u;
@@ -373,9 +375,11 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     if constexpr (REGULAR) {
         // one thread divides for the whole workgroup (64-bit divisions are long instruction sequences)
         if (threadIdx.x == 0) {
-            const uint64_t te = tb + kBlockTile, entries = nseg + 1;
-            const uint64_t q0 = tb / seg_len, q1 = te / seg_len;
-            const uint64_t h0 = q0 + (q0 * seg_len != tb ? 1u : 0u), h1 = q1 + (q1 * seg_len != te ? 1u : 0u);
+            // entry s lies on position s * seg_len + shift: the tile's range relative to `shift` (for the first
+            // tile with shift > 0 the values in front are not used: it takes every entry from 0 on)
+            const uint64_t b = tb > shift ? tb - shift : 0, e = tb + kBlockTile - shift, entries = nseg + 1;
+            const uint64_t q0 = b / seg_len, q1 = e / seg_len;
+            const uint64_t h0 = q0 + (q0 * seg_len != b ? 1u : 0u), h1 = q1 + (q1 * seg_len != e ? 1u : 0u);
             s_bound[0] = h0;
             s_bound[1] = h1 < entries ? h1 : entries;
             s_bound[2] = q0 + 1;
@@ -400,7 +404,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     const bool has_entries = head_lo < end_hi;
     if (has_entries) {
         for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s] + shift) - tb;
+            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) + shift - tb;
             if (s - head_lo < (uint64_t)kPositions) s_position[s - head_lo] = (uint16_t)pos;
             if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
             if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
@@ -466,8 +470,8 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
                 end = s_position[i];
                 begin = i > 0 ? (uint32_t)s_position[i - 1] : 0u;
             } else {
-                end = (uint32_t)((REGULAR ? s * seg_len : offsets[s] + shift) - tb);
-                begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1] + shift) - tb);
+                end = (uint32_t)((REGULAR ? s * seg_len : offsets[s]) + shift - tb);
+                begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1]) + shift - tb);
             }
             const uint32_t at = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
             const bool empty = i > 0 && end == begin;

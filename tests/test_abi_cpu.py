@@ -53,11 +53,12 @@ def test_argument_validation_happens_before_any_device_work(lib):
     assert raw.tcr_segmented_scan(base, base + 2048, 65, 16, None) == inv
     assert raw.tcr_segmented_reduce(None, base, 64, 16, None) == inv             # null input
     assert raw.tcr_segmented_scan(base, None, 64, 16, None) == inv               # null output
-    assert raw.tcr_segmented_scan(base + 2, base + 2048, 64, 16, None) == inv    # misaligned input
-    assert raw.tcr_segmented_scan(base, base + 2048 + 4, 64, 16, None) == inv    # misaligned output
+    assert raw.tcr_segmented_scan(base + 1, base + 2048, 64, 16, None) == inv    # input not aligned to its elements
+    assert raw.tcr_segmented_scan(base, base + 2048 + 2, 64, 16, None) == inv    # output not aligned to its elements
     assert raw.tcr_segmented_reduce(base, base + 2048 + 2, 64, 16, None) == inv
     assert raw.tcr_reduce(base, None, 64, None) == inv
-    assert raw.tcr_scan(base + 8, base + 2048, 64, None) == inv
+    assert raw.tcr_scan(base + 3, base + 2048, 64, None) == inv
+    assert raw.tcr_segmented_scan_ex(base, base + 2048 + 1, 64, 16, 2, None) == inv      # binary16 output at an odd address
     # unknown flag bits of the scan variants
     assert raw.tcr_segmented_scan_ex(base, base + 2048, 64, 16, 4, None) == inv
     assert raw.tcr_scan_ex(base, base + 2048, 64, 8, None) == inv

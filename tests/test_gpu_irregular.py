@@ -283,3 +283,34 @@ def test_unaligned_arrays(tcr, oracle, in_shift, out_shift):
     got = buf.cpu().numpy().astype(np.float64)[out_shift:out_shift + n]
     assert np.array_equal(got[3:n - 9], oracle.irregular_scan(x, off)[3:n - 9])
     assert np.all(got[:3] == -3.0) and np.all(got[n - 9:] == -3.0)
+
+
+@pytest.mark.parametrize("seg", [1, 5, 16, 64, 100, 256, 1000, 4096, 32768, 40000, 1 << 17])
+@pytest.mark.parametrize("in_shift,out_shift", [(1, 1), (5, 2), (0, 3), (4, 4)])
+def test_regular_calls_behind_unaligned_pointers(tcr, oracle, seg, in_shift, out_shift):
+    # the regular entry points accept views that are not 16-byte aligned: the tiled kernels run them
+    nseg = max(3, (150000 // seg) | 1)
+    n = seg * nseg
+    base = workloads.make_input(n + 8, "int4", 80 + seg % 13)
+    x = base[in_shift:in_shift + n].copy()
+    xd = torch.from_numpy(base).cuda()[in_shift:in_shift + n]
+    red = tcr.segmented_reduce(xd, seg).cpu().numpy().astype(np.float64)
+    assert np.array_equal(red, oracle.segmented_reduce(x, seg))
+    if in_shift:
+        a, q = tcr.segmented_moments(xd, seg)
+        ra, rq = oracle.segmented_moments(x, seg)
+        assert np.array_equal(a.cpu().numpy().astype(np.float64), ra) and np.array_equal(q.cpu().numpy().astype(np.float64), rq)
+        assert float(tcr.reduce(xd).cpu()[0]) == oracle.reduce(x)
+    for flags in (0, 1, 3):
+        dtype = torch.float16 if flags & 2 else torch.float32
+        buf = torch.full((n + 16,), -3.0, dtype=dtype, device="cuda")
+        tcr.segmented_scan_ex(xd, seg, flags, out=buf[out_shift:out_shift + n])
+        ref = oracle.segmented_scan_exclusive(x, seg) if flags & 1 else oracle.segmented_scan(x, seg)
+        if flags & 2:
+            ref = ref.astype(np.float16).astype(np.float64)
+        got = buf.cpu().numpy().astype(np.float64)
+        assert np.array_equal(got[out_shift:out_shift + n], ref), f"flags={flags}"
+        assert np.all(got[:out_shift] == -3.0) and np.all(got[out_shift + n:] == -3.0), f"flags={flags}: wrote outside"
+    full = torch.full((n + 16,), -3.0, dtype=torch.float32, device="cuda")
+    tcr.scan(xd, out=full[out_shift:out_shift + n])
+    assert np.array_equal(full.cpu().numpy().astype(np.float64)[out_shift:out_shift + n], oracle.scan(x))

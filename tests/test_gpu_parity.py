@@ -354,8 +354,10 @@ def test_errors_on_device(tcr):
     out = torch.zeros(4096 + 8, dtype=torch.float32, device="cuda")
     raw = tcr.raw()
     assert raw.tcr_segmented_scan(x.data_ptr(), out.data_ptr(), 4096, 48, None) == tcr.ERR_INVALID_ARG   # 48 does not divide 4096
-    assert raw.tcr_segmented_scan(x.data_ptr() + 2, out.data_ptr(), 4096, 16, None) == tcr.ERR_INVALID_ARG
-    assert raw.tcr_scan(x.data_ptr(), out.data_ptr() + 4, 4096, None) == tcr.ERR_INVALID_ARG
+    assert raw.tcr_segmented_scan(x.data_ptr() + 1, out.data_ptr(), 4096, 16, None) == tcr.ERR_INVALID_ARG   # odd address
+    assert raw.tcr_scan(x.data_ptr(), out.data_ptr() + 2, 4096, None) == tcr.ERR_INVALID_ARG                 # floats at 2 mod 4
+    assert raw.tcr_segmented_scan(x.data_ptr() + 2, out.data_ptr(), 4096, 16, None) == tcr.OK                # natural alignment
+    assert raw.tcr_scan(x.data_ptr(), out.data_ptr() + 4, 4096, None) == tcr.OK
     with pytest.raises(TypeError):
         tcr.scan(x.float())
     with pytest.raises(tcr.TcrError):
