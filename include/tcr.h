@@ -178,7 +178,8 @@ tcr_status tcr_tuning_import(const char *text);
 /*
  * Name of the kernel the dispatcher would launch for (op, n, seg_len) under the current
  * variant settings; op is 0 = segmented_reduce, 1 = segmented_scan, 2 = reduce, 3 = scan,
- * 4 = irregular_reduce, 5 = irregular_scan (seg_len is ignored).  Arrays are taken to be 16-byte aligned.
+ * 4 = irregular_reduce, 5 = irregular_scan (seg_len is ignored).  The arrays are taken to be 16-byte aligned
+ * (regular calls on arrays that are not run irregular_reduce_kernel<regular> / irregular_scan_kernel<regular>).
  * Returns a static string ("" when nothing would be launched); never NULL.
  */
 const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);
