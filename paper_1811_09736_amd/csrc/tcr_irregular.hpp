@@ -252,7 +252,9 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         }
     }
     // the part [valid_lo, valid_hi) of this wavefront's share lies in a segment (all of it, nearly always)
-    const uint64_t first = (REGULAR ? 0 : offsets[0]) + shift, last = REGULAR ? n : offsets[nseg] + shift;
+    // (an offsets array that reaches beyond n is the caller's error; nothing is stored beyond n all the same)
+    const uint64_t first = (REGULAR ? 0 : offsets[0]) + shift;
+    const uint64_t last = REGULAR || offsets[nseg] + shift > n ? n : offsets[nseg] + shift;
     const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
     const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
     const bool inside = valid_lo == 0u && valid_hi == kChunk && vector_stores != 0u;
