@@ -143,3 +143,45 @@ def test_irregular_segments_beyond_2_31_elements(tcr, oracle, data):
         piece = x[off[s]:off[s + 1]]
         assert float(red[s].cpu()) == oracle.reduce(piece) if piece.size else float(red[s].cpu()) == 0.0
     tcr.check_device_flags()
+
+
+def test_beyond_2_32_elements(tcr):
+    """Element indices that no longer fit 32 bits (the closed forms above, no host oracle: 8 GiB of input)."""
+    if torch.cuda.get_device_properties(0).total_memory < 100 * (1 << 30):
+        pytest.skip("needs 100 GiB of device memory")
+    n = (1 << 32) + (1 << 20) + 24
+    xd = torch.from_numpy(np.tile(PATTERN, n // 7 + 1)[:n].copy()).cuda()
+    dev = xd.device
+    incl = torch.tensor(np.cumsum(PATTERN.astype(np.float64)), dtype=torch.float32, device=dev)
+
+    def before(start):                                       # sum of x[0 .. start)
+        return torch.where(start % 7 == 0, torch.zeros((), device=dev), incl[(start - 1) % 7])
+
+    for seg in (n, 1 << 20, 256, 3001):
+        m = (n // seg) * seg
+        print(f"  scan n={m} seg={seg} kernel={tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, m, seg)}", flush=True)
+        out = tcr.segmented_scan(xd[:m], seg)
+        for lo in range(0, m, CHUNK):
+            hi = min(lo + CHUNK, m)
+            want = _expected_scan_chunk(lo, hi, seg, dev)
+            if not torch.equal(out[lo:hi], want):
+                raise AssertionError(f"scan seg {seg}: first mismatch at {lo + int(torch.nonzero(out[lo:hi] != want)[0])}")
+        del out
+    for seg in (16, 100, 4096, 1 << 20, 3001):
+        m = (n // seg) * seg
+        print(f"  reduce n={m} seg={seg} kernel={tcr.kernel_name(tcr.OP_SEGMENTED_REDUCE, m, seg)}", flush=True)
+        k = torch.arange(0, m // seg, dtype=torch.int64, device=dev) * seg
+        assert torch.equal(tcr.segmented_reduce(xd[:m], seg), before(k + seg) - before(k)), f"reduce seg {seg}"
+    assert float(tcr.reduce(xd).cpu()[0]) == float(np.sum(PATTERN[: n % 7].astype(np.float64)))
+    rng = np.random.default_rng(3)
+    cuts = np.concatenate([rng.integers(0, n, 100000, endpoint=True), (1 << 32) - 3000 + np.arange(0, 6000, 5)])
+    od = torch.from_numpy(np.concatenate([[0], np.sort(cuts), [n]]).astype(np.int64)).cuda()
+    out = tcr.irregular_scan(xd, od)
+    for lo in range(0, n, CHUNK):
+        k = torch.arange(lo, min(lo + CHUNK, n), dtype=torch.int64, device=dev)
+        want = incl[k % 7] - before(od[torch.searchsorted(od, k, right=True) - 1])
+        assert torch.equal(out[lo:lo + CHUNK], want), f"irregular scan, chunk at {lo}"
+    del out
+    want = torch.where(od[1:] > od[:-1], before(od[1:]) - before(od[:-1]), torch.zeros((), device=dev))
+    assert torch.equal(tcr.irregular_reduce(xd, od), want)
+    tcr.check_device_flags()
