@@ -105,22 +105,31 @@ def _draw_offsets(rng, n):
 
 @pytest.mark.parametrize("block", range(6))
 def test_random_irregular_segments(tcr, oracle, block):
+    # offsets, scan flags and the misalignment of both arrays drawn at random
     rng = np.random.default_rng(5000 + block)
     for case in range(20):
         n = int(rng.integers(1, MAX_N)) if rng.integers(0, 4) else int(rng.integers(1, 70000))
         off = _draw_offsets(rng, n)
-        x = workloads.make_input(n, "int4", int(rng.integers(0, 1 << 30)))
-        what = f"block {block} case {case}: n={n} nseg={off.size - 1} cover=[{off[0]}, {off[-1]})"
+        in_shift, out_shift = (int(rng.integers(0, 8)), int(rng.integers(0, 4))) if rng.integers(0, 2) else (0, 0)
+        flags = int(rng.integers(0, 4))
+        base = workloads.make_input(n + 8, "int4", int(rng.integers(0, 1 << 30)))
+        x = base[in_shift:in_shift + n].copy()
+        what = (f"block {block} case {case}: n={n} nseg={off.size - 1} cover=[{off[0]}, {off[-1]}) "
+                f"shifts=({in_shift}, {out_shift}) flags={flags}")
         print("  " + what, flush=True)
-        xd, od = torch.from_numpy(x).cuda(), torch.from_numpy(off).cuda()
-        out = torch.full((n,), -7.0, dtype=torch.float32, device="cuda")
-        tcr.irregular_scan(xd, od, out=out)
+        xd, od = torch.from_numpy(base).cuda()[in_shift:in_shift + n], torch.from_numpy(off).cuda()
+        buf = torch.full((n + 8,), -7.0, dtype=torch.float16 if flags & 2 else torch.float32, device="cuda")
+        tcr.irregular_scan_ex(xd, od, flags, out=buf[out_shift:out_shift + n])
         red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
-        scan = out.cpu().numpy().astype(np.float64)
-        ref = oracle.irregular_scan(x, off)
+        got = buf.cpu().numpy().astype(np.float64)
+        scan = got[out_shift:out_shift + n]
+        ref = oracle.irregular_scan_exclusive(x, off) if flags & 1 else oracle.irregular_scan(x, off)
         assert np.max(np.abs(ref)) < 2 ** 24
+        if flags & 2:
+            ref = ref.astype(np.float16).astype(np.float64)
         lo, hi = int(off[0]), int(off[-1])
         assert np.array_equal(scan[lo:hi], ref[lo:hi]), what + " (scan)"
-        assert np.all(scan[:lo] == -7.0) and np.all(scan[hi:] == -7.0), what + " (outside)"
+        assert np.all(scan[:lo] == -7.0) and np.all(scan[hi:] == -7.0), what + " (outside the segments)"
+        assert np.all(got[:out_shift] == -7.0) and np.all(got[out_shift + n:] == -7.0), what + " (outside the array)"
         assert np.array_equal(red, oracle.irregular_reduce(x, off)), what + " (reduce)"
     tcr.check_device_flags()
