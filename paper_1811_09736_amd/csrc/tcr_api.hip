@@ -273,7 +273,7 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
             if (seg_len < kTiledReduceMax) return "irregular_reduce_kernel<regular>+irregular_groups_kernel+irregular_carry_kernel";
             return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";
         }
-        if (seg_len < kTiledScanMin) return "tiny_reduce_kernel";                    // seg_len 1: the conversion (plain scan)
+        if (is_pow2(seg_len) && seg_len <= 8) return "tiny_scan_kernel";            // (the plain scan; other modes: the tiles)
         if (chain_takes_any_length(seg_len)) return "scan_chain_kernel<mfma>";
         return segment_kernel_takes(seg_len) ? "scan_segment_kernel" : "irregular_scan_kernel<regular>";
     }

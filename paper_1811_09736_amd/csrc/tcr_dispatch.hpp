@@ -542,11 +542,20 @@ template <bool SCAN>
 inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
     const uint64_t nseg = n / seg_len;
     const bool excl = (flags & TCR_SCAN_EXCLUSIVE) != 0, f16 = (flags & TCR_OUT_F16) != 0;
-    // 1, 2, 4 or 8 elements (and the plain scan of single elements): whole segments inside a lane's 8 elements.
+    // 1, 2, 4 or 8 elements (scans: the plain binary32 inclusive one): whole segments inside a lane's 8 elements.
     // `out` is 16-byte aligned for scans; reductions need it for their 128-bit stores.
-    if (is_pow2(seg_len) && seg_len <= 8 && (SCAN ? (flags == 0 && seg_len == 1) : aligned(out, 16))) {
+    if (is_pow2(seg_len) && seg_len <= 8 && (SCAN ? flags == 0 : aligned(out, 16))) {
         const dim3 grid((unsigned)ceil_div(n, (uint64_t)kGenericThreads * 8)), block(kGenericThreads);
         float* o = static_cast<float*>(out);
+        if constexpr (SCAN) {
+            switch (seg_len) {
+                case 1: tiny_scan_kernel<0><<<grid, block, 0, s>>>(in, o, n); break;
+                case 2: tiny_scan_kernel<1><<<grid, block, 0, s>>>(in, o, n); break;
+                case 4: tiny_scan_kernel<2><<<grid, block, 0, s>>>(in, o, n); break;
+                default: tiny_scan_kernel<3><<<grid, block, 0, s>>>(in, o, n); break;
+            }
+            return check_launch("tiny_scan_kernel");
+        }
         switch (seg_len) {
             case 1: tiny_reduce_kernel<0><<<grid, block, 0, s>>>(in, o, n); break;
             case 2: tiny_reduce_kernel<1><<<grid, block, 0, s>>>(in, o, n); break;

@@ -79,6 +79,27 @@ __global__ __launch_bounds__(kGenericThreads) void tiny_reduce_kernel(const _Flo
     }
 }
 
+// The inclusive scan of segments of 1, 2, 4 or 8 elements: running sums inside a lane's 8 elements, restarted
+// every 1 << LOG2L of them (seg_len 1: the conversion again).
+template <int LOG2L>
+__global__ __launch_bounds__(kGenericThreads) void tiny_scan_kernel(const _Float16* __restrict__ in,
+                                                                    float* __restrict__ out, uint64_t n) {
+    static_assert(LOG2L >= 0 && LOG2L <= 3, "");
+    const uint64_t g = ((uint64_t)blockIdx.x * kGenericThreads + threadIdx.x) * 8;
+    if (g >= n) return;
+    const half8 x = load8_guarded(in, g, n);
+    float r[8];
+    float acc = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if ((e & ((1 << LOG2L) - 1)) == 0) acc = 0.0f;
+        acc += (float)x[e];
+        r[e] = acc;
+    }
+    store4_guarded(out, g, n, (float4v){r[0], r[1], r[2], r[3]});
+    store4_guarded(out, g + 4, n, (float4v){r[4], r[5], r[6], r[7]});
+}
+
 // ---------------------------------------------------------------------------------------- masked tiles
 // 8 inputs at element g (a multiple of 8), those outside [begin, end) read as zero.
 template <bool STREAM = false>

@@ -128,7 +128,8 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SCAN, 5000, 5000) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SCAN, 8192, 8192) == "scan_block_kernel<mfma,nocarry>"
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "irregular_scan_kernel<regular>"     # untuned lengths: fixed tiles
-    assert k(lib.OP_SEGMENTED_SCAN, 48000, 1) == "tiny_reduce_kernel"
+    assert k(lib.OP_SEGMENTED_SCAN, 48000, 1) == "tiny_scan_kernel"
+    assert k(lib.OP_SEGMENTED_SCAN, 48000, 8) == "tiny_scan_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6) == "generic_thread_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 48).startswith("irregular_reduce_kernel<regular>+")
