@@ -128,8 +128,8 @@ tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *
  * seg_len == n.  The sums of squares come from products of the data with itself on the matrix cores (exact
  * products, binary32 accumulation); both are exact for integer-valued inputs while the sums stay below 2^24.
  * Powers of two up to 512: a tile per wavefront like the reductions; other lengths from 8 to 999: the fixed tiles
- * of the irregular kernels, once per moment (they use the workspace); longer ones: one wavefront per segment
- * (per 65536-element piece of a long one).
+ * of the irregular kernels with both moments in one pass (they use the workspace); longer ones: one wavefront
+ * per segment (per 65536-element piece of a long one).
  */
 tcr_status tcr_segmented_moments(const void *in, float *sum, float *sumsq, uint64_t n, uint64_t seg_len, void *stream);
 

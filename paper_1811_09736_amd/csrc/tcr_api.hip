@@ -100,13 +100,9 @@ extern "C" tcr_status tcr_segmented_moments(const void* in, float* sum, float* s
     tcr_status st = validate(in, sum, n, seg_len, 4);
     if (st != TCR_OK || n == 0) return st;
     if (sumsq == nullptr || !aligned(sumsq, 4)) return TCR_ERR_INVALID_ARG;
-    if (!aligned(in, 16)) {                  // the tiled reduction, once per moment
-        const _Float16* x = static_cast<const _Float16*>(in);
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        st = launch_irregular_reduce(x, nullptr, sum, n, n / seg_len, seg_len, s, false);
-        if (st != TCR_OK) return st;
-        return launch_irregular_reduce(x, nullptr, sumsq, n, n / seg_len, seg_len, s, true);
-    }
+    if (!aligned(in, 16))                    // the tiled reduction with both moments as its two channels
+        return launch_irregular_reduce(static_cast<const _Float16*>(in), nullptr, sum, n, n / seg_len, seg_len,
+                                       static_cast<hipStream_t>(stream), kBoth, sumsq);
     return launch_moments(static_cast<const _Float16*>(in), sum, sumsq, n, seg_len, static_cast<hipStream_t>(stream));
 }
 

@@ -479,9 +479,9 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
 }
 
 // offsets == nullptr: regular segments of seg_len elements (no look-up tables).
-// square (regular segments only): sums of squares.
+// kind (regular segments only): kSum, kSquares, or kBoth with the sums of squares in out2.
 inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
-                                          uint64_t seg_len, hipStream_t s, bool square = false) {
+                                          uint64_t seg_len, hipStream_t s, int kind = kSum, float* out2 = nullptr) {
     constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
     const uint32_t shift = alignment_shift(in);
     in -= shift;
@@ -489,40 +489,42 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     const uint64_t tiles = irregular_tiles(false, n);
     const uint64_t groups = ceil_div(tiles, kWave);
     const bool regular = offsets == nullptr;
+    const unsigned ch = kind == kBoth ? 2u : 1u;
     Workspace* ws = nullptr;
     bool capturing = false;
     tcr_status st = get_workspace(s, &ws, &capturing);
     if (st != TCR_OK) return st;
-    st = ensure_partials(ws, s, 2 * irregular_words(false, n), capturing);
+    st = ensure_partials(ws, s, 2 * (irregular_words(false, n) + (ch - 1) * (tiles + groups)), capturing);
     if (st != TCR_OK) return st;
     uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
     uint64_t* ends = starts + (tiles + 1);
     uint64_t* carried = ends + (tiles + 1);
-    TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);
-    TilePair* group_pairs = pairs + tiles;
+    TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);              // ch * tiles
+    TilePair* group_pairs = pairs + ch * tiles;                                   // ch * groups
     const dim3 grid((unsigned)tiles), block(kIrregularReduceW * kWave);
-    if (regular && square) {
-        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr,
-                                                                                                       nullptr, seg_len, nseg, shift, pairs,
-                                                                                                       carried);
-    } else if (regular) {
-        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true><<<grid, block, 0, s>>>(in, nullptr, out, n, nullptr, nullptr,
-                                                                                                 seg_len, nseg, shift, pairs, carried);
+    if (regular) {
+        const auto launch = [&](auto kind_tag) {
+            irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true, decltype(kind_tag)::value><<<grid, block, 0, s>>>(
+                in, nullptr, out, out2, n, nullptr, nullptr, seg_len, nseg, shift, pairs, carried);
+        };
+        if (kind == kBoth) launch(std::integral_constant<int, kBoth>());
+        else if (kind == kSquares) launch(std::integral_constant<int, kSquares>());
+        else launch(std::integral_constant<int, kSum>());
     } else {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
             offsets, nseg + 1, kElems, tiles + 1, shift, starts, ends);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
-        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(in, offsets, out, n, starts, ends, 0,
-                                                                                                  nseg, shift, pairs, carried);
+        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(in, offsets, out, nullptr, n, starts,
+                                                                                                  ends, 0, nseg, shift, pairs, carried);
     }
     st = check_launch("irregular_reduce_kernel");
     if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it
-    irregular_groups_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, tiles, group_pairs);
+    const dim3 carry_grid((unsigned)ceil_div(groups, kCarryWaves), ch);
+    irregular_groups_kernel<<<carry_grid, dim3(kCarryWaves * kWave), 0, s>>>(pairs, tiles, group_pairs);
     st = check_launch("irregular_groups_kernel");
     if (st != TCR_OK) return st;
-    irregular_carry_kernel<<<dim3((unsigned)ceil_div(groups, kCarryWaves)), dim3(kCarryWaves * kWave), 0, s>>>(pairs, group_pairs, carried,
-                                                                                                            tiles, out);
+    irregular_carry_kernel<<<carry_grid, dim3(kCarryWaves * kWave), 0, s>>>(pairs, group_pairs, carried, tiles, out, out2);
     return check_launch("irregular_carry_kernel");
 }
 
@@ -634,10 +636,8 @@ inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, u
         return check_launch("moments_small_kernel");
     }
     if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax) {
-        // fixed tiles with the segment starts marked, once for each moment
-        const tcr_status st = launch_irregular_reduce(in, nullptr, sum, n, nseg, seg_len, s, false);
-        if (st != TCR_OK) return st;
-        return launch_irregular_reduce(in, nullptr, sumsq, n, nseg, seg_len, s, true);
+        // fixed tiles with the segment starts marked, both moments as two channels of one pass
+        return launch_irregular_reduce(in, nullptr, sum, n, nseg, seg_len, s, kBoth, sumsq);
     }
     if (seg_len <= kGenericThreadMax) {
         generic_moments_kernel<<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(

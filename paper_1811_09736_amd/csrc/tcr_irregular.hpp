@@ -45,18 +45,22 @@ __device__ __forceinline__ uint32_t wave_shr1_u32(uint32_t x) {
 }
 
 // One step of the segmented scan: the pair CTRL places to the left (or the identity (0, 0) where the
-// DPP pattern delivers nothing) is combined in front of this lane's pair.
-template <int CTRL, int ROW_MASK, bool BOUND>
-__device__ __forceinline__ void seg_combine_left(uint32_t& f, float& v) {
+// DPP pattern delivers nothing) is combined in front of this lane's pair.  CH values may share one flag.
+template <int CTRL, int ROW_MASK, bool BOUND, int CH>
+__device__ __forceinline__ void seg_combine_left(uint32_t& f, float (&v)[CH]) {
     const uint32_t fl = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)f, CTRL, ROW_MASK, 0xf, BOUND);
-    const float vl = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, BOUND));
-    v = f ? v : v + vl;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const float vl = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[c]), CTRL, ROW_MASK, 0xf, BOUND));
+        v[c] = f ? v[c] : v[c] + vl;
+    }
     f |= fl;
 }
 
 // Inclusive segmented scan over the 64 lanes: on return (f, v) of lane l is the combination of the
 // pairs of lanes 0 .. l.
-__device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float& v) {
+template <int CH>
+__device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float (&v)[CH]) {
     seg_combine_left<0x111, 0xf, true>(f, v);
     seg_combine_left<0x112, 0xf, true>(f, v);
     seg_combine_left<0x114, 0xf, true>(f, v);
@@ -64,21 +68,90 @@ __device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float& v) {
     seg_combine_left<0x142, 0xa, false>(f, v);     // lane 15 of rows 0 and 2 -> rows 1 and 3
     seg_combine_left<0x143, 0xc, false>(f, v);     // lane 31 -> rows 2 and 3
 }
-
-// The value an element contributes: itself, or its square (exact in binary32) for the second moment.
-template <bool SQUARE>
-__device__ __forceinline__ float term(_Float16 h) {
-    const float v = (float)h;
-    return SQUARE ? v * v : v;
+__device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float& v) {
+    float one[1] = {v};
+    wave_seg_scan_inclusive<1>(f, one);
+    v = one[0];
 }
 
-// Sum of a lane's 8 elements behind its last segment start (all 8 if it has none).
-template <bool SQUARE>
-__device__ __forceinline__ float lane_tail_sum(half8 x, uint32_t heads) {
-    float q = 0.0f;
+// What is summed (KIND): 0 the elements, 1 their squares (exact in binary32), 2 both at once, as two
+// channels that share the segment starts.
+constexpr int kSum = 0, kSquares = 1, kBoth = 2;
+template <int KIND>
+constexpr int channels() { return KIND == kBoth ? 2 : 1; }
+template <int KIND, int C>
+__device__ __forceinline__ float term(_Float16 h) {
+    const float v = (float)h;
+    return (KIND == kSquares || (KIND == kBoth && C == 1)) ? v * v : v;
+}
+
+// Per channel, the sum of a lane's 8 elements behind its last segment start (all 8 if it has none).
+template <int KIND>
+__device__ __forceinline__ void lane_tail_sum(half8 x, uint32_t heads, float (&q)[channels<KIND>()]) {
+    constexpr int CH = channels<KIND>();
 #pragma unroll
-    for (int e = 0; e < 8; ++e) q = ((heads >> e) & 1u ? 0.0f : q) + term<SQUARE>(x[e]);
-    return q;
+    for (int c = 0; c < CH; ++c) q[c] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const bool head = (heads >> e) & 1u;
+        q[0] = (head ? 0.0f : q[0]) + term<KIND, 0>(x[e]);
+        if constexpr (CH == 2) q[1] = (head ? 0.0f : q[1]) + term<KIND, 1>(x[e]);
+    }
+}
+
+// Per sub-tile: the pair of every lane's predecessors and the sub-tile's own pair, chained over the
+// wavefront's U sub-tiles.  `run` / `chunk_flag` leave as the pair of the wavefront's whole share.
+template <int U, int CH = 1>
+struct WaveShare {
+    uint32_t heads[U];            // bits 0..7: heads among the lane's 8 elements; bit 8: a head in a lane in front
+    uint32_t seen_before[U];
+    float lane_value[CH][U], before[CH][U];
+    float run[CH];
+    uint32_t chunk_flag;
+};
+
+template <int U, int KIND = kSum>
+__device__ __forceinline__ void wave_share_scan(WaveShare<U, channels<KIND>()>& w, const half8 (&x)[U], const uint8_t* head_bytes,
+                                                bool has_heads, int lane) {
+    constexpr int CH = channels<KIND>();
+#pragma unroll
+    for (int c = 0; c < CH; ++c) w.run[c] = 0.0f;
+    w.chunk_flag = 0u;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        w.heads[u] = has_heads ? (uint32_t)head_bytes[(kTile / 8) * u + lane] : 0u;
+        uint32_t f = w.heads[u] != 0u ? 1u : 0u;
+        float v[CH];
+        lane_tail_sum<KIND>(x[u], w.heads[u], v);
+        wave_seg_scan_inclusive<CH>(f, v);
+        w.heads[u] |= wave_shr1_u32(f) << 8;
+        const uint32_t sub_flag = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
+        w.seen_before[u] = w.chunk_flag;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            w.lane_value[c][u] = wave_shr1(v[c]);
+            const float sub_value = read_lane(v[c], 63);
+            w.before[c][u] = w.run[c];
+            w.run[c] = sub_flag ? sub_value : w.run[c] + sub_value;
+        }
+        w.chunk_flag |= sub_flag;
+    }
+}
+
+// Running sums (channel C) of a lane's 8 elements of sub-tile u, given the sum `ext` that reaches the
+// wavefront's share from in front of it.
+template <int U, int EXCL = 0, int KIND = kSum, int C = 0>
+__device__ __forceinline__ void wave_share_finish(const WaveShare<U, channels<KIND>()>& w, const half8 (&x)[U], int u, float ext,
+                                                  float (&p)[8]) {
+    const float into_sub = w.seen_before[u] ? w.before[C][u] : w.before[C][u] + ext;
+    float q = (w.heads[u] >> 8) ? w.lane_value[C][u] : w.lane_value[C][u] + into_sub;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        q = (w.heads[u] >> e) & 1u ? 0.0f : q;
+        if constexpr (EXCL) p[e] = q;
+        q += term<KIND, C>(x[u][e]);
+        if constexpr (!EXCL) p[e] = q;
+    }
 }
 
 // starts_below[i] = number of entries of offsets[0 .. count) below i * tile_elems, i = 0 .. boundaries - 1;
@@ -108,54 +181,6 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
         if (c < kWave) break;
     }
     if (lane == 0) ends_below[i] = below + on;
-}
-
-// Per sub-tile: the pair of every lane's predecessors and the sub-tile's own pair, chained over the
-// wavefront's U sub-tiles.  `run` / `chunk_flag` leave as the pair of the wavefront's whole share.
-template <int U>
-struct WaveShare {
-    uint32_t heads[U];            // bits 0..7: heads among the lane's 8 elements; bit 8: a head in a lane in front
-    uint32_t seen_before[U];
-    float lane_value[U], before[U];
-    float run;
-    uint32_t chunk_flag;
-};
-
-template <int U, bool SQUARE = false>
-__device__ __forceinline__ void wave_share_scan(WaveShare<U>& w, const half8 (&x)[U], const uint8_t* head_bytes, bool has_heads,
-                                                int lane) {
-    w.run = 0.0f;
-    w.chunk_flag = 0u;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        w.heads[u] = has_heads ? (uint32_t)head_bytes[(kTile / 8) * u + lane] : 0u;
-        uint32_t f = w.heads[u] != 0u ? 1u : 0u;
-        float v = lane_tail_sum<SQUARE>(x[u], w.heads[u]);
-        wave_seg_scan_inclusive(f, v);
-        w.heads[u] |= wave_shr1_u32(f) << 8;
-        w.lane_value[u] = wave_shr1(v);
-        const uint32_t sub_flag = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
-        const float sub_value = read_lane(v, 63);
-        w.before[u] = w.run;
-        w.seen_before[u] = w.chunk_flag;
-        w.run = sub_flag ? sub_value : w.run + sub_value;
-        w.chunk_flag |= sub_flag;
-    }
-}
-
-// Running sums of a lane's 8 elements of sub-tile u, given the sum `ext` that reaches the wavefront's share
-// from in front of it.
-template <int U, int EXCL = 0, bool SQUARE = false>
-__device__ __forceinline__ void wave_share_finish(const WaveShare<U>& w, const half8 (&x)[U], int u, float ext, float (&p)[8]) {
-    const float into_sub = w.seen_before[u] ? w.before[u] : w.before[u] + ext;
-    float q = (w.heads[u] >> 8) ? w.lane_value[u] : w.lane_value[u] + into_sub;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        q = (w.heads[u] >> e) & 1u ? 0.0f : q;
-        if constexpr (EXCL) p[e] = q;
-        q += term<SQUARE>(x[u][e]);
-        if constexpr (!EXCL) p[e] = q;
-    }
 }
 
 // Tile geometry of both kernels: WAVES wavefronts, each with U consecutive 512-element sub-tiles; a lane holds
@@ -236,7 +261,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     WaveShare<U> w;
     wave_share_scan<U>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
     if (lane == 0) {
-        s_wave_value[wave] = w.run;
+        s_wave_value[wave] = w.run[0];
         s_wave_flag[wave] = w.chunk_flag;
     }
     __syncthreads();
@@ -332,11 +357,13 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
 constexpr uint32_t kPositions = 4096;
 // REGULAR: entry s is s * seg_len, s = 0 .. nseg, instead of offsets[s] (offsets and the tables are not read).
 // shift: as for irregular_scan_kernel (`in` points that many elements in front of the caller's array).
-// SQUARE: the sums are of the squares of the elements (second moments).
-template <int U, int WAVES, bool REGULAR, bool SQUARE = false>
+// KIND: sums of the elements, of their squares, or both (out2 and the pairs of the second channel, which
+// follow the first channel's `tiles` pairs, are used for kBoth only).
+template <int U, int WAVES, bool REGULAR, int KIND = kSum>
 __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _Float16* __restrict__ in,
                                                                          const uint64_t* __restrict__ offsets,
-                                                                         float* __restrict__ out, uint64_t n,
+                                                                         float* __restrict__ out, float* __restrict__ out2,
+                                                                         uint64_t n,
                                                                          const uint64_t* __restrict__ starts_below,
                                                                          const uint64_t* __restrict__ ends_below,
                                                                          uint64_t seg_len, uint64_t nseg, uint32_t shift,
@@ -351,9 +378,10 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     __shared__ uint16_t s_position[kPositions];   // entry head_lo + i lies on element tb + s_position[i]
     __shared__ uint64_t s_bound[4];
     static_assert(kBlockTile <= 65535u, "positions are kept in 16 bits");
-    __shared__ float s_wave_value[WAVES];
+    constexpr int CH = channels<KIND>();
+    __shared__ float s_wave_value[CH][WAVES];
     __shared__ uint32_t s_wave_flag[WAVES];
-    __shared__ __attribute__((aligned(16))) float s_stage[WAVES][kTile];
+    __shared__ __attribute__((aligned(16))) float s_stage[CH][WAVES][kTile];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -416,33 +444,41 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     }
     const bool has_heads = head_lo < head_hi;
 
-    WaveShare<U> w;
-    wave_share_scan<U, SQUARE>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
+    WaveShare<U, CH> w;
+    wave_share_scan<U, KIND>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
     if (lane == 0) {
-        s_wave_value[wave] = w.run;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) s_wave_value[c][wave] = w.run[c];
         s_wave_flag[wave] = w.chunk_flag;
     }
     __syncthreads();
 
     if (wave == 0 && lane == 0) {
-        float total = 0.0f;
+        float total[CH];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) total[c] = 0.0f;
         uint32_t closed = 0u;
         for (int v = WAVES - 1; v >= 0; --v) {
-            total += s_wave_value[v];
+#pragma unroll
+            for (int c = 0; c < CH; ++c) total[c] += s_wave_value[c][v];
             if (s_wave_flag[v]) {
                 closed = 1u;
                 break;
             }
         }
-        pairs[tile] = TilePair{total, closed};
+#pragma unroll
+        for (int c = 0; c < CH; ++c) pairs[(uint64_t)c * gridDim.x + tile] = TilePair{total[c], closed};
         // the first segment end of the tile closes a segment begun earlier unless an entry sits on tb itself
         carried[tile] = (end_lo < end_hi && end_lo == head_lo && end_lo >= 1) ? end_lo - 1 : kNoSegment;
     }
     if (end_lo == end_hi) return;             // no segment ends here: nothing to write
 
-    float ext = 0.0f;                         // carry from the wavefronts in front, inside this tile only
+    float ext[CH];                            // carry from the wavefronts in front, inside this tile only
+#pragma unroll
+    for (int c = 0; c < CH; ++c) ext[c] = 0.0f;
     for (int v = wave - 1; v >= 0; --v) {
-        ext += s_wave_value[v];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) ext[c] += s_wave_value[c][v];
         if (s_wave_flag[v]) break;
     }
     // entries that end a segment in each of this wavefront's sub-tiles
@@ -454,11 +490,20 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
         const uint32_t count = (uint32_t)__builtin_amdgcn_readlane((int)mine, sub);
         if (count == 0u) continue;
         const uint64_t entry0 = end_lo + (uint64_t)((uint32_t)__builtin_amdgcn_readlane((int)upto, sub) - count);
-        float p[8];
-        wave_share_finish<U, 0, SQUARE>(w, x, u, ext, p);
-        float4v* dst = reinterpret_cast<float4v*>(&s_stage[wave][8 * lane]);
-        dst[0] = (float4v){p[0], p[1], p[2], p[3]};
-        dst[1] = (float4v){p[4], p[5], p[6], p[7]};
+        {
+            float p[8];
+            wave_share_finish<U, 0, KIND, 0>(w, x, u, ext[0], p);
+            float4v* dst = reinterpret_cast<float4v*>(&s_stage[0][wave][8 * lane]);
+            dst[0] = (float4v){p[0], p[1], p[2], p[3]};
+            dst[1] = (float4v){p[4], p[5], p[6], p[7]};
+        }
+        if constexpr (CH == 2) {
+            float p[8];
+            wave_share_finish<U, 0, KIND, 1>(w, x, u, ext[CH - 1], p);
+            float4v* dst = reinterpret_cast<float4v*>(&s_stage[CH - 1][wave][8 * lane]);
+            dst[0] = (float4v){p[0], p[1], p[2], p[3]};
+            dst[1] = (float4v){p[4], p[5], p[6], p[7]};
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -476,8 +521,9 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
                 begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1]) + shift - tb);
             }
             const uint32_t at = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
-            const bool empty = i > 0 && end == begin;
-            out[s - 1] = (!empty && at < (uint32_t)kTile) ? s_stage[wave][at] : 0.0f;
+            const bool take = !(i > 0 && end == begin) && at < (uint32_t)kTile;     // not an empty segment
+            out[s - 1] = take ? s_stage[0][wave][at] : 0.0f;
+            if constexpr (CH == 2) out2[s - 1] = take ? s_stage[CH - 1][wave][at] : 0.0f;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -485,7 +531,8 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     }
 }
 
-// The pairs of 64 consecutive tiles combined into one (one wavefront per group).
+// The pairs of 64 consecutive tiles combined into one (one wavefront per group).  blockIdx.y is the channel:
+// channel c has its `tiles` pairs behind those of channel c - 1, likewise its groups.
 constexpr int kCarryWaves = 4;
 __global__ __launch_bounds__(kCarryWaves * kWave) void irregular_groups_kernel(const TilePair* __restrict__ pairs,
                                                                                uint64_t tiles,
@@ -493,6 +540,8 @@ __global__ __launch_bounds__(kCarryWaves * kWave) void irregular_groups_kernel(c
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t g = (uint64_t)blockIdx.x * kCarryWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (g * kWave >= tiles) return;
+    pairs += (uint64_t)blockIdx.y * tiles;
+    groups += (uint64_t)blockIdx.y * ((tiles + kWave - 1) / kWave);
     const uint64_t t = g * kWave + (uint64_t)lane;
     TilePair mine = {0.0f, 0u};
     if (t < tiles) mine = pairs[t];
@@ -502,14 +551,18 @@ __global__ __launch_bounds__(kCarryWaves * kWave) void irregular_groups_kernel(c
 
 // Adds to the one carried result of every tile the sum that reaches the tile from the tiles in front of
 // it: the groups back to the nearest one with a head, then the tiles of its own group.  Plain loads, fixed
-// order: the results do not vary from run to run.
+// order: the results do not vary from run to run.  blockIdx.y is the channel (results: out, then out2).
 __global__ __launch_bounds__(kCarryWaves * kWave) void irregular_carry_kernel(const TilePair* __restrict__ pairs,
                                                                               const TilePair* __restrict__ groups,
                                                                               const uint64_t* __restrict__ carried,
-                                                                              uint64_t tiles, float* __restrict__ out) {
+                                                                              uint64_t tiles, float* __restrict__ out,
+                                                                              float* __restrict__ out2) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t g = (uint64_t)blockIdx.x * kCarryWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (g * kWave >= tiles) return;
+    pairs += (uint64_t)blockIdx.y * tiles;
+    groups += (uint64_t)blockIdx.y * ((tiles + kWave - 1) / kWave);
+    if (blockIdx.y) out = out2;
     const uint64_t t = g * kWave + (uint64_t)lane;
     const uint64_t seg = t < tiles ? carried[t] : kNoSegment;
     if (__ballot(seg != kNoSegment) == 0ull) return;

@@ -157,7 +157,9 @@ __global__ __launch_bounds__(WAVES * kWave) void moments_small_kernel(const _Flo
     }
     const int slot = id.lane;                            // this lane stores results `slot` of the wavefront
     const int slot_tile = slot / RT, slot_seg = slot % RT;
-    const int src = LOG2L == 4 ? (slot_seg >> 1) + 32 * (slot_seg & 1) : ((slot_seg + 1) << (LOG2L - 5)) - 1;
+    int src;                                             // lane that holds segment slot_seg of a tile
+    if constexpr (LOG2L == 4) src = (slot_seg >> 1) + 32 * (slot_seg & 1);
+    else src = ((slot_seg + 1) << (LOG2L - 5)) - 1;
     float a = 0.0f, b = 0.0f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {

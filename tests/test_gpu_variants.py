@@ -194,7 +194,7 @@ def test_other_segment_lengths_take_every_flag(tcr, oracle, seg, flags):
 
 # ------------------------------------------------------------------ first two moments
 
-@pytest.mark.parametrize("seg", [1, 5, 8, 12, 16, 32, 64, 96, 97, 128, 200, 256, 300, 512, 999, 1000, 4096, 3001, 1 << 16, (1 << 17) + 8, 3 << 18, 1 << 21])
+@pytest.mark.parametrize("seg", [1, 5, 8, 12, 16, 32, 49, 64, 96, 97, 128, 196, 200, 256, 300, 512, 784, 999, 1000, 3136, 4096, 3001, 1 << 16, (1 << 17) + 8, 3 << 18, 1 << 21])
 def test_segmented_moments(tcr, oracle, seg):
     nseg = max(2, (1 << 21) // seg) | 1 if seg < (1 << 20) else 2
     n = seg * nseg
