@@ -191,6 +191,9 @@ def main() -> int:
                                  (lambda e=e: tcr.segmented_scan_ex(x, 1 << e, tcr.OUT_F16, out=out_h)), n, (2 * n, 2 * n)))
     variant_rows.append(("segmented_moments seg_len=2^12 (sum and sum of squares, X.X^T diagonal on the matrix cores)",
                          lambda: tcr.segmented_moments(x, 1 << 12), n, (2 * n, 8 * (n >> 12))))
+    n196 = (n // 196) * 196
+    variant_rows.append(("segmented_moments seg_len=196 (14x14 feature maps: two channels of the tiled reduction)",
+                         lambda: tcr.segmented_moments(x[:n196], 196), n196, (2 * n196, 8 * (n196 // 196))))
     if args.formulation == "mfma":
         variant_rows.append(("segmented_scan_ex seg_len=2^12 exclusive",
                              lambda: tcr.segmented_scan_ex(x, 1 << 12, tcr.SCAN_EXCLUSIVE, out=out_scan), n, (2 * n, 4 * n)))
