@@ -132,6 +132,10 @@ tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *
  * per segment (per 65536-element piece of a long one).
  */
 tcr_status tcr_segmented_moments(const void *in, float *sum, float *sumsq, uint64_t n, uint64_t seg_len, void *stream);
+/* The same for irregular segments (offsets, n, nseg as for tcr_irregular_reduce; empty segments give 0 and 0):
+ * both moments in one pass over the fixed tiles. */
+tcr_status tcr_irregular_moments(const void *in, const uint64_t *offsets, float *sum, float *sumsq, uint64_t n, uint64_t nseg,
+                                 void *stream);
 
 /*
  * Full reduction (device level, Section 4): out[0] = sum of all n inputs (0 for n == 0).

@@ -48,6 +48,7 @@ def _bind(path: str):
         ("oracle_irregular_reduce", [u16p, u64p, f64p, u64]),
         ("oracle_irregular_scan", [u16p, u64p, f64p, u64]),
         ("oracle_irregular_scan_exclusive", [u16p, u64p, f64p, u64]),
+        ("oracle_irregular_moments", [u16p, u64p, f64p, f64p, u64]),
         ("oracle_reduce", [u16p, f64p, u64]),
         ("oracle_scan", [u16p, f64p, u64]),
         ("oracle_segmented_scan_at", [u16p, u64, u64, u64p, u64, f64p]),
@@ -115,6 +116,18 @@ class Oracle:
         q = np.empty(n // seg_len, dtype=np.float64)
         if self._lib.oracle_segmented_moments(_in_ptr(x), _out_ptr(a), _out_ptr(q), n, seg_len):
             raise ValueError("oracle_segmented_moments rejected its arguments")
+        return a, q
+
+    def irregular_moments(self, x: np.ndarray, offsets):
+        """(sum, sum of squares) of every segment [offsets[s], offsets[s+1])."""
+        off = np.ascontiguousarray(offsets, dtype=np.uint64)
+        if off.ndim != 1 or off.size < 1 or (off.size > 1 and int(off.max()) > x.shape[0]):
+            raise ValueError("offsets must hold nseg + 1 indices into x")
+        a = np.zeros(off.size - 1, dtype=np.float64)
+        q = np.zeros(off.size - 1, dtype=np.float64)
+        if self._lib.oracle_irregular_moments(_in_ptr(x), off.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+                                              _out_ptr(a), _out_ptr(q), off.size - 1):
+            raise ValueError("oracle_irregular_moments rejected its arguments")
         return a, q
 
     def irregular_reduce(self, x: np.ndarray, offsets) -> np.ndarray:
@@ -222,3 +235,7 @@ def segmented_scan_at(x, seg_len, idx):
 
 def segmented_moments(x, seg_len):
     return _get().segmented_moments(x, seg_len)
+
+
+def irregular_moments(x, offsets):
+    return _get().irregular_moments(x, offsets)

@@ -177,6 +177,24 @@ int oracle_segmented_moments(const uint16_t *in, double *sum, double *sumsq, uin
     return 0;
 }
 
+/* The two moments of irregular segments: segment s is in[offsets[s] .. offsets[s+1]); empty segments give 0, 0. */
+int oracle_irregular_moments(const uint16_t *in, const uint64_t *offsets, double *sum, double *sumsq, uint64_t nseg)
+{
+    if (nseg > 0 && (in == NULL || offsets == NULL || sum == NULL || sumsq == NULL)) return 1;
+    for (uint64_t s = 0; s < nseg; ++s) {
+        if (offsets[s + 1] < offsets[s]) return 1;
+        double a = 0.0, q = 0.0;
+        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {
+            const double v = oracle_half_to_double(in[k]);
+            a += v;
+            q += v * v;
+        }
+        sum[s] = a;
+        sumsq[s] = q;
+    }
+    return 0;
+}
+
 /* Full (unsegmented) forms: one segment that spans the whole input. */
 int oracle_reduce(const uint16_t *in, double *out, uint64_t n)
 {

@@ -22,7 +22,7 @@ SCAN_EXCLUSIVE, OUT_F16 = 1, 2
 
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
-    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
+    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_irregular_moments", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
     "tcr_workspace_bytes", "tcr_set_workspace", "tcr_segmented_moments",
     "tcr_set_variant",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
@@ -55,6 +55,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_irregular_scan.argtypes = [vp, vp, fp, u64, u64, vp]
     lib.tcr_irregular_scan_ex.argtypes = [vp, vp, vp, u64, u64, ctypes.c_uint32, vp]
     lib.tcr_irregular_scan_ex.restype = ctypes.c_int
+    lib.tcr_irregular_moments.argtypes = [vp, vp, fp, fp, u64, u64, vp]
+    lib.tcr_irregular_moments.restype = ctypes.c_int
     lib.tcr_irregular_reduce.restype = ctypes.c_int
     lib.tcr_irregular_scan.restype = ctypes.c_int
     lib.tcr_reduce.argtypes = [vp, fp, u64, vp]
@@ -214,6 +216,21 @@ def irregular_scan(x: torch.Tensor, offsets: torch.Tensor, out: Optional[torch.T
     if st != OK:
         raise TcrError(st, "tcr_irregular_scan")
     return out
+
+
+def irregular_moments(x: torch.Tensor, offsets: torch.Tensor, stream: Optional[torch.cuda.Stream] = None):
+    """tcr_irregular_moments: (sum, sum of squares) of x[offsets[s]:offsets[s+1]] for every s."""
+    if not (x.is_cuda and x.dtype == torch.float16 and x.dim() == 1 and x.is_contiguous()):
+        raise TypeError("input must be a contiguous 1-D float16 CUDA tensor")
+    nseg = _check_offsets(x, offsets)
+    a = torch.empty(nseg, dtype=torch.float32, device=x.device)
+    q = torch.empty(nseg, dtype=torch.float32, device=x.device)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_irregular_moments(x.data_ptr(), offsets.data_ptr(), a.data_ptr(), q.data_ptr(), x.numel(), nseg,
+                                        _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_irregular_moments")
+    return a, q
 
 
 def irregular_scan_ex(x: torch.Tensor, offsets: torch.Tensor, flags: int, out: Optional[torch.Tensor] = None,

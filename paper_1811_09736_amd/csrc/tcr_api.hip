@@ -74,6 +74,21 @@ extern "C" tcr_status tcr_irregular_reduce(const void* in, const uint64_t* offse
     return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, out, n, nseg, 0, s);
 }
 
+extern "C" tcr_status tcr_irregular_moments(const void* in, const uint64_t* offsets, float* sum, float* sumsq, uint64_t n,
+                                            uint64_t nseg, void* stream) {
+    if (nseg == 0) return TCR_OK;
+    const tcr_status st = validate_irregular(in, offsets, sum, n, nseg);
+    if (st != TCR_OK) return st;
+    if (sumsq == nullptr || !aligned(sumsq, 4) || sumsq == sum) return TCR_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n == 0) {                            // every segment is empty
+        fill_zero_kernel<<<dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, s>>>(sum, nseg);
+        fill_zero_kernel<<<dim3((unsigned)ceil_div(nseg, 256)), dim3(256), 0, s>>>(sumsq, nseg);
+        return check_launch("fill_zero_kernel");
+    }
+    return launch_irregular_reduce(static_cast<const _Float16*>(in), offsets, sum, n, nseg, 0, s, kBoth, sumsq);
+}
+
 extern "C" tcr_status tcr_irregular_scan_ex(const void* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
                                             uint32_t flags, void* stream) {
     if ((flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) != 0) return TCR_ERR_INVALID_ARG;

@@ -479,7 +479,7 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
 }
 
 // offsets == nullptr: regular segments of seg_len elements (no look-up tables).
-// kind (regular segments only): kSum, kSquares, or kBoth with the sums of squares in out2.
+// kind: kSum, kSquares (regular segments only), or kBoth with the sums of squares in out2.
 inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
                                           uint64_t seg_len, hipStream_t s, int kind = kSum, float* out2 = nullptr) {
     constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
@@ -515,8 +515,12 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
             offsets, nseg + 1, kElems, tiles + 1, shift, starts, ends);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
-        irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(in, offsets, out, nullptr, n, starts,
-                                                                                                  ends, 0, nseg, shift, pairs, carried);
+        if (kind == kBoth)
+            irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false, kBoth><<<grid, block, 0, s>>>(
+                in, offsets, out, out2, n, starts, ends, 0, nseg, shift, pairs, carried);
+        else
+            irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(
+                in, offsets, out, nullptr, n, starts, ends, 0, nseg, shift, pairs, carried);
     }
     st = check_launch("irregular_reduce_kernel");
     if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it

@@ -314,3 +314,23 @@ def test_regular_calls_behind_unaligned_pointers(tcr, oracle, seg, in_shift, out
     full = torch.full((n + 16,), -3.0, dtype=torch.float32, device="cuda")
     tcr.scan(xd, out=full[out_shift:out_shift + n])
     assert np.array_equal(full.cpu().numpy().astype(np.float64)[out_shift:out_shift + n], oracle.scan(x))
+
+
+@pytest.mark.parametrize("recipe", ["uniform1", "uniform16", "uniform300", "lognormal256", "few5"])
+@pytest.mark.parametrize("in_shift", [0, 3])
+def test_irregular_moments(tcr, oracle, recipe, in_shift):
+    n = 4 * SCAN_TILE + 200
+    base = workloads.make_input(n + 8, "int1", 90)                 # |x| <= 1: the sums of squares stay below 2^24
+    x = base[in_shift:in_shift + n].copy()
+    xd = torch.from_numpy(base).cuda()[in_shift:in_shift + n]
+    off = workloads.make_offsets(n - 50, recipe, 9).view(np.int64) + 20
+    od = torch.from_numpy(off).cuda()
+    a, q = tcr.irregular_moments(xd, od)
+    ra, rq = oracle.irregular_moments(x, off)
+    assert np.array_equal(a.cpu().numpy().astype(np.float64), ra) and np.array_equal(q.cpu().numpy().astype(np.float64), rq)
+    assert torch.equal(a, tcr.irregular_reduce(xd, od))
+    y = workloads.make_input(n, "normal", 7)
+    a, q = tcr.irregular_moments(torch.from_numpy(y).cuda(), od)
+    ra, rq = oracle.irregular_moments(y, off)
+    assert np.all(np.abs(q.cpu().numpy().astype(np.float64) - rq) <= 1e-3 * rq)
+    assert np.all(np.abs(a.cpu().numpy().astype(np.float64) - ra) <= 1e-3 * np.maximum(np.abs(ra), np.sqrt(rq)))

@@ -207,6 +207,8 @@ def test_irregular_hand_values(oracle):
     assert oracle.irregular_reduce(x, off).tolist() == [6, 0, 4, 26]
     assert oracle.irregular_scan(x, off).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
     assert oracle.irregular_scan_exclusive(x, off).tolist() == [0, 1, 3, 0, 0, 5, 11, 18]
+    a, q = oracle.irregular_moments(x, off)                  # squares 1 4 9 | | 16 | 25 36 49 64
+    assert a.tolist() == [6, 0, 4, 26] and q.tolist() == [14, 0, 16, 174]
     # segments need not cover the input: untouched outputs stay zero
     assert oracle.irregular_scan(x, [2, 5]).tolist() == [0, 0, 3, 7, 12, 0, 0, 0]
     assert oracle.irregular_reduce(x, [2, 5]).tolist() == [12]
@@ -238,6 +240,14 @@ def test_irregular_equals_per_piece_definition(oracle):
     assert np.array_equal(oracle.irregular_reduce(x, reg), oracle.segmented_reduce(x, 125))
     assert np.array_equal(oracle.irregular_scan(x, reg), oracle.segmented_scan(x, 125))
     assert np.array_equal(oracle.irregular_scan_exclusive(x, reg), oracle.segmented_scan_exclusive(x, 125))
+    ra, rq = oracle.segmented_moments(x, 125)
+    ia, iq = oracle.irregular_moments(x, reg)
+    assert np.array_equal(ia, ra) and np.array_equal(iq, rq)
+    ia, iq = oracle.irregular_moments(x, off)
+    assert np.array_equal(ia, red)
+    q2 = q * q                                                # exact integers: the squares times 2^48
+    for s in range(off.size - 1):
+        assert iq[s] * 2.0 ** 48 == float(q2[int(off[s]):int(off[s + 1])].sum())
     # exclusive + own element = inclusive (exact: every term is a multiple of 2^-24 far below 2^53)
     covered = slice(int(off[0]), int(off[-1]))
     assert np.array_equal((oracle.irregular_scan_exclusive(x, off) + xd)[covered], scan[covered])

@@ -35,6 +35,8 @@ MUTANTS = {
                                                  "            acc += oracle_half_to_double(in[k]);\n            out[k] = acc;"),
     "irregular_exclusive_carry_not_reset": ("        double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {\n            out[k] = acc;",
                                             "        static double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {\n            out[k] = acc;"),
+    "irregular_moments_square_of_sum": ("            a += v;\n            q += v * v;\n        }\n        sum[s] = a;\n        sumsq[s] = q;\n    }\n    return 0;\n}\n\n/* Full",
+                                        "            a += v;\n            q += v;\n        }\n        sum[s] = a;\n        sumsq[s] = q;\n    }\n    return 0;\n}\n\n/* Full"),
     "moments_square_of_sum": ("            q += v * v;", "            q += v;"),
     "moments_sum_of_abs": ("            a += v;\n            q += v * v;", "            a += v < 0 ? -v : v;\n            q += v * v;"),
     "moments_carry_not_reset": ("        double a = 0.0, q = 0.0;", "        double a = 0.0; static double q = 0.0;"),
@@ -57,6 +59,8 @@ def _pins(o) -> None:
     assert o.irregular_reduce(x, [0, 3, 3, 4, 7]).tolist() == [6, 0, 4, 18]
     assert o.irregular_scan(x, [0, 3, 3, 4, 8]).tolist() == [1, 3, 6, 4, 5, 11, 18, 26]
     assert o.irregular_scan_exclusive(x, [0, 3, 3, 4, 8]).tolist() == [0, 1, 3, 0, 0, 5, 11, 18]
+    ia, iq = o.irregular_moments(x, [0, 3, 3, 4, 8])
+    assert ia.tolist() == [6, 0, 4, 26] and iq.tolist() == [14, 0, 16, 174]
     assert o.reduce(x) == 36.0
     a, q = o.segmented_moments(np.array([1, -2, 3, 4, -5, 6], dtype=np.float16), 3)
     assert a.tolist() == [2, 5] and q.tolist() == [14, 77]
