@@ -283,6 +283,19 @@ def main() -> int:
                "sample": f"the same 16 calls on the first 2^{sample_log2} elements of the input (seg_len capped at the sample), "
                          f"sequential binary64 C loops, {dt:.1f} s"}
 
+    cpu_openmp = None
+    if not args.no_cpu_baseline:
+        # the same loops with the segments shared among the host's cores (bit-identical results); context
+        omp = oracle.openmp()
+        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+        t0 = time.perf_counter()
+        for op, e in calls:
+            e = min(e, sample_log2)
+            (omp.segmented_reduce if op == "segmented_reduce" else omp.segmented_scan)(xs, 1 << e)
+        dt = time.perf_counter() - t0
+        cpu_openmp = {"value": round(2 * (1 << sample_log2) * len(calls) / dt * 1e-9, 4), "unit": "GB/s", "cores": threads,
+                      "kind": "oracle, OpenMP over segments", "sample": f"as cpu_baseline, {dt:.1f} s"}
+
     props = torch.cuda.get_device_properties(0)
     device = {"name": props.name, "compute_units": props.multi_processor_count,
               "memory_GiB": round(props.total_memory / 2 ** 30, 1)}
@@ -297,7 +310,7 @@ def main() -> int:
                                "seg_len=2^{%s}; fp32 accumulate and output" % (args.log2n, ",".join(map(str, sweep))),
                    "formulation": args.formulation, "scan_carry": args.scan_carry,
                    "input_sha256": workloads.sha256(x_host)[:16]},
-        "roofline": roofline, "cpu_baseline": cpu, "measured_copy_GBps": copy_gbps, "device": device, "tuning": tcr.tuning_export(), "rows": rows, "context_rows": extra,
+        "roofline": roofline, "cpu_baseline": cpu, "cpu_baseline_openmp": cpu_openmp, "measured_copy_GBps": copy_gbps, "device": device, "tuning": tcr.tuning_export(), "rows": rows, "context_rows": extra,
     }
     print(json.dumps(line))
     return 0

@@ -32,6 +32,19 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+_LIB_OPENMP = os.path.join(_HERE, "libtcr_oracle_omp.so")
+
+
+def build_openmp(force: bool = False) -> str:
+    """The same source compiled with -fopenmp: the regular segmented reduce and scan share their segments among
+    threads (every segment is still one sequential binary64 loop, so the results are bit-identical).  Only the
+    multi-core timing of bench.py and the test that compares it with the sequential build use it."""
+    if force or not os.path.exists(_LIB_OPENMP) or os.path.getmtime(_LIB_OPENMP) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB_OPENMP, _SRC, "-lm"])
+    return _LIB_OPENMP
+
+
 def _bind(path: str):
     lib = ctypes.CDLL(path)
     u16p = ctypes.POINTER(ctypes.c_uint16)
@@ -184,6 +197,17 @@ class Oracle:
 
 
 _default = None
+
+
+_openmp = None
+
+
+def openmp() -> "Oracle":
+    """The OpenMP build behind the same class."""
+    global _openmp
+    if _openmp is None:
+        _openmp = Oracle(build_openmp())
+    return _openmp
 
 
 def _get() -> Oracle:

@@ -58,6 +58,9 @@ int oracle_segmented_reduce(const uint16_t *in, double *out, uint64_t n, uint64_
 {
     if (bad_args(in, out, n, seg_len)) return 1;
     const uint64_t segs = n / seg_len;
+#ifdef _OPENMP                      /* the timed multi-core build: the same loop, segments shared among threads */
+#pragma omp parallel for schedule(static)
+#endif
     for (uint64_t s = 0; s < segs; ++s) {
         double acc = 0.0;
         for (uint64_t k = 0; k < seg_len; ++k)
@@ -72,6 +75,9 @@ int oracle_segmented_scan(const uint16_t *in, double *out, uint64_t n, uint64_t 
 {
     if (bad_args(in, out, n, seg_len)) return 1;
     const uint64_t segs = n / seg_len;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
     for (uint64_t s = 0; s < segs; ++s) {
         double acc = 0.0;
         for (uint64_t k = 0; k < seg_len; ++k) {

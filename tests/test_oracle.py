@@ -339,3 +339,13 @@ def test_moments_exact_rational_and_invariants(oracle):
     assert np.array_equal(q, (zd * zd).sum(axis=1))
     with pytest.raises(ValueError):
         oracle.segmented_moments(z, 7)
+
+
+def test_openmp_build_equals_the_sequential_one(oracle):
+    # the multi-core build that bench.py also times: every segment is the same sequential loop, so bit-identical
+    omp = oracle.openmp()
+    x = workloads.make_input(1 << 18, "uniform_pm1", 21)
+    for seg in (1, 16, 100, 256, 4096, 1 << 18):
+        n = (x.size // seg) * seg
+        assert np.array_equal(omp.segmented_reduce(x[:n], seg), oracle.segmented_reduce(x[:n], seg))
+        assert np.array_equal(omp.segmented_scan(x[:n], seg), oracle.segmented_scan(x[:n], seg))
