@@ -228,7 +228,26 @@ def main() -> int:
                                    (2 * n + 8 * (nseg + 1), 4 * nseg)))
             irregular_rows.append((f"irregular_scan, {nseg} segments ({what})",
                                    (lambda off=off: tcr.irregular_scan(x, off, out=out_scan)), n, (2 * n + 8 * (nseg + 1), 4 * n)))
-    for label, fn, nn, rd_wr in [] if args.no_context else [row for row in variant_rows + library_rows + irregular_rows + [
+    # configurations 1 and 2 (n = 2^20 and 2^24): small enough to sit in the 256 MiB memory-side cache, so every call
+    # takes the next slice of the 512 MiB input (256 resp. 16 distinct buffers); the figures are per call
+    small_rows = []
+    if args.log2n >= 25 and not args.no_context:
+        k1 = n >> 20
+        out1 = torch.empty((1 << 20) // 256, dtype=torch.float32, device="cuda")
+
+        def cfg1():
+            for i in range(k1):
+                tcr.segmented_reduce(x[i << 20:(i + 1) << 20], 256, out=out1)
+        small_rows.append((f"configuration 1: segmented_reduce n=2^20 seg_len=256, per call over {k1} rotating slices "
+                           "(latency/cache-bound, not a roofline row)", cfg1, 1 << 20, (2 << 20, 4 * ((1 << 20) // 256)), k1))
+        k2 = n >> 24
+        for L in (16, 64, 256, 1024, 4096):
+            def cfg2(L=L):
+                for i in range(k2):
+                    tcr.segmented_scan(x[i << 24:(i + 1) << 24], L, out=out_scan[i << 24:(i + 1) << 24])
+            small_rows.append((f"configuration 2: segmented_scan n=2^24 seg_len={L}, per call over {k2} rotating slices "
+                               "(latency/cache-bound, not a roofline row)", cfg2, 1 << 24, (2 << 24, 4 << 24), k2))
+    for label, fn, nn, rd_wr, *per in [] if args.no_context else [row for row in small_rows + variant_rows + library_rows + irregular_rows + [
             ("reduce (full)", lambda: tcr.reduce(x, out=out_one), n, (2 * n, 4)),
             ("scan (full)", lambda: tcr.scan(x, out=out_scan), n, (2 * n, 4 * n)),
             ("segmented_reduce seg_len=3*2^20 (no power of two: masked pieces + second kernel)",
@@ -254,7 +273,7 @@ def main() -> int:
             fn()
         e1.record(stream)
         torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) / reps * 1e3
+        us = e0.elapsed_time(e1) / reps * 1e3 / (per[0] if per else 1)
         extra.append({"call": label, "avg_us": round(us, 2), "total_GBps": round(sum(rd_wr) / us * 1e-3, 1),
                       "pct_of_hbm_peak": round(sum(rd_wr) / us * 1e-3 / HBM_PEAK_GBS * 100, 1)})
     tcr.check_device_flags()
