@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--tuning", default="", help="launch-shape choices to import first (tcr_tuning_import text)")
     ap.add_argument("--autotune", action="store_true",
                     help="let tcr_autotune re-pick the launch shape of every timed call first (default: shipped shapes)")
+    ap.add_argument("--no-small-configs", action="store_true",
+                    help="skip the context rows of configurations 1 and 2 (n = 2^20, 2^24), whose launches would mix with "
+                         "those of the sweep in per-kernel profile statistics")
     ap.add_argument("--context-filter", default="", help="run only the context rows whose label contains this text")
     ap.add_argument("--no-context", action="store_true", help="skip the context rows (variants, library calls, full operations)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -231,7 +234,7 @@ def main() -> int:
     # configurations 1 and 2 (n = 2^20 and 2^24): small enough to sit in the 256 MiB memory-side cache, so every call
     # takes the next slice of the 512 MiB input (256 resp. 16 distinct buffers); the figures are per call
     small_rows = []
-    if args.log2n >= 25 and not args.no_context:
+    if args.log2n >= 25 and not args.no_context and not args.no_small_configs:
         k1 = n >> 20
         out1 = torch.empty((1 << 20) // 256, dtype=torch.float32, device="cuda")
 
