@@ -539,10 +539,8 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
 // 350-400 us above, and 13 ms for 15 segments of 2^24 + 1 elements); reductions 146-231 us (against
 // 230-1060 us).  Longer reductions keep one wavefront per segment over zero-masked tiles (116 us at
 // 1000 elements, 85 us at 3001), the shortest segments one thread each.
-constexpr uint64_t kGenericThreadMax = 96;           // moments: up to here one thread walks a segment
 constexpr uint64_t kTiledScanMin = 2;
 constexpr uint64_t kTiledReduceMin = 8, kTiledReduceMax = 1000;
-constexpr uint64_t kMaskedMin = 256;                 // moments: from here on a wavefront walks masked 512-element tiles
 
 template <bool SCAN>
 inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
@@ -643,7 +641,7 @@ inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, u
         // fixed tiles with the segment starts marked, both moments as two channels of one pass
         return launch_irregular_reduce(in, nullptr, sum, n, nseg, seg_len, s, kBoth, sumsq);
     }
-    if (seg_len <= kGenericThreadMax) {
+    if (seg_len < kTiledReduceMin) {         // under 8 elements: one thread per segment
         generic_moments_kernel<<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
             in, sum, sumsq, nseg, seg_len);
         return check_launch("generic_moments_kernel");
