@@ -77,6 +77,22 @@ tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t
 tcr_status tcr_segmented_scan(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 
 /*
+ * tcr_segmented_scan for callers that cannot allocate device memory: code under HIP graph capture set-ups, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results (binary32 inclusive scan, every
+ * seg_len >= 1 that divides n, seg_len == n for the full scan), same kernels -- but the workspace of the chained
+ * kernels (ticket counter, per-tile descriptors, totals of the multi-kernel variants) is a fixed array in the
+ * library's own device image: 256 + 2^16 * 8 + 2^14 * 4 bytes (about 0.56 MiB), present on every GPU the library
+ * runs on until the process ends.  The call never calls hipMalloc / hipFree or a routine that allocates, and
+ * never synchronises: what must start from zero is cleared by a small kernel on `stream` in front of the first
+ * launch that needs it (and again after a failed launch or 2^30 launches).
+ *   n <= 2^30 elements; more returns TCR_ERR_UNSUPPORTED and enqueues nothing.
+ *   All calls on one GPU share that GPU's array, which keeps the last call's counters: calls on one GPU must be
+ *   ordered (one stream, or events between streams); calls that overlap on one GPU race.  Not for use by several
+ *   host threads at once on one GPU.  tcr_set_workspace does not affect it.
+ */
+tcr_status tcr_segmented_scan_noalloc(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
+
+/*
  * Scan variants.  flags is a combination of
  *   TCR_SCAN_EXCLUSIVE  out[s*seg_len + k] = sum_{j < k} in[s*seg_len + j] (the first output of a segment
  *                       is 0): the exclusive scan that Section 5 uses for its column scans;

@@ -24,7 +24,7 @@ EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
     "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_irregular_moments", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
     "tcr_workspace_bytes", "tcr_set_workspace", "tcr_segmented_moments",
-    "tcr_set_variant",
+    "tcr_set_variant", "tcr_segmented_scan_noalloc",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
 )
 
@@ -63,6 +63,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_scan.argtypes = [vp, fp, u64, vp]
     for name in ("tcr_segmented_reduce", "tcr_segmented_scan", "tcr_reduce", "tcr_scan"):
         getattr(lib, name).restype = ctypes.c_int
+    lib.tcr_segmented_scan_noalloc.argtypes = [vp, fp, u64, u64, vp]
+    lib.tcr_segmented_scan_noalloc.restype = ctypes.c_int
     lib.tcr_autotune.argtypes = [ctypes.c_int, vp, fp, u64, u64, vp]
     lib.tcr_autotune.restype = ctypes.c_int
     lib.tcr_tuning_export.argtypes = [ctypes.c_char_p, u64]
@@ -140,6 +142,21 @@ def segmented_scan(x: torch.Tensor, seg_len: int, out: Optional[torch.Tensor] = 
         st = _lib.tcr_segmented_scan(x.data_ptr(), out.data_ptr(), n, seg_len, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_segmented_scan")
+    return out
+
+
+def segmented_scan_noalloc(x: torch.Tensor, seg_len: int, out: torch.Tensor,
+                           stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """tcr_segmented_scan_noalloc: tcr_segmented_scan on the library's fixed device scratch (the caller passes `out`)."""
+    _check_input(x)
+    n = x.numel()
+    if seg_len <= 0 or n % seg_len:
+        raise TcrError(ERR_INVALID_ARG, "tcr_segmented_scan_noalloc")
+    _check_output(out, n, x)
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_segmented_scan_noalloc(x.data_ptr(), out.data_ptr(), n, seg_len, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_segmented_scan_noalloc")
     return out
 
 

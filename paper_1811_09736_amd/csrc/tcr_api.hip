@@ -47,6 +47,66 @@ extern "C" tcr_status tcr_segmented_scan(const void* in, float* out, uint64_t n,
     return tcr_segmented_scan_ex(in, out, n, seg_len, 0u, stream);
 }
 
+// ------------------------------------------------------------------------------ the call that allocates nothing
+// Device memory of the allocation-free scan: a workspace laid out like a caller-supplied one -- a 256-byte header
+// (ticket counter, give-up flag, two state words), a descriptor area and a partials area -- in a file-scope
+// array, one copy per GPU, held until the process ends.  Host code never uses the array's name as an address:
+// the address on each device comes from hipGetSymbolAddress, once, with that device current.
+constexpr uint64_t kStaticMaxElements = 1ull << 30;
+constexpr uint64_t kStaticDescriptors = kStaticMaxElements / 16384;       // the smallest share handed out by ticket
+constexpr uint64_t kStaticPartials = kStaticMaxElements / kCarryTile;     // binary32 totals of the multi-kernel strategies
+constexpr uint64_t kStaticBytes = kWorkspaceHeader + kStaticDescriptors * 8 + kStaticPartials * 4;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+Workspace g_static_workspace[kMaxDevices];        // host-side bookkeeping of each device's copy of `scratch`
+bool g_static_ready[kMaxDevices] = {};
+
+// The workspace over the current device's copy of `scratch`; its address is looked up on the first call there.
+tcr_status static_workspace(Workspace** out) {
+    int dev = 0;
+    TCR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return TCR_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Workspace& w = g_static_workspace[dev];
+    if (!g_static_ready[dev]) {
+        unsigned char* ptr = nullptr;
+        TCR_HIP(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+        if (ptr == nullptr || !aligned(ptr, 256)) return TCR_ERR_HIP;
+        w = Workspace();
+        w.caller_owned = true;                        // never grown, never freed
+        w.clear_in_stream = true;                     // cleared by a kernel on the call's stream, not from the host
+        w.counters = reinterpret_cast<uint32_t*>(ptr);
+        w.desc = reinterpret_cast<unsigned long long*>(ptr + kWorkspaceHeader);
+        w.desc_capacity = kStaticDescriptors;
+        w.partials = reinterpret_cast<float*>(ptr + kWorkspaceHeader + kStaticDescriptors * 8);
+        w.partials_capacity = kStaticPartials;
+        w.dirty = true;                               // the first call that chains tiles clears it
+        w.flag_valid = false;
+        g_static_ready[dev] = true;
+    }
+    *out = &w;
+    return TCR_OK;
+}
+}  // namespace
+
+extern "C" tcr_status tcr_segmented_scan_noalloc(const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
+    const tcr_status valid = validate(in, out, n, seg_len, 4);
+    if (valid != TCR_OK || n == 0) return valid;
+    if (n > kStaticMaxElements) {
+        g_hip_error = "tcr_segmented_scan_noalloc: n exceeds 2^30 elements, the size its fixed device scratch is laid out for";
+        return TCR_ERR_UNSUPPORTED;
+    }
+    Workspace* ws = nullptr;
+    const tcr_status st = static_workspace(&ws);
+    if (st != TCR_OK) return st;
+    g_forced_workspace = ws;
+    const tcr_status result = tcr_segmented_scan_ex(in, out, n, seg_len, 0u, stream);
+    g_forced_workspace = nullptr;
+    return result;
+}
+
 extern "C" tcr_status tcr_scan_ex(const void* in, void* out, uint64_t n, uint32_t flags, void* stream) {
     if (n == 0) return (flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) ? TCR_ERR_INVALID_ARG : TCR_OK;
     return tcr_segmented_scan_ex(in, out, n, n, flags, stream);
@@ -325,10 +385,17 @@ extern "C" tcr_status tcr_check_device_flags(void* stream) {
     int dev = 0;
     TCR_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
-    for (auto& kv : g_workspaces) {
-        if (kv.first.first != dev || kv.second.counters == nullptr) continue;
+    // every workspace of this device whose flag word has been initialised: library-owned, the caller's, the static one
+    std::vector<const Workspace*> all;
+    for (auto& kv : g_workspaces)
+        if (kv.first.first == dev) all.push_back(&kv.second);
+    auto own = g_caller_workspaces.find(dev);
+    if (own != g_caller_workspaces.end()) all.push_back(&own->second);
+    if (dev >= 0 && dev < kMaxDevices && g_static_ready[dev]) all.push_back(&g_static_workspace[dev]);
+    for (const Workspace* w : all) {
+        if (w->counters == nullptr || !w->flag_valid) continue;
         uint32_t flag = 0;
-        TCR_HIP(hipMemcpy(&flag, kv.second.counters + 1, sizeof(flag), hipMemcpyDeviceToHost));
+        TCR_HIP(hipMemcpy(&flag, w->counters + 1, sizeof(flag), hipMemcpyDeviceToHost));
         if (flag != 0) {
             g_hip_error = "a look-back wait expired";
             return TCR_ERR_HIP;

@@ -182,6 +182,23 @@ __global__ __launch_bounds__(kBeginThreads) void chain_begin_kernel(uint32_t* __
     }
 }
 
+// Host-managed workspaces that must not be cleared from the host (no synchronisation, no runtime call that may
+// allocate): every descriptor and the running counters back to zero, in stream order.  The give-up flag
+// (counters[1]) survives unless keep_flag == 0.
+constexpr int kClearThreads = 256;
+__global__ __launch_bounds__(kClearThreads) void workspace_clear_kernel(uint32_t* __restrict__ counters,
+                                                                        unsigned long long* __restrict__ desc,
+                                                                        uint64_t desc_capacity, uint32_t keep_flag) {
+    const uint64_t stride = (uint64_t)gridDim.x * kClearThreads;
+    for (uint64_t i = (uint64_t)blockIdx.x * kClearThreads + threadIdx.x; i < desc_capacity; i += stride) desc[i] = 0ull;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        counters[0] = 0u;
+        if (!keep_flag) counters[1] = 0u;
+        counters[2] = 0u;
+        counters[3] = 0u;
+    }
+}
+
 __device__ __forceinline__ unsigned long long pack_desc(uint32_t epoch, uint32_t status, float v) {
     return ((unsigned long long)(epoch * 4u + status) << 32) | (unsigned long long)__builtin_bit_cast(uint32_t, v);
 }

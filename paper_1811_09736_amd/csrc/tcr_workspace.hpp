@@ -75,6 +75,7 @@ struct Workspace {
     bool dirty = true;              // counters / descriptors must be re-zeroed before use
     bool caller_owned = false;      // memory supplied through tcr_set_workspace: never grown, never freed
     bool flag_valid = true;         // false until the first clean-up has written the caller's (uninitialised) flag word
+    bool clear_in_stream = false;   // clean-ups run as a kernel on the call's stream instead of host-side memsets
 };
 
 inline std::mutex g_mutex;
@@ -83,6 +84,8 @@ inline std::map<std::pair<int, hipStream_t>, Workspace> g_workspaces;
 // the two areas of equal size.  While one is set, every call on that device uses it, whatever its stream.
 inline std::map<int, Workspace> g_caller_workspaces;
 constexpr uint64_t kWorkspaceHeader = 256;
+// Set by an entry point for the duration of one call: the workspace that call must use, whatever the maps hold.
+inline thread_local Workspace* g_forced_workspace = nullptr;
 
 // Look-back descriptor tables are allocated uncached (polling them through the L2 path measured
 // ~5 % slower on the full scan).  Uncached allocations are never handed back to the runtime:
@@ -122,6 +125,10 @@ inline tcr_status get_workspace(hipStream_t stream, Workspace** out, bool* captu
     hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
     TCR_HIP(hipStreamIsCapturing(stream, &capture));
     *capturing = capture != hipStreamCaptureStatusNone;
+    if (g_forced_workspace != nullptr) {
+        *out = g_forced_workspace;
+        return TCR_OK;
+    }
     int dev = 0;
     TCR_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
@@ -175,13 +182,22 @@ inline tcr_status begin_lookback(Workspace* ws, hipStream_t stream, uint64_t til
     }
     if (ws->dirty || (!ws->device_managed && ws->epoch >= (1u << 30) - 2u)) {
         // first use, growth, a failed launch, or epoch wrap: start from a clean slate
-        TCR_HIP(hipStreamSynchronize(stream));
-        if (ws->desc_capacity) TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
-        uint32_t keep_flag = 0;
-        if (ws->flag_valid) TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (ws->clear_in_stream) {
+            // a kernel in front of the launch, ordered by the stream: no synchronisation, no runtime memset
+            const uint64_t want = (ws->desc_capacity + kClearThreads - 1) / kClearThreads;
+            const unsigned blocks = want < 1 ? 1u : (want > 1024 ? 1024u : (unsigned)want);
+            workspace_clear_kernel<<<dim3(blocks), dim3(kClearThreads), 0, stream>>>(ws->counters, ws->desc, ws->desc_capacity,
+                                                                                     ws->flag_valid ? 1u : 0u);
+            if (hip_failed(hipGetLastError(), "workspace_clear_kernel")) return TCR_ERR_HIP;
+        } else {
+            TCR_HIP(hipStreamSynchronize(stream));
+            if (ws->desc_capacity) TCR_HIP(hipMemset(ws->desc, 0, ws->desc_capacity * sizeof(unsigned long long)));
+            uint32_t keep_flag = 0;
+            if (ws->flag_valid) TCR_HIP(hipMemcpy(&keep_flag, ws->counters + 1, sizeof(uint32_t), hipMemcpyDeviceToHost));
+            uint32_t init[4] = {0u, keep_flag, 0u, 0u};
+            TCR_HIP(hipMemcpy(ws->counters, init, sizeof(init), hipMemcpyHostToDevice));
+        }
         ws->flag_valid = true;
-        uint32_t init[4] = {0u, keep_flag, 0u, 0u};
-        TCR_HIP(hipMemcpy(ws->counters, init, sizeof(init), hipMemcpyHostToDevice));
         ws->tickets_issued = 0;
         ws->epoch = 0;
         ws->dirty = false;
