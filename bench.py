@@ -195,7 +195,7 @@ def main() -> int:
     variant_rows.append(("segmented_moments seg_len=2^12 (sum and sum of squares, X.X^T diagonal on the matrix cores)",
                          lambda: tcr.segmented_moments(x, 1 << 12), n, (2 * n, 8 * (n >> 12))))
     n196 = (n // 196) * 196
-    variant_rows.append(("segmented_moments seg_len=196 (14x14 feature maps: two channels of the tiled reduction)",
+    variant_rows.append(("segmented_moments seg_len=196 (14x14 feature maps: masked row products, sums and sums of squares)",
                          lambda: tcr.segmented_moments(x[:n196], 196), n196, (2 * n196, 8 * (n196 // 196))))
     if args.formulation == "mfma":
         variant_rows.append(("segmented_scan_ex seg_len=2^12 exclusive",
@@ -257,7 +257,7 @@ def main() -> int:
              lambda: tcr.segmented_reduce(x[:nb], big, out=out_g[: nb // big]), nb, (2 * nb, 4 * (nb // big))),
             ("segmented_scan seg_len=3*2^20 (no power of two: chain on a per-segment tile grid)",
              lambda: tcr.segmented_scan(x[:nb], big, out=out_scan[:nb]), nb, (2 * nb, 4 * nb)),
-            ("segmented_reduce seg_len=3000 (no power of two: masked tiles)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
+            ("segmented_reduce seg_len=3000 (no power of two: masked row products)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
             ("segmented_scan seg_len=3000 (no power of two: one workgroup per segment)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
              (2 * n3, 4 * n3)),
@@ -265,7 +265,7 @@ def main() -> int:
              (2 * n1, 4 * n1)),
             ("segmented_scan seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n100], 100, out=out_scan[:n100]), n100,
              (2 * n100, 4 * n100)),
-            ("segmented_reduce seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_reduce(x[:n100], 100, out=out_h100), n100,
+            ("segmented_reduce seg_len=100 (no power of two: masked row products)", lambda: tcr.segmented_reduce(x[:n100], 100, out=out_h100), n100,
              (2 * n100, 4 * (n100 // 100)))] if args.context_filter in row[0]]:
         fn()
         torch.cuda.synchronize()

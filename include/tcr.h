@@ -59,12 +59,14 @@ typedef enum {
  *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
- * seg_len == n.  Other lengths: reductions of 8 to 999 elements and all scans run on fixed tiles of the array
- * with the segment starts marked (the kernels of the irregular calls below; they use the workspace), except
- * scans of a multiple of 8 elements above 512, which have one workgroup per segment or, from 65536 elements,
- * the chained scan; longer reductions run one wavefront per segment (per 65536-element piece of one, from
- * 131072 elements) over zero-masked tiles of the array, the paper's padding of such segments (Section 4)
- * applied in registers.
+ * seg_len == n.  Other lengths: reductions of 32 to 8160 elements take whole segments per workgroup and mask the
+ * data operand of the products row by row where a segment ends (the masking that Section 4 proposes for
+ * arbitrary segment sizes, moved from the constant matrix to the data; no workspace); reductions of 8 to 31
+ * elements and all scans run on fixed tiles of the array with the segment starts marked (the kernels of the
+ * irregular calls below; they use the workspace), except scans of a multiple of 8 elements above 512, which have
+ * one workgroup per segment or, from 65536 elements, the chained scan; longer reductions run one wavefront per
+ * segment (per 65536-element piece of one, from 131072 elements) over zero-masked tiles of the array, the
+ * paper's padding of such segments (Section 4) applied in registers.
  */
 tcr_status tcr_segmented_reduce(const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
 
@@ -143,9 +145,10 @@ tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *
  * sum, sumsq: n/seg_len floats each, 4-byte aligned, distinct.  Every seg_len >= 1 that divides n, including
  * seg_len == n.  The sums of squares come from products of the data with itself on the matrix cores (exact
  * products, binary32 accumulation); both are exact for integer-valued inputs while the sums stay below 2^24.
- * Powers of two up to 512: a tile per wavefront like the reductions; other lengths from 8 to 999: the fixed tiles
- * of the irregular kernels with both moments in one pass (they use the workspace); longer ones: one wavefront
- * per segment (per 65536-element piece of a long one).
+ * Powers of two up to 512: a tile per wavefront like the reductions; other lengths from 32 to 2999: whole
+ * segments per workgroup with the data operand masked row by row, the squares from the masked operand times
+ * itself; from 8 to 31: the fixed tiles of the irregular kernels with both moments in one pass (they use the
+ * workspace); longer ones: one wavefront per segment (per 65536-element piece of a long one).
  */
 tcr_status tcr_segmented_moments(const void *in, float *sum, float *sumsq, uint64_t n, uint64_t seg_len, void *stream);
 /* The same for irregular segments (offsets, n, nseg as for tcr_irregular_reduce; empty segments give 0 and 0):
@@ -171,6 +174,9 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
  *   "scan_carry"   "lookback" (default: single pass, decoupled look-back) | "reduce_then_scan" |
  *                  "scan_then_propagate" (the paper's three-kernel device-level scan, Section 5;
  *                  plain binary32 inclusive scan only)
+ *   "untuned_reduce" "rows" (default: reductions and moments of 32 .. 8160 elements, no power of two, as masked
+ *                  row products) | "tiles" (the fixed tiles with marked segment starts / one wavefront per segment
+ *                  that took these lengths before; kept as the measured alternative)
  *   "reduce_finish" "second_kernel" (default: the paper's two-kernel device-level reduction, Section 4) |
  *                  "fused" (one kernel: the workgroup that finishes last adds up the partials)
  *   "reset"        any value: back to the defaults
@@ -213,8 +219,9 @@ tcr_status tcr_check_device_flags(void *stream);
 
 /*
  * Caller-supplied workspace, for callers that manage device memory themselves.
- * tcr_workspace_bytes: an upper bound, over every variant and launch shape, of the workspace a call with
- *   these arguments can need (op as for tcr_kernel_name; 0 for arguments no call accepts).
+ * tcr_workspace_bytes: an upper bound, over every variant, launch shape and pointer alignment, of the workspace a
+ *   call with these arguments can need (op as for tcr_kernel_name, and 6 = segmented_moments,
+ *   7 = irregular_moments; 0 for arguments no call accepts).
  * tcr_set_workspace: from now on every call on the CURRENT device uses [dev_ptr, dev_ptr + bytes) instead of
  *   library-owned memory, whatever its stream, and allocates nothing; a call that needs more returns
  *   TCR_ERR_WORKSPACE.  dev_ptr: device memory, 256-byte aligned, at least 768 bytes, contents arbitrary (the

@@ -15,7 +15,10 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     const _Float16* x = static_cast<const _Float16*>(in);
     // the tuned kernels load 128 bits at a time; an input that is not aligned for that takes the fixed tiles laid
     // out from the 16-byte boundary below it
-    if (!aligned(in, 16)) return launch_irregular_reduce(x, nullptr, out, n, n / seg_len, seg_len, s);
+    if (!aligned(in, 16)) {
+        if (rows_reduce_takes(seg_len)) return launch_rows_reduce(x, out, nullptr, n, seg_len, kSum, s);    // (any length it fits)
+        return launch_irregular_reduce(x, nullptr, out, n, n / seg_len, seg_len, s);
+    }
     if (seg_len == n) return reduce_long(x, out, n, n, true, s);
     if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<false>(x, out, n, seg_len, 0u, s);
     if (seg_len <= kTile)
@@ -175,6 +178,8 @@ extern "C" tcr_status tcr_segmented_moments(const void* in, float* sum, float* s
     tcr_status st = validate(in, sum, n, seg_len, 4);
     if (st != TCR_OK || n == 0) return st;
     if (sumsq == nullptr || !aligned(sumsq, 4)) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 16) && rows_reduce_takes(seg_len, kBoth))
+        return launch_rows_reduce(static_cast<const _Float16*>(in), sum, sumsq, n, seg_len, kBoth, static_cast<hipStream_t>(stream));
     if (!aligned(in, 16))                    // the tiled reduction with both moments as its two channels
         return launch_irregular_reduce(static_cast<const _Float16*>(in), nullptr, sum, n, n / seg_len, seg_len,
                                        static_cast<hipStream_t>(stream), kBoth, sumsq);
@@ -214,6 +219,12 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
         if (std::strcmp(value, "lookback") == 0) g_variant.scan_carry = kStrategyLookback;
         else if (std::strcmp(value, "reduce_then_scan") == 0) g_variant.scan_carry = kStrategyReduceThenScan;
         else if (std::strcmp(value, "scan_then_propagate") == 0) g_variant.scan_carry = kStrategyScanThenPropagate;
+        else return TCR_ERR_INVALID_ARG;
+        return TCR_OK;
+    }
+    if (std::strcmp(key, "untuned_reduce") == 0) {
+        if (std::strcmp(value, "rows") == 0) g_variant.rows_reduce = true;
+        else if (std::strcmp(value, "tiles") == 0) g_variant.rows_reduce = false;
         else return TCR_ERR_INVALID_ARG;
         return TCR_OK;
     }
@@ -341,6 +352,7 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         if (op == 0) {
             if (is_pow2(seg_len) && seg_len <= 8) return "tiny_reduce_kernel";       // (16-byte aligned results)
             if (seg_len < kTiledReduceMin) return "generic_thread_kernel";
+            if (rows_reduce_takes(seg_len)) return "rows_reduce_kernel";
             if (seg_len < kTiledReduceMax) return "irregular_reduce_kernel<regular>+irregular_groups_kernel+irregular_carry_kernel";
             return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";
         }
@@ -405,22 +417,37 @@ extern "C" tcr_status tcr_check_device_flags(void* stream) {
 }
 
 extern "C" uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len) {
-    if (op < 0 || op > 5 || n == 0) return 0;
-    if (op >= 4) {
-        // the irregular kernels keep 8-byte words in the partials area (look-up tables, pairs) and the scan one
-        // descriptor per tile; the two areas of a workspace are of equal size
-        const uint64_t bytes = 8 * (irregular_words(op == 5, n) > irregular_tiles(true, n) ? irregular_words(op == 5, n)
-                                                                                         : irregular_tiles(true, n));
-        return kWorkspaceHeader + 2 * ((bytes + 255) / 256 * 256);
+    if (op < 0 || op > 7 || n == 0) return 0;
+    const bool irregular = op == 4 || op == 5 || op == 7;
+    if (op == 2 || op == 3) seg_len = n;
+    if (!irregular && (seg_len == 0 || n % seg_len != 0)) return 0;
+    const bool scan = op == 1 || op == 3 || op == 5;
+    const bool moments = op == 6 || op == 7;
+    // A workspace has two areas of equal size: 8-byte tile descriptors, and binary32 partials (which the tiled
+    // kernels of the irregular calls use as 8-byte words: look-up tables, carried-segment indices, pairs).
+    // The tiled kernels lay their tiles out from the 16-byte boundary below `in`: up to 7 elements more.
+    const uint64_t padded = n + 7;
+    uint64_t desc = 0, words = 0;
+    if (scan) {
+        desc = irregular_tiles(true, padded);                     // chained tiles of 32768 elements
+        if (irregular) words = irregular_words(true, padded);     // where the tile boundaries fall among the offsets
+    } else {
+        // tables, one carried-segment index and one pair per tile and per group of 64 tiles; the sums of squares
+        // add a second set of pairs
+        const uint64_t tiles = irregular_tiles(false, padded);
+        words = irregular_words(false, padded) + (moments ? tiles + ceil_div(tiles, kWave) : 0);
     }
-    if (op >= 2) seg_len = n;
-    if (seg_len == 0 || n % seg_len != 0) return 0;
-    // Upper bounds over every variant and launch shape: one 8-byte descriptor per 16384-element share (the
-    // smallest share handed out by ticket), one binary32 partial per 16384 elements (the smallest span a
-    // reduction leaves a partial for is 65536, as is the share of the multi-kernel scans).
-    const uint64_t shares = ceil_div(n, 16384);
-    const uint64_t area = (shares * 8 + 255) / 256 * 256;
-    return kWorkspaceHeader + 2 * area;
+    if (!irregular) {
+        // Regular calls run the tiled kernels above for some lengths and alignments; otherwise, over every variant
+        // and launch shape: one descriptor per 16384-element share (the smallest share handed out by ticket),
+        // and at most one binary32 partial per 16384 elements (the smallest span a reduction leaves a partial
+        // for is 65536, as is the share of the multi-kernel scans; the moments keep two per span).
+        const uint64_t shares = ceil_div(n, 16384);
+        if (scan && shares > desc) desc = shares;
+        if (ceil_div(shares, 2) > words) words = ceil_div(shares, 2);
+    }
+    const uint64_t bytes = 8 * (desc > words ? desc : words);
+    return kWorkspaceHeader + 2 * ((bytes + 255) / 256 * 256);
 }
 
 extern "C" tcr_status tcr_set_workspace(void* dev_ptr, uint64_t bytes) {

@@ -197,8 +197,10 @@ typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* ptr, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(ptr), 0, (int)bytes, 0x00020000);
 }
+// STREAM = true: non-temporal, as for load8.
+template <bool STREAM = false>
 __device__ __forceinline__ half8 buffer_load8(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
-    return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
+    return __builtin_bit_cast(half8, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, STREAM ? 2 : 0));
 }
 // Four consecutive results of one lane at element `elem` of the resource, binary32 or binary16.
 template <int F16>

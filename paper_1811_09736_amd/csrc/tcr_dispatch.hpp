@@ -532,6 +532,33 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     return check_launch("irregular_carry_kernel");
 }
 
+// Regular segments from 32 elements on, no power of two: whole segments per workgroup, masked row products
+// (tcr_rows.hpp).  `in` needs only 2-byte alignment.  kind: kSum, or kBoth with the sums of squares in out2.
+// Measured at n = 2^28 against the kernels that took these lengths before: sums 77-98 us from 33 to 8000
+// elements (fixed tiles with marked starts: 114-157 us below 1000; one wavefront per segment over masked tiles:
+// 114 us at 1000, 89 at 2000, 80 from 3000 on); both moments 88-108 us (fixed tiles 184-249 us; masked tiles 119 us
+// at 1000, 93 at 2000, 82 from 3000 on, where they stay).
+constexpr uint64_t kRowsReduceMin = 32, kRowsReduceMax = kRowsMaxSegLen, kRowsMomentsMax = 2999;
+inline bool rows_reduce_takes(uint64_t seg_len, int kind = kSum) {
+    return g_variant.rows_reduce && seg_len >= kRowsReduceMin && seg_len <= (kind == kBoth ? kRowsMomentsMax : kRowsReduceMax);
+}
+inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2, uint64_t n, uint64_t seg_len, int kind,
+                                     hipStream_t s) {
+    constexpr int U = 4, W = 8;
+    const uint32_t shift = alignment_shift(in);
+    RowsGrid grid;
+    grid.seg_len = seg_len;
+    grid.nseg = n / seg_len;
+    grid.n = n + shift;
+    grid.shift = shift;
+    grid.per_group = (uint32_t)(kRowsGroupElems / seg_len);
+    grid.magic = (uint32_t)(((1ull << 32) + seg_len - 1) / seg_len);
+    const dim3 blocks((unsigned)ceil_div(grid.nseg, grid.per_group)), block(W * kWave);
+    if (kind == kBoth) rows_reduce_kernel<kBoth, U, W><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
+    else rows_reduce_kernel<kSum, U, W><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);
+    return check_launch("rows_reduce_kernel");
+}
+
 // Any other seg_len >= 1 (no power of two, or below 16): no kernel is tuned for it.
 // Scans from 2 elements on and reductions of 8 to 999 elements run on the fixed tiles of the irregular
 // kernels with the multiples of seg_len as segment starts.  Measured at n = 2^28: scans 300-325 us
@@ -578,6 +605,7 @@ inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint
             }
         }
     } else {
+        if (rows_reduce_takes(seg_len)) return launch_rows_reduce(in, static_cast<float*>(out), nullptr, n, seg_len, kSum, s);
         if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax)
             return launch_irregular_reduce(in, nullptr, static_cast<float*>(out), n, nseg, seg_len, s);
     }
@@ -637,6 +665,7 @@ inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, u
         }
         return check_launch("moments_small_kernel");
     }
+    if (rows_reduce_takes(seg_len, kBoth)) return launch_rows_reduce(in, sum, sumsq, n, seg_len, kBoth, s);
     if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax) {
         // fixed tiles with the segment starts marked, both moments as two channels of one pass
         return launch_irregular_reduce(in, nullptr, sum, n, nseg, seg_len, s, kBoth, sumsq);

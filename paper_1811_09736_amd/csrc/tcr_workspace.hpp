@@ -17,6 +17,7 @@
 #include "tcr_scan.hpp"
 #include "tcr_generic.hpp"
 #include "tcr_irregular.hpp"
+#include "tcr_rows.hpp"
 
 namespace tcr {
 namespace host {
@@ -41,6 +42,7 @@ struct Variant {
     int formulation = kMfma;
     int scan_carry = kStrategyLookback;
     bool reduce_fused = false;      // long reductions: a second kernel adds the partials (true: the last workgroup does)
+    bool rows_reduce = true;        // untuned lengths from 32 elements: masked row products (false: the fixed tiles with marked starts)
 };
 inline Variant g_variant;
 

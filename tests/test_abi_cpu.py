@@ -132,12 +132,18 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 8) == "tiny_scan_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6) == "generic_thread_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 24).startswith("irregular_reduce_kernel<regular>+")   # boundaries share tile rows
+    for seg in (33, 48, 999, 1001, 8160):                  # from 32 elements: masked row products, whole segments per workgroup
+        assert k(lib.OP_SEGMENTED_REDUCE, seg * 5, seg) == "rows_reduce_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 8168 * 5, 8168) == "masked_wave_reduce_kernel"
+    lib.set_variant("untuned_reduce", "tiles")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 48).startswith("irregular_reduce_kernel<regular>+")
-    assert k(lib.OP_SEGMENTED_REDUCE, 999 * 5, 999).startswith("irregular_reduce_kernel<regular>+")
     assert k(lib.OP_SEGMENTED_REDUCE, 1001 * 5, 1001) == "masked_wave_reduce_kernel"
+    lib.set_variant("reset")
     assert k(lib.OP_IRREGULAR_REDUCE, 1 << 20, 0).startswith("irregular_bounds_kernel+irregular_reduce_kernel")
     assert k(lib.OP_IRREGULAR_SCAN, 1 << 20, 0) == "irregular_bounds_kernel+irregular_scan_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 3 << 20, 3 << 10) == "masked_wave_reduce_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 3 << 20, 3 << 10) == "rows_reduce_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 3 << 20, 3 << 12) == "masked_wave_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 3 << 24, 3 << 20) == "masked_span_reduce_kernel+reduce_final_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "scan_chain_kernel<mfma>"        # long, a multiple of 8
     assert k(lib.OP_SEGMENTED_SCAN, 100003 * 5, 100003) == "irregular_scan_kernel<regular>"   # long, odd
@@ -180,15 +186,44 @@ def test_workspace_bytes_is_a_host_side_bound(lib):
     wb = lib.workspace_bytes
     assert wb(lib.OP_SEGMENTED_SCAN, 0, 16) == 0
     assert wb(lib.OP_SEGMENTED_SCAN, 48, 5) == 0            # 5 does not divide 48
-    assert wb(7, 1 << 20, 16) == 0
+    assert wb(8, 1 << 20, 16) == 0
     small, big = wb(lib.OP_SCAN, 1 << 20, 0), wb(lib.OP_SCAN, 1 << 28, 0)
     assert 768 <= small < big
     assert big == 256 + 2 * (1 << 28) // 16384 * 8          # header + descriptors + partials
     assert big % 256 == 0
-    assert wb(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == big
     # irregular segments: look-up tables and per-tile pairs (reduce), one descriptor per 32768-element tile (scan)
     ired, iscan = wb(lib.OP_IRREGULAR_REDUCE, 1 << 28, 0), wb(lib.OP_IRREGULAR_SCAN, 1 << 28, 0)
     assert ired % 256 == 0 and iscan % 256 == 0
     assert ired >= 256 + 2 * 8 * (4 * (1 << 14) + 2) and iscan >= 256 + 2 * 8 * ((1 << 13) + 1)
     assert ired < 4 << 20 and iscan < 1 << 20
     assert wb(lib.OP_IRREGULAR_SCAN, 0, 0) == 0
+
+
+def _tiled_reduce_words(n, channels):
+    """8-byte words the tiled reduction keeps in the partials area for an array of n elements laid out from the
+    16-byte boundary below it (up to 7 elements more): two look-up tables of tiles + 1 entries, one carried-segment
+    index per tile, and per channel one pair per tile and per group of 64 tiles."""
+    tiles = -(-(n + 7) // 16384)
+    groups = -(-tiles // 64)
+    return 2 * (tiles + 1) + tiles + channels * (tiles + groups)
+
+
+@pytest.mark.parametrize("n", [1, 9, 16384, 16385, (1 << 20) - 7, 1 << 20, (1 << 28) + 24])
+def test_workspace_bytes_covers_the_tiled_kernels_behind_regular_calls(lib, n):
+    # A regular call lands on the tiled kernels of the irregular calls for some lengths (reductions of 8 .. 31
+    # elements that are no power of two) and for every length when `in` is not 16-byte aligned; the bound must
+    # hold for those too, for both moments as well, and one area must hold the scan's descriptors.
+    wb = lib.workspace_bytes
+    area = lambda op, seg: (wb(op, n, seg) - 256) // 2
+    assert area(lib.OP_SEGMENTED_REDUCE, 1) >= 8 * _tiled_reduce_words(n, 1)
+    assert area(lib.OP_REDUCE, 0) >= 8 * _tiled_reduce_words(n, 1)
+    assert area(lib.OP_IRREGULAR_REDUCE, 0) >= 8 * _tiled_reduce_words(n, 1)
+    assert area(lib.OP_SEGMENTED_MOMENTS, 1) >= 8 * _tiled_reduce_words(n, 2)
+    assert area(lib.OP_IRREGULAR_MOMENTS, 0) >= 8 * _tiled_reduce_words(n, 2)
+    scan_tiles = -(-(n + 7) // 32768)
+    for op in (lib.OP_SEGMENTED_SCAN, lib.OP_SCAN, lib.OP_IRREGULAR_SCAN):
+        assert area(op, 1) >= 8 * scan_tiles
+    assert area(lib.OP_IRREGULAR_SCAN, 0) >= 8 * (scan_tiles + 1)         # its look-up table
+    # the long power-of-two paths: a descriptor per 16384-element share, a partial per 65536-element span
+    assert area(lib.OP_SEGMENTED_SCAN, 1) >= 8 * -(-n // 16384)
+    assert area(lib.OP_SEGMENTED_REDUCE, 1) >= 4 * -(-n // 65536) * 2
