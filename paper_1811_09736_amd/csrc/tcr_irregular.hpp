@@ -208,6 +208,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     __shared__ float s_wave_value[WAVES];
     __shared__ uint32_t s_wave_flag[WAVES];
     __shared__ float s_prefix;
+    __shared__ uint32_t s_ready;              // set once s_prefix holds the carry from earlier tiles
     __shared__ uint32_t s_tile;
     __shared__ uint64_t s_bound[2];
 
@@ -216,6 +217,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // tiles are handed out in launch order, so every predecessor of a waiting tile is running or finished
     if (threadIdx.x == 0) {
+        s_ready = 0u;
         const uint32_t t = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
         s_tile = t;
         if constexpr (REGULAR) {
@@ -283,9 +285,11 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
     const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
     const bool inside = valid_lo == 0u && valid_hi == kChunk && vector_stores != 0u;
-    // A wavefront behind a head needs nothing from earlier tiles and goes straight to its stores instead of
-    // waiting for the look-up (the barrier only counts the wavefronts that are still running, so it opens
-    // for the others once these have finished).  Wavefront 0 is always open.
+    // A wavefront behind a head needs nothing from earlier tiles and goes straight to its stores.  The others
+    // wait for the carry that wavefront 0 (always open) looks up -- on a flag in LDS, not at a barrier: a barrier
+    // that only some wavefronts of a workgroup execute is outside what the language defines, and one that all
+    // execute would hold the closed wavefronts back until the look-up ends (measured: 337 -> 429 us with short
+    // segments).  The wait ends: the look-up's own waits are bounded, so wavefront 0 always sets the flag.
     if (open) {
         if (wave == 0) {
             float total = 0.0f;
@@ -299,13 +303,16 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
             }
             // nothing in front of the tile can reach into it if it starts with a head (or is the first)
             const uint32_t reach = (has_heads && (s_heads[0] & 1u)) ? 0u : tile;
-                        // 8 descriptors per round: most tiles hold a head and finish their predecessor's wait at distance 1,
+            // 8 descriptors per round: most tiles hold a head and finish their predecessor's wait at distance 1,
             // and chains of open tiles are short with two workgroups per compute unit (measured at n = 2^28:
             // 302 / 340 us for short / long segments with 4-8 per round, 303 / 396 with 1, 323 / 362 with 64)
             const float pre = lookback_carry<8>(ws, tile, reach, closed, total, lane);
-            if (lane == 0) s_prefix = pre;
+            if (lane == 0) {
+                s_prefix = pre;
+                __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
         }
-        __syncthreads();
+        while (__hip_atomic_load(&s_ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0u) __builtin_amdgcn_s_sleep(1);
         ext += s_prefix;
     }
     void* const dst = F16 ? static_cast<void*>(static_cast<_Float16*>(out) + base) : static_cast<void*>(static_cast<float*>(out) + base);
