@@ -53,6 +53,10 @@ def _bind(path: str):
     u64 = ctypes.c_uint64
     lib.oracle_half_to_double.argtypes = [ctypes.c_uint16]
     lib.oracle_half_to_double.restype = ctypes.c_double
+    lib.oracle_double_to_half.argtypes = [ctypes.c_double]
+    lib.oracle_double_to_half.restype = ctypes.c_uint16
+    lib.oracle_segmented_scan_half_acc.argtypes = [u16p, u16p, u64, u64, ctypes.c_int]
+    lib.oracle_segmented_scan_half_acc.restype = ctypes.c_int
     for name, args in (
         ("oracle_segmented_reduce", [u16p, f64p, u64, u64]),
         ("oracle_segmented_scan", [u16p, f64p, u64, u64]),
@@ -110,6 +114,20 @@ class Oracle:
         if self._lib.oracle_segmented_scan(_in_ptr(x), _out_ptr(out), n, seg_len):
             raise ValueError("oracle_segmented_scan rejected its arguments")
         return out
+
+    def double_to_half(self, v: float) -> int:
+        return int(self._lib.oracle_double_to_half(float(v)))
+
+    def segmented_scan_half_acc(self, x: np.ndarray, seg_len: int, exclusive: bool = False) -> np.ndarray:
+        """The scan with every addition rounded to binary16 (left to right); a float16 array."""
+        n = x.shape[0]
+        if seg_len <= 0 or n % seg_len:
+            raise ValueError("seg_len must be positive and divide n")
+        out = np.empty(n, dtype=np.uint16)
+        if self._lib.oracle_segmented_scan_half_acc(_in_ptr(x), out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), n, seg_len,
+                                                    1 if exclusive else 0):
+            raise ValueError("oracle_segmented_scan_half_acc rejected its arguments")
+        return out.view(np.float16)
 
     def segmented_scan_exclusive(self, x: np.ndarray, seg_len: int) -> np.ndarray:
         n = x.shape[0]
@@ -231,6 +249,14 @@ def segmented_scan(x, seg_len):
 
 def segmented_scan_exclusive(x, seg_len):
     return _get().segmented_scan_exclusive(x, seg_len)
+
+
+def double_to_half(v):
+    return _get().double_to_half(v)
+
+
+def segmented_scan_half_acc(x, seg_len, exclusive=False):
+    return _get().segmented_scan_half_acc(x, seg_len, exclusive)
 
 
 def irregular_reduce(x, offsets):

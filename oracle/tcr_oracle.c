@@ -201,6 +201,62 @@ int oracle_irregular_moments(const uint16_t *in, const uint64_t *offsets, double
     return 0;
 }
 
+/*
+ * binary64 value -> nearest binary16 bit pattern, ties to the even significand, magnitudes from 65520 on to
+ * infinity, results below 2^-14 as subnormals (multiples of 2^-24).  Written out on the integer significand; no
+ * half-precision library type or conversion instruction is used.
+ */
+uint16_t oracle_double_to_half(double v)
+{
+    const uint16_t sign = signbit(v) ? 0x8000u : 0u;
+    if (isnan(v)) return (uint16_t)(sign | 0x7e00u);
+    double a = fabs(v);
+    if (isinf(a)) return (uint16_t)(sign | 0x7c00u);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                            /* a = m * 2^e with 0.5 <= m < 1: a lies in [2^(e-1), 2^e) */
+    int ulp_exp = e - 1 - 10;                      /* a normal binary16 number near a is a multiple of 2^(e-11) */
+    if (ulp_exp < -24) ulp_exp = -24;              /* subnormal range: multiples of 2^-24 */
+    const double scaled = ldexp(a, -ulp_exp);      /* exact: a in units of the spacing; < 2048 */
+    double whole = floor(scaled);
+    const double rest = scaled - whole;            /* exact */
+    if (rest > 0.5 || (rest == 0.5 && fmod(whole, 2.0) == 1.0)) whole += 1.0;
+    const double r = ldexp(whole, ulp_exp);        /* the rounded magnitude, exact in binary64 */
+    if (r >= 65536.0) return (uint16_t)(sign | 0x7c00u);
+    if (r == 0.0) return sign;
+    /* encode r: it is a binary16 value now */
+    int re;
+    (void)frexp(r, &re);
+    if (re - 1 < -14) return (uint16_t)(sign | (uint16_t)ldexp(r, 24));         /* subnormal: fraction = r / 2^-24 */
+    const int biased = re - 1 + 15;
+    const uint16_t frac = (uint16_t)(ldexp(r, 10 - (re - 1)) - 1024.0);
+    return (uint16_t)(sign | (uint16_t)(biased << 10) | frac);
+}
+
+/*
+ * The scan with a binary16 accumulator, the precision of the paper's half-precision mode (Section 2.2: the
+ * matrix units take binary16 inputs and accumulate in binary16 or binary32; Section 6 counts 2 bytes per
+ * scanned output).  The definition of Section 3 is taken in its own order, left to right, and every addition
+ * is rounded to binary16 at once:
+ *     acc_0 = 0,   acc_{k+1} = round16(acc_k + x_k),   inclusive: out[k] = acc_{k+1},   exclusive: out[k] = acc_k.
+ * The sum of two binary16 values is exact in binary64 (their bits span less than 53 positions), so each step
+ * rounds exactly once.  out receives binary16 bit patterns.
+ */
+int oracle_segmented_scan_half_acc(const uint16_t *in, uint16_t *out, uint64_t n, uint64_t seg_len, int exclusive)
+{
+    if (bad_args(in, out, n, seg_len)) return 1;
+    const uint64_t segs = n / seg_len;
+    for (uint64_t s = 0; s < segs; ++s) {
+        uint16_t acc = 0;
+        for (uint64_t k = 0; k < seg_len; ++k) {
+            const uint16_t next = oracle_double_to_half(oracle_half_to_double(acc) + oracle_half_to_double(in[s * seg_len + k]));
+            out[s * seg_len + k] = exclusive ? acc : next;
+            acc = next;
+        }
+    }
+    return 0;
+}
+
 /* Full (unsegmented) forms: one segment that spans the whole input. */
 int oracle_reduce(const uint16_t *in, double *out, uint64_t n)
 {

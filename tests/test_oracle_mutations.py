@@ -35,8 +35,8 @@ MUTANTS = {
                                                  "            acc += oracle_half_to_double(in[k]);\n            out[k] = acc;"),
     "irregular_exclusive_carry_not_reset": ("        double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {\n            out[k] = acc;",
                                             "        static double acc = 0.0;\n        for (uint64_t k = offsets[s]; k < offsets[s + 1]; ++k) {\n            out[k] = acc;"),
-    "irregular_moments_square_of_sum": ("            a += v;\n            q += v * v;\n        }\n        sum[s] = a;\n        sumsq[s] = q;\n    }\n    return 0;\n}\n\n/* Full",
-                                        "            a += v;\n            q += v;\n        }\n        sum[s] = a;\n        sumsq[s] = q;\n    }\n    return 0;\n}\n\n/* Full"),
+    "irregular_moments_square_of_sum": ("            a += v;\n            q += v * v;\n        }\n        sum[s] = a;\n        sumsq[s] = q;\n    }\n    return 0;\n}\n\n/*\n * binary64",
+                                        "            a += v;\n            q += v;\n        }\n        sum[s] = a;\n        sumsq[s] = q;\n    }\n    return 0;\n}\n\n/*\n * binary64"),
     "moments_square_of_sum": ("            q += v * v;", "            q += v;"),
     "moments_sum_of_abs": ("            a += v;\n            q += v * v;", "            a += v < 0 ? -v : v;\n            q += v * v;"),
     "moments_carry_not_reset": ("        double a = 0.0, q = 0.0;", "        double a = 0.0; static double q = 0.0;"),
