@@ -192,6 +192,13 @@ def main() -> int:
         if e <= args.log2n and args.formulation == "mfma" and args.scan_carry != "scan_then_propagate":
             variant_rows.append((f"segmented_scan_ex seg_len=2^{e} binary16 output (the paper's precision, 4 B/elem)",
                                  (lambda e=e: tcr.segmented_scan_ex(x, 1 << e, tcr.OUT_F16, out=out_h)), n, (2 * n, 2 * n)))
+    if args.formulation == "mfma":
+        for e in (12, 20):
+            if e <= args.log2n:
+                variant_rows.append((f"segmented_scan_ex seg_len=2^{e} binary16 accumulator and output (the paper's half-precision "
+                                     "mode, 4 B/elem; cross-lane binary16 adds, no matrix cores)",
+                                     (lambda e=e: tcr.segmented_scan_ex(x, 1 << e, tcr.OUT_F16 | tcr.ACC_F16, out=out_h)), n,
+                                     (2 * n, 2 * n)))
     variant_rows.append(("segmented_moments seg_len=2^12 (sum and sum of squares, X.X^T diagonal on the matrix cores)",
                          lambda: tcr.segmented_moments(x, 1 << 12), n, (2 * n, 8 * (n >> 12))))
     n196 = (n // 196) * 196

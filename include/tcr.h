@@ -101,12 +101,23 @@ tcr_status tcr_segmented_scan_noalloc(const void *in, float *out, uint64_t n, ui
  *   TCR_OUT_F16         results are rounded (to nearest even) to binary16 and `out` points to n binary16
  *                       values -- the paper's own output precision (Section 6 counts 4 bytes per scanned
  *                       element).  Accumulation stays binary32; sums beyond 65504 become infinities.
- * flags == 0 is tcr_segmented_scan / tcr_scan.  out: n elements.  Unknown flag bits
+ *   TCR_ACC_F16         (with TCR_OUT_F16 only) the ACCUMULATOR is binary16 as well, the half-precision mode of
+ *                       the paper's matrix units (Section 2.2): every addition rounds to binary16.  The gfx950
+ *                       binary16 MFMA accumulates in binary32 only, so this mode runs on cross-lane adds; the
+ *                       additions form a tree, so a result equals the left-to-right binary16 scan bit for bit
+ *                       only while no addition rounds (all sums of consecutive elements of a segment are
+ *                       binary16 values, e.g. integers within +-2048); otherwise each output has gone through
+ *                       at most 40 roundings of relative size 2^-11 (a running count of ones stalls at 2048, as
+ *                       it does for any binary16 accumulator).  Powers of two and seg_len == n, 16-byte aligned
+ *                       arrays; TCR_ERR_UNSUPPORTED otherwise.
+ * flags == 0 is tcr_segmented_scan / tcr_scan.  out: n elements.  Unknown flag bits (and TCR_ACC_F16 without
+ * TCR_OUT_F16)
  * return TCR_ERR_INVALID_ARG.  Under the "dpp" formulation only flags == 0 has tuned kernels
  * (TCR_ERR_UNSUPPORTED otherwise); segment lengths without a tuned path accept every flag.
  */
 #define TCR_SCAN_EXCLUSIVE 1u
 #define TCR_OUT_F16 2u
+#define TCR_ACC_F16 4u
 tcr_status tcr_segmented_scan_ex(const void *in, void *out, uint64_t n, uint64_t seg_len, uint32_t flags, void *stream);
 tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, void *stream);
 

@@ -19,7 +19,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = range(5)
 OP_SEGMENTED_REDUCE, OP_SEGMENTED_SCAN, OP_REDUCE, OP_SCAN, OP_IRREGULAR_REDUCE, OP_IRREGULAR_SCAN = range(6)
 OP_SEGMENTED_MOMENTS, OP_IRREGULAR_MOMENTS = 6, 7          # tcr_workspace_bytes only
 
-SCAN_EXCLUSIVE, OUT_F16 = 1, 2
+SCAN_EXCLUSIVE, OUT_F16, ACC_F16 = 1, 2, 4
 
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",

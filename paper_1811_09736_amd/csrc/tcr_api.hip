@@ -29,10 +29,16 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
 
 extern "C" tcr_status tcr_segmented_scan_ex(const void* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags,
                                             void* stream) {
-    if ((flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) != 0) return TCR_ERR_INVALID_ARG;
+    if ((flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16 | TCR_ACC_F16)) != 0) return TCR_ERR_INVALID_ARG;
+    if ((flags & TCR_ACC_F16) && !(flags & TCR_OUT_F16)) return TCR_ERR_INVALID_ARG;     // a binary16 accumulator has binary16 results
     tcr_status st = validate(in, out, n, seg_len, (flags & TCR_OUT_F16) ? 2 : 4);
     if (st != TCR_OK || n == 0) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (flags & TCR_ACC_F16) {
+        const _Float16* x = static_cast<const _Float16*>(in);
+        _Float16* y = static_cast<_Float16*>(out);
+        return (flags & TCR_SCAN_EXCLUSIVE) ? scan_half<1>(x, y, n, seg_len, s) : scan_half<0>(x, y, n, seg_len, s);
+    }
     if (!aligned(in, 16) || !aligned(out, 16)) {
         // arrays that are not aligned for 128-bit accesses: the fixed tiles, laid out from the boundary below `in`
         const _Float16* x = static_cast<const _Float16*>(in);
@@ -111,7 +117,10 @@ extern "C" tcr_status tcr_segmented_scan_noalloc(const void* in, float* out, uin
 }
 
 extern "C" tcr_status tcr_scan_ex(const void* in, void* out, uint64_t n, uint32_t flags, void* stream) {
-    if (n == 0) return (flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16)) ? TCR_ERR_INVALID_ARG : TCR_OK;
+    if (n == 0) {
+        if (flags & ~(uint32_t)(TCR_SCAN_EXCLUSIVE | TCR_OUT_F16 | TCR_ACC_F16)) return TCR_ERR_INVALID_ARG;
+        return ((flags & TCR_ACC_F16) && !(flags & TCR_OUT_F16)) ? TCR_ERR_INVALID_ARG : TCR_OK;
+    }
     return tcr_segmented_scan_ex(in, out, n, n, flags, stream);
 }
 

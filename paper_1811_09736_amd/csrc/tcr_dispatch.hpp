@@ -772,6 +772,48 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
     }
 }
 
+// The scan with a binary16 accumulator (TCR_ACC_F16): powers of two and the one-segment scan, 16-byte aligned arrays.
+template <int U, int W, int CARRY, int EXCL>
+inline void launch_scan_half_shape(const _Float16* in, _Float16* out, uint64_t n, uint64_t seg_mask, uint64_t seg_len,
+                                   const ScanWorkspace& dev, hipStream_t s) {
+    const unsigned blocks = (unsigned)ceil_div(n, (uint64_t)kTile * U * W);
+    scan_half_kernel<U, W, CARRY, EXCL><<<dim3(blocks), dim3(W * kWave), 0, s>>>(in, out, n, seg_mask, seg_len, dev);
+}
+
+template <int EXCL>
+inline tcr_status scan_half(const _Float16* in, _Float16* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+    const bool whole = seg_len == n;
+    if (!whole && !is_pow2(seg_len)) return TCR_ERR_UNSUPPORTED;
+    if (!aligned(in, 16) || !aligned(out, 16)) return TCR_ERR_UNSUPPORTED;
+    const uint64_t len = seg_len;                                  // decides the launch shape
+    const uint64_t seg_mask = (whole && !is_pow2(n)) ? ~0ull : seg_len - 1;
+    if (whole && !is_pow2(n)) seg_len = ~0ull;                     // one segment of any length: never restarts
+    const ScanWorkspace none = {};
+    if (len <= 1024) launch_scan_half_shape<1, 2, kNoCarry, EXCL>(in, out, n, seg_mask, seg_len, none, s);
+    else if (len <= 4096) launch_scan_half_shape<1, 8, kNoCarry, EXCL>(in, out, n, seg_mask, seg_len, none, s);
+    else if (len <= 16384) launch_scan_half_shape<2, 16, kNoCarry, EXCL>(in, out, n, seg_mask, seg_len, none, s);
+    else if (len <= 65536) launch_scan_half_shape<8, 16, kNoCarry, EXCL>(in, out, n, seg_mask, seg_len, none, s);
+    else {
+        const uint64_t tiles = ceil_div(n, (uint64_t)kTile * 8 * 16);
+        ScanWorkspace dev = {};
+        Workspace* ws = nullptr;
+        bool capturing = false;
+        tcr_status st = get_workspace(s, &ws, &capturing);
+        if (st != TCR_OK) return st;
+        st = begin_lookback(ws, s, tiles, &dev, capturing);
+        if (st != TCR_OK) return st;
+        launch_scan_half_shape<8, 16, kLookback, EXCL>(in, out, n, seg_mask, seg_len, dev, s);
+        st = check_launch("scan_half_kernel");
+        if (st != TCR_OK) {
+            ws->dirty = true;
+            return st;
+        }
+        ws->tickets_issued += (uint32_t)tiles;
+        return TCR_OK;
+    }
+    return check_launch("scan_half_kernel");
+}
+
 // out_align: the natural alignment of the output's elements.
 inline tcr_status validate(const void* in, const void* out, uint64_t n, uint64_t seg_len, uintptr_t out_align) {
     if (seg_len == 0) return TCR_ERR_INVALID_ARG;

@@ -18,6 +18,7 @@
 #include "tcr_generic.hpp"
 #include "tcr_irregular.hpp"
 #include "tcr_rows.hpp"
+#include "tcr_half.hpp"
 
 namespace tcr {
 namespace host {
