@@ -214,6 +214,70 @@ __device__ __forceinline__ void buffer_store4_t(__amdgpu_buffer_rsrc_t r, uint32
     }
 }
 
+// Binary16 output in the operand map: lane (j, g) holds positions 4g .. 4g+3 (lo) and 16+4g .. 16+4g+3 (hi) of tile
+// row j, two 64-bit pieces.  Lane rows g and g+1 (g even) exchange one piece each (v_permlane16_swap: the odd
+// lane rows of one register against the even lane rows of another), after which every lane holds 8 CONSECUTIVE
+// results -- g even: positions 16+4g .. 16+4g+7, g odd: 4(g-1) .. 4(g-1)+7 -- and stores them as 128 bits like
+// the binary32 results.  (With 64-bit stores the binary16 scans ran at 64-70 % of the HBM peak against 72-77 %
+// for binary32 output.)  Returns the 8 values; `elem` receives their position inside the tile.
+typedef unsigned int uint2w __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4v pair_rows_f16(float4v lo, float4v hi, int j, int g, uint32_t& elem) {
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    const uint2w l = __builtin_bit_cast(uint2w, (h4){(_Float16)lo[0], (_Float16)lo[1], (_Float16)lo[2], (_Float16)lo[3]});
+    const uint2w h = __builtin_bit_cast(uint2w, (h4){(_Float16)hi[0], (_Float16)hi[1], (_Float16)hi[2], (_Float16)hi[3]});
+    const uint2w a = __builtin_amdgcn_permlane16_swap(h[0], l[0], false, false);
+    const uint2w b = __builtin_amdgcn_permlane16_swap(h[1], l[1], false, false);
+    elem = (uint32_t)(kRow * j + ((g & 1) ? 4 * (g - 1) : 16 + 4 * g));
+    return (uint4v){a[0], b[0], a[1], b[1]};
+}
+// Both pieces of a lane's results for one tile: binary32 as two 128-bit stores, binary16 as one.
+template <int F16>
+__device__ __forceinline__ void store_tile_rows_t(void* __restrict__ out, uint64_t tile_base, int j, int g, float4v lo, float4v hi) {
+    if constexpr (F16) {
+        uint32_t elem;
+        const uint4v v = pair_rows_f16(lo, hi, j, g, elem);
+        *reinterpret_cast<uint4v*>(static_cast<_Float16*>(out) + tile_base + elem) = v;
+    } else {
+        float* o = static_cast<float*>(out) + tile_base + (uint64_t)(kRow * j + 4 * g);
+        *reinterpret_cast<float4v*>(o) = lo;
+        *reinterpret_cast<float4v*>(o + 16) = hi;
+    }
+}
+// The same through a buffer resource; tile_elem: first element of the tile inside the resource.
+template <int F16>
+__device__ __forceinline__ void buffer_store_tile_rows_t(__amdgpu_buffer_rsrc_t r, uint32_t tile_elem, int j, int g, float4v lo, float4v hi) {
+    if constexpr (F16) {
+        uint32_t elem;
+        const uint4v v = pair_rows_f16(lo, hi, j, g, elem);
+        __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)((tile_elem + elem) * 2u), 0, 0);
+    } else {
+        const uint32_t elem = tile_elem + (uint32_t)(kRow * j + 4 * g);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4v, lo), r, (int)(elem * 4u), 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4v, hi), r, (int)((elem + 16u) * 4u), 0, 0);
+    }
+}
+// Eight consecutive results of one lane (the lane-ordered tile), binary32 or binary16.
+template <int F16>
+__device__ __forceinline__ void store8_t(void* __restrict__ out, uint64_t off, float4v a, float4v b) {
+    if constexpr (F16) {
+        const half8 h = {(_Float16)a[0], (_Float16)a[1], (_Float16)a[2], (_Float16)a[3], (_Float16)b[0], (_Float16)b[1], (_Float16)b[2], (_Float16)b[3]};
+        *reinterpret_cast<half8*>(static_cast<_Float16*>(out) + off) = h;
+    } else {
+        *reinterpret_cast<float4v*>(static_cast<float*>(out) + off) = a;
+        *reinterpret_cast<float4v*>(static_cast<float*>(out) + off + 4) = b;
+    }
+}
+template <int F16>
+__device__ __forceinline__ void buffer_store8_t(__amdgpu_buffer_rsrc_t r, uint32_t elem, float4v a, float4v b) {
+    if constexpr (F16) {
+        const half8 h = {(_Float16)a[0], (_Float16)a[1], (_Float16)a[2], (_Float16)a[3], (_Float16)b[0], (_Float16)b[1], (_Float16)b[2], (_Float16)b[3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4v, h), r, (int)(elem * 2u), 0, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4v, a), r, (int)(elem * 4u), 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uint4v, b), r, (int)((elem + 4u) * 4u), 0, 0);
+    }
+}
+
 // Output in binary32 (F16 = 0) or rounded to binary16 (F16 = 1, the paper's own output precision):
 // four consecutive results of one lane, `off` counted in elements.
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));

@@ -322,8 +322,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         wave_share_finish<U, EXCL>(w, x, u, ext, p);
         const uint32_t k = (uint32_t)(kTile * u + 8 * lane);
         if (inside) {
-            store4_t<F16>(dst, k, (float4v){p[0], p[1], p[2], p[3]});
-            store4_t<F16>(dst, k + 4, (float4v){p[4], p[5], p[6], p[7]});
+            store8_t<F16>(dst, k, (float4v){p[0], p[1], p[2], p[3]}, (float4v){p[4], p[5], p[6], p[7]});
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {

@@ -124,8 +124,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
             off_hi = off_lo + 4;
         }
         if (full) {
-            store4_t<F16>(out, off_lo, lo);
-            store4_t<F16>(out, off_hi, hi);
+            if constexpr (FORM == kMfma) store_tile_rows_t<F16>(out, tbase, id.j, id.g, lo, hi);
+            else store8_t<F16>(out, off_lo, lo, hi);
         } else {
             store4_guarded_t<F16>(out, off_lo, n, lo);
             store4_guarded_t<F16>(out, off_hi, n, hi);
@@ -397,8 +397,8 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_block_kernel(const _Float1
             off_hi = off_lo + 4;
         }
         if (full) {
-            store4_t<F16>(out, off_lo, lo);
-            store4_t<F16>(out, off_hi, hi);
+            if constexpr (FORM == kMfma) store_tile_rows_t<F16>(out, tbase, id.j, id.g, lo, hi);
+            else store8_t<F16>(out, off_lo, lo, hi);
         } else {
             store4_guarded_t<F16>(out, off_lo, n, lo);
             store4_guarded_t<F16>(out, off_hi, n, hi);
@@ -598,15 +598,12 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
         if constexpr (FORM == kMfma) {
             const float4v lo = mfma(const_tri_lo<EXCL>(id), t.x[u], splat(carry));
             const float4v hi = mfma(const_tri_hi<EXCL>(id), t.x[u], splat(carry));
-            const uint32_t elem = (uint32_t)(kTile * u + kRow * id.j + 4 * id.g);
-            buffer_store4_t<F16>(dst, elem, lo);
-            buffer_store4_t<F16>(dst, elem + 16u, hi);
+            buffer_store_tile_rows_t<F16>(dst, (uint32_t)(kTile * u), id.j, id.g, lo, hi);
         } else {
             float p[8];                           // the in-lane scan is recomputed here rather than kept for a step
             scan8<EXCL>(t.x[u], p);
-            const uint32_t elem = (uint32_t)(kTile * u + 8 * id.lane);
-            buffer_store4_t<F16>(dst, elem, (float4v){p[0] + carry, p[1] + carry, p[2] + carry, p[3] + carry});
-            buffer_store4_t<F16>(dst, elem + 4u, (float4v){p[4] + carry, p[5] + carry, p[6] + carry, p[7] + carry});
+            buffer_store8_t<F16>(dst, (uint32_t)(kTile * u + 8 * id.lane), (float4v){p[0] + carry, p[1] + carry, p[2] + carry, p[3] + carry},
+                                 (float4v){p[4] + carry, p[5] + carry, p[6] + carry, p[7] + carry});
         }
     }
     return fresh;
@@ -720,9 +717,7 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_segment_kernel(const _Floa
         const float carry = pre[u] + ext;
         const float4v lo = mfma(const_tri_lo<EXCL>(id), x[u], splat(carry));
         const float4v hi = mfma(const_tri_hi<EXCL>(id), x[u], splat(carry));
-        const uint32_t elem = (uint32_t)(kTile * u + kRow * id.j + 4 * id.g);
-        buffer_store4_t<F16>(dst, elem, lo);
-        buffer_store4_t<F16>(dst, elem + 16u, hi);
+        buffer_store_tile_rows_t<F16>(dst, (uint32_t)(kTile * u), id.j, id.g, lo, hi);
     }
 }
 
