@@ -123,6 +123,11 @@ def main() -> int:
             tcr.autotune(ids[op], x, out_scan, 1 << e)
         tcr.autotune(tcr.OP_REDUCE, x, out_scan, 0)
         tcr.autotune(tcr.OP_SCAN, x, out_scan, 0)
+        for seg in (100, 196, 3000, 3001, 3 << 20):          # the lengths of the context rows without a tuned path
+            m = (n // seg) * seg
+            if m:
+                tcr.autotune(tcr.OP_SEGMENTED_SCAN, x[:m], out_scan, seg)
+                tcr.autotune(tcr.OP_SEGMENTED_REDUCE, x[:m], out_scan, seg)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -197,18 +197,32 @@ tcr_status tcr_set_variant(const char *key, const char *value);
 
 /*
  * Auto-tuning (the paper picks algorithm, wavefronts per workgroup and coarsening per segment size with an
- * auto-tuner, Section 6).  The library ships with launch shapes frozen from sweeps on MI355X; tcr_autotune
- * re-times every candidate shape for this (op, n, seg_len) on the caller's buffers -- op: 0 segmented_reduce,
- * 1 segmented_scan, 2 reduce, 3 scan (seg_len ignored) -- and makes the fastest one the choice for that class
- * of segment lengths (same log2(seg_len); one class for the one-segment operations) for the rest of the
- * process.  It SYNCHRONISES the stream, overwrites `out` with (correct) results several times, and is a no-op
- * for segment lengths with a single shape (below 1024, or not a power of two).  Every shape gives the same
- * results up to the order of binary32 additions.
- * tcr_tuning_export writes the current choices as text ("scan:14=7;reduce:20=1;", NUL terminated, truncated
- * to `capacity`) and returns the size needed; tcr_tuning_import replaces the choices with such a text
- * (TCR_ERR_INVALID_ARG if it does not parse; the empty string restores the defaults).  Not thread safe.
+ * auto-tuner, Section 6).  The library ships with choices frozen from sweeps on MI355X; tcr_autotune re-times
+ * every candidate for this (op, n, seg_len) on the caller's buffers -- op: 0 segmented_reduce, 1 segmented_scan,
+ * 2 reduce, 3 scan (seg_len ignored) -- and makes the fastest one the choice for that class of segment lengths
+ * for the rest of the process.  What is searched, per class:
+ *   powers of two from 16 to 512 (class log2(seg_len)): tiles per wavefront and wavefronts per workgroup of the
+ *     small-segment kernels, and the formulation (matrix cores or cross-lane adds);
+ *   longer powers of two and the one-segment operations (class 41): the launch shape -- scans: 12 shapes of
+ *     share size, ticketed or not, persistent chain or not, plus the two multi-kernel carry strategies of
+ *     tcr_set_variant("scan_carry"); reductions: span per wavefront and wavefronts combined -- and the formulation;
+ *   every other length from 8 elements (class floor(log2(seg_len))): which kernel takes it -- scans: fixed tiles
+ *     with marked starts (two tile shapes), one workgroup per segment, the chain on a per-segment tile grid;
+ *     reductions: masked row products, fixed tiles (two shapes), one wavefront per segment over masked tiles.
+ * tcr_autotune_irregular does the same for the tile shape of tcr_irregular_reduce (op 4; also used by
+ * tcr_irregular_moments) and tcr_irregular_scan (op 5) on the caller's offsets.
+ * Both SYNCHRONISE the stream and overwrite `out` with (correct) results several times; they are no-ops where
+ * there is a single candidate.  Every candidate gives the same results up to the order of binary32 additions.
+ * tcr_tuning_export writes the current choices as text -- "table:class=value;" items, tables scan, reduce,
+ * scan_any, reduce_any, irregular (class 0 reduce, 1 scan); value = candidate id, plus 32 in the first two tables
+ * when the class runs the cross-lane formulation -- NUL terminated, truncated to `capacity`, and returns the
+ * size needed; tcr_tuning_import replaces the choices with such a text (TCR_ERR_INVALID_ARG if it does not
+ * parse; the empty string restores the defaults; an id that does not fit a length falls back to the default
+ * when that length is used).  Not thread safe.
  */
 tcr_status tcr_autotune(int op, const void *in, float *out, uint64_t n, uint64_t seg_len, void *stream);
+tcr_status tcr_autotune_irregular(int op, const void *in, const uint64_t *offsets, float *out, uint64_t n, uint64_t nseg,
+                                  void *stream);
 uint64_t tcr_tuning_export(char *buffer, uint64_t capacity);
 tcr_status tcr_tuning_import(const char *text);
 

@@ -23,7 +23,7 @@ SCAN_EXCLUSIVE, OUT_F16, ACC_F16 = 1, 2, 4
 
 EXPORTS = (
     "tcr_segmented_reduce", "tcr_segmented_scan", "tcr_segmented_scan_ex", "tcr_scan_ex", "tcr_reduce", "tcr_scan",
-    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_irregular_moments", "tcr_autotune", "tcr_tuning_export", "tcr_tuning_import",
+    "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_irregular_moments", "tcr_autotune", "tcr_autotune_irregular", "tcr_tuning_export", "tcr_tuning_import",
     "tcr_workspace_bytes", "tcr_set_workspace", "tcr_segmented_moments",
     "tcr_set_variant", "tcr_segmented_scan_noalloc",
     "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
@@ -68,6 +68,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_segmented_scan_noalloc.restype = ctypes.c_int
     lib.tcr_autotune.argtypes = [ctypes.c_int, vp, fp, u64, u64, vp]
     lib.tcr_autotune.restype = ctypes.c_int
+    lib.tcr_autotune_irregular.argtypes = [ctypes.c_int, vp, vp, fp, u64, u64, vp]
+    lib.tcr_autotune_irregular.restype = ctypes.c_int
     lib.tcr_tuning_export.argtypes = [ctypes.c_char_p, u64]
     lib.tcr_tuning_export.restype = u64
     lib.tcr_tuning_import.argtypes = [ctypes.c_char_p]
@@ -311,6 +313,20 @@ def autotune(op: int, x: torch.Tensor, out: torch.Tensor, seg_len: int,
         st = _lib.tcr_autotune(op, x.data_ptr(), out.data_ptr(), x.numel(), seg_len, _stream_handle(stream))
     if st != OK:
         raise TcrError(st, "tcr_autotune")
+
+
+def autotune_irregular(op: int, x: torch.Tensor, offsets: torch.Tensor, out: torch.Tensor,
+                       stream: Optional[torch.cuda.Stream] = None) -> None:
+    """tcr_autotune_irregular: time the tile shapes of the irregular reduce (op 4) or scan (op 5) and keep the fastest."""
+    _check_input(x)
+    nseg = _check_offsets(x, offsets)
+    need = x.numel() if op == OP_IRREGULAR_SCAN else nseg
+    if not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.device == x.device and out.numel() >= need):
+        raise TypeError(f"out must be a contiguous float32 CUDA tensor of at least {need} elements on the input's device")
+    with torch.cuda.device(x.device):
+        st = _lib.tcr_autotune_irregular(op, x.data_ptr(), offsets.data_ptr(), out.data_ptr(), x.numel(), nseg, _stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_autotune_irregular")
 
 
 def tuning_export() -> str:

@@ -22,8 +22,8 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     if (seg_len == n) return reduce_long(x, out, n, n, true, s);
     if (!is_pow2(seg_len) || seg_len < 16) return launch_generic<false>(x, out, n, seg_len, 0u, s);
     if (seg_len <= kTile)
-        return g_variant.formulation == kMfma ? launch_reduce_small<kMfma>(x, out, n, log2u(seg_len), s)
-                                              : launch_reduce_small<kDpp>(x, out, n, log2u(seg_len), s);
+        return tuned_formulation(kTuneReduce, log2u(seg_len)) == kMfma ? launch_reduce_small<kMfma>(x, out, n, log2u(seg_len), s)
+                                                                       : launch_reduce_small<kDpp>(x, out, n, log2u(seg_len), s);
     return reduce_long(x, out, n, seg_len, false, s);
 }
 
@@ -269,6 +269,35 @@ float time_calls(F f, hipStream_t s, int reps) {
 
 }  // namespace
 
+namespace {
+
+// Times every candidate value of one table entry with `call` and leaves the fastest one there.
+// candidates: values (id + 32 * formulation) that are valid for the call at hand.
+template <typename F>
+tcr_status tune_entry(int table, int cls, const std::vector<int>& candidates, F call, hipStream_t s) {
+    init_tuning();
+    if (candidates.size() < 2) return TCR_OK;                    // nothing to choose
+    signed char* slot = &g_tuned[table][cls];
+    int best = -1;
+    float best_us = 0.0f;
+    for (int v : candidates) {
+        *slot = (signed char)v;
+        const float us = time_calls(call, s, 5);
+        if (us < 0.0f) {
+            *slot = -1;
+            return TCR_ERR_HIP;
+        }
+        if (best < 0 || us < best_us) {
+            best = v;
+            best_us = us;
+        }
+    }
+    *slot = (signed char)best;
+    return TCR_OK;
+}
+
+}  // namespace
+
 extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t n, uint64_t seg_len, void* stream) {
     if (op < 0 || op > 3) return TCR_ERR_INVALID_ARG;
     if (op >= 2) seg_len = n;
@@ -278,43 +307,62 @@ extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t 
     if (n == 0) return TCR_OK;
     if (!aligned(in, 16) || (is_scan && !aligned(out, 16))) return TCR_ERR_INVALID_ARG;     // the tuned kernels' alignment
     const bool whole = seg_len == n;
-    if (!whole && (!is_pow2(seg_len) || seg_len < 1024)) return TCR_OK;       // a single shape: nothing to choose
-    if (whole && n < 1024) return TCR_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    init_tuning();
+    const auto call = [&]() -> tcr_status {
+        return is_scan ? tcr_segmented_scan(in, out, n, seg_len, stream) : tcr_segmented_reduce(in, out, n, seg_len, stream);
+    };
+    std::vector<int> cand;
+    if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
+        // lengths without a tuned path: which kernel takes them
+        if (seg_len < 8 || (is_pow2(seg_len) && seg_len <= 8)) return TCR_OK;
+        for (int id = 0; id < (is_scan ? (int)kScanAnyCount : (int)kReduceAnyCount); ++id)
+            if (is_scan ? scan_any_valid(id, seg_len) : reduce_any_valid(id, seg_len)) cand.push_back(id);
+        return tune_entry(is_scan ? kTuneScanAny : kTuneReduceAny, floor_log2(seg_len), cand, call, s);
+    }
     const int cls = tuning_class(seg_len, whole);
-    signed char* slot = is_scan ? &g_tuned_scan[cls] : &g_tuned_reduce[cls];
-    ReduceShape cand[4];
-    const int count = is_scan ? kScanShapeCount : reduce_candidates(n, seg_len, whole, cand);
-    int best = -1;
-    float best_us = 0.0f;
-    for (int id = 0; id < count; ++id) {
-        if (is_scan && !scan_shape_valid(id, seg_len, whole)) continue;
-        if (is_scan && !kScanShapes[id].ticket && scan_shape_tile(id) > 8 * seg_len && !whole) continue;   // far oversized shares
-        *slot = (signed char)id;
-        const float us = time_calls([&]() -> tcr_status {
-            return is_scan ? tcr_segmented_scan(in, out, n, seg_len, stream) : tcr_segmented_reduce(in, out, n, seg_len, stream);
-        }, s, 5);
-        if (us < 0.0f) {
-            *slot = -1;
-            return TCR_ERR_HIP;
-        }
-        if (best < 0 || us < best_us) {
-            best = id;
-            best_us = us;
+    // both formulations of the tile arithmetic, unless tcr_set_variant has forced the cross-lane one everywhere
+    const int forms = g_variant.formulation == kMfma ? 2 : 1;
+    for (int form = 0; form < forms; ++form) {
+        const int bit = form ? kTuneFormBit : 0;
+        if (!whole && seg_len <= (uint64_t)kTile) {
+            for (int id = 0; id < kSmallShapeCount; ++id)
+                if (is_scan || small_reduce_shape_valid(id, log2u(seg_len))) cand.push_back(id + bit);
+        } else if (is_scan) {
+            for (int id = 0; id < kScanIdCount; ++id) {
+                if (!scan_shape_valid(id, seg_len, whole)) continue;
+                if (id < kScanShapeCount && !kScanShapes[id].ticket && scan_shape_tile(id) > 8 * seg_len && !whole) continue;   // far oversized shares
+                cand.push_back(id + bit);
+            }
+        } else {
+            ReduceShape shapes[4];
+            const int count = reduce_candidates(n, seg_len, whole, shapes);
+            for (int id = 0; id < count; ++id) cand.push_back(id + bit);
         }
     }
-    *slot = (signed char)best;
-    return TCR_OK;
+    return tune_entry(is_scan ? kTuneScan : kTuneReduce, cls, cand, call, s);
+}
+
+extern "C" tcr_status tcr_autotune_irregular(int op, const void* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
+                                             void* stream) {
+    if (op != 4 && op != 5) return TCR_ERR_INVALID_ARG;
+    if (nseg == 0 || n == 0) return TCR_OK;
+    const tcr_status st = validate_irregular(in, offsets, out, n, nseg);
+    if (st != TCR_OK) return st;
+    const bool is_scan = op == 5;
+    std::vector<int> cand;
+    for (int id = 0; id < (is_scan ? kIrregularScanShapeCount : kIrregularReduceShapeCount); ++id) cand.push_back(id);
+    return tune_entry(kTuneIrregular, is_scan ? 1 : 0, cand, [&]() -> tcr_status {
+        return is_scan ? tcr_irregular_scan(in, offsets, out, n, nseg, stream) : tcr_irregular_reduce(in, offsets, out, n, nseg, stream);
+    }, static_cast<hipStream_t>(stream));
 }
 
 extern "C" uint64_t tcr_tuning_export(char* buffer, uint64_t capacity) {
     init_tuning();
     std::string text;
-    for (int c = 0; c <= kWholeClass; ++c) {
-        if (g_tuned_scan[c] >= 0) text += "scan:" + std::to_string(c) + "=" + std::to_string((int)g_tuned_scan[c]) + ";";
-        if (g_tuned_reduce[c] >= 0) text += "reduce:" + std::to_string(c) + "=" + std::to_string((int)g_tuned_reduce[c]) + ";";
-    }
+    for (int t = 0; t < kTuneTables; ++t)
+        for (int c = 0; c <= kWholeClass; ++c)
+            if (g_tuned[t][c] >= 0)
+                text += std::string(kTuneTableNames[t]) + ":" + std::to_string(c) + "=" + std::to_string((int)g_tuned[t][c]) + ";";
     if (buffer != nullptr && capacity > 0) {
         const uint64_t m = text.size() < capacity - 1 ? text.size() : capacity - 1;
         std::memcpy(buffer, text.data(), m);
@@ -325,27 +373,38 @@ extern "C" uint64_t tcr_tuning_export(char* buffer, uint64_t capacity) {
 
 extern "C" tcr_status tcr_tuning_import(const char* text) {
     if (text == nullptr) return TCR_ERR_INVALID_ARG;
-    signed char scan[kWholeClass + 1], reduce[kWholeClass + 1];
-    std::memset(scan, -1, sizeof(scan));
-    std::memset(reduce, -1, sizeof(reduce));
+    signed char fresh[kTuneTables][kWholeClass + 1];
+    std::memset(fresh, -1, sizeof(fresh));
+    // ids a table accepts (a formulation bit on top for the first two); whether an id fits a given length is
+    // decided when the class is used, and an id that does not fit falls back to the default
+    const int id_limit[kTuneTables] = {kScanIdCount, 4, kScanAnyCount, kReduceAnyCount, 3};
     const char* p = text;
     while (*p != '\0') {
-        const bool is_scan = std::strncmp(p, "scan:", 5) == 0;
-        const bool is_reduce = std::strncmp(p, "reduce:", 7) == 0;
-        if (!is_scan && !is_reduce) return TCR_ERR_INVALID_ARG;
-        p += is_scan ? 5 : 7;
+        int table = -1;
+        size_t len = 0;
+        for (int t = 0; t < kTuneTables; ++t) {
+            const size_t l = std::strlen(kTuneTableNames[t]);
+            if (std::strncmp(p, kTuneTableNames[t], l) == 0 && p[l] == ':' && l > len) {
+                table = t;
+                len = l;
+            }
+        }
+        if (table < 0) return TCR_ERR_INVALID_ARG;
+        p += len + 1;
         char* end = nullptr;
         const long cls = std::strtol(p, &end, 10);
         if (end == p || *end != '=' || cls < 0 || cls > kWholeClass) return TCR_ERR_INVALID_ARG;
         p = end + 1;
-        const long id = std::strtol(p, &end, 10);
-        if (end == p || *end != ';' || id < 0 || id >= (is_scan ? kScanShapeCount : 4)) return TCR_ERR_INVALID_ARG;
+        const long v = std::strtol(p, &end, 10);
+        if (end == p || *end != ';' || v < 0 || v >= 2 * kTuneFormBit) return TCR_ERR_INVALID_ARG;
+        const bool has_form = table == kTuneScan || table == kTuneReduce;
+        if ((v & (kTuneFormBit - 1)) >= id_limit[table] || (!has_form && v >= kTuneFormBit)) return TCR_ERR_INVALID_ARG;
+        if (table == kTuneIrregular && cls > 1) return TCR_ERR_INVALID_ARG;
         p = end + 1;
-        (is_scan ? scan : reduce)[cls] = (signed char)id;
+        fresh[table][cls] = (signed char)v;
     }
     init_tuning();
-    std::memcpy(g_tuned_scan, scan, sizeof(scan));
-    std::memcpy(g_tuned_reduce, reduce, sizeof(reduce));
+    std::memcpy(g_tuned, fresh, sizeof(fresh));
     return TCR_OK;
 }
 
@@ -354,22 +413,25 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     if (op == 5) return n ? "irregular_bounds_kernel+irregular_scan_kernel" : "";
     if (op == 2 || op == 3) seg_len = n;
     if (n == 0 || seg_len == 0 || n % seg_len != 0) return "";
-    const bool mf = g_variant.formulation == kMfma;
     const bool whole = seg_len == n;
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
         if (op != 0 && op != 1) return "";
         if (op == 0) {
             if (is_pow2(seg_len) && seg_len <= 8) return "tiny_reduce_kernel";       // (16-byte aligned results)
             if (seg_len < kTiledReduceMin) return "generic_thread_kernel";
-            if (rows_reduce_takes(seg_len)) return "rows_reduce_kernel";
-            if (seg_len < kTiledReduceMax) return "irregular_reduce_kernel<regular>+irregular_groups_kernel+irregular_carry_kernel";
+            const int pick = pick_reduce_any(seg_len);
+            if (pick == kReduceAnyRows) return "rows_reduce_kernel";
+            if (pick == kReduceAnyTiles || pick == kReduceAnyTilesAlt) return "irregular_reduce_kernel<regular>+irregular_groups_kernel+irregular_carry_kernel";
             return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";
         }
         if (is_pow2(seg_len) && seg_len <= 8) return "tiny_scan_kernel";            // (the plain scan; other modes: the tiles)
-        if (chain_takes_any_length(seg_len)) return "scan_chain_kernel<mfma>";
-        return segment_kernel_takes(seg_len) ? "scan_segment_kernel" : "irregular_scan_kernel<regular>";
+        const int pick = pick_scan_any(seg_len);
+        if (pick == kScanAnyChain) return "scan_chain_kernel<mfma>";
+        return pick == kScanAnySegment ? "scan_segment_kernel" : "irregular_scan_kernel<regular>";
     }
+    const int cls = tuning_class(seg_len, whole);
     if (op == 0 || op == 2) {
+        const bool mf = tuned_formulation(kTuneReduce, cls) == kMfma;
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";
         const ReducePlan p = plan_reduce(n, seg_len, whole);
         if (p.combine == 1) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
@@ -380,15 +442,21 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         return mf ? "reduce_span_kernel<mfma,block>+reduce_final_kernel" : "reduce_span_kernel<dpp,block>+reduce_final_kernel";
     }
     if (op == 1 || op == 3) {
+        const bool mf = tuned_formulation(kTuneScan, cls) == kMfma;
         if (!whole && seg_len <= kTile) return mf ? "scan_small_kernel<mfma>" : "scan_small_kernel<dpp>";
-        const bool table = g_variant.scan_carry != kStrategyLookback;
+        // the carry strategy as scan_long resolves it
+        int strategy = g_variant.scan_carry;
+        int shape = strategy == kStrategyLookback ? pick_scan_shape(seg_len, whole) : -1;
+        if (shape == kScanIdReduceThenScan) strategy = kStrategyReduceThenScan;
+        if (shape == kScanIdScanThenPropagate) strategy = kStrategyScanThenPropagate;
+        if (shape >= kScanShapeCount) shape = default_scan_shape(seg_len, whole, mf ? kMfma : kDpp);
+        const bool table = strategy != kStrategyLookback;
         if (table && seg_len <= kCarryTile)
             return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
-        if (g_variant.scan_carry == kStrategyScanThenPropagate)
+        if (strategy == kStrategyScanThenPropagate)
             return mf ? "scan_block_kernel<mfma,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel"
                       : "scan_block_kernel<dpp,nocarry>+gather_totals_kernel+scan_partials_kernel+uniform_add_kernel";
         if (!table) {
-            const int shape = pick_scan_shape(seg_len, whole);
             if (kScanShapes[shape].persistent) return mf ? "scan_chain_kernel<mfma>" : "scan_chain_kernel<dpp>";
             if (!kScanShapes[shape].ticket) return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";
             if (scan_shape_tile(shape) >= seg_len) return mf ? "scan_block_kernel<mfma,ticket>" : "scan_block_kernel<dpp,ticket>";
@@ -438,13 +506,13 @@ extern "C" uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len) {
     const uint64_t padded = n + 7;
     uint64_t desc = 0, words = 0;
     if (scan) {
-        desc = irregular_tiles(true, padded);                     // chained tiles of 32768 elements
-        if (irregular) words = irregular_words(true, padded);     // where the tile boundaries fall among the offsets
+        desc = irregular_tiles_max(true, padded);                 // chained tiles (of the smallest tile shape)
+        if (irregular) words = irregular_words_max(true, padded); // where the tile boundaries fall among the offsets
     } else {
         // tables, one carried-segment index and one pair per tile and per group of 64 tiles; the sums of squares
         // add a second set of pairs
-        const uint64_t tiles = irregular_tiles(false, padded);
-        words = irregular_words(false, padded) + (moments ? tiles + ceil_div(tiles, kWave) : 0);
+        const uint64_t tiles = irregular_tiles_max(false, padded);
+        words = irregular_words_max(false, padded) + (moments ? tiles + ceil_div(tiles, kWave) : 0);
     }
     if (!irregular) {
         // Regular calls run the tiled kernels above for some lengths and alignments; otherwise, over every variant

@@ -28,20 +28,86 @@ inline tcr_status check_launch(const char* what) {
 }
 
 
+// ---------------------------------------------------------------------------- tuning table
+// The paper selects algorithm, wavefronts per workgroup and coarsening per segment size with an
+// auto-tuner (Section 6).  Here the defaults are frozen from sweeps on MI355X; tcr_autotune can
+// re-time the candidates on the machine at hand and override the default for one class of
+// segment lengths (index log2(seg_len), or kWholeClass for the one-segment operations).
+constexpr int kWholeClass = 41;
+// One table per kind of choice; an entry is -1 (the frozen default) or  id + 32 * formulation:
+//   kTuneScan, kTuneReduce      powers of two from 16 and the one-segment operations, class = log2(seg_len) or
+//                               kWholeClass.  id: a launch shape (small segments: kSmallScanShapes /
+//                               kSmallReduceShapes; longer: kScanShapes incl. the two multi-kernel carry
+//                               strategies / reduce_candidates); formulation 1 forces the cross-lane (DPP)
+//                               arithmetic for the class (0: whatever tcr_set_variant says, matrix cores by default).
+//   kTuneScanAny, kTuneReduceAny  every other seg_len, class = floor(log2(seg_len)).  id: which kernel takes the
+//                               length (see scan_any_candidates / reduce_any_candidates).
+//   kTuneIrregular              class 0: tile shape of tcr_irregular_reduce / _moments, class 1: of tcr_irregular_scan.
+enum TuneTable { kTuneScan = 0, kTuneReduce = 1, kTuneScanAny = 2, kTuneReduceAny = 3, kTuneIrregular = 4, kTuneTables = 5 };
+constexpr const char* kTuneTableNames[kTuneTables] = {"scan", "reduce", "scan_any", "reduce_any", "irregular"};
+constexpr int kTuneFormBit = 32;
+inline signed char g_tuned[kTuneTables][kWholeClass + 1];
+inline bool g_tuning_initialised = false;
+inline void init_tuning() {
+    if (g_tuning_initialised) return;
+    std::memset(g_tuned, -1, sizeof(g_tuned));
+    g_tuning_initialised = true;
+}
+inline int tuning_class(uint64_t seg_len, bool whole) { return whole ? kWholeClass : log2u(seg_len); }
+inline int floor_log2(uint64_t v) {
+    int l = 0;
+    while ((v >> (l + 1)) != 0) ++l;
+    return l;
+}
+// The shape id chosen for a class (-1: none) and the formulation its kernels run.
+inline int tuned_id(int table, int cls) {
+    init_tuning();
+    const int v = g_tuned[table][cls];
+    return v < 0 ? -1 : (v & (kTuneFormBit - 1));
+}
+inline int tuned_formulation(int table, int cls) {
+    init_tuning();
+    const int v = g_tuned[table][cls];
+    return (v >= 0 && (v & kTuneFormBit)) ? kDpp : g_variant.formulation;
+}
+
+
 // ---------------------------------------------------------------------------- reduce dispatch
-template <int FORM>
-inline tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
-    constexpr int U = kSmallReduceU, W = kSmallReduceW;
+// Launch shapes of the small-segment kernels (U tiles per wavefront, W wavefronts per workgroup); id 0 is the
+// frozen default of each.
+struct SmallShape { int u, w; };
+constexpr SmallShape kSmallReduceShapes[] = {{kSmallReduceU, kSmallReduceW}, {1, 4}, {1, 8}, {4, 4}};
+constexpr SmallShape kSmallScanShapes[] = {{1, kSmallScanW}, {1, 4}, {2, 2}, {2, 4}};
+constexpr int kSmallShapeCount = 4;
+// reduce_small keeps one result per lane: U * 512 / seg_len <= 64
+inline bool small_reduce_shape_valid(int id, int log2l) {
+    return id >= 0 && id < kSmallShapeCount && ((kTile >> log2l) * kSmallReduceShapes[id].u <= kWave);
+}
+
+template <int FORM, int U, int W>
+inline void launch_reduce_small_shape(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
     const uint64_t blocks = ceil_div(n, (uint64_t)kTile * U * W);
     const dim3 grid((unsigned)blocks), block(W * kWave);
     switch (log2l) {
-        case 4: reduce_small_kernel<FORM, 4, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+        case 4: if constexpr (U <= 2) reduce_small_kernel<FORM, 4, U, W><<<grid, block, 0, s>>>(in, out, n); break;
         case 5: reduce_small_kernel<FORM, 5, U, W><<<grid, block, 0, s>>>(in, out, n); break;
         case 6: reduce_small_kernel<FORM, 6, U, W><<<grid, block, 0, s>>>(in, out, n); break;
         case 7: reduce_small_kernel<FORM, 7, U, W><<<grid, block, 0, s>>>(in, out, n); break;
         case 8: reduce_small_kernel<FORM, 8, U, W><<<grid, block, 0, s>>>(in, out, n); break;
-        case 9: reduce_small_kernel<FORM, 9, U, W><<<grid, block, 0, s>>>(in, out, n); break;
-        default: return TCR_ERR_UNSUPPORTED;
+        default: reduce_small_kernel<FORM, 9, U, W><<<grid, block, 0, s>>>(in, out, n); break;
+    }
+}
+
+template <int FORM>
+inline tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n, int log2l, hipStream_t s) {
+    if (log2l < 4 || log2l > 9) return TCR_ERR_UNSUPPORTED;
+    int shape = tuned_id(kTuneReduce, log2l);
+    if (!small_reduce_shape_valid(shape, log2l)) shape = 0;
+    switch (shape) {
+        case 1: launch_reduce_small_shape<FORM, 1, 4>(in, out, n, log2l, s); break;
+        case 2: launch_reduce_small_shape<FORM, 1, 8>(in, out, n, log2l, s); break;
+        case 3: launch_reduce_small_shape<FORM, 4, 4>(in, out, n, log2l, s); break;
+        default: launch_reduce_small_shape<FORM, kSmallReduceU, kSmallReduceW>(in, out, n, log2l, s); break;
     }
     return check_launch("reduce_small_kernel");
 }
@@ -86,23 +152,6 @@ struct ReducePlan {
 };
 
 
-// ---------------------------------------------------------------------------- tuning table
-// The paper selects algorithm, wavefronts per workgroup and coarsening per segment size with an
-// auto-tuner (Section 6).  Here the defaults are frozen from sweeps on MI355X; tcr_autotune can
-// re-time the candidates on the machine at hand and override the default for one class of
-// segment lengths (index log2(seg_len), or kWholeClass for the one-segment operations).
-constexpr int kWholeClass = 41;
-inline signed char g_tuned_scan[kWholeClass + 1];
-inline signed char g_tuned_reduce[kWholeClass + 1];
-inline bool g_tuning_initialised = false;
-inline void init_tuning() {
-    if (g_tuning_initialised) return;
-    std::memset(g_tuned_scan, -1, sizeof(g_tuned_scan));
-    std::memset(g_tuned_reduce, -1, sizeof(g_tuned_reduce));
-    g_tuning_initialised = true;
-}
-inline int tuning_class(uint64_t seg_len, bool whole) { return whole ? kWholeClass : log2u(seg_len); }
-
 // Reduce candidates for seg_len >= 1024 (power of two) or one segment: (span, combine) pairs.
 struct ReduceShape { uint64_t span; int combine; };
 inline int reduce_candidates(uint64_t n, uint64_t seg_len, bool whole, ReduceShape* c) {
@@ -135,10 +184,9 @@ inline int reduce_candidates(uint64_t n, uint64_t seg_len, bool whole, ReduceSha
 
 // seg_len >= 1024 (a power of two), or one segment of any length (whole).
 inline ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
-    init_tuning();
     ReduceShape cand[4];
     const int count = reduce_candidates(n, seg_len, whole, cand);
-    int pick = g_tuned_reduce[tuning_class(seg_len, whole)];
+    int pick = tuned_id(kTuneReduce, tuning_class(seg_len, whole));
     if (pick < 0 || pick >= count) {
         // frozen defaults: segments of 8192 .. 32768 elements are split over 2 or 4 wavefronts
         pick = (whole || seg_len < 8192 || seg_len > 32768) ? 0 : (seg_len == 8192 ? 1 : 2);
@@ -154,6 +202,7 @@ inline ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
 
 inline tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64_t seg_len, bool whole, hipStream_t s) {
     const ReducePlan p = plan_reduce(n, seg_len, whole);
+    const int form = tuned_formulation(kTuneReduce, tuning_class(seg_len, whole));
     const uint64_t nseg = whole ? 1 : n / seg_len;
     float* dst = out;
     Workspace* ws = nullptr;
@@ -172,7 +221,7 @@ inline tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64
         tcr_status st = begin_lookback(ws, s, 0, &dev, false);   // the running counter that also hands out scan tiles
         if (st != TCR_OK) return st;
         const ReduceFinish fin = {out, dev.ticket, dev.ticket_base, (uint32_t)nseg, (uint32_t)p.per};
-        st = g_variant.formulation == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s, &fin)
+        st = form == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s, &fin)
                                             : launch_reduce_span<kDpp>(in, dst, n, p.span, p.nspans, p.combine, s, &fin);
         if (st != TCR_OK) {
             ws->dirty = true;
@@ -181,7 +230,7 @@ inline tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64
         ws->tickets_issued += (uint32_t)(nseg * p.per);   // one count per workgroup
         return TCR_OK;
     }
-    tcr_status st = g_variant.formulation == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s)
+    tcr_status st = form == kMfma ? launch_reduce_span<kMfma>(in, dst, n, p.span, p.nspans, p.combine, s)
                                                    : launch_reduce_span<kDpp>(in, dst, n, p.span, p.nspans, p.combine, s);
     if (st != TCR_OK) return st;
     if (p.per > 1) {
@@ -194,19 +243,30 @@ inline tcr_status reduce_long(const _Float16* in, float* out, uint64_t n, uint64
 
 // ---------------------------------------------------------------------------- scan dispatch
 // MODE bit 0: exclusive, bit 1: binary16 output (TCR_SCAN_EXCLUSIVE, TCR_OUT_F16).
-template <int FORM, int MODE>
-inline tcr_status launch_scan_small(const _Float16* in, void* out, uint64_t n, int log2l, hipStream_t s) {
-    constexpr int W = kSmallScanW;
-    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * W);
+template <int FORM, int MODE, int U, int W>
+inline void launch_scan_small_shape(const _Float16* in, void* out, uint64_t n, int log2l, hipStream_t s) {
+    const uint64_t blocks = ceil_div(n, (uint64_t)kTile * U * W);
     const dim3 grid((unsigned)blocks), block(W * kWave);
     switch (log2l) {
-        case 4: scan_small_kernel<FORM, 4, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
-        case 5: scan_small_kernel<FORM, 5, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
-        case 6: scan_small_kernel<FORM, 6, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
-        case 7: scan_small_kernel<FORM, 7, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
-        case 8: scan_small_kernel<FORM, 8, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
-        case 9: scan_small_kernel<FORM, 9, 1, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
-        default: return TCR_ERR_UNSUPPORTED;
+        case 4: scan_small_kernel<FORM, 4, U, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 5: scan_small_kernel<FORM, 5, U, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 6: scan_small_kernel<FORM, 6, U, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 7: scan_small_kernel<FORM, 7, U, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        case 8: scan_small_kernel<FORM, 8, U, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+        default: scan_small_kernel<FORM, 9, U, W, MODE><<<grid, block, 0, s>>>(in, out, n); break;
+    }
+}
+
+template <int FORM, int MODE>
+inline tcr_status launch_scan_small(const _Float16* in, void* out, uint64_t n, int log2l, hipStream_t s) {
+    if (log2l < 4 || log2l > 9) return TCR_ERR_UNSUPPORTED;
+    int shape = tuned_id(kTuneScan, log2l);
+    if (shape < 0 || shape >= kSmallShapeCount) shape = 0;
+    switch (shape) {
+        case 1: launch_scan_small_shape<FORM, MODE, 1, 4>(in, out, n, log2l, s); break;
+        case 2: launch_scan_small_shape<FORM, MODE, 2, 2>(in, out, n, log2l, s); break;
+        case 3: launch_scan_small_shape<FORM, MODE, 2, 4>(in, out, n, log2l, s); break;
+        default: launch_scan_small_shape<FORM, MODE, 1, kSmallScanW>(in, out, n, log2l, s); break;
     }
     return check_launch("scan_small_kernel");
 }
@@ -234,9 +294,13 @@ constexpr ScanShape kScanShapes[] = {{1, 2, false, 0}, {1, 4, false, 0}, {1, 8, 
                                      {2, 16, false, 0}, {4, 16, false, 0}, {8, 16, false, 0}, {2, 16, true, 0},
                                      {4, 16, true, 0}, {8, 16, true, 0}, {4, 16, true, 1}, {8, 8, true, 1}};
 constexpr int kScanShapeCount = 12;
+// Two more ids choose a multi-kernel carry strategy instead of a single-pass shape (segments longer than one
+// 65536-element share only): the paper's three-kernel scan-then-propagate (Section 5) and reduce-then-scan.
+constexpr int kScanIdReduceThenScan = 12, kScanIdScanThenPropagate = 13, kScanIdCount = 14;
 inline uint64_t scan_shape_tile(int id) { return (uint64_t)kTile * kScanShapes[id].u * kScanShapes[id].w; }
 
 inline bool scan_shape_valid(int id, uint64_t len, bool whole) {      // len: seg_len, or n for the one-segment scan
+    if (id == kScanIdReduceThenScan || id == kScanIdScanThenPropagate) return len > kCarryTile;
     if (id < 0 || id >= kScanShapeCount) return false;
     if (kScanShapes[id].persistent)                             // (whole: len == n, which must be a multiple of 8)
         return whole ? len % 8 == 0 : len >= scan_shape_tile(id);
@@ -256,7 +320,7 @@ inline int compute_units() {
     return cached[dev];
 }
 
-inline int default_scan_shape(uint64_t len, bool whole) {
+inline int default_scan_shape(uint64_t len, bool whole, int form) {
     if (len <= 1024) return 0;
     if (len <= 2048) return 1;
     if (len <= 4096) return 2;
@@ -264,15 +328,15 @@ inline int default_scan_shape(uint64_t len, bool whole) {
     if (!whole && len <= 16384) return 7;          // one ticketed share per segment (two segments of 8192)
     // the pipelined chain: segments of 32768 and more, one segment with n % 8 == 0.  (16 wavefronts of 4 tiles
     // for the matrix cores; the DPP arithmetic needs more registers and takes 8 wavefronts of 8 tiles.)
-    if (scan_shape_valid(10, len, whole)) return g_variant.formulation == kMfma ? 10 : 11;
+    if (scan_shape_valid(10, len, whole)) return form == kMfma ? 10 : 11;
     // n not a multiple of 8: scan_block_kernel shares of 65536 / 32768 elements with decoupled look-back
     return (whole || len >= (1u << 20)) ? 9 : 8;
 }
 
-int pick_scan_shape(uint64_t len, bool whole) {
-    init_tuning();
-    const int tuned = g_tuned_scan[tuning_class(len, whole)];
-    return scan_shape_valid(tuned, len, whole) ? tuned : default_scan_shape(len, whole);
+inline int pick_scan_shape(uint64_t len, bool whole) {
+    const int cls = tuning_class(len, whole);
+    const int tuned = tuned_id(kTuneScan, cls);
+    return scan_shape_valid(tuned, len, whole) ? tuned : default_scan_shape(len, whole, tuned_formulation(kTuneScan, cls));
 }
 
 template <int FORM, int CARRY, int MODE>
@@ -339,14 +403,19 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
     const uint64_t seg_mask = whole ? ~0ull : seg_len - 1;
     const uint64_t host_seg_len = seg_len;            // decides the launch; the kernels see a saturated
     if (whole) seg_len = ~0ull;                       // length for the one-segment case (n need not be a power of two)
-    const bool table = g_variant.scan_carry != kStrategyLookback;     // the two multi-kernel strategies
+    // the carry strategy: forced by tcr_set_variant, else the class's tuned choice, else the single pass
+    int strategy = g_variant.scan_carry;
+    int shape = strategy == kStrategyLookback ? pick_scan_shape(host_seg_len, whole) : -1;
+    if (shape == kScanIdReduceThenScan) strategy = kStrategyReduceThenScan;
+    if (shape == kScanIdScanThenPropagate) strategy = MODE == 0 ? kStrategyScanThenPropagate : kStrategyLookback;
+    if (shape >= kScanShapeCount) shape = default_scan_shape(host_seg_len, whole, FORM);    // (the strategies have fixed shapes)
+    const bool table = strategy != kStrategyLookback;     // the two multi-kernel strategies
     if (table && host_seg_len <= kCarryTile) {
         const ScanWorkspace none = {};
         launch_scan_shape<FORM, kNoCarry, MODE>(nocarry_shape_for(host_seg_len), in, out, n, seg_mask, seg_len, none, nullptr, s);
         return check_launch("scan_block_kernel");
     }
     if (!table) {
-        const int shape = pick_scan_shape(host_seg_len, whole);
         if (!kScanShapes[shape].ticket) {
             const ScanWorkspace none = {};
             launch_scan_shape<FORM, kNoCarry, MODE>(shape, in, out, n, seg_mask, seg_len, none, nullptr, s);
@@ -370,7 +439,7 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
         ws->tickets_issued += (uint32_t)tiles;      // one per workgroup; wraps modulo 2^32 like the device counter
         return TCR_OK;
     }
-    if (g_variant.scan_carry == kStrategyScanThenPropagate) {
+    if (strategy == kStrategyScanThenPropagate) {
         // the paper's three kernels; totals are read back from the binary32 inclusive output
         if (MODE != 0) return TCR_ERR_UNSUPPORTED;
         const uint64_t shares = ceil_div(n, kCarryTile);
@@ -416,59 +485,87 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
     return check_launch("scan_block_kernel");
 }
 
-// Irregular segments over 16-byte aligned arrays: fixed tiles of the flat array, whatever the segments.
-constexpr int kIrregularScanU = 4, kIrregularScanW = 16;        // 32768-element tiles, chained
-constexpr int kIrregularReduceU = 4, kIrregularReduceW = 8;     // 16384-element tiles, independent
-inline uint64_t irregular_tiles(bool scan, uint64_t n) {
-    return ceil_div(n, (uint64_t)kTile * (scan ? kIrregularScanU * kIrregularScanW : kIrregularReduceU * kIrregularReduceW));
+// Irregular segments: fixed tiles of the flat array, whatever the segments.  Tile shapes (U sub-tiles of 512
+// elements per wavefront, W wavefronts); id 0 is the frozen default: 32768-element tiles for the chained scan,
+// 16384-element tiles for the reduction, whose tiles are independent.
+constexpr SmallShape kIrregularScanShapes[] = {{4, 16}, {2, 16}};
+constexpr SmallShape kIrregularReduceShapes[] = {{4, 8}, {8, 8}, {2, 8}};
+constexpr int kIrregularScanShapeCount = 2, kIrregularReduceShapeCount = 3;
+inline int irregular_shape(bool scan) {
+    const int id = tuned_id(kTuneIrregular, scan ? 1 : 0);
+    return (id >= 0 && id < (scan ? kIrregularScanShapeCount : kIrregularReduceShapeCount)) ? id : 0;
 }
+inline uint64_t irregular_tile_elems(bool scan, int shape) {
+    const SmallShape t = scan ? kIrregularScanShapes[shape] : kIrregularReduceShapes[shape];
+    return (uint64_t)kTile * t.u * t.w;
+}
+inline uint64_t irregular_tiles(bool scan, uint64_t n, int shape) { return ceil_div(n, irregular_tile_elems(scan, shape)); }
 // 8-byte words of the partials area: the look-up table(s) of the tile boundaries, and for the reduction one
 // carried-segment index and one pair per tile and one pair per group of 64 tiles.
-inline uint64_t irregular_words(bool scan, uint64_t n) {
-    const uint64_t tiles = irregular_tiles(scan, n);
+inline uint64_t irregular_words(bool scan, uint64_t n, int shape) {
+    const uint64_t tiles = irregular_tiles(scan, n, shape);
     return scan ? tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
+}
+// The largest of these over the tile shapes (the smallest tiles): what tcr_workspace_bytes reports.
+inline uint64_t irregular_tiles_max(bool scan, uint64_t n) {
+    uint64_t m = 0;
+    for (int id = 0; id < (scan ? kIrregularScanShapeCount : kIrregularReduceShapeCount); ++id)
+        if (irregular_tiles(scan, n, id) > m) m = irregular_tiles(scan, n, id);
+    return m;
+}
+inline uint64_t irregular_words_max(bool scan, uint64_t n) {
+    uint64_t m = 0;
+    for (int id = 0; id < (scan ? kIrregularScanShapeCount : kIrregularReduceShapeCount); ++id)
+        if (irregular_words(scan, n, id) > m) m = irregular_words(scan, n, id);
+    return m;
 }
 
 // The tiles start at the 16-byte boundary at or below `in`: `shift` elements in front of it (0 for aligned arrays).
 inline uint32_t alignment_shift(const _Float16* in) { return (uint32_t)((reinterpret_cast<uintptr_t>(in) & 15u) / 2u); }
 
 // offsets == nullptr: regular segments of seg_len elements (no look-up table; MODE as for the other scans).
-// in: 2-byte aligned; out: aligned to its element size.
+// in: 2-byte aligned; out: aligned to its element size.  shape: an id of kIrregularScanShapes.
+template <int MODE, int U, int W>
+inline void launch_irregular_scan_shape(bool regular, const _Float16* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
+                                        const uint64_t* starts, uint64_t seg_len, uint32_t shift, uint32_t vector_stores,
+                                        const ScanWorkspace& dev, uint64_t tiles, hipStream_t s) {
+    const dim3 grid((unsigned)tiles), block(W * kWave);
+    if (regular) irregular_scan_kernel<U, W, true, MODE><<<grid, block, 0, s>>>(in, nullptr, out, n, nseg, nullptr, seg_len, shift, vector_stores, dev);
+    else irregular_scan_kernel<U, W, false, MODE><<<grid, block, 0, s>>>(in, offsets, out, n, nseg, starts, 0, shift, vector_stores, dev);
+}
+
 template <int MODE>
 inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offsets, void* out, uint64_t n, uint64_t nseg,
-                                        uint64_t seg_len, hipStream_t s) {
-    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularScanU * kIrregularScanW;
+                                        uint64_t seg_len, hipStream_t s, int shape = -1) {
+    if (shape < 0) shape = irregular_shape(true);
+    const uint64_t elems = irregular_tile_elems(true, shape);
     const uint32_t shift = alignment_shift(in);
     in -= shift;
     out = static_cast<char*>(out) - (size_t)shift * ((MODE & 2) ? 2 : 4);
     n += shift;
     const uint32_t vector_stores = aligned(out, 16) ? 1u : 0u;
-    const uint64_t tiles = irregular_tiles(true, n);
+    const uint64_t tiles = irregular_tiles(true, n, shape);
     const bool regular = offsets == nullptr;
     Workspace* ws = nullptr;
     bool capturing = false;
     tcr_status st = get_workspace(s, &ws, &capturing);
     if (st != TCR_OK) return st;
     if (!regular) {
-        st = ensure_partials(ws, s, 2 * irregular_words(true, n), capturing);
+        st = ensure_partials(ws, s, 2 * irregular_words(true, n, shape), capturing);
         if (st != TCR_OK) return st;
     }
     ScanWorkspace dev = {};
     st = begin_lookback(ws, s, tiles, &dev, capturing);
     if (st != TCR_OK) return st;
     uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
-    const dim3 grid((unsigned)tiles), block(kIrregularScanW * kWave);
-    if (regular) {
-        irregular_scan_kernel<kIrregularScanU, kIrregularScanW, true, MODE><<<grid, block, 0, s>>>(in, nullptr, out, n, nseg, nullptr,
-                                                                                                 seg_len, shift, vector_stores, dev);
-    } else {
+    if (!regular) {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-            offsets, nseg + 1, kElems, tiles + 1, shift, starts, nullptr);
+            offsets, nseg + 1, elems, tiles + 1, shift, starts, nullptr);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
-        irregular_scan_kernel<kIrregularScanU, kIrregularScanW, false, MODE><<<grid, block, 0, s>>>(in, offsets, out, n, nseg, starts,
-                                                                                                  0, shift, vector_stores, dev);
     }
+    if (shape == 1) launch_irregular_scan_shape<MODE, 2, 16>(regular, in, offsets, out, n, nseg, starts, seg_len, shift, vector_stores, dev, tiles, s);
+    else launch_irregular_scan_shape<MODE, 4, 16>(regular, in, offsets, out, n, nseg, starts, seg_len, shift, vector_stores, dev, tiles, s);
     st = check_launch("irregular_scan_kernel");
     if (st != TCR_OK) {
         ws->dirty = true;
@@ -479,14 +576,31 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
 }
 
 // offsets == nullptr: regular segments of seg_len elements (no look-up tables).
-// kind: kSum, kSquares (regular segments only), or kBoth with the sums of squares in out2.
+// kind: kSum, kSquares (regular segments only), or kBoth with the sums of squares in out2.  shape: an id of
+// kIrregularReduceShapes.
+template <int U, int W>
+inline void launch_irregular_reduce_shape(bool regular, int kind, const _Float16* in, const uint64_t* offsets, float* out, float* out2,
+                                          uint64_t n, const uint64_t* starts, const uint64_t* ends, uint64_t seg_len, uint64_t nseg,
+                                          uint32_t shift, TilePair* pairs, uint64_t* carried, uint64_t tiles, hipStream_t s) {
+    const dim3 grid((unsigned)tiles), block(W * kWave);
+    if (regular) {
+        if (kind == kBoth) irregular_reduce_kernel<U, W, true, kBoth><<<grid, block, 0, s>>>(in, nullptr, out, out2, n, nullptr, nullptr, seg_len, nseg, shift, pairs, carried);
+        else if (kind == kSquares) irregular_reduce_kernel<U, W, true, kSquares><<<grid, block, 0, s>>>(in, nullptr, out, out2, n, nullptr, nullptr, seg_len, nseg, shift, pairs, carried);
+        else irregular_reduce_kernel<U, W, true, kSum><<<grid, block, 0, s>>>(in, nullptr, out, out2, n, nullptr, nullptr, seg_len, nseg, shift, pairs, carried);
+    } else {
+        if (kind == kBoth) irregular_reduce_kernel<U, W, false, kBoth><<<grid, block, 0, s>>>(in, offsets, out, out2, n, starts, ends, 0, nseg, shift, pairs, carried);
+        else irregular_reduce_kernel<U, W, false, kSum><<<grid, block, 0, s>>>(in, offsets, out, nullptr, n, starts, ends, 0, nseg, shift, pairs, carried);
+    }
+}
+
 inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* offsets, float* out, uint64_t n, uint64_t nseg,
-                                          uint64_t seg_len, hipStream_t s, int kind = kSum, float* out2 = nullptr) {
-    constexpr uint64_t kElems = (uint64_t)kTile * kIrregularReduceU * kIrregularReduceW;
+                                          uint64_t seg_len, hipStream_t s, int kind = kSum, float* out2 = nullptr, int shape = -1) {
+    if (shape < 0) shape = irregular_shape(false);
+    const uint64_t elems = irregular_tile_elems(false, shape);
     const uint32_t shift = alignment_shift(in);
     in -= shift;
     n += shift;
-    const uint64_t tiles = irregular_tiles(false, n);
+    const uint64_t tiles = irregular_tiles(false, n, shape);
     const uint64_t groups = ceil_div(tiles, kWave);
     const bool regular = offsets == nullptr;
     const unsigned ch = kind == kBoth ? 2u : 1u;
@@ -494,34 +608,22 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     bool capturing = false;
     tcr_status st = get_workspace(s, &ws, &capturing);
     if (st != TCR_OK) return st;
-    st = ensure_partials(ws, s, 2 * (irregular_words(false, n) + (ch - 1) * (tiles + groups)), capturing);
+    st = ensure_partials(ws, s, 2 * (irregular_words(false, n, shape) + (ch - 1) * (tiles + groups)), capturing);
     if (st != TCR_OK) return st;
     uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
     uint64_t* ends = starts + (tiles + 1);
     uint64_t* carried = ends + (tiles + 1);
     TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);              // ch * tiles
     TilePair* group_pairs = pairs + ch * tiles;                                   // ch * groups
-    const dim3 grid((unsigned)tiles), block(kIrregularReduceW * kWave);
-    if (regular) {
-        const auto launch = [&](auto kind_tag) {
-            irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, true, decltype(kind_tag)::value><<<grid, block, 0, s>>>(
-                in, nullptr, out, out2, n, nullptr, nullptr, seg_len, nseg, shift, pairs, carried);
-        };
-        if (kind == kBoth) launch(std::integral_constant<int, kBoth>());
-        else if (kind == kSquares) launch(std::integral_constant<int, kSquares>());
-        else launch(std::integral_constant<int, kSum>());
-    } else {
+    if (!regular) {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-            offsets, nseg + 1, kElems, tiles + 1, shift, starts, ends);
+            offsets, nseg + 1, elems, tiles + 1, shift, starts, ends);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
-        if (kind == kBoth)
-            irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false, kBoth><<<grid, block, 0, s>>>(
-                in, offsets, out, out2, n, starts, ends, 0, nseg, shift, pairs, carried);
-        else
-            irregular_reduce_kernel<kIrregularReduceU, kIrregularReduceW, false><<<grid, block, 0, s>>>(
-                in, offsets, out, nullptr, n, starts, ends, 0, nseg, shift, pairs, carried);
     }
+    if (shape == 1) launch_irregular_reduce_shape<8, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
+    else if (shape == 2) launch_irregular_reduce_shape<2, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
+    else launch_irregular_reduce_shape<4, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
     st = check_launch("irregular_reduce_kernel");
     if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it
     const dim3 carry_grid((unsigned)ceil_div(groups, kCarryWaves), ch);
@@ -569,8 +671,31 @@ inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2
 constexpr uint64_t kTiledScanMin = 2;
 constexpr uint64_t kTiledReduceMin = 8, kTiledReduceMax = 1000;
 
+// Which kernel takes a reduction whose seg_len is no power of two (or below 16); class = floor(log2(seg_len)).
+// The default is the first valid one of: rows, tiles, the rest (one wavefront per segment over masked tiles from
+// 1000 elements, one thread per segment below 8).
+enum ReduceAny { kReduceAnyRows = 0, kReduceAnyTiles = 1, kReduceAnyTilesAlt = 2, kReduceAnyMasked = 3, kReduceAnyCount = 4 };
+constexpr uint64_t kMaskedReduceMin = 256;              // (valid for any length; pointless for short segments)
+inline bool reduce_any_valid(int id, uint64_t seg_len) {
+    switch (id) {
+        case kReduceAnyRows: return rows_reduce_takes(seg_len);
+        case kReduceAnyTiles:
+        case kReduceAnyTilesAlt: return seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax;
+        case kReduceAnyMasked: return seg_len >= kMaskedReduceMin;
+        default: return false;
+    }
+}
+inline int pick_reduce_any(uint64_t seg_len) {
+    const int tuned = tuned_id(kTuneReduceAny, floor_log2(seg_len));
+    if (reduce_any_valid(tuned, seg_len)) return tuned;
+    if (reduce_any_valid(kReduceAnyRows, seg_len)) return kReduceAnyRows;
+    if (reduce_any_valid(kReduceAnyTiles, seg_len)) return kReduceAnyTiles;
+    return kReduceAnyMasked;                            // (or one thread per segment, below 8 elements)
+}
+
 template <bool SCAN>
-inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
+inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s,
+                                 int tiles_shape = 0) {
     const uint64_t nseg = n / seg_len;
     const bool excl = (flags & TCR_SCAN_EXCLUSIVE) != 0, f16 = (flags & TCR_OUT_F16) != 0;
     // 1, 2, 4 or 8 elements (scans: the plain binary32 inclusive one): whole segments inside a lane's 8 elements.
@@ -598,16 +723,18 @@ inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint
     if constexpr (SCAN) {
         if (seg_len >= kTiledScanMin) {
             switch (flags & 3u) {
-                case 0: return launch_irregular_scan<0>(in, nullptr, out, n, nseg, seg_len, s);
-                case 1: return launch_irregular_scan<1>(in, nullptr, out, n, nseg, seg_len, s);
-                case 2: return launch_irregular_scan<2>(in, nullptr, out, n, nseg, seg_len, s);
-                default: return launch_irregular_scan<3>(in, nullptr, out, n, nseg, seg_len, s);
+                case 0: return launch_irregular_scan<0>(in, nullptr, out, n, nseg, seg_len, s, tiles_shape);
+                case 1: return launch_irregular_scan<1>(in, nullptr, out, n, nseg, seg_len, s, tiles_shape);
+                case 2: return launch_irregular_scan<2>(in, nullptr, out, n, nseg, seg_len, s, tiles_shape);
+                default: return launch_irregular_scan<3>(in, nullptr, out, n, nseg, seg_len, s, tiles_shape);
             }
         }
     } else {
-        if (rows_reduce_takes(seg_len)) return launch_rows_reduce(in, static_cast<float*>(out), nullptr, n, seg_len, kSum, s);
-        if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax)
-            return launch_irregular_reduce(in, nullptr, static_cast<float*>(out), n, nseg, seg_len, s);
+        const int pick = pick_reduce_any(seg_len);
+        if (pick == kReduceAnyRows) return launch_rows_reduce(in, static_cast<float*>(out), nullptr, n, seg_len, kSum, s);
+        if (pick == kReduceAnyTiles || pick == kReduceAnyTilesAlt)
+            return launch_irregular_reduce(in, nullptr, static_cast<float*>(out), n, nseg, seg_len, s, kSum, nullptr,
+                                           pick == kReduceAnyTilesAlt ? 1 : 0);
     }
     if (SCAN || seg_len < kTiledReduceMin) {
         generic_thread_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
@@ -736,11 +863,32 @@ inline bool chain_takes_any_length(uint64_t seg_len) {
            seg_len >= 2 * scan_shape_tile(10);
 }
 
+// Which kernel takes a scan whose seg_len is no power of two (or below 16); class = floor(log2(seg_len)).  The
+// default is the first valid one of: chain, segment, tiles.
+enum ScanAny { kScanAnyTiles = 0, kScanAnyTilesAlt = 1, kScanAnySegment = 2, kScanAnyChain = 3, kScanAnyCount = 4 };
+inline bool scan_any_valid(int id, uint64_t seg_len) {
+    switch (id) {
+        case kScanAnyTiles:
+        case kScanAnyTilesAlt: return seg_len >= kTiledScanMin;
+        case kScanAnySegment: return segment_kernel_takes(seg_len);
+        case kScanAnyChain: return chain_takes_any_length(seg_len);
+        default: return false;
+    }
+}
+inline int pick_scan_any(uint64_t seg_len) {
+    const int tuned = tuned_id(kTuneScanAny, floor_log2(seg_len));
+    if (scan_any_valid(tuned, seg_len)) return tuned;
+    if (scan_any_valid(kScanAnyChain, seg_len)) return kScanAnyChain;
+    if (scan_any_valid(kScanAnySegment, seg_len)) return kScanAnySegment;
+    return kScanAnyTiles;
+}
+
 inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_len, uint32_t flags, hipStream_t s) {
     const _Float16* x = static_cast<const _Float16*>(in);
     const int mode = (int)(flags & 3u);
     if (seg_len != n && (!is_pow2(seg_len) || seg_len < 16)) {
-        if (chain_takes_any_length(seg_len)) {
+        const int pick = pick_scan_any(seg_len);
+        if (pick == kScanAnyChain) {
             // long segments of any length that keeps 8-element groups whole: the chain on a per-segment tile grid
             switch (mode) {
                 case 0: return launch_chain<kMfma, 0>(10, x, out, n, seg_len, s);
@@ -749,7 +897,7 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
                 default: return launch_chain<kMfma, 3>(10, x, out, n, seg_len, s);
             }
         }
-        if (segment_kernel_takes(seg_len)) {
+        if (pick == kScanAnySegment) {
             switch (mode) {
                 case 0: return launch_scan_segment<0>(x, out, n, seg_len, s);
                 case 1: return launch_scan_segment<1>(x, out, n, seg_len, s);
@@ -757,13 +905,12 @@ inline tcr_status scan_any(const void* in, void* out, uint64_t n, uint64_t seg_l
                 default: return launch_scan_segment<3>(x, out, n, seg_len, s);
             }
         }
-        return launch_generic<true>(x, out, n, seg_len, flags, s);
+        return launch_generic<true>(x, out, n, seg_len, flags, s, pick == kScanAnyTilesAlt ? 1 : 0);
     }
-    if (g_variant.formulation == kDpp) {
-        // the wavefront-primitive alternative is kept for the default mode only
-        if (mode != 0) return TCR_ERR_UNSUPPORTED;
-        return scan_tuned<kDpp, 0>(x, out, n, seg_len, s);
-    }
+    // the cross-lane alternative is kept for the default mode only
+    const int form = tuned_formulation(kTuneScan, tuning_class(seg_len, seg_len == n));
+    if (form == kDpp && mode == 0) return scan_tuned<kDpp, 0>(x, out, n, seg_len, s);
+    if (g_variant.formulation == kDpp) return TCR_ERR_UNSUPPORTED;        // forced for every class: the other modes have no kernels
     switch (mode) {
         case 0: return scan_tuned<kMfma, 0>(x, out, n, seg_len, s);
         case 1: return scan_tuned<kMfma, 1>(x, out, n, seg_len, s);

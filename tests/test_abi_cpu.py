@@ -159,7 +159,7 @@ def test_tuning_table_text_round_trip(lib):
     assert lib.tuning_export() == ""
     try:
         lib.tuning_import("scan:14=8;reduce:20=1;scan:41=9;")
-        assert lib.tuning_export() == "scan:14=8;reduce:20=1;scan:41=9;"
+        assert lib.tuning_export() == "scan:14=8;scan:41=9;reduce:20=1;"           # table by table, class by class
         # the dispatcher follows the table where the choice is valid for the segment length ...
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
         lib.tuning_import("scan:14=4;")
@@ -173,10 +173,31 @@ def test_tuning_table_text_round_trip(lib):
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 16) == "scan_block_kernel<mfma,lookback>"
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
         lib.tuning_import("scan:16=0;")
-        for bad in ("scan:14", "scan:99=1;", "scan:14=12;", "reduce:20=4;", "sort:3=1;", "scan:14=8"):
+        for bad in ("scan:14", "scan:99=1;", "scan:14=14;", "reduce:20=4;", "sort:3=1;", "scan:14=8", "scan:14=64;",
+                    "scan_any:6=32;", "reduce_any:6=4;", "irregular:2=0;", "irregular:0=3;", "scan_an:6=1;"):
             with pytest.raises(lib.TcrError):
                 lib.tuning_import(bad)
         assert lib.tuning_export() == "scan:16=0;"       # a rejected text leaves the table untouched
+        # the wider tables: formulation per class (+32), carry strategies (12, 13), kernels for untuned lengths
+        n = 1 << 28
+        lib.tuning_import("scan:8=33;reduce:8=34;scan:20=12;scan:41=13;reduce:41=32;scan_any:6=1;reduce_any:9=1;irregular:0=1;irregular:1=1;")
+        assert lib.tuning_export() == "scan:8=33;scan:20=12;scan:41=13;reduce:8=34;reduce:41=32;scan_any:6=1;reduce_any:9=1;irregular:0=1;irregular:1=1;"
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, n, 256) == "scan_small_kernel<dpp>"
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, n, 512) == "scan_small_kernel<mfma>"
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, n, 256) == "reduce_small_kernel<dpp>"
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, n, 1 << 20).startswith("reduce_span_kernel+scan_partials_kernel+")
+        assert lib.kernel_name(lib.OP_SCAN, n, 0).endswith("+uniform_add_kernel")
+        assert lib.kernel_name(lib.OP_REDUCE, n, 0) == "reduce_span_kernel<dpp,block>+reduce_final_kernel"
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 600 * 7, 600).startswith("irregular_reduce_kernel<regular>")
+        lib.tuning_import("reduce_any:9=3;scan_any:11=0;scan_any:17=0;scan:12=12;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 600 * 7, 600) == "masked_wave_reduce_kernel"
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "irregular_scan_kernel<regular>"
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 3 << 20, 3 << 16) == "irregular_scan_kernel<regular>"
+        assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, n, 1 << 12) == "scan_block_kernel<mfma,nocarry>"   # a strategy needs long segments
+        lib.tuning_import("reduce_any:5=1;")                 # tiles are for 8 .. 999 elements; 33 fits, ...
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 33 * 5, 33).startswith("irregular_reduce_kernel<regular>")
+        lib.tuning_import("reduce_any:12=1;")                # ... 5000 does not: the default stays
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 5000 * 5, 5000) == "rows_reduce_kernel"
     finally:
         lib.tuning_import("")
     assert lib.tuning_export() == ""
@@ -189,7 +210,8 @@ def test_workspace_bytes_is_a_host_side_bound(lib):
     assert wb(8, 1 << 20, 16) == 0
     small, big = wb(lib.OP_SCAN, 1 << 20, 0), wb(lib.OP_SCAN, 1 << 28, 0)
     assert 768 <= small < big
-    assert big == 256 + 2 * (1 << 28) // 16384 * 8          # header + descriptors + partials
+    exact = 256 + 2 * (1 << 28) // 16384 * 8                # header + descriptors + partials: one per 16384 elements
+    assert exact <= big <= exact + 512                      # (+ one tile for an array that starts 7 elements into a tile)
     assert big % 256 == 0
     # irregular segments: look-up tables and per-tile pairs (reduce), one descriptor per 32768-element tile (scan)
     ired, iscan = wb(lib.OP_IRREGULAR_REDUCE, 1 << 28, 0), wb(lib.OP_IRREGULAR_SCAN, 1 << 28, 0)

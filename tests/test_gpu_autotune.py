@@ -97,6 +97,133 @@ def test_every_full_reduce_shape_matches_oracle(tcr, oracle, data, shape):
     assert got == oracle.reduce(x)
 
 
+# ------------------------------------------------------------------ the wider search space
+
+@pytest.mark.parametrize("form", [0, 32])
+@pytest.mark.parametrize("shape", range(4))
+@pytest.mark.parametrize("log2_seg", [4, 5, 6, 9])
+def test_every_small_segment_shape_and_formulation_matches_oracle(tcr, oracle, data, log2_seg, shape, form):
+    seg = 1 << log2_seg
+    x, xd = data
+    n = N + 512 * 37                                           # a ragged last workgroup for every shape
+    tcr.tuning_import(f"scan:{log2_seg}={shape + form};reduce:{log2_seg}={shape + form};")
+    try:
+        want = "dpp" if form else "mfma"
+        assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, n, seg) == f"scan_small_kernel<{want}>"
+        assert tcr.kernel_name(tcr.OP_SEGMENTED_REDUCE, n, seg) == f"reduce_small_kernel<{want}>"
+        scan = tcr.segmented_scan(xd[:n], seg).cpu().numpy().astype(np.float64)
+        red = tcr.segmented_reduce(xd[:n], seg).cpu().numpy().astype(np.float64)
+        excl = tcr.segmented_scan_ex(xd[:n], seg, 1).cpu().numpy().astype(np.float64)     # the other modes stay on the matrix cores
+    finally:
+        tcr.tuning_import("")
+    assert np.array_equal(scan, oracle.segmented_scan(x[:n], seg))
+    assert np.array_equal(red, oracle.segmented_reduce(x[:n], seg))
+    assert np.array_equal(excl, oracle.segmented_scan_exclusive(x[:n], seg))
+
+
+@pytest.mark.parametrize("value", [12, 13, 32 + 12, 32 + 13, 32 + 7, 32 + 9, 32 + 10, 32 + 11])
+@pytest.mark.parametrize("log2_seg", [17, 20, 41])
+def test_carry_strategies_and_formulations_as_tuned_choices(tcr, oracle, data, log2_seg, value):
+    x, xd = data
+    seg = N if log2_seg == 41 else 1 << log2_seg
+    tcr.tuning_import(f"scan:{log2_seg}={value};reduce:{log2_seg}={32 if value >= 32 else 0};")
+    try:
+        name = tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, N, seg)
+        assert ("dpp" in name) == (value >= 32)
+        if value % 32 == 12:
+            assert name.startswith("reduce_span_kernel+scan_partials_kernel+")
+        if value % 32 == 13:
+            assert name.endswith("+uniform_add_kernel")
+        scan = tcr.segmented_scan(xd[:N], seg).cpu().numpy().astype(np.float64)
+        red = tcr.segmented_reduce(xd[:N], seg).cpu().numpy().astype(np.float64)
+        f16 = tcr.segmented_scan_ex(xd[:N], seg, 2).cpu().numpy().astype(np.float64)    # no three-kernel form: falls back
+    finally:
+        tcr.tuning_import("")
+    ref = oracle.segmented_scan(x[:N], seg)
+    assert np.array_equal(scan, ref)
+    assert np.array_equal(red, oracle.segmented_reduce(x[:N], seg))
+    assert np.array_equal(f16, ref.astype(np.float16).astype(np.float64))
+    tcr.check_device_flags()
+
+
+@pytest.mark.parametrize("choice", range(4))
+@pytest.mark.parametrize("seg", [24, 100, 520, 999, 3000, 3001, 40000, 3 << 16, 100003])
+def test_every_kernel_for_other_lengths_matches_oracle(tcr, oracle, seg, choice):
+    nseg = max(3, (300000 // seg) | 1)
+    x = workloads.make_input(seg * nseg, "int4", seg % 89)
+    xd = torch.from_numpy(x).cuda()
+    cls = seg.bit_length() - 1
+    tcr.tuning_import(f"scan_any:{cls}={choice};reduce_any:{cls}={choice};")
+    try:
+        names = (tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, x.size, seg), tcr.kernel_name(tcr.OP_SEGMENTED_REDUCE, x.size, seg))
+        scan = tcr.segmented_scan(xd, seg).cpu().numpy().astype(np.float64)
+        red = tcr.segmented_reduce(xd, seg).cpu().numpy().astype(np.float64)
+        excl16 = tcr.segmented_scan_ex(xd, seg, 3).cpu().numpy().astype(np.float64)
+    finally:
+        tcr.tuning_import("")
+    assert np.array_equal(scan, oracle.segmented_scan(x, seg)), names
+    assert np.array_equal(red, oracle.segmented_reduce(x, seg)), names
+    assert np.array_equal(excl16, oracle.segmented_scan_exclusive(x, seg).astype(np.float16).astype(np.float64)), names
+    tcr.check_device_flags()
+
+
+@pytest.mark.parametrize("recipe", ["uniform16", "lognormal256", "few7"])
+@pytest.mark.parametrize("reduce_shape,scan_shape", [(0, 0), (1, 1), (2, 1)])
+def test_every_irregular_tile_shape_matches_oracle(tcr, oracle, recipe, reduce_shape, scan_shape):
+    n = (1 << 20) + 4321
+    x = workloads.make_input(n, "int8", 13)
+    off = workloads.make_offsets(n, recipe, 3).view(np.int64)
+    xd, od = torch.from_numpy(x).cuda(), torch.from_numpy(off).cuda()
+    tcr.tuning_import(f"irregular:0={reduce_shape};irregular:1={scan_shape};")
+    try:
+        red = tcr.irregular_reduce(xd, od).cpu().numpy().astype(np.float64)
+        scan = tcr.irregular_scan(xd, od).cpu().numpy().astype(np.float64)
+        a, q = tcr.irregular_moments(xd, od)
+        excl = tcr.irregular_scan_ex(xd, od, 1).cpu().numpy().astype(np.float64)
+    finally:
+        tcr.tuning_import("")
+    assert np.array_equal(red, oracle.irregular_reduce(x, off))
+    lo, hi = int(off[0]), int(off[-1])
+    assert np.array_equal(scan[lo:hi], oracle.irregular_scan(x, off)[lo:hi])
+    assert np.array_equal(excl[lo:hi], oracle.irregular_scan_exclusive(x, off)[lo:hi])
+    ra, rq = oracle.irregular_moments(x, off)
+    assert np.array_equal(a.cpu().numpy().astype(np.float64), ra) and np.array_equal(q.cpu().numpy().astype(np.float64), rq)
+    tcr.check_device_flags()
+
+
+def test_autotune_searches_every_class(tcr, oracle, data):
+    x, xd = data
+    out = torch.empty(N, dtype=torch.float32, device="cuda")
+    off = workloads.make_offsets(N, "lognormal256", 3).view(np.int64)
+    od = torch.from_numpy(off).cuda()
+    n100 = (N // 100) * 100
+    n3k = (N // 3000) * 3000
+    try:
+        tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:N], out, 64)
+        tcr.autotune(tcr.OP_SEGMENTED_REDUCE, xd[:N], out, 64)
+        tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:n100], out, 100)
+        tcr.autotune(tcr.OP_SEGMENTED_REDUCE, xd[:n100], out, 100)
+        tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:n3k], out, 3000)
+        tcr.autotune_irregular(tcr.OP_IRREGULAR_REDUCE, xd[:N], od, out)
+        tcr.autotune_irregular(tcr.OP_IRREGULAR_SCAN, xd[:N], od, out)
+        tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:N], out, 4)              # a single kernel: no entry
+        table = dict(item.split("=") for item in tcr.tuning_export().split(";") if item)
+        assert set(table) == {"scan:6", "reduce:6", "scan_any:6", "reduce_any:6", "scan_any:11", "irregular:0", "irregular:1"}
+        assert int(table["scan:6"]) % 32 in range(4) and int(table["reduce:6"]) % 32 in range(4)
+        assert int(table["reduce_any:6"]) in (0, 1, 2)                   # rows or tiles; the masked tiles start at 256
+        assert int(table["scan_any:11"]) in (0, 1, 2)                    # tiles or one workgroup per segment
+        assert np.array_equal(tcr.segmented_scan(xd[:N], 64).cpu().numpy().astype(np.float64), oracle.segmented_scan(x[:N], 64))
+        assert np.array_equal(tcr.segmented_reduce(xd[:N], 64).cpu().numpy().astype(np.float64), oracle.segmented_reduce(x[:N], 64))
+        assert np.array_equal(tcr.segmented_scan(xd[:n100], 100).cpu().numpy().astype(np.float64), oracle.segmented_scan(x[:n100], 100))
+        assert np.array_equal(tcr.segmented_reduce(xd[:n100], 100).cpu().numpy().astype(np.float64), oracle.segmented_reduce(x[:n100], 100))
+        assert np.array_equal(tcr.segmented_scan(xd[:n3k], 3000).cpu().numpy().astype(np.float64), oracle.segmented_scan(x[:n3k], 3000))
+        assert np.array_equal(tcr.irregular_reduce(xd[:N], od).cpu().numpy().astype(np.float64), oracle.irregular_reduce(x[:N], off))
+        assert np.array_equal(tcr.irregular_scan(xd[:N], od).cpu().numpy().astype(np.float64), oracle.irregular_scan(x[:N], off))
+        tcr.check_device_flags()
+    finally:
+        tcr.tuning_import("")
+
+
 def test_autotune_picks_valid_shapes_and_results_stay_exact(tcr, oracle, data):
     x, xd = data
     out = torch.empty(N, dtype=torch.float32, device="cuda")
@@ -105,11 +232,11 @@ def test_autotune_picks_valid_shapes_and_results_stay_exact(tcr, oracle, data):
         tcr.autotune(tcr.OP_SEGMENTED_REDUCE, xd[:N], out, 1 << 14)
         tcr.autotune(tcr.OP_SCAN, xd[:N], out, 0)
         tcr.autotune(tcr.OP_REDUCE, xd[:N], out, 0)
-        tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:N], out, 64)             # single shape: no entry
+        tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:N], out, 8)              # a single kernel: no entry
         table = dict(item.split("=") for item in tcr.tuning_export().split(";") if item)
         assert set(table) == {"scan:14", "reduce:14", "scan:41", "reduce:41"}
-        assert int(table["scan:14"]) in range(4, 10)                     # shares that hold a 16384-element segment
-        assert int(table["scan:41"]) in (7, 8, 9, 10, 11)
+        assert int(table["scan:14"]) % 32 in range(4, 10)                # shares that hold a 16384-element segment
+        assert int(table["scan:41"]) % 32 in (7, 8, 9, 10, 11, 12, 13)
         assert np.array_equal(tcr.segmented_scan(xd[:N], 1 << 14).cpu().numpy().astype(np.float64),
                               oracle.segmented_scan(x[:N], 1 << 14))
         assert np.array_equal(tcr.segmented_reduce(xd[:N], 1 << 14).cpu().numpy().astype(np.float64),
