@@ -16,7 +16,11 @@
  *   out     DEVICE pointer, caller owned, must not overlap `in`.  Scans: 16-byte aligned for the tuned kernels,
  *           at least the alignment of an element otherwise; reductions: 4-byte aligned.
  *   stream  a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
- *           and return; they never synchronise with the host.
+ *           and return.  They do not wait for the work; the exceptions are the calls that set up or grow a
+ *           library-owned workspace (the first chained call on a stream, a larger n, the call after a failed
+ *           launch, and one call in 2^30 per workspace), which synchronise the stream once while they allocate
+ *           and clear it.  With a caller-supplied workspace only the clearing remains; tcr_segmented_scan_noalloc
+ *           never synchronises.
  *   Inputs must be finite.  (A zero entry of a constant matrix times an infinity is NaN, so
  *   non-finite inputs poison outputs that the plain definition would leave finite.)
  *   Results for integer-valued inputs whose partial sums stay below 2^24 in magnitude are
@@ -237,8 +241,11 @@ const char *tcr_kernel_name(int op, uint64_t n, uint64_t seg_len);
 
 /*
  * Waits for `stream` and reports whether any scan kernel issued so far on the current
- * device gave up waiting for a predecessor tile's carry (a bounded wait that should never
- * expire).  Returns TCR_OK if none did, TCR_ERR_HIP otherwise.  Synchronises; for tests.
+ * device gave up waiting for a predecessor tile's carry (a bounded wait of 2^20 polls that should never
+ * expire: every predecessor holds an earlier ticket and is running).  A kernel that gives up leaves wrong
+ * results behind and the call that launched it has long returned TCR_OK; this is the only place where it
+ * shows.  Covers library-owned workspaces, the caller's and the fixed one of tcr_segmented_scan_noalloc.
+ * Returns TCR_OK if none did, TCR_ERR_HIP otherwise.  Synchronises; for tests.
  */
 tcr_status tcr_check_device_flags(void *stream);
 
@@ -261,8 +268,13 @@ tcr_status tcr_set_workspace(void *dev_ptr, uint64_t bytes);
 /* Releases every library-owned workspace.  The caller must have synchronised all streams.
  * The (small, uncached) look-back tables are kept for reuse until the process ends. */
 void tcr_release(void);
+/* Releases the library-owned workspace of `stream` on the current device (a no-op if it has none): the library
+ * keeps one per (device, stream) until told otherwise, so a caller that creates and destroys streams freely calls
+ * this before destroying one.  The caller must have synchronised the stream. */
+tcr_status tcr_release_stream(void *stream);
 
-const char *tcr_status_string(tcr_status s);
+/* Text for a status code (any int: values that are no tcr_status give "unknown status"). */
+const char *tcr_status_string(int status);
 
 /* Text of the last HIP error seen by this library on the calling thread ("" if none). */
 const char *tcr_last_hip_error(void);

@@ -26,7 +26,7 @@ EXPORTS = (
     "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_irregular_moments", "tcr_autotune", "tcr_autotune_irregular", "tcr_tuning_export", "tcr_tuning_import",
     "tcr_workspace_bytes", "tcr_set_workspace", "tcr_segmented_moments",
     "tcr_set_variant", "tcr_segmented_scan_noalloc",
-    "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_status_string", "tcr_last_hip_error",
+    "tcr_kernel_name", "tcr_check_device_flags", "tcr_release", "tcr_release_stream", "tcr_status_string", "tcr_last_hip_error",
 )
 
 
@@ -88,6 +88,8 @@ def _load() -> ctypes.CDLL:
     lib.tcr_check_device_flags.restype = ctypes.c_int
     lib.tcr_release.argtypes = []
     lib.tcr_release.restype = None
+    lib.tcr_release_stream.argtypes = [vp]
+    lib.tcr_release_stream.restype = ctypes.c_int
     lib.tcr_status_string.argtypes = [ctypes.c_int]
     lib.tcr_status_string.restype = ctypes.c_char_p
     lib.tcr_last_hip_error.argtypes = []
@@ -392,6 +394,12 @@ def check_device_flags(stream: Optional[torch.cuda.Stream] = None) -> None:
 
 def release() -> None:
     _lib.tcr_release()
+
+
+def release_stream(stream: Optional[torch.cuda.Stream] = None) -> None:
+    st = _lib.tcr_release_stream(_stream_handle(stream))
+    if st != OK:
+        raise TcrError(st, "tcr_release_stream")
 
 
 def raw() -> ctypes.CDLL:

@@ -561,8 +561,22 @@ extern "C" void tcr_release(void) {
     g_workspaces.clear();
 }
 
-extern "C" const char* tcr_status_string(tcr_status s) {
-    switch (s) {
+extern "C" tcr_status tcr_release_stream(void* stream) {
+    int dev = 0;
+    TCR_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    auto it = g_workspaces.find(std::make_pair(dev, static_cast<hipStream_t>(stream)));
+    if (it == g_workspaces.end()) return TCR_OK;
+    Workspace& w = it->second;
+    if (w.desc) g_parked_tables.push_back({dev, w.desc, w.desc_capacity});       // uncached: parked, not freed
+    if (w.partials) (void)hipFree(w.partials);
+    if (w.counters) (void)hipFree(w.counters);
+    g_workspaces.erase(it);
+    return TCR_OK;
+}
+
+extern "C" const char* tcr_status_string(int status) {
+    switch (status) {
         case TCR_OK: return "ok";
         case TCR_ERR_INVALID_ARG: return "invalid argument";
         case TCR_ERR_UNSUPPORTED: return "unsupported size or variant";

@@ -408,6 +408,25 @@ def test_workspace_grows_shrinks_and_survives_release(tcr, oracle):
     tcr.check_device_flags()
 
 
+def test_streams_that_come_and_go_release_their_workspaces(tcr, oracle):
+    # one library-owned workspace per (device, stream): a caller that creates streams freely drops each one's
+    x = workloads.make_input((1 << 19) + 8, "int8", 33)
+    xd = dev(x)
+    ref = oracle.scan(x)
+    out = torch.empty(x.size, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    for _ in range(8):
+        st = torch.cuda.Stream()
+        tcr.scan(xd, out=out, stream=st)
+        st.synchronize()
+        assert_exact(out, ref, "scan on a fresh stream")
+        tcr.release_stream(st)
+        tcr.release_stream(st)                          # nothing left: a no-op
+    tcr.scan(xd, out=out)                               # the default stream's workspace is untouched
+    assert_exact(out, ref, "default stream afterwards")
+    tcr.check_device_flags()
+
+
 @pytest.mark.parametrize("finish", ["fused", "second_kernel"])
 def test_long_reductions_both_finishes(tcr, oracle, form, finish):
     # device-level reduction: the last workgroup adds the partials (one kernel) or a second kernel does

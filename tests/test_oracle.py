@@ -342,10 +342,28 @@ def test_moments_exact_rational_and_invariants(oracle):
 
 
 def test_openmp_build_equals_the_sequential_one(oracle):
-    # the multi-core build that bench.py also times: every segment is the same sequential loop, so bit-identical
+    # the multi-core build that bench.py also times.  Segments up to 131072 elements: every segment is the same
+    # sequential loop, shared among threads, so bit-identical.
     omp = oracle.openmp()
     x = workloads.make_input(1 << 18, "uniform_pm1", 21)
-    for seg in (1, 16, 100, 256, 4096, 1 << 18):
+    for seg in (1, 16, 100, 256, 4096, 1 << 17):
         n = (x.size // seg) * seg
         assert np.array_equal(omp.segmented_reduce(x[:n], seg), oracle.segmented_reduce(x[:n], seg))
         assert np.array_equal(omp.segmented_scan(x[:n], seg), oracle.segmented_scan(x[:n], seg))
+
+
+@pytest.mark.parametrize("seg", [(1 << 17) + 8, 3 * 65536 + 17, 1 << 20])
+def test_openmp_build_chunks_long_segments(oracle, seg):
+    # longer segments (and the one-segment operations): chunks of 65536 elements side by side -- partial sums for
+    # the reduction, the two-pass form for the scan.  Only the order of binary64 additions changes: identical on
+    # integer-valued data, within parts in 10^12 of the sums' scale otherwise.
+    omp = oracle.openmp()
+    n = 2 * seg
+    xi = workloads.make_input(n, "int8", 5)
+    assert np.array_equal(omp.segmented_reduce(xi, seg), oracle.segmented_reduce(xi, seg))
+    assert np.array_equal(omp.segmented_scan(xi, seg), oracle.segmented_scan(xi, seg))
+    assert np.array_equal(omp.scan(xi), oracle.scan(xi)) and omp.reduce(xi) == oracle.reduce(xi)
+    xr = workloads.make_input(n, "normal", 6)
+    scale = np.cumsum(np.abs(xr.astype(np.float64)).reshape(-1, seg), axis=1)
+    assert np.all(np.abs(omp.segmented_scan(xr, seg) - oracle.segmented_scan(xr, seg)) <= 1e-12 * scale.reshape(-1))
+    assert np.all(np.abs(omp.segmented_reduce(xr, seg) - oracle.segmented_reduce(xr, seg)) <= 1e-12 * scale[:, -1])
