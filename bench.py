@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--log2n", type=int, default=LOG2N, help="elements = 2^log2n (default: the headline size)")
     ap.add_argument("--formulation", default="mfma", choices=["mfma", "dpp"])
     ap.add_argument("--scan-carry", default="lookback", choices=["lookback", "reduce_then_scan", "scan_then_propagate"])
+    ap.add_argument("--tile-load", default="direct", choices=["direct", "lds", "lds_dma"],
+                    help="how tiles reach the matrix-core operands for seg_len 16..512 (measured alternatives to the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tuning", default="", help="launch-shape choices to import first (tcr_tuning_import text)")
     ap.add_argument("--autotune", action="store_true",
@@ -71,6 +73,7 @@ def main() -> int:
     tcr.set_variant("reset")
     tcr.set_variant("formulation", args.formulation)
     tcr.set_variant("scan_carry", args.scan_carry)
+    tcr.set_variant("tile_load", args.tile_load)
 
     n = 1 << args.log2n
     sweep = [e for e in SWEEP if e <= args.log2n]
@@ -342,7 +345,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "cfg5 sweep: n=2^%d fp16 uniform[0,1) seed 4; segmented_reduce and segmented_scan at "
                                "seg_len=2^{%s}; fp32 accumulate and output" % (args.log2n, ",".join(map(str, sweep))),
-                   "formulation": args.formulation, "scan_carry": args.scan_carry,
+                   "formulation": args.formulation, "scan_carry": args.scan_carry, "tile_load": args.tile_load,
                    "input_sha256": workloads.sha256(x_host)[:16]},
         "roofline": roofline, "cpu_baseline": cpu, "cpu_baseline_openmp": cpu_openmp, "measured_copy_GBps": copy_gbps, "device": device, "tuning": tcr.tuning_export(), "rows": rows, "context_rows": extra,
     }

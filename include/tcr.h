@@ -189,6 +189,11 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
  *   "scan_carry"   "lookback" (default: single pass, decoupled look-back) | "reduce_then_scan" |
  *                  "scan_then_propagate" (the paper's three-kernel device-level scan, Section 5;
  *                  plain binary32 inclusive scan only)
+ *   "tile_load"    "direct" (default: every lane loads its matrix-core operand straight from memory) | "lds" (lanes
+ *                  load in lane order, stage the tile in LDS and read their operand back: the staging of the
+ *                  paper's own kernels) | "lds_dma" (the same with gfx950's load from memory into LDS).  Applies
+ *                  to tcr_segmented_reduce / tcr_segmented_scan with seg_len 16 .. 512 in their default launch
+ *                  shape; kept for the measurement that chose "direct"
  *   "untuned_reduce" "rows" (default: reductions and moments of 32 .. 8160 elements, no power of two, as masked
  *                  row products) | "tiles" (the fixed tiles with marked segment starts / one wavefront per segment
  *                  that took these lengths before; kept as the measured alternative)

@@ -231,6 +231,13 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
         else return TCR_ERR_INVALID_ARG;
         return TCR_OK;
     }
+    if (std::strcmp(key, "tile_load") == 0) {
+        if (std::strcmp(value, "direct") == 0) g_variant.tile_load = kLoadDirect;
+        else if (std::strcmp(value, "lds") == 0) g_variant.tile_load = kLoadStaged;
+        else if (std::strcmp(value, "lds_dma") == 0) g_variant.tile_load = kLoadLdsDma;
+        else return TCR_ERR_INVALID_ARG;
+        return TCR_OK;
+    }
     if (std::strcmp(key, "untuned_reduce") == 0) {
         if (std::strcmp(value, "rows") == 0) g_variant.rows_reduce = true;
         else if (std::strcmp(value, "tiles") == 0) g_variant.rows_reduce = false;

@@ -175,6 +175,35 @@ __device__ __forceinline__ half8 load8_guarded(const _Float16* __restrict__ in, 
     return v;
 }
 
+// How a tile reaches the MFMA operand registers (kept switchable for the measurement that chose kLoadDirect):
+//   kLoadDirect   every lane loads its operand -- X[j][8g .. 8g+7] for lane (j, g) -- straight from memory; the 64
+//                 loads of a wavefront still cover one contiguous KiB, only the order of the lanes inside it differs;
+//   kLoadStaged   lanes load in lane order (lane l: elements 8l .. 8l+7), write to LDS, and read their operand back
+//                 from there (the staging through shared memory of the paper's WMMA kernels);
+//   kLoadLdsDma   the same staging without the trip through registers: gfx950's 128-bit load from memory into LDS.
+// Full tiles only (tile_base + 512 <= n).
+enum TileLoad { kLoadDirect = 0, kLoadStaged = 1, kLoadLdsDma = 2 };
+template <int LOAD, bool STREAM>
+__device__ __forceinline__ half8 load_tile_operand(const _Float16* __restrict__ in, uint64_t tile_base, int j, int g, int lane, int wave) {
+    if constexpr (LOAD == kLoadDirect) {
+        return load8<STREAM>(in, tile_base + (uint64_t)(kRow * j + 8 * g));
+    } else {
+        __shared__ half8 s_stage[16][kWave];              // one KiB per wavefront, touched by that wavefront only
+        if constexpr (LOAD == kLoadStaged) {
+            s_stage[wave][lane] = load8<STREAM>(in, tile_base + (uint64_t)(8 * lane));
+        } else {
+            // lane l's 16 bytes land at the wavefront's LDS base + 16 l
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(in + tile_base + (uint64_t)(8 * lane)),
+                                             (void __attribute__((address_space(3)))*)&s_stage[wave][0], 16, 0, 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): the data has arrived in LDS
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        return s_stage[wave][4 * j + g];                  // element 32 j + 8 g of the tile
+    }
+}
+
 __device__ __forceinline__ void store4_guarded(float* __restrict__ out, uint64_t off, uint64_t n, float4v v) {
     if (off + 4 <= n) {
         *reinterpret_cast<float4v*>(out + off) = v;

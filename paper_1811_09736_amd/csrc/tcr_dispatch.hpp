@@ -103,6 +103,19 @@ inline tcr_status launch_reduce_small(const _Float16* in, float* out, uint64_t n
     if (log2l < 4 || log2l > 9) return TCR_ERR_UNSUPPORTED;
     int shape = tuned_id(kTuneReduce, log2l);
     if (!small_reduce_shape_valid(shape, log2l)) shape = 0;
+    if (FORM == kMfma && shape == 0 && g_variant.tile_load != kLoadDirect) {
+        // the measured alternatives to loading operands directly (default shape only)
+        constexpr int U = kSmallReduceU, W = kSmallReduceW;
+        const dim3 grid((unsigned)ceil_div(n, (uint64_t)kTile * U * W)), block(W * kWave);
+        const bool dma = g_variant.tile_load == kLoadLdsDma;
+        switch (log2l) {
+#define TCR_CASE(L) case L: if (dma) reduce_small_kernel<kMfma, L, U, W, kLoadLdsDma><<<grid, block, 0, s>>>(in, out, n); \
+                            else reduce_small_kernel<kMfma, L, U, W, kLoadStaged><<<grid, block, 0, s>>>(in, out, n); break;
+            TCR_CASE(4) TCR_CASE(5) TCR_CASE(6) TCR_CASE(7) TCR_CASE(8) TCR_CASE(9)
+#undef TCR_CASE
+        }
+        return check_launch("reduce_small_kernel");
+    }
     switch (shape) {
         case 1: launch_reduce_small_shape<FORM, 1, 4>(in, out, n, log2l, s); break;
         case 2: launch_reduce_small_shape<FORM, 1, 8>(in, out, n, log2l, s); break;
@@ -262,6 +275,21 @@ inline tcr_status launch_scan_small(const _Float16* in, void* out, uint64_t n, i
     if (log2l < 4 || log2l > 9) return TCR_ERR_UNSUPPORTED;
     int shape = tuned_id(kTuneScan, log2l);
     if (shape < 0 || shape >= kSmallShapeCount) shape = 0;
+    if constexpr (FORM == kMfma && MODE == 0) {
+        if (shape == 0 && g_variant.tile_load != kLoadDirect) {
+            // the measured alternatives to loading operands directly (default shape, plain mode only)
+            constexpr int W = kSmallScanW;
+            const dim3 grid((unsigned)ceil_div(n, (uint64_t)kTile * W)), block(W * kWave);
+            const bool dma = g_variant.tile_load == kLoadLdsDma;
+            switch (log2l) {
+#define TCR_CASE(L) case L: if (dma) scan_small_kernel<kMfma, L, 1, W, 0, kLoadLdsDma><<<grid, block, 0, s>>>(in, out, n); \
+                            else scan_small_kernel<kMfma, L, 1, W, 0, kLoadStaged><<<grid, block, 0, s>>>(in, out, n); break;
+                TCR_CASE(4) TCR_CASE(5) TCR_CASE(6) TCR_CASE(7) TCR_CASE(8) TCR_CASE(9)
+#undef TCR_CASE
+            }
+            return check_launch("scan_small_kernel");
+        }
+    }
     switch (shape) {
         case 1: launch_scan_small_shape<FORM, MODE, 1, 4>(in, out, n, log2l, s); break;
         case 2: launch_scan_small_shape<FORM, MODE, 2, 2>(in, out, n, log2l, s); break;

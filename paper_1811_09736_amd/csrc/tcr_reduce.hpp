@@ -43,7 +43,8 @@ __device__ __forceinline__ float sum8(half8 v) {
 
 // ------------------------------------------------------------------------------ small segments
 // Grid: one workgroup (WAVES wavefronts) per WAVES*U tiles.  n is a multiple of seg_len = 1 << LOG2L.
-template <int FORM, int LOG2L, int U, int WAVES>
+// LOAD: how the tiles reach the operand registers (TileLoad; matrix-core formulation, full tiles).
+template <int FORM, int LOG2L, int U, int WAVES, int LOAD = kLoadDirect>
 __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Float16* __restrict__ in,
                                                                      float* __restrict__ out, uint64_t n) {
     static_assert(LOG2L >= 4 && LOG2L <= 9, "");
@@ -58,7 +59,10 @@ __global__ __launch_bounds__(WAVES * kWave) void reduce_small_kernel(const _Floa
     half8 x[U];
     if (base + (uint64_t)(kTile * U) <= n) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = load8<true>(in, base + (uint64_t)(kTile * u + lane_off));
+        for (int u = 0; u < U; ++u) {
+            if constexpr (FORM == kMfma && LOAD != kLoadDirect) x[u] = load_tile_operand<LOAD, true>(in, base + (uint64_t)(kTile * u), id.j, id.g, id.lane, wave);
+            else x[u] = load8<true>(in, base + (uint64_t)(kTile * u + lane_off));
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) x[u] = load8_guarded<true>(in, base + (uint64_t)(kTile * u + lane_off), n);

@@ -67,7 +67,8 @@ __device__ __forceinline__ float scan8(half8 v, float (&p)[8]) {
 
 // ------------------------------------------------------------------------------ small segments
 // MODE bit 0: exclusive scan; bit 1: binary16 output.
-template <int FORM, int LOG2L, int U, int WAVES, int MODE = 0>
+// LOAD: how the tiles reach the operand registers (TileLoad; matrix-core formulation, full tiles).
+template <int FORM, int LOG2L, int U, int WAVES, int MODE = 0, int LOAD = kLoadDirect>
 __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float16* __restrict__ in,
                                                                    void* __restrict__ out, uint64_t n) {
     constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
@@ -82,7 +83,10 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_small_kernel(const _Float1
     half8 x[U];
     if (full) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = load8(in, base + (uint64_t)(kTile * u + lane_off));
+        for (int u = 0; u < U; ++u) {
+            if constexpr (FORM == kMfma && LOAD != kLoadDirect) x[u] = load_tile_operand<LOAD, false>(in, base + (uint64_t)(kTile * u), id.j, id.g, id.lane, wave);
+            else x[u] = load8(in, base + (uint64_t)(kTile * u + lane_off));
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + lane_off), n);

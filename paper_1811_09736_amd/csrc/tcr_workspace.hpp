@@ -43,6 +43,7 @@ struct Variant {
     int formulation = kMfma;
     int scan_carry = kStrategyLookback;
     bool reduce_fused = false;      // long reductions: a second kernel adds the partials (true: the last workgroup does)
+    int tile_load = kLoadDirect;    // small power-of-two segments, default shape and mode: how tiles reach the operand registers
     bool rows_reduce = true;        // untuned lengths from 32 elements: masked row products (false: the fixed tiles with marked starts)
 };
 inline Variant g_variant;
