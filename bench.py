@@ -174,13 +174,13 @@ def main() -> int:
         k["launches"] += len(ms)
     dom_name, dom = max(per_kernel.items(), key=lambda kv: kv[1]["ms"])
     achieved = dom["bytes"] / (dom["ms"] * 1e-3) * 1e-9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
-    if os.path.exists(tpath) and args.log2n == LOG2N:
-        with open(tpath) as fh:
-            traffic = (json.load(fh).get(dom_name) or {}).get("total_bytes")
+    # HBM bytes per launch from the committed rocprofv3 counter runs -- null unless they were taken on exactly
+    # these sources (a hash of csrc/) at the headline size and cover the dominant kernel
+    from paper_1811_09736_amd import profiling
+    traffic, traffic_note = (profiling.traffic_for(dom_name) if args.log2n == LOG2N
+                             else (None, "the counter runs are for n = 2^%d" % LOG2N))
     roofline = {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_note": traffic_note,
                 "avg_launch_us": round(dom["ms"] / dom["launches"] * 1e3, 2),
                 "algorithmic_bytes_per_launch": dom["bytes"] // dom["launches"]}
 
