@@ -81,6 +81,14 @@ __device__ __forceinline__ float read_lane(float x, int lane) {
 // Sum over all 64 lanes, returned uniformly.
 __device__ __forceinline__ float wave_sum(float x) { return read_lane(wave_scan_inclusive(x), 63); }
 
+// A workgroup barrier that orders LDS accesses only: unlike __syncthreads() it does not wait for the wavefront's
+// outstanding loads from memory, so data requested before it keeps arriving while the workgroup works on LDS.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---------------------------------------------------------------- constant operand matrices
 
 // A-operand registers of lane (i, g): entries C[i][8g .. 8g+7] of a 16 x 32 constant matrix.

@@ -515,9 +515,12 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
 
 // Irregular segments: fixed tiles of the flat array, whatever the segments.  Tile shapes (U sub-tiles of 512
 // elements per wavefront, W wavefronts); id 0 is the frozen default: 32768-element tiles for the chained scan,
-// 16384-element tiles for the reduction, whose tiles are independent.
+// 8192-element tiles of four wavefronts for the reduction, whose tiles are independent (measured at n = 2^28:
+// 109 us against 121 us with eight wavefronts of four sub-tiles on log-normal lengths, 192 against 199 us on
+// segments of 16 elements on average: a tile's work is a chain of dependent steps -- its range of offsets
+// entries, the entries, the marks, the sums -- and small workgroups keep more tiles in flight per compute unit).
 constexpr SmallShape kIrregularScanShapes[] = {{4, 16}, {2, 16}};
-constexpr SmallShape kIrregularReduceShapes[] = {{4, 8}, {8, 8}, {2, 8}};
+constexpr SmallShape kIrregularReduceShapes[] = {{4, 4}, {4, 8}, {2, 8}};
 constexpr int kIrregularScanShapeCount = 2, kIrregularReduceShapeCount = 3;
 inline int irregular_shape(bool scan) {
     const int id = tuned_id(kTuneIrregular, scan ? 1 : 0);
@@ -649,9 +652,9 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
     }
-    if (shape == 1) launch_irregular_reduce_shape<8, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
+    if (shape == 1) launch_irregular_reduce_shape<4, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
     else if (shape == 2) launch_irregular_reduce_shape<2, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
-    else launch_irregular_reduce_shape<4, 8>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
+    else launch_irregular_reduce_shape<4, 4>(regular, kind, in, offsets, out, out2, n, starts, ends, seg_len, nseg, shift, pairs, carried, tiles, s);
     st = check_launch("irregular_reduce_kernel");
     if (st != TCR_OK || tiles == 1) return st;          // a single tile has nothing in front of it
     const dim3 carry_grid((unsigned)ceil_div(groups, kCarryWaves), ch);

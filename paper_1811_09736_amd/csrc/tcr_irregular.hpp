@@ -395,6 +395,15 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     const uint64_t tb = (uint64_t)tile * kBlockTile;
     const uint64_t base = tb + (uint64_t)wave * kChunk;
     const bool full = base + kChunk <= n;
+    // which offsets entries fall into the tile: asked for first, so that the entries themselves can be requested
+    // while the tile's data is still on its way (the barriers below order LDS only and wait for neither)
+    uint64_t head_lo = 0, head_hi = 0, end_lo = 0, end_hi = 0;
+    if constexpr (!REGULAR) {
+        head_lo = starts_below[tile];
+        head_hi = starts_below[tile + 1];
+        end_lo = ends_below[tile];
+        end_hi = ends_below[tile + 1];
+    }
     half8 x[U];
     if (full) {
 #pragma unroll
@@ -422,18 +431,12 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
             s_bound[3] = q1 + 1 < entries ? q1 + 1 : entries;
         }
     }
-    __syncthreads();
-    uint64_t head_lo, head_hi, end_lo, end_hi;
+    lds_barrier();
     if constexpr (REGULAR) {
         head_lo = s_bound[0];
         head_hi = s_bound[1];
         end_lo = s_bound[2];
         end_hi = s_bound[3];
-    } else {
-        head_lo = starts_below[tile];
-        head_hi = starts_below[tile + 1];
-        end_lo = ends_below[tile];
-        end_hi = ends_below[tile + 1];
     }
     // (the first tile also takes the entries on position 0, which close empty segments in front of everything)
     if (tile == 0) end_lo = 0;
@@ -446,7 +449,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
             if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
             else if (pos == 0 && tile == 0) atomicAdd(&s_ends[0], 1u);
         }
-        __syncthreads();
+        lds_barrier();
     }
     const bool has_heads = head_lo < head_hi;
 
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
         for (int c = 0; c < CH; ++c) s_wave_value[c][wave] = w.run[c];
         s_wave_flag[wave] = w.chunk_flag;
     }
-    __syncthreads();
+    lds_barrier();
 
     if (wave == 0 && lane == 0) {
         float total[CH];
