@@ -9,6 +9,8 @@ writes text.  Usage (the rocprofv3 commands themselves are quoted in every summa
     python -m paper_1811_09736_amd.profiling mix           <kernel-stats dir> <dir of SQ counters, mfma> <dir of SQ counters, dpp>
     python -m paper_1811_09736_amd.profiling irregular     <kt dir> <fetch dir> <write dir>  (three times, one per length mix)
     python -m paper_1811_09736_amd.profiling counters      <name> <title> <kernel-stats dir> <pmc dir> [<pmc dir> ...]
+    python -m paper_1811_09736_amd.profiling repeatability <bench JSON line file> ...
+    python -m paper_1811_09736_amd.profiling tile-load     <five bench JSON line files>
 """
 from __future__ import annotations
 
@@ -295,6 +297,57 @@ def counters(name: str, title: str, kt_dir: str, pmc_dirs, commands=None) -> Non
     _write(name, out)
 
 
+def repeatability(json_files) -> None:
+    """Five (or more) JSON lines of `python bench.py --no-cpu-baseline --no-context`, run one after the other."""
+    runs = []
+    for f in json_files:
+        with open(f) as fh:
+            runs.append(json.loads(fh.read().strip().splitlines()[-1]))
+    values = [r["value"] for r in runs]
+    out = [f"# Repeatability of bench.py, cfg5 sweep (n=2^28): {len(runs)} runs in a row on one MI355X box", "",
+           f"Sources: csrc stamp {source_stamp()}, commit {_commit()}.", f"Command, {len(runs)} times:", "",
+           "    python bench.py --no-cpu-baseline --no-context", "",
+           "`value` (input GB/s over the whole step): " + ", ".join(f"{v:.1f}" for v in values) +
+           f"; spread {100 * (max(values) - min(values)) / min(values):.2f} %.", "",
+           "Per call: average of the 20 HIP-event timings of a run (us); minimum, median and maximum over the runs.", "",
+           "| op | seg_len | min | median | max | spread |", "|---|---|---:|---:|---:|---:|"]
+    for i, row in enumerate(runs[0]["rows"]):
+        t = sorted(r["rows"][i]["avg_us"] for r in runs)
+        out.append(f"| {row['op']} | 2^{row['seg_len_log2']} | {t[0]:.1f} | {t[len(t) // 2]:.1f} | {t[-1]:.1f} | "
+                   f"{100 * (t[-1] - t[0]) / t[0]:.1f} % |")
+    _write("bench_cfg5_sweep_repeatability.md", out)
+
+
+def tile_load(json_files) -> None:
+    """JSON lines of bench.py --no-context with --tile-load direct | lds | lds_dma, --formulation dpp, and direct again."""
+    names = ["direct", "lds", "lds_dma", "dpp (lane-ordered loads, no LDS)", "direct (again)"]
+    runs = []
+    for f in json_files:
+        with open(f) as fh:
+            runs.append(json.loads(fh.read().strip().splitlines()[-1]))
+    out = ["# How a tile reaches the matrix-core operands: direct operand-layout loads vs LDS staging (n = 2^28)", "",
+           f"Sources: csrc stamp {source_stamp()}, commit {_commit()}.",
+           "Commands, one after the other on one MI355X box (HIP-event averages of the `rows` of each JSON line, us):", "",
+           "    python bench.py --no-cpu-baseline --steps 10 --warmup 3 --no-context --tile-load direct",
+           "    python bench.py --no-cpu-baseline --steps 10 --warmup 3 --no-context --tile-load lds",
+           "    python bench.py --no-cpu-baseline --steps 10 --warmup 3 --no-context --tile-load lds_dma",
+           "    python bench.py --no-cpu-baseline --steps 10 --warmup 3 --no-context --formulation dpp",
+           "    python bench.py --no-cpu-baseline --steps 10 --warmup 3 --no-context --tile-load direct", "",
+           "direct: lane (j, g) loads X[j][8g .. 8g+7], its MFMA operand, with one 128-bit load (the 64 loads of a wavefront",
+           "cover one contiguous KiB in a permuted lane order).  lds: lanes load in lane order, write the tile to LDS and",
+           "read their operand back (the shared-memory staging of the paper's kernels).  lds_dma: the same with gfx950's",
+           "128-bit load from memory into LDS.  dpp: lane-ordered loads feeding the cross-lane formulation, no LDS.",
+           "The variants exist for seg_len 16 .. 512 (`reduce_small_kernel`, `scan_small_kernel`); the other rows are the",
+           "same kernels in every column and show the run-to-run spread.", "",
+           "| op | seg_len | " + " | ".join(names) + " |", "|---|---|" + "---:|" * len(names)]
+    for i, row in enumerate(runs[0]["rows"]):
+        out.append(f"| {row['op']} | 2^{row['seg_len_log2']} | " + " | ".join(f"{r['rows'][i]['avg_us']:.1f}" for r in runs) + " |")
+    out += ["", "Reading: staging through LDS buys nothing for the reductions (within the spread) and costs the scans 10-11 %",
+            "(the LDS round trip sits between a wavefront's only load and its stores); the load from memory into LDS is",
+            "slower still for short segments.  Operands are therefore loaded directly."]
+    _write("tile_load_direct_vs_lds_n2^28.md", out)
+
+
 def main(argv) -> int:
     if len(argv) < 2:
         print(__doc__)
@@ -310,6 +363,10 @@ def main(argv) -> int:
         irregular(args)
     elif kind == "counters":
         counters(args[0], args[1], args[2], args[3:])
+    elif kind == "repeatability":
+        repeatability(args)
+    elif kind == "tile-load":
+        tile_load(args)
     elif kind == "stamp":
         print(source_stamp())
     else:
