@@ -238,6 +238,13 @@ extern "C" tcr_status tcr_set_variant(const char* key, const char* value) {
         else return TCR_ERR_INVALID_ARG;
         return TCR_OK;
     }
+    if (std::strcmp(key, "irregular_scan") == 0) {
+        if (std::strcmp(value, "auto") == 0) g_variant.irregular_scan = 0;
+        else if (std::strcmp(value, "single") == 0) g_variant.irregular_scan = 1;
+        else if (std::strcmp(value, "chain") == 0) g_variant.irregular_scan = 2;
+        else return TCR_ERR_INVALID_ARG;
+        return TCR_OK;
+    }
     if (std::strcmp(key, "untuned_reduce") == 0) {
         if (std::strcmp(value, "rows") == 0) g_variant.rows_reduce = true;
         else if (std::strcmp(value, "tiles") == 0) g_variant.rows_reduce = false;
@@ -513,7 +520,8 @@ extern "C" uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len) {
     const uint64_t padded = n + 7;
     uint64_t desc = 0, words = 0;
     if (scan) {
-        desc = irregular_tiles_max(true, padded);                 // chained tiles (of the smallest tile shape)
+        // chained tiles (of the smallest tile shape); two tables of them for the two-kernel scan of irregular segments
+        desc = (irregular ? 2 : 1) * irregular_tiles_max(true, padded);
         if (irregular) words = irregular_words_max(true, padded); // where the tile boundaries fall among the offsets
     } else {
         // tables, one carried-segment index and one pair per tile and per group of 64 tiles; the sums of squares

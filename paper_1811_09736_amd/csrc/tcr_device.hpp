@@ -150,6 +150,24 @@ __device__ __forceinline__ half8 const_half_rows(const LaneId& id) {
     return c;
 }
 
+// The first `count` (0 .. 8) of a lane's eight binary16 values kept, the others cleared.
+__device__ __forceinline__ half8 keep_leading(half8 x, int count) {
+    const int c = count < 0 ? 0 : (count > 8 ? 8 : count);
+    const int clo = c < 4 ? c : 4, chi = c - clo;
+    u64x2 m;
+    m[0] = clo ? ~0ull >> (16 * (4 - clo)) : 0ull;
+    m[1] = chi ? ~0ull >> (16 * (4 - chi)) : 0ull;
+    return __builtin_bit_cast(half8, __builtin_bit_cast(u64x2, x) & m);
+}
+__device__ __forceinline__ half8 drop_leading(half8 x, int count) {
+    const int c = count < 0 ? 0 : (count > 8 ? 8 : count);
+    const int clo = c < 4 ? c : 4, chi = c - clo;
+    u64x2 m;
+    m[0] = clo ? ~0ull >> (16 * (4 - clo)) : 0ull;
+    m[1] = chi ? ~0ull >> (16 * (4 - chi)) : 0ull;
+    return __builtin_bit_cast(half8, __builtin_bit_cast(u64x2, x) & ~m);
+}
+
 __device__ __forceinline__ float4v mfma(half8 constant, half8 data, float4v acc) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(constant, data, acc, 0, 0, 0);
 }

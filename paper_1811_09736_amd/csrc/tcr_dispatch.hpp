@@ -414,8 +414,8 @@ tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, ui
     const uint64_t resident = (uint64_t)compute_units() * (uint64_t)kScanShapes[shape].persistent;
     const uint64_t groups = tiles < resident ? tiles : resident;
     const ChainGrid grid = {seg_len, (uint32_t)per_segment, (uint32_t)tiles};
-    if (shape == 10) scan_chain_kernel<FORM, 4, 16, MODE><<<dim3((unsigned)groups), dim3(16 * kWave), 0, s>>>(in, out, grid, dev);
-    else scan_chain_kernel<FORM, 8, 8, MODE><<<dim3((unsigned)groups), dim3(8 * kWave), 0, s>>>(in, out, grid, dev);
+    if (shape == 10) scan_chain_kernel<FORM, 4, 16, MODE><<<dim3((unsigned)groups), dim3(16 * kWave), 0, s>>>(in, out, grid, dev, nullptr);
+    else scan_chain_kernel<FORM, 8, 8, MODE><<<dim3((unsigned)groups), dim3(8 * kWave), 0, s>>>(in, out, grid, dev, nullptr);
     st = check_launch("scan_chain_kernel");
     if (st != TCR_OK) {
         ws->dirty = true;
@@ -535,7 +535,8 @@ inline uint64_t irregular_tiles(bool scan, uint64_t n, int shape) { return ceil_
 // carried-segment index and one pair per tile and one pair per group of 64 tiles.
 inline uint64_t irregular_words(bool scan, uint64_t n, int shape) {
     const uint64_t tiles = irregular_tiles(scan, n, shape);
-    return scan ? tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
+    // (scan: the look-up table and one TileLink per tile)
+    return scan ? 2 * tiles + 1 : 2 * (tiles + 1) + 2 * tiles + ceil_div(tiles, kWave);
 }
 // The largest of these over the tile shapes (the smallest tiles): what tcr_workspace_bytes reports.
 inline uint64_t irregular_tiles_max(bool scan, uint64_t n) {
@@ -585,15 +586,38 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
         st = ensure_partials(ws, s, 2 * irregular_words(true, n, shape), capturing);
         if (st != TCR_OK) return st;
     }
+    // Long segments -- fewer segments than a quarter of the tiles, so most tiles hold no segment start: the
+    // pipelined chain scans the tiles without a start, a second kernel the others.  (Default tile shape, 16-byte
+    // aligned arrays.)
+    const bool two_kernels = !regular && shape == 0 && shift == 0 && vector_stores != 0 && g_variant.formulation == kMfma &&
+                             g_variant.irregular_scan != 1 && (g_variant.irregular_scan == 2 || nseg <= tiles / 4);
     ScanWorkspace dev = {};
-    st = begin_lookback(ws, s, tiles, &dev, capturing);
+    st = begin_lookback(ws, s, two_kernels ? 2 * tiles : tiles, &dev, capturing);      // (two kernels: a second table behind the first)
     if (st != TCR_OK) return st;
     uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
+    TileLink* links = reinterpret_cast<TileLink*>(starts + (tiles + 1));
     if (!regular) {
         irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
-            offsets, nseg + 1, elems, tiles + 1, shift, starts, nullptr);
+            offsets, nseg + 1, elems, tiles + 1, shift, starts, nullptr, two_kernels ? links : nullptr);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
+    }
+    if (two_kernels) {
+        const uint64_t resident = (uint64_t)compute_units();
+        const uint64_t groups = tiles < resident ? tiles : resident;
+        scan_chain_kernel<kMfma, 4, 16, MODE, true><<<dim3((unsigned)groups), dim3(16 * kWave), 0, s>>>(
+            in, out, ChainGrid{n, (uint32_t)tiles, (uint32_t)tiles}, dev, links);
+        st = check_launch("scan_chain_kernel");
+        if (st != TCR_OK) {
+            ws->dirty = true;
+            return st;
+        }
+        ws->tickets_issued += (uint32_t)(tiles + 3 * groups);
+        // (every workgroup of the second kernel looks at up to 64 tiles)
+        const uint64_t second = ceil_div(tiles, kWave) > resident ? ceil_div(tiles, kWave) : (tiles < resident ? tiles : resident);
+        irregular_scan_kernel<4, 16, false, MODE, true><<<dim3((unsigned)second), dim3(16 * kWave), 0, s>>>(
+            in, offsets, out, n, nseg, starts, 0, shift, vector_stores, dev, links);
+        return check_launch("irregular_scan_kernel");
     }
     if (shape == 1) launch_irregular_scan_shape<MODE, 2, 16>(regular, in, offsets, out, n, nseg, starts, seg_len, shift, vector_stores, dev, tiles, s);
     else launch_irregular_scan_shape<MODE, 4, 16>(regular, in, offsets, out, n, nseg, starts, seg_len, shift, vector_stores, dev, tiles, s);

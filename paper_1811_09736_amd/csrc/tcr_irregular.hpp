@@ -164,7 +164,8 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
                                                                                 uint64_t count, uint64_t tile_elems,
                                                                                 uint64_t boundaries, uint32_t shift,
                                                                                 uint64_t* __restrict__ starts_below,
-                                                                                uint64_t* __restrict__ ends_below) {
+                                                                                uint64_t* __restrict__ ends_below,
+                                                                                TileLink* __restrict__ links = nullptr) {
     const int lane = threadIdx.x & (kWave - 1);
     const uint64_t i = (uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (i >= boundaries) return;
@@ -172,6 +173,18 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
     const uint64_t key = reachable ? i * tile_elems - shift : 0;
     const uint64_t below = wave_lower_bound(offsets, count, key, lane);
     if (lane == 0) starts_below[i] = below;
+    if (links != nullptr && lane == 0) {
+        // the last entry in front of boundary i: the nearest start for tile i, and the last start of tile i - 1
+        // if it lies there (boundaries = tiles + 1: tile i exists for i < boundaries - 1)
+        // (a tile without a start is covered by a segment iff some entry lies in front of it, but not all of them)
+        const bool any = below > 0;
+        const uint64_t at = any ? offsets[below - 1] + shift : 0;
+        const uint64_t in_tile = at / tile_elems;
+        if (i + 1 < boundaries) links[i].prev_head_tile = (any && in_tile < i) ? (uint32_t)in_tile : kNoHead;
+        if (i >= 1)
+            links[i - 1].last_head = (any && in_tile == i - 1) ? (uint32_t)(at - in_tile * tile_elems)
+                                                               : ((any && below < count) ? kNoHead : kOutside);
+    }
     if (ends_below == nullptr) return;
     uint64_t on = 0;                          // entries equal to key follow directly
     while (reachable) {
@@ -196,11 +209,17 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
 // arrays, where `in` is 16-byte aligned, n counts from there and entry s lies on position offsets[s] + shift;
 // the elements in front of offsets[0] + shift belong to no segment like any others outside the segments.
 // vector_stores == 0: `out` is not 16-byte aligned there and every result is stored on its own.
-template <int U, int WAVES, bool REGULAR, int MODE>
-__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(8, 8)))
-void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, void* __restrict__ out,
-                           uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, uint64_t seg_len,
-                           uint32_t shift, uint32_t vector_stores, ScanWorkspace ws_arg) {
+// SECOND == true: the second kernel of the two-kernel scan of long segments.  scan_chain_kernel has scanned every
+// tile without a segment start and published, for EVERY tile, the sum behind its last start; this kernel takes
+// the tiles WITH starts.  Nothing is waited for and nothing published: the carry of the elements in front of
+// the tile's first start is the sum of the published values from the nearest tile with a start on.
+// One tile; `given` is the tile's number for SECOND (otherwise it is drawn by ticket).
+template <int U, int WAVES, bool REGULAR, int MODE, bool SECOND>
+__device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets,
+                                                    void* __restrict__ out, uint64_t n, uint64_t nseg,
+                                                    const uint64_t* __restrict__ starts_below, uint64_t seg_len, uint32_t shift,
+                                                    uint32_t vector_stores, const ScanWorkspace& ws_arg,
+                                                    const TileLink* __restrict__ links, uint32_t given) {
     constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
     constexpr uint32_t kChunk = (uint32_t)kTile * U;          // one wavefront's share
     constexpr uint32_t kBlockTile = kChunk * WAVES;           // one workgroup's share
@@ -218,7 +237,8 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     // tiles are handed out in launch order, so every predecessor of a waiting tile is running or finished
     if (threadIdx.x == 0) {
         s_ready = 0u;
-        const uint32_t t = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
+        const uint32_t t = SECOND ? given
+                                  : __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
         s_tile = t;
         if constexpr (REGULAR) {
             // heads in [tb, tb + tile) are the multiples head_lo .. head_hi - 1 of seg_len; one thread divides for
@@ -234,7 +254,7 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
     for (uint32_t i = threadIdx.x; i < kBlockTile / 32; i += WAVES * kWave) s_heads[i] = 0u;
     __syncthreads();
     const uint32_t tile = s_tile;
-    if (tile == 0 && threadIdx.x == 0 && ws.state != nullptr && !ws.device_managed) ws.state[0] = ws.epoch;
+    if (!SECOND && tile == 0 && threadIdx.x == 0 && ws.state != nullptr && !ws.device_managed) ws.state[0] = ws.epoch;
 
     const uint64_t tb = (uint64_t)tile * kBlockTile;
     const uint64_t base = tb + (uint64_t)wave * kChunk;
@@ -306,7 +326,16 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
             // 8 descriptors per round: most tiles hold a head and finish their predecessor's wait at distance 1,
             // and chains of open tiles are short with two workgroups per compute unit (measured at n = 2^28:
             // 302 / 340 us for short / long segments with 4-8 per round, 303 / 396 with 1, 323 / 362 with 64)
-            const float pre = lookback_carry<8>(ws, tile, reach, closed, total, lane);
+            float pre = 0.0f;
+            if constexpr (SECOND) {
+                // the running sum at the end of the tile in front (the chain's second table: tiles .. 2 tiles - 1)
+                if (reach != 0u && links[tile].prev_head_tile < tile) {
+                    const uint32_t tiles = (uint32_t)((n + kBlockTile - 1) / kBlockTile);
+                    pre = __builtin_bit_cast(float, (uint32_t)load_descriptor(&ws.desc[tiles + tile - 1u]));
+                }
+            } else {
+                pre = lookback_carry<8>(ws, tile, reach, closed, total, lane);
+            }
             if (lane == 0) {
                 s_prefix = pre;
                 __hip_atomic_store(&s_ready, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -334,6 +363,32 @@ void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __re
         }
     }
 }
+
+template <int U, int WAVES, bool REGULAR, int MODE, bool SECOND = false>
+__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, void* __restrict__ out,
+                           uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, uint64_t seg_len,
+                           uint32_t shift, uint32_t vector_stores, ScanWorkspace ws_arg, const TileLink* __restrict__ links = nullptr) {
+    if constexpr (!SECOND) {
+        irregular_scan_tile<U, WAVES, REGULAR, MODE, false>(in, offsets, out, n, nseg, starts_below, seg_len, shift, vector_stores, ws_arg,
+                                                            links, 0u);
+    } else {
+        // Workgroup b looks at tiles b, b + G, b + 2 G, ... (G workgroups, at most 64 tiles each: one per lane) and
+        // takes those that hold a segment start -- a handful when segments are long.
+        constexpr uint64_t kBlockTile = (uint64_t)kTile * U * WAVES;
+        const uint64_t tiles = (n + kBlockTile - 1) / kBlockTile;
+        const uint64_t mine = (uint64_t)blockIdx.x + (uint64_t)gridDim.x * (uint64_t)(threadIdx.x & (kWave - 1));
+        unsigned long long todo = __ballot(mine < tiles && links[mine < tiles ? mine : 0].last_head < kOutside);
+        while (todo != 0ull) {
+            const uint32_t bit = (uint32_t)__builtin_ctzll(todo);
+            todo &= todo - 1ull;
+            irregular_scan_tile<U, WAVES, REGULAR, MODE, true>(in, offsets, out, n, nseg, starts_below, seg_len, shift, vector_stores,
+                                                               ws_arg, links, blockIdx.x + gridDim.x * bit);
+            __syncthreads();                  // the tile's LDS is free for the next one
+        }
+    }
+}
+
 
 // Sum of one tile since its last head (all of it if it has none) and whether it has one: the pair that later
 // tiles may need of it.

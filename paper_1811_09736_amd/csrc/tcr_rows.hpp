@@ -40,24 +40,6 @@ struct RowsGrid {
 constexpr uint32_t kRowsGroupElems = 16320;       // a workgroup's segments span at most 512 rows of 32 elements
 constexpr uint64_t kRowsMaxSegLen = 8160;         // at least two segments per workgroup
 
-// The first `count` (0 .. 8) of a lane's eight binary16 values kept, the others cleared.
-__device__ __forceinline__ half8 keep_leading(half8 x, int count) {
-    const int c = count < 0 ? 0 : (count > 8 ? 8 : count);
-    const int clo = c < 4 ? c : 4, chi = c - clo;
-    u64x2 m;
-    m[0] = clo ? ~0ull >> (16 * (4 - clo)) : 0ull;
-    m[1] = chi ? ~0ull >> (16 * (4 - chi)) : 0ull;
-    return __builtin_bit_cast(half8, __builtin_bit_cast(u64x2, x) & m);
-}
-__device__ __forceinline__ half8 drop_leading(half8 x, int count) {
-    const int c = count < 0 ? 0 : (count > 8 ? 8 : count);
-    const int clo = c < 4 ? c : 4, chi = c - clo;
-    u64x2 m;
-    m[0] = clo ? ~0ull >> (16 * (4 - clo)) : 0ull;
-    m[1] = chi ? ~0ull >> (16 * (4 - chi)) : 0ull;
-    return __builtin_bit_cast(half8, __builtin_bit_cast(u64x2, x) & ~m);
-}
-
 // Inclusive segmented scan over the 16 lanes of each row of lanes (the 16 data rows of a sub-tile, held
 // redundantly by the four lane rows).
 template <int CH>

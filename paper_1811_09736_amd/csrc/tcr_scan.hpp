@@ -479,6 +479,16 @@ __device__ __forceinline__ float chain_sum_totals(const ScanWorkspace& ws, uint3
     return acc;
 }
 
+// What the chain needs to know of a tile of an IRREGULAR scan without reading the offsets: where the tile's
+// last segment start lies (kNoHead: it has none; kOutside: it has none and lies outside [offsets[0],
+// offsets[nseg]), so nothing of it is stored), and which tile in front of it holds the nearest segment start
+// (kNoHead: none does).  Written by irregular_bounds_kernel.
+struct TileLink {
+    uint32_t last_head;
+    uint32_t prev_head_tile;
+};
+constexpr uint32_t kNoHead = 0xffffffffu, kOutside = 0xfffffffeu;
+
 struct ChainShared {
     float wave_total[16];
     float prefix;
@@ -496,11 +506,18 @@ struct ChainTile {
     uint32_t pos;        // index of the tile inside its segment
     uint32_t count;      // elements of the wavefront's share that exist (the last tile of a segment is ragged)
     uint64_t base;       // first element of the wavefront's share
+    uint32_t last_head, prev_head_tile;      // irregular segments only: the tile's TileLink (the same in every lane)
 };
 
 // Tiles are laid out per segment: segment s owns tiles s * per_segment .. (s + 1) * per_segment - 1, which
 // start at s * seg_len and may overhang its end (the overhang is cut off by the buffer range check).  seg_len
 // is any multiple of 8 that is at least one tile; the one-segment scan has seg_len = n and per_segment = tiles.
+// Irregular segments (IRREG, a table of TileLinks): one grid over the whole array (seg_len = n, per_segment =
+// tiles); the kernel scans and stores only the tiles WITHOUT a segment start that lie inside the covered part of
+// the array -- such a tile continues the segment of the tiles in front of it, back to the nearest tile with a
+// start -- and publishes for every tile the sum behind its last start (all of it if it has none), which is
+// exactly what the tiles behind it need of it, and the running sum at its end in a second table behind the
+// first.  The tiles with starts are left to a second kernel.
 struct ChainGrid {
     uint64_t seg_len;
     uint32_t per_segment;
@@ -508,9 +525,10 @@ struct ChainGrid {
 };
 
 // Stage C: request the data of ticket `tile`.
-template <int FORM, int U, int WAVES>
+template <int FORM, int U, int WAVES, bool IRREG = false>
 __device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const _Float16* __restrict__ in,
-                                           const ChainGrid& grid, const LaneId& id, int wave) {
+                                           const ChainGrid& grid, const LaneId& id, int wave,
+                                           const TileLink* __restrict__ links = nullptr) {
     constexpr uint32_t kChunk = (uint32_t)kTile * U;
     constexpr uint64_t kBlockTile = (uint64_t)kChunk * WAVES;
     const uint32_t seg = tile / grid.per_segment;
@@ -526,13 +544,31 @@ __device__ __forceinline__ void chain_load(ChainTile<U>& t, uint32_t tile, const
 #pragma unroll
     for (int u = 0; u < U; ++u)
         t.x[u] = buffer_load8(src, (uint32_t)(kTile * u + (FORM == kMfma ? kRow * id.j + 8 * id.g : 8 * id.lane)) * 2u);
+    if constexpr (IRREG) {
+        // the same address in every lane: a scalar load, its two words in scalar registers until the next step
+        const TileLink link = links[tile < grid.tiles ? tile : 0u];
+        t.last_head = link.last_head;
+        t.prev_head_tile = link.prev_head_tile;
+    }
 }
 
 // Stage B: totals of the tile, carries inside the workgroup, aggregate published.  Contains one barrier,
 // executed also for a ticket past the last tile.
-template <int FORM, int U, int WAVES>
+template <int FORM, int U, int WAVES, bool IRREG = false>
 __device__ __forceinline__ void chain_publish(ChainTile<U>& t, const ScanWorkspace& ws, uint32_t tiles, ChainShared& sh,
                                               const LaneId& id, int wave) {
+    if constexpr (IRREG) {
+        static_assert(!IRREG || FORM == kMfma, "");
+        // a tile with a segment start is not scanned here: only the sum behind its last start is wanted of it,
+        // so everything in front of that start is cleared (the masking of Section 4, on the data operand)
+        if (t.last_head < kOutside) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int at = (int)((uint32_t)wave * (uint32_t)(kTile * U) + (uint32_t)(kTile * u + kRow * id.j + 8 * id.g));
+                t.x[u] = drop_leading(t.x[u], (int)t.last_head - at);
+            }
+        }
+    }
     float run = 0.0f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -567,20 +603,33 @@ __device__ __forceinline__ void chain_publish(ChainTile<U>& t, const ScanWorkspa
 // Stage A: carry from the earlier tiles of the segment, results, stores.  Returns a freshly drawn ticket.
 // own_end / own_incl (wavefront 0): index after the tile this workgroup finished last (0: none yet) and
 // that tile's inclusive prefix.
-template <int FORM, int U, int WAVES, int MODE>
+template <int FORM, int U, int WAVES, int MODE, bool IRREG = false>
 __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restrict__ out,
                                                  const ScanWorkspace& ws, ChainShared& sh, const LaneId& id, int wave,
-                                                 uint32_t& own_end, float& own_incl) {
+                                                 uint32_t& own_end, float& own_incl, uint32_t tiles) {
     constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
     if (wave == 0) {
         uint32_t drawn = 0u;                      // used only after the reads below, so the draw rides along with them
         if (id.lane == 0) drawn = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t seg_first = t.tile - t.pos;                  // first tile of the segment
+        uint32_t seg_first = t.tile - t.pos;                        // first tile of the segment
+        bool closed = false;                                        // irregular: the tile holds a segment start
+        if constexpr (IRREG) {
+            // the segment reaches back to the nearest tile with a start, whose published sum begins at that start
+            closed = t.last_head < kOutside;
+            seg_first = (closed || t.prev_head_tile >= t.tile) ? t.tile : t.prev_head_tile;
+        }
         const bool resume = own_end > seg_first;  // the workgroup's previous tile lies in the same segment
         float before = chain_sum_totals(ws, resume ? own_end : seg_first, t.tile, id.lane);
         if (resume) before += own_incl;
         own_end = t.tile + 1u;
-        own_incl = before + t.total;
+        own_incl = closed ? t.total : before + t.total;
+        if constexpr (IRREG) {
+            // the running sum at the end of this tile (since the last start), for the second kernel: one read
+            // there instead of a sum over all the tiles back to that start
+            if (id.lane == 0)
+                __hip_atomic_store(&ws.desc[tiles + t.tile], pack_desc(ws.epoch, kStatusPrefix, own_incl), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
         // The reads above have drained this wavefront's memory operations (or, with nothing to read, this
         // does); saying so explicitly keeps the pending ticket draw from counting, after the branch
         // rejoins, as a pending write to a register in all wavefronts.
@@ -594,8 +643,13 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
     const float ext = t.ext + sh.prefix;
     const uint32_t fresh = __builtin_amdgcn_readfirstlane(sh.ticket);
 
+    uint32_t store = t.count;
+    if constexpr (IRREG) {
+        // only tiles without a start, inside the covered part of the array (everything else: an empty range)
+        if (t.last_head != kNoHead) store = 0u;
+    }
     const __amdgpu_buffer_rsrc_t dst =
-        make_rsrc(static_cast<char*>(out) + (t.count ? t.base : 0) * (F16 ? 2u : 4u), t.count * (F16 ? 2u : 4u));
+        make_rsrc(static_cast<char*>(out) + (store ? t.base : 0) * (F16 ? 2u : 4u), store * (F16 ? 2u : 4u));
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const float carry = t.pre[u] + ext;
@@ -613,10 +667,10 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
     return fresh;
 }
 
-template <int FORM, int U, int WAVES, int MODE>
+template <int FORM, int U, int WAVES, int MODE, bool IRREG = false>
 __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float16* __restrict__ in,
                                                                    void* __restrict__ out, ChainGrid grid,
-                                                                   ScanWorkspace ws_arg) {
+                                                                   ScanWorkspace ws_arg, const TileLink* __restrict__ links) {
     static_assert(WAVES <= 16, "");
     const uint32_t tiles = grid.tiles;
     const ScanWorkspace ws = resolve_workspace(ws_arg);
@@ -643,14 +697,14 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
         return;
     }
     ChainTile<U> a, b, c;
-    chain_load<FORM, U, WAVES>(a, first, in, grid, id, wave);
+    chain_load<FORM, U, WAVES, IRREG>(a, first, in, grid, id, wave, links);
     __syncthreads();                              // s_draw has been read by everyone
     if (threadIdx.x == 0)
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
     __syncthreads();
     const uint32_t second = __builtin_amdgcn_readfirstlane(s_draw);
-    chain_load<FORM, U, WAVES>(b, second, in, grid, id, wave);
-    chain_publish<FORM, U, WAVES>(a, ws, tiles, sh, id, wave);          // (its barrier also orders the reads of s_draw)
+    chain_load<FORM, U, WAVES, IRREG>(b, second, in, grid, id, wave, links);
+    chain_publish<FORM, U, WAVES, IRREG>(a, ws, tiles, sh, id, wave);          // (its barrier also orders the reads of s_draw)
     if (threadIdx.x == 0)
         s_draw = __hip_atomic_fetch_add(ws.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - ws.ticket_base;
     __syncthreads();
@@ -664,17 +718,17 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
     // three tiles per trip, the register sets rotating through the stages, so no tile is ever copied between
     // registers (a copy would have to wait for the loads it copies, and with them for the stores before)
     while (true) {
-        chain_load<FORM, U, WAVES>(c, fresh, in, grid, id, wave);
-        chain_publish<FORM, U, WAVES>(b, ws, tiles, sh, id, wave);
-        fresh = chain_finish<FORM, U, WAVES, MODE>(a, out, ws, sh, id, wave, own_end, own_incl);
+        chain_load<FORM, U, WAVES, IRREG>(c, fresh, in, grid, id, wave, links);
+        chain_publish<FORM, U, WAVES, IRREG>(b, ws, tiles, sh, id, wave);
+        fresh = chain_finish<FORM, U, WAVES, MODE, IRREG>(a, out, ws, sh, id, wave, own_end, own_incl, tiles);
         if (b.tile >= tiles) break;
-        chain_load<FORM, U, WAVES>(a, fresh, in, grid, id, wave);
-        chain_publish<FORM, U, WAVES>(c, ws, tiles, sh, id, wave);
-        fresh = chain_finish<FORM, U, WAVES, MODE>(b, out, ws, sh, id, wave, own_end, own_incl);
+        chain_load<FORM, U, WAVES, IRREG>(a, fresh, in, grid, id, wave, links);
+        chain_publish<FORM, U, WAVES, IRREG>(c, ws, tiles, sh, id, wave);
+        fresh = chain_finish<FORM, U, WAVES, MODE, IRREG>(b, out, ws, sh, id, wave, own_end, own_incl, tiles);
         if (c.tile >= tiles) break;
-        chain_load<FORM, U, WAVES>(b, fresh, in, grid, id, wave);
-        chain_publish<FORM, U, WAVES>(a, ws, tiles, sh, id, wave);
-        fresh = chain_finish<FORM, U, WAVES, MODE>(c, out, ws, sh, id, wave, own_end, own_incl);
+        chain_load<FORM, U, WAVES, IRREG>(b, fresh, in, grid, id, wave, links);
+        chain_publish<FORM, U, WAVES, IRREG>(a, ws, tiles, sh, id, wave);
+        fresh = chain_finish<FORM, U, WAVES, MODE, IRREG>(c, out, ws, sh, id, wave, own_end, own_incl, tiles);
         if (a.tile >= tiles) break;
     }
 }

@@ -44,6 +44,7 @@ struct Variant {
     int scan_carry = kStrategyLookback;
     bool reduce_fused = false;      // long reductions: a second kernel adds the partials (true: the last workgroup does)
     int tile_load = kLoadDirect;    // small power-of-two segments, default shape and mode: how tiles reach the operand registers
+    int irregular_scan = 0;         // 0: one kernel or two by the number of segments; 1: always one; 2: always two (where possible)
     bool rows_reduce = true;        // untuned lengths from 32 elements: masked row products (false: the fixed tiles with marked starts)
 };
 inline Variant g_variant;

@@ -334,3 +334,48 @@ def test_irregular_moments(tcr, oracle, recipe, in_shift):
     ra, rq = oracle.irregular_moments(y, off)
     assert np.all(np.abs(q.cpu().numpy().astype(np.float64) - rq) <= 1e-3 * rq)
     assert np.all(np.abs(a.cpu().numpy().astype(np.float64) - ra) <= 1e-3 * np.maximum(np.abs(ra), np.sqrt(rq)))
+
+
+# ------------------------------------------------------------------ long segments: the two-kernel scan
+
+@pytest.mark.parametrize("recipe", ["uniform16", "uniform1024", "uniform20000", "lognormal256", "few2", "few7", "few40"])
+@pytest.mark.parametrize("n", [9 * SCAN_TILE + 1234, (1 << 20) + 8, 3 * SCAN_TILE - 3])
+def test_two_kernel_scan_on_every_mix(tcr, oracle, recipe, n):
+    # forced: the pipelined chain for the tiles without a segment start, a second kernel for the others -- also
+    # on mixes where every tile holds starts and the chain has nothing to store
+    off = workloads.make_offsets(n, recipe, (n % 1000, 9)).view(np.int64)
+    tcr.set_variant("irregular_scan", "chain")
+    try:
+        _run(tcr, oracle, workloads.make_input(n, "int8", 15), off, True, f"chain {recipe} n={n} int8")
+        _run(tcr, oracle, workloads.make_input(n, "uniform_pm1", 16), off, False, f"chain {recipe} n={n} uniform_pm1")
+    finally:
+        tcr.set_variant("reset")
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+def test_two_kernel_scan_is_chosen_for_few_long_segments(tcr, oracle, flags):
+    # 40 tiles, 7 segments: fewer segments than a quarter of the tiles; partial cover, starts on and next to tile
+    # boundaries, an empty segment, every scan mode
+    n = 40 * SCAN_TILE + 4000
+    x = workloads.make_input(n, "int4", 17)
+    off = np.array([5, SCAN_TILE, SCAN_TILE, 3 * SCAN_TILE + 1, 11 * SCAN_TILE - 1, 11 * SCAN_TILE + 8, 30 * SCAN_TILE + 777, n - 9], dtype=np.int64)
+    xd, od = torch.from_numpy(x).cuda(), torch.from_numpy(off).cuda()
+    fill = -3.0
+    out = torch.full((n,), fill, dtype=torch.float16 if flags & 2 else torch.float32, device="cuda")
+    tcr.irregular_scan_ex(xd, od, flags, out=out)
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.irregular_scan_exclusive(x, off) if flags & 1 else oracle.irregular_scan(x, off)
+    if flags & 2:
+        ref = ref.astype(np.float16).astype(np.float64)
+    lo, hi = int(off[0]), int(off[-1])
+    assert np.array_equal(got[lo:hi], ref[lo:hi])
+    assert np.all(got[:lo] == fill) and np.all(got[hi:] == fill), "wrote outside the segments"
+    # and the single-kernel form on the same input
+    tcr.set_variant("irregular_scan", "single")
+    try:
+        out2 = torch.full_like(out, fill)
+        tcr.irregular_scan_ex(xd, od, flags, out=out2)
+    finally:
+        tcr.set_variant("reset")
+    assert torch.equal(out, out2)
+    tcr.check_device_flags()
