@@ -173,6 +173,10 @@ __device__ __forceinline__ float4v mfma(half8 constant, half8 data, float4v acc)
 }
 
 __device__ __forceinline__ float4v splat(float v) { return (float4v){v, v, v, v}; }
+__device__ __forceinline__ half8 splat_half(float v) {
+    const _Float16 h = (_Float16)v;
+    return (half8){h, h, h, h, h, h, h, h};
+}
 
 // ---------------------------------------------------------------- loads and stores
 

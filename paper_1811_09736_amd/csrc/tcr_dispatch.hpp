@@ -597,7 +597,7 @@ inline tcr_status launch_irregular_scan(const _Float16* in, const uint64_t* offs
     uint64_t* starts = reinterpret_cast<uint64_t*>(ws->partials);
     TileLink* links = reinterpret_cast<TileLink*>(starts + (tiles + 1));
     if (!regular) {
-        irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+        irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves * kBoundsPerWave)), dim3(kBoundsWaves * kWave), 0, s>>>(
             offsets, nseg + 1, elems, tiles + 1, shift, starts, nullptr, two_kernels ? links : nullptr);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;
@@ -671,7 +671,7 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     TilePair* pairs = reinterpret_cast<TilePair*>(carried + tiles);              // ch * tiles
     TilePair* group_pairs = pairs + ch * tiles;                                   // ch * groups
     if (!regular) {
-        irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves)), dim3(kBoundsWaves * kWave), 0, s>>>(
+        irregular_bounds_kernel<<<dim3((unsigned)ceil_div(tiles + 1, kBoundsWaves * kBoundsPerWave)), dim3(kBoundsWaves * kWave), 0, s>>>(
             offsets, nseg + 1, elems, tiles + 1, shift, starts, ends);
         st = check_launch("irregular_bounds_kernel");
         if (st != TCR_OK) return st;

@@ -74,6 +74,34 @@ __device__ __forceinline__ void wave_seg_scan_inclusive(uint32_t& f, float& v) {
     v = one[0];
 }
 
+// The same scan with the flags as one bit per lane in a scalar register pair: the shifts of the flags are then
+// scalar instructions and a step costs the vector unit one cross-lane addition and one select.  Returns the
+// inclusive flags (bit l: a flag in lanes 0 .. l).
+template <int CH>
+__device__ __forceinline__ uint64_t wave_seg_scan_inclusive_bits(uint64_t flags, float (&v)[CH]) {
+    auto step = [&](auto ctrl, auto row_mask, auto bound, uint64_t from_left) {
+        const bool f = __builtin_amdgcn_inverse_ballot_w64(flags);
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const float vl = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v[c]), decltype(ctrl)::value,
+                                                                                   decltype(row_mask)::value, 0xf, decltype(bound)::value));
+            v[c] = f ? v[c] : v[c] + vl;
+        }
+        flags |= from_left;
+    };
+    using std::integral_constant;
+    step(integral_constant<int, 0x111>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{}, (flags << 1) & 0xfffefffefffefffeull);
+    step(integral_constant<int, 0x112>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{}, (flags << 2) & 0xfffcfffcfffcfffcull);
+    step(integral_constant<int, 0x114>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{}, (flags << 4) & 0xfff0fff0fff0fff0ull);
+    step(integral_constant<int, 0x118>{}, integral_constant<int, 0xf>{}, integral_constant<bool, true>{}, (flags << 8) & 0xff00ff00ff00ff00ull);
+    // lane 15 of rows 0 and 2 -> every lane of rows 1 and 3; lane 31 -> every lane of rows 2 and 3
+    step(integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}, integral_constant<bool, false>{},
+         ((flags >> 15) & 1ull ? 0x00000000ffff0000ull : 0ull) | ((flags >> 47) & 1ull ? 0xffff000000000000ull : 0ull));
+    step(integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}, integral_constant<bool, false>{},
+         (flags >> 31) & 1ull ? 0xffffffff00000000ull : 0ull);
+    return flags;
+}
+
 // What is summed (KIND): 0 the elements, 1 their squares (exact in binary32), 2 both at once, as two
 // channels that share the segment starts.
 constexpr int kSum = 0, kSquares = 1, kBoth = 2;
@@ -96,6 +124,19 @@ __device__ __forceinline__ void lane_tail_sum(half8 x, uint32_t heads, float (&q
         const bool head = (heads >> e) & 1u;
         q[0] = (head ? 0.0f : q[0]) + term<KIND, 0>(x[e]);
         if constexpr (CH == 2) q[1] = (head ? 0.0f : q[1]) + term<KIND, 1>(x[e]);
+    }
+}
+
+// Running sums (channel C) of a lane's 8 elements that restart at heads, one fused multiply-add per element:
+// keep[e] is 0 where element e is a head and 1 elsewhere, so q * keep + x either continues the sum or restarts
+// it (products with 0 and 1 are exact, so this rounds like the additions alone).
+template <int KIND, int C>
+__device__ __forceinline__ void lane_keep_scan(half8 x, half8 keep, float (&p)[8]) {
+    float q = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        q = __builtin_fmaf(q, (float)keep[e], term<KIND, C>(x[e]));
+        p[e] = q;
     }
 }
 
@@ -154,10 +195,36 @@ __device__ __forceinline__ void wave_share_finish(const WaveShare<U, channels<KI
     }
 }
 
+// The same by aligned groups of G lanes, each group with a key of its own (the same in all of its lanes) and G
+// probes per round: a round of the whole wavefront is still one load instruction, but 64 / G searches share
+// it.  (A probe is a memory request of its own until the last rounds, and requests are what the search costs:
+// 64 probes per round need the fewest rounds and the most requests.)
+template <int G>
+__device__ __forceinline__ uint64_t group_lower_bound(const uint64_t* __restrict__ a, uint64_t count, uint64_t key, int lane) {
+    static_assert(G >= 2 && G < kWave && (G & (G - 1)) == 0, "");
+    const int member = lane & (G - 1), first_lane = lane & ~(G - 1);
+    uint64_t lo = 0, hi = count;             // a[i] < key for i < lo;  a[i] >= key for i >= hi
+    while (__ballot(lo < hi) != 0) {
+        const bool open = lo < hi;
+        const uint64_t step = (hi - lo + (uint64_t)(G - 1)) / (uint64_t)G;
+        const uint64_t idx = lo + step * (uint64_t)(member + 1) - 1;
+        const bool below = open && idx < hi && a[idx] < key;
+        const uint64_t c = (uint64_t)__builtin_popcountll((__ballot(below) >> first_lane) & ((1ull << G) - 1ull));
+        if (open) {
+            const uint64_t first_not_below = lo + step * (c + 1) - 1;                  // member c's probe, if it made one
+            hi = first_not_below < hi ? first_not_below : hi;
+            lo = lo + step * c;
+        }
+    }
+    return lo;
+}
+
 // starts_below[i] = number of entries of offsets[0 .. count) below i * tile_elems, i = 0 .. boundaries - 1;
 // ends_below[i] (optional) = the same for i * tile_elems + 1, i.e. with the entries ON the boundary added,
-// which turns "segment starts in [begin, end)" into "segment ends in (begin, end]".  One wavefront per boundary.
+// which turns "segment starts in [begin, end)" into "segment ends in (begin, end]".  kBoundsGroup lanes per boundary.
 constexpr int kBoundsWaves = 4;
+constexpr int kBoundsGroup = 8;
+constexpr int kBoundsPerWave = kWave / kBoundsGroup;
 // shift: the tiles are laid out from `shift` elements in front of the array (see irregular_scan_kernel), so
 // entry s lies on tile position offsets[s] + shift.
 __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(const uint64_t* __restrict__ offsets,
@@ -166,34 +233,45 @@ __global__ __launch_bounds__(kBoundsWaves * kWave) void irregular_bounds_kernel(
                                                                                 uint64_t* __restrict__ starts_below,
                                                                                 uint64_t* __restrict__ ends_below,
                                                                                 TileLink* __restrict__ links = nullptr) {
+    constexpr int G = kBoundsGroup;
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t i = (uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (i >= boundaries) return;
+    const int member = lane & (G - 1), first_lane = lane & ~(G - 1);
+    const uint64_t wave_first = ((uint64_t)blockIdx.x * kBoundsWaves + (uint64_t)__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * kBoundsPerWave;
+    if (wave_first >= boundaries) return;
+    // (a group beyond the last boundary repeats the last one's search and writes nothing)
+    const uint64_t wanted = wave_first + (uint64_t)(lane / G);
+    const bool mine = wanted < boundaries && member == 0;          // this lane writes the group's results
+    const uint64_t i = wanted < boundaries ? wanted : boundaries - 1;
     const bool reachable = i * tile_elems >= (uint64_t)shift;       // no entry lies in front of position `shift`
     const uint64_t key = reachable ? i * tile_elems - shift : 0;
-    const uint64_t below = wave_lower_bound(offsets, count, key, lane);
-    if (lane == 0) starts_below[i] = below;
-    if (links != nullptr && lane == 0) {
+    const uint64_t below = group_lower_bound<G>(offsets, count, key, lane);
+    if (mine) starts_below[i] = below;
+    if (links != nullptr && mine) {
         // the last entry in front of boundary i: the nearest start for tile i, and the last start of tile i - 1
         // if it lies there (boundaries = tiles + 1: tile i exists for i < boundaries - 1)
         // (a tile without a start is covered by a segment iff some entry lies in front of it, but not all of them)
+        const int tile_log2 = __builtin_ctzll(tile_elems);        // (every tile size is a power of two)
         const bool any = below > 0;
         const uint64_t at = any ? offsets[below - 1] + shift : 0;
-        const uint64_t in_tile = at / tile_elems;
+        const uint64_t in_tile = at >> tile_log2;
         if (i + 1 < boundaries) links[i].prev_head_tile = (any && in_tile < i) ? (uint32_t)in_tile : kNoHead;
         if (i >= 1)
-            links[i - 1].last_head = (any && in_tile == i - 1) ? (uint32_t)(at - in_tile * tile_elems)
+            links[i - 1].last_head = (any && in_tile == i - 1) ? (uint32_t)(at - (in_tile << tile_log2))
                                                                : ((any && below < count) ? kNoHead : kOutside);
     }
     if (ends_below == nullptr) return;
     uint64_t on = 0;                          // entries equal to key follow directly
-    while (reachable) {
-        const uint64_t idx = below + on + (uint64_t)lane;
-        const int c = __builtin_popcountll(__ballot(idx < count && offsets[idx] == key));
-        on += (uint64_t)c;
-        if (c < kWave) break;
+    bool more = reachable;
+    while (__ballot(more) != 0) {
+        const uint64_t idx = below + on + (uint64_t)member;
+        const bool equal = more && idx < count && offsets[idx] == key;
+        const int c = __builtin_popcountll((__ballot(equal) >> first_lane) & ((1ull << G) - 1ull));
+        if (more) {
+            on += (uint64_t)c;
+            more = c == G;
+        }
     }
-    if (lane == 0) ends_below[i] = below + on;
+    if (mine) ends_below[i] = below + on;
 }
 
 // Tile geometry of both kernels: WAVES wavefronts, each with U consecutive 512-element sub-tiles; a lane holds
@@ -409,13 +487,17 @@ __device__ __forceinline__ uint32_t wave_scan_inclusive_u32(uint32_t x) {
 }
 
 // Reduction: out[s] = sum of segment s.  Tiles are independent.  While the heads are marked, the position of
-// every entry of offsets that falls into the tile is kept in LDS (the first kPositions of them; a tile with
-// more -- segments under four elements on average -- reads the rest from memory again).  A wavefront then
-// stages the running sums of a sub-tile in its own 2 KiB of LDS and its lanes walk the entries that end a
-// segment inside that sub-tile, so consecutive lanes write consecutive results.  The one result per tile that
-// belongs to a segment begun in an earlier tile is written without that earlier part; the tile records
-// which segment it is (carried[tile], or none) and its own pair (pairs[tile]) for the carry kernels.
-constexpr uint32_t kPositions = 4096;
+// every entry of offsets that falls into the tile is kept in LDS (a tile with more entries than an eighth of its
+// elements reads them from memory again), and every element gets a factor: 0 on a head, 1 elsewhere.  A lane's
+// running sums are then one fused multiply-add per element (sum * factor + element: the sum restarts where the
+// factor is 0), the sums behind the lanes' last heads are combined across the wavefront with the flags as a
+// lane mask in scalar registers, and nothing is added to the eight running sums afterwards: a wavefront stages
+// them in LDS as they are, next to the 64 sums that reach its lanes from in front, and its lanes walk the
+// entries that end a segment inside the sub-tile -- the result is the staged sum plus, unless a head lies
+// between the lane's first element and the segment's last, the sum from in front -- so consecutive lanes write
+// consecutive results.  The one result per tile that belongs to a segment begun in an earlier tile is written
+// without that earlier part; the tile records which segment it is (carried[tile], or none) and its own pair
+// (pairs[tile]) for the carry kernels.
 // REGULAR: entry s is s * seg_len, s = 0 .. nseg, instead of offsets[s] (offsets and the tables are not read).
 // shift: as for irregular_scan_kernel (`in` points that many elements in front of the caller's array).
 // KIND: sums of the elements, of their squares, or both (out2 and the pairs of the second channel, which
@@ -436,13 +518,20 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     static_assert(kSubs <= kWave, "one lane per sub-tile count");
     __shared__ uint32_t s_heads[kBlockTile / 32];
     __shared__ uint32_t s_ends[kSubs];            // segment ends per sub-tile
-    __shared__ uint16_t s_position[kPositions];   // entry head_lo + i lies on element tb + s_position[i]
+    // entry head_lo + i lies on element tb + s_position[i + 1]; s_position[0] is no position
+    constexpr uint32_t kPositions = kBlockTile / 8 + 62;
+    __shared__ uint16_t s_position[kPositions + 2];
     __shared__ uint64_t s_bound[4];
     static_assert(kBlockTile <= 65535u, "positions are kept in 16 bits");
     constexpr int CH = channels<KIND>();
     __shared__ float s_wave_value[CH][WAVES];
     __shared__ uint32_t s_wave_flag[WAVES];
-    __shared__ __attribute__((aligned(16))) float s_stage[CH][WAVES][kTile];
+    // Per wavefront: first one binary16 value per element of its share, 0 on a head and 1 elsewhere (the factor
+    // that continues or restarts a lane's running sum); later, sub-tile by sub-tile, the running sums of 512
+    // elements and the 64 sums that reach the lanes from in front, per channel.
+    constexpr uint32_t kStageFloats = (uint32_t)kTile + (uint32_t)kWave;
+    constexpr uint32_t kRegionBytes = kChunk * 2u > CH * kStageFloats * 4u ? kChunk * 2u : CH * kStageFloats * 4u;
+    __shared__ __attribute__((aligned(16))) unsigned char s_region[WAVES][kRegionBytes];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -469,6 +558,10 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     }
     for (uint32_t i = threadIdx.x; i < kBlockTile / 32; i += WAVES * kWave) s_heads[i] = 0u;
     if (threadIdx.x < kSubs) s_ends[threadIdx.x] = 0u;
+    if (threadIdx.x == 0) s_position[0] = 0xffffu;
+    half8* const my_keep = reinterpret_cast<half8*>(s_region[wave]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) my_keep[u * kWave + lane] = splat_half(1.0f);
 
     // entries [head_lo, head_hi) lie in [tb, tb + tile): heads; entries [end_lo, end_hi) lie in
     // (tb, tb + tile]: each closes the segment in front of it.  head_lo <= end_lo, head_hi <= end_hi.
@@ -486,6 +579,17 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
             s_bound[3] = q1 + 1 < entries ? q1 + 1 : entries;
         }
     }
+    // the first entries of every thread are requested in front of the barrier (a tile of segments of 16 elements
+    // has two per thread), so that their way from memory overlaps the data's
+    constexpr int kAhead = 2;
+    uint64_t ahead[kAhead] = {};
+    if constexpr (!REGULAR) {
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k) {
+            const uint64_t s = head_lo + threadIdx.x + (uint64_t)(k * WAVES * kWave);
+            if (s < end_hi) ahead[k] = offsets[s];
+        }
+    }
     lds_barrier();
     if constexpr (REGULAR) {
         head_lo = s_bound[0];
@@ -497,23 +601,81 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     if (tile == 0) end_lo = 0;
     const bool has_entries = head_lo < end_hi;
     if (has_entries) {
-        for (uint64_t s = head_lo + threadIdx.x; s < end_hi; s += (uint64_t)(WAVES * kWave)) {
-            const uint64_t pos = (REGULAR ? s * seg_len : offsets[s]) + shift - tb;
-            if (s - head_lo < (uint64_t)kPositions) s_position[s - head_lo] = (uint16_t)pos;
-            if (pos < (uint64_t)kBlockTile) atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
-            if (pos - 1 < (uint64_t)kBlockTile) atomicAdd(&s_ends[(pos - 1) >> 9], 1u);
-            else if (pos == 0 && tile == 0) atomicAdd(&s_ends[0], 1u);
+        // Entry s: its position is kept, its bit and its factor are set, and it counts as a segment end for the
+        // sub-tile of the element in front of it.  Consecutive lanes hold consecutive entries, which mostly end
+        // segments in the same sub-tile: every run of lanes with the same sub-tile adds its length once (64
+        // additions to one LDS word take 64 turns).
+        auto mark = [&](uint64_t s, bool valid, uint64_t entry) {
+            uint32_t sub = ~0u;
+            if (valid) {
+                const uint64_t pos = entry + shift - tb;
+                if (s - head_lo < (uint64_t)kPositions) s_position[s - head_lo + 1] = (uint16_t)pos;
+                if (pos < (uint64_t)kBlockTile) {
+                    atomicOr(&s_heads[pos >> 5], 1u << (pos & 31u));
+                    reinterpret_cast<_Float16*>(s_region[pos / kChunk])[pos % kChunk] = (_Float16)0.0f;
+                }
+                if (pos - 1 < (uint64_t)kBlockTile) sub = (uint32_t)(pos - 1) >> 9;
+                else if (pos == 0 && tile == 0) sub = 0u;
+            }
+            const uint32_t left = (uint32_t)__builtin_amdgcn_update_dpp((int)~sub, (int)sub, 0x138, 0xf, 0xf, false);
+            const bool first = lane == 0 || left != sub;                       // of a run of equal values
+            const uint64_t later = (__ballot(first) >> 1) >> lane;             // bit k: lane + 1 + k starts a run
+            const uint32_t length = later ? (uint32_t)__builtin_ctzll(later) + 1u : (uint32_t)(kWave - lane);
+            if (first && sub != ~0u) atomicAdd(&s_ends[sub], length);
+        };
+        // (every wavefront makes whole trips: the lanes of a trip are asked about together)
+        uint64_t s0 = head_lo + (uint64_t)(wave * kWave);
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k, s0 += (uint64_t)(WAVES * kWave))
+            if (s0 < end_hi) mark(s0 + lane, s0 + lane < end_hi, REGULAR ? (s0 + lane) * seg_len : ahead[k]);
+        for (; s0 < end_hi; s0 += (uint64_t)(WAVES * kWave)) {
+            const uint64_t s = s0 + lane;
+            mark(s, s < end_hi, REGULAR ? s * seg_len : (s < end_hi ? offsets[s] : 0));
         }
         lds_barrier();
     }
     const bool has_heads = head_lo < head_hi;
 
-    WaveShare<U, CH> w;
-    wave_share_scan<U, KIND>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
+    // Running sums inside every lane (restarting at heads, nothing carried in yet), then the pairs
+    // (head in the lane, sum behind its last head) combined across the lanes and the wavefront's sub-tiles.
+    float p[CH][U][8];
+    uint64_t flag_before[U];                      // bit l: a head in a lane in front of lane l inside the sub-tile
+    uint32_t seen_before[U];                      // a head in a sub-tile in front
+    float lane_value[CH][U], before[CH][U], run[CH];
+    uint32_t chunk_flag = 0u;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) run[c] = 0.0f;
+    const uint8_t* head_bytes = reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        uint64_t flags = 0;
+        half8 keep = splat_half(1.0f);
+        if (has_heads) {
+            flags = __ballot(head_bytes[(kTile / 8) * u + lane] != 0);
+            keep = my_keep[u * kWave + lane];
+        }
+        lane_keep_scan<KIND, 0>(x[u], keep, p[0][u]);
+        if constexpr (CH == 2) lane_keep_scan<KIND, 1>(x[u], keep, p[CH - 1][u]);
+        float v[CH];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) v[c] = p[c][u][7];
+        flags = wave_seg_scan_inclusive_bits<CH>(flags, v);
+        flag_before[u] = flags << 1;
+        const uint32_t sub_flag = (uint32_t)(flags >> 63);
+        seen_before[u] = chunk_flag;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            lane_value[c][u] = wave_shr1(v[c]);
+            const float sub_value = read_lane(v[c], 63);
+            before[c][u] = run[c];
+            run[c] = sub_flag ? sub_value : run[c] + sub_value;
+        }
+        chunk_flag |= sub_flag;
+    }
     if (lane == 0) {
 #pragma unroll
-        for (int c = 0; c < CH; ++c) s_wave_value[c][wave] = w.run[c];
-        s_wave_flag[wave] = w.chunk_flag;
+        for (int c = 0; c < CH; ++c) s_wave_value[c][wave] = run[c];
+        s_wave_flag[wave] = chunk_flag;
     }
     lds_barrier();
 
@@ -548,46 +710,62 @@ __global__ __launch_bounds__(WAVES * kWave) void irregular_reduce_kernel(const _
     // entries that end a segment in each of this wavefront's sub-tiles
     const uint32_t mine = lane < kSubs ? s_ends[lane] : 0u;
     const uint32_t upto = wave_scan_inclusive_u32(mine);
+    // (this wavefront has read all of its keep values: the region now stages running sums.  Per channel: a
+    // lane's sums 0..3 at 16 bytes per lane, its sums 4..7 likewise in a second plane -- 128-bit stores without
+    // bank conflicts -- then the 64 sums that reach the lanes from in front)
+    float* const stage = reinterpret_cast<float*>(my_keep);
+    // the entries as 32-bit numbers counted from head_lo: entry head_lo + i closes segment head_lo + i - 1
+    const bool listed = end_hi - head_lo <= (uint64_t)kPositions;      // every position of the tile is in LDS
+    const uint64_t room = nseg >= head_lo ? nseg - head_lo : 0;         // (beyond it: offsets not sorted)
+    const uint32_t i_limit = room < 0xfffffffeull ? (uint32_t)room : 0xfffffffeu;
+    const uint32_t i_first = head_lo == 0 ? 1u : 0u;                    // offsets[0] closes nothing
+    float* const out_from = out + head_lo;                              // (out_from[i - 1] is never touched for head_lo + i == 0)
+    float* const out2_from = CH == 2 ? out2 + head_lo : nullptr;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int sub = wave * U + u;
         const uint32_t count = (uint32_t)__builtin_amdgcn_readlane((int)mine, sub);
         if (count == 0u) continue;
-        const uint64_t entry0 = end_lo + (uint64_t)((uint32_t)__builtin_amdgcn_readlane((int)upto, sub) - count);
-        {
-            float p[8];
-            wave_share_finish<U, 0, KIND, 0>(w, x, u, ext[0], p);
-            float4v* dst = reinterpret_cast<float4v*>(&s_stage[0][wave][8 * lane]);
-            dst[0] = (float4v){p[0], p[1], p[2], p[3]};
-            dst[1] = (float4v){p[4], p[5], p[6], p[7]};
-        }
-        if constexpr (CH == 2) {
-            float p[8];
-            wave_share_finish<U, 0, KIND, 1>(w, x, u, ext[CH - 1], p);
-            float4v* dst = reinterpret_cast<float4v*>(&s_stage[CH - 1][wave][8 * lane]);
-            dst[0] = (float4v){p[0], p[1], p[2], p[3]};
-            dst[1] = (float4v){p[4], p[5], p[6], p[7]};
+        const uint32_t i0 = (uint32_t)(end_lo - head_lo) + ((uint32_t)__builtin_amdgcn_readlane((int)upto, sub) - count);
+        // the sub-tile's running sums without what reaches the lane from in front of it, and that sum per lane
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            float* const mine_at = stage + c * kStageFloats;
+            *reinterpret_cast<float4v*>(mine_at + 4 * lane) = (float4v){p[c][u][0], p[c][u][1], p[c][u][2], p[c][u][3]};
+            *reinterpret_cast<float4v*>(mine_at + kTile / 2 + 4 * lane) = (float4v){p[c][u][4], p[c][u][5], p[c][u][6], p[c][u][7]};
+            const float into_sub = seen_before[u] ? before[c][u] : before[c][u] + ext[c];
+            mine_at[kTile + lane] = __builtin_amdgcn_inverse_ballot_w64(flag_before[u]) ? lane_value[c][u] : lane_value[c][u] + into_sub;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         for (uint32_t r = (uint32_t)lane; r < count; r += (uint32_t)kWave) {
-            const uint64_t s = entry0 + r;
-            if (s == 0 || s > nseg) continue;                      // offsets[0] closes nothing; (s > nseg: offsets not sorted)
-            const uint64_t i = s - head_lo;
-            // positions of this entry and the one before it (which lies in front of the tile if i == 0)
+            const uint32_t i = i0 + r;
+            if (i < i_first || i > i_limit) continue;
+            // positions of this entry and the one before it (no position if that one lies in front of the tile)
             uint32_t end, begin;
-            if (i < (uint64_t)kPositions) {
-                end = s_position[i];
-                begin = i > 0 ? (uint32_t)s_position[i - 1] : 0u;
+            if (listed) {
+                end = s_position[i + 1];
+                begin = s_position[i];
             } else {
+                const uint64_t s = head_lo + i;
                 end = (uint32_t)((REGULAR ? s * seg_len : offsets[s]) + shift - tb);
-                begin = (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1]) + shift - tb);
+                begin = i > 0 ? (uint32_t)((REGULAR ? (s - 1) * seg_len : offsets[s - 1]) + shift - tb) : 0xffffu;
             }
-            const uint32_t at = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
-            const bool take = !(i > 0 && end == begin) && at < (uint32_t)kTile;     // not an empty segment
-            out[s - 1] = take ? s_stage[0][wave][at] : 0.0f;
-            if constexpr (CH == 2) out2[s - 1] = take ? s_stage[CH - 1][wave][at] : 0.0f;
+            const uint32_t last = end - 1u - (uint32_t)(sub * kTile);   // the segment's last element
+            const bool take = end != begin && last < (uint32_t)kTile;   // not an empty segment
+            const uint32_t at = last & (uint32_t)(kTile - 1);
+            const uint32_t at_lane = at >> 3, e = at & 7u;
+            // the sum from in front of the lane belongs to the result unless a head lies between the lane's
+            // first element and this one
+            const uint32_t heads_upto = (uint32_t)head_bytes[(kTile / 8) * u + at_lane] & ((2u << e) - 1u);
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const float* const mine_at = stage + c * kStageFloats;
+                const float from_front = mine_at[kTile + at_lane];
+                const float value = mine_at[(e >> 2) * (kTile / 2) + 4 * at_lane + (e & 3u)] + (heads_upto ? 0.0f : from_front);
+                (c == 0 ? out_from : out2_from)[(int64_t)i - 1] = take ? value : 0.0f;
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
