@@ -516,7 +516,7 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
 // Irregular segments: fixed tiles of the flat array, whatever the segments.  Tile shapes (U sub-tiles of 512
 // elements per wavefront, W wavefronts); id 0 is the frozen default: 32768-element tiles for the chained scan,
 // 8192-element tiles of four wavefronts for the reduction, whose tiles are independent (measured at n = 2^28:
-// 109 us against 121 us with eight wavefronts of four sub-tiles on log-normal lengths, 192 against 199 us on
+// 90 us against 92 us with eight wavefronts of four sub-tiles on log-normal lengths, 143 against 153 us on
 // segments of 16 elements on average: a tile's work is a chain of dependent steps -- its range of offsets
 // entries, the entries, the marks, the sums -- and small workgroups keep more tiles in flight per compute unit).
 constexpr SmallShape kIrregularScanShapes[] = {{4, 16}, {2, 16}};
@@ -724,11 +724,13 @@ inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2
 // 230-1060 us).  Longer reductions keep one wavefront per segment over zero-masked tiles (116 us at
 // 1000 elements, 85 us at 3001), the shortest segments one thread each.
 constexpr uint64_t kTiledScanMin = 2;
-constexpr uint64_t kTiledReduceMin = 8, kTiledReduceMax = 1000;
+// (sums from 5 elements on: 161-183 us at 5..7 against 193-210 us with one thread per segment, 274 either way at 3;
+// both moments from 8 on: below, one thread per segment is faster, 213-232 against 231-259 us)
+constexpr uint64_t kTiledReduceMin = 5, kTiledMomentsMin = 8, kTiledReduceMax = 1000;
 
 // Which kernel takes a reduction whose seg_len is no power of two (or below 16); class = floor(log2(seg_len)).
 // The default is the first valid one of: rows, tiles, the rest (one wavefront per segment over masked tiles from
-// 1000 elements, one thread per segment below 8).
+// 1000 elements, one thread per segment below 5).
 enum ReduceAny { kReduceAnyRows = 0, kReduceAnyTiles = 1, kReduceAnyTilesAlt = 2, kReduceAnyMasked = 3, kReduceAnyCount = 4 };
 constexpr uint64_t kMaskedReduceMin = 256;              // (valid for any length; pointless for short segments)
 inline bool reduce_any_valid(int id, uint64_t seg_len) {
@@ -848,11 +850,11 @@ inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, u
         return check_launch("moments_small_kernel");
     }
     if (rows_reduce_takes(seg_len, kBoth)) return launch_rows_reduce(in, sum, sumsq, n, seg_len, kBoth, s);
-    if (seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax) {
+    if (seg_len >= kTiledMomentsMin && seg_len < kTiledReduceMax) {
         // fixed tiles with the segment starts marked, both moments as two channels of one pass
         return launch_irregular_reduce(in, nullptr, sum, n, nseg, seg_len, s, kBoth, sumsq);
     }
-    if (seg_len < kTiledReduceMin) {         // under 8 elements: one thread per segment
+    if (seg_len < kTiledMomentsMin) {        // under 8 elements: one thread per segment
         generic_moments_kernel<<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
             in, sum, sumsq, nseg, seg_len);
         return check_launch("generic_moments_kernel");

@@ -23,23 +23,6 @@
 
 namespace tcr {
 
-// Number of entries of the sorted array a[0 .. count) that are smaller than key, found by one whole
-// wavefront probing 64 places per round.  Returned uniformly.
-__device__ __forceinline__ uint64_t wave_lower_bound(const uint64_t* __restrict__ a, uint64_t count, uint64_t key,
-                                                      int lane) {
-    uint64_t lo = 0, hi = count;             // a[i] < key for i < lo;  a[i] >= key for i >= hi
-    while (lo < hi) {
-        const uint64_t step = (hi - lo + (uint64_t)(kWave - 1)) / (uint64_t)kWave;
-        const uint64_t idx = lo + step * (uint64_t)(lane + 1) - 1;
-        const bool below = idx < hi && a[idx] < key;
-        const uint64_t c = (uint64_t)__builtin_popcountll(__ballot(below));        // a sorted: the first c lanes
-        const uint64_t first_not_below = lo + step * (c + 1) - 1;                  // lane c's probe, if it made one
-        hi = first_not_below < hi ? first_not_below : hi;
-        lo = lo + step * c;
-    }
-    return lo;
-}
-
 __device__ __forceinline__ uint32_t wave_shr1_u32(uint32_t x) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x138, 0xf, 0xf, true);
 }
@@ -195,10 +178,12 @@ __device__ __forceinline__ void wave_share_finish(const WaveShare<U, channels<KI
     }
 }
 
-// The same by aligned groups of G lanes, each group with a key of its own (the same in all of its lanes) and G
-// probes per round: a round of the whole wavefront is still one load instruction, but 64 / G searches share
-// it.  (A probe is a memory request of its own until the last rounds, and requests are what the search costs:
-// 64 probes per round need the fewest rounds and the most requests.)
+// Number of entries of the sorted array a[0 .. count) that are smaller than key, found by an aligned group of G
+// lanes with G probes per round; every group has a key of its own (the same in all of its lanes), so a round of
+// the whole wavefront is one load instruction shared by 64 / G searches.  (A probe is a memory request of its own
+// until the last rounds, and requests are what the search costs: 64 probes per round need the fewest rounds and
+// the most requests.  32769 boundaries among 16.8 million entries: 25 us with G = 64, 13 with 16, 10 with 8, 11
+// with 4.)
 template <int G>
 __device__ __forceinline__ uint64_t group_lower_bound(const uint64_t* __restrict__ a, uint64_t count, uint64_t key, int lane) {
     static_assert(G >= 2 && G < kWave && (G & (G - 1)) == 0, "");
@@ -345,6 +330,18 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
 #pragma unroll
         for (int u = 0; u < U; ++u) x[u] = load8_guarded(in, base + (uint64_t)(kTile * u + 8 * lane), n);
     }
+    // everything else that depends on the tile's number alone is asked for now as well: the covered part of the
+    // array and, for the second kernel, the running sum at the end of the tile in front (used only if a segment
+    // reaches in from there) -- a tile's work is a chain of loads, and these need not be links of it
+    const uint64_t first = (REGULAR ? 0 : offsets[0]) + shift;
+    const uint64_t last = REGULAR || offsets[nseg] + shift > n ? n : offsets[nseg] + shift;
+    float second_pre = 0.0f;
+    if constexpr (SECOND) {
+        if (wave == 0 && tile != 0u && links[tile].prev_head_tile < tile) {
+            const uint32_t tiles = (uint32_t)((n + kBlockTile - 1) / kBlockTile);
+            second_pre = __builtin_bit_cast(float, (uint32_t)load_descriptor(&ws.desc[tiles + tile - 1u]));
+        }
+    }
 
     // heads in [tb, tb + tile): entries head_lo .. head_hi - 1
     const uint64_t head_lo = REGULAR ? s_bound[0] : starts_below[tile];
@@ -378,8 +375,6 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
     }
     // the part [valid_lo, valid_hi) of this wavefront's share lies in a segment (all of it, nearly always)
     // (an offsets array that reaches beyond n is the caller's error; nothing is stored beyond n all the same)
-    const uint64_t first = (REGULAR ? 0 : offsets[0]) + shift;
-    const uint64_t last = REGULAR || offsets[nseg] + shift > n ? n : offsets[nseg] + shift;
     const uint32_t valid_lo = first > base ? (uint32_t)(first - base < kChunk ? first - base : kChunk) : 0u;
     const uint32_t valid_hi = last > base ? (uint32_t)(last - base < kChunk ? last - base : kChunk) : 0u;
     const bool inside = valid_lo == 0u && valid_hi == kChunk && vector_stores != 0u;
@@ -407,10 +402,7 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
             float pre = 0.0f;
             if constexpr (SECOND) {
                 // the running sum at the end of the tile in front (the chain's second table: tiles .. 2 tiles - 1)
-                if (reach != 0u && links[tile].prev_head_tile < tile) {
-                    const uint32_t tiles = (uint32_t)((n + kBlockTile - 1) / kBlockTile);
-                    pre = __builtin_bit_cast(float, (uint32_t)load_descriptor(&ws.desc[tiles + tile - 1u]));
-                }
+                if (reach != 0u) pre = second_pre;
             } else {
                 pre = lookback_carry<8>(ws, tile, reach, closed, total, lane);
             }
@@ -443,7 +435,7 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
 }
 
 template <int U, int WAVES, bool REGULAR, int MODE, bool SECOND = false>
-__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(8, 8)))
+__global__ __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(SECOND ? 4 : 8, 8)))
 void irregular_scan_kernel(const _Float16* __restrict__ in, const uint64_t* __restrict__ offsets, void* __restrict__ out,
                            uint64_t n, uint64_t nseg, const uint64_t* __restrict__ starts_below, uint64_t seg_len,
                            uint32_t shift, uint32_t vector_stores, ScanWorkspace ws_arg, const TileLink* __restrict__ links = nullptr) {

@@ -623,17 +623,18 @@ __device__ __forceinline__ uint32_t chain_finish(ChainTile<U>& t, void* __restri
         if (resume) before += own_incl;
         own_end = t.tile + 1u;
         own_incl = closed ? t.total : before + t.total;
-        if constexpr (IRREG) {
-            // the running sum at the end of this tile (since the last start), for the second kernel: one read
-            // there instead of a sum over all the tiles back to that start
-            if (id.lane == 0)
-                __hip_atomic_store(&ws.desc[tiles + t.tile], pack_desc(ws.epoch, kStatusPrefix, own_incl), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-        }
         // The reads above have drained this wavefront's memory operations (or, with nothing to read, this
         // does); saying so explicitly keeps the pending ticket draw from counting, after the branch
         // rejoins, as a pending write to a register in all wavefronts.
         __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+        if constexpr (IRREG) {
+            // the running sum at the end of this tile (since the last start), for the second kernel: one read
+            // there instead of a sum over all the tiles back to that start.  (Behind the wait: nothing in this
+            // kernel reads it, so nobody waits for the store's way to memory either.)
+            if (id.lane == 0)
+                __hip_atomic_store(&ws.desc[tiles + t.tile], pack_desc(ws.epoch, kStatusPrefix, own_incl), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
         if (id.lane == 0) {
             sh.prefix = before;
             sh.ticket = drawn - ws.ticket_base;

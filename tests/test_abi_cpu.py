@@ -130,7 +130,8 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "irregular_scan_kernel<regular>"     # untuned lengths: fixed tiles
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 1) == "tiny_scan_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 8) == "tiny_scan_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6) == "generic_thread_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 3) == "generic_thread_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6).startswith("irregular_reduce_kernel<regular>")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 24).startswith("irregular_reduce_kernel<regular>+")   # boundaries share tile rows
     for seg in (33, 48, 999, 1001, 8160):                  # from 32 elements: masked row products, whole segments per workgroup
