@@ -136,7 +136,9 @@ tcr_status tcr_scan_ex(const void *in, void *out, uint64_t n, uint32_t flags, vo
  *                         (positions outside [offsets[0], offsets[nseg]) are not written).
  * The work is divided by elements, not by segments: fixed tiles of the array at a speed that hardly depends on
  * the mix of segment lengths.  Both use the workspace (tcr_workspace_bytes, op 4 and 5): one small kernel looks
- * up where the tile boundaries fall among the offsets; the scan chains its tiles like the long regular scans;
+ * up where the tile boundaries fall among the offsets; the scan chains its tiles like the long regular scans
+ * (with fewer segments than a quarter of the tiles it runs as two kernels: the pipelined chain of the long
+ * regular scans takes the tiles without a segment start, a second kernel the others);
  * the reduction keeps its tiles independent and two small kernels add the one sum per tile that reaches in
  * from earlier tiles -- plain loads in a fixed order, so the reduction's results are the same from run to run.
  * in and out need only their natural alignment (2 and 4 bytes): the tiles start at the 16-byte boundary at or
@@ -197,6 +199,9 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
  *   "untuned_reduce" "rows" (default: reductions and moments of 32 .. 8160 elements, no power of two, as masked
  *                  row products) | "tiles" (the fixed tiles with marked segment starts / one wavefront per segment
  *                  that took these lengths before; kept as the measured alternative)
+ *   "irregular_scan" "auto" (default: one kernel or two by the number of segments) | "single" (always the one
+ *                  kernel of chained tiles) | "chain" (always two, where the launch allows it: default tile shape,
+ *                  16-byte aligned arrays, matrix-core formulation)
  *   "reduce_finish" "second_kernel" (default: the paper's two-kernel device-level reduction, Section 4) |
  *                  "fused" (one kernel: the workgroup that finishes last adds up the partials)
  *   "reset"        any value: back to the defaults

@@ -96,20 +96,6 @@ __device__ __forceinline__ float term(_Float16 h) {
     return (KIND == kSquares || (KIND == kBoth && C == 1)) ? v * v : v;
 }
 
-// Per channel, the sum of a lane's 8 elements behind its last segment start (all 8 if it has none).
-template <int KIND>
-__device__ __forceinline__ void lane_tail_sum(half8 x, uint32_t heads, float (&q)[channels<KIND>()]) {
-    constexpr int CH = channels<KIND>();
-#pragma unroll
-    for (int c = 0; c < CH; ++c) q[c] = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const bool head = (heads >> e) & 1u;
-        q[0] = (head ? 0.0f : q[0]) + term<KIND, 0>(x[e]);
-        if constexpr (CH == 2) q[1] = (head ? 0.0f : q[1]) + term<KIND, 1>(x[e]);
-    }
-}
-
 // Running sums (channel C) of a lane's 8 elements that restart at heads, one fused multiply-add per element:
 // keep[e] is 0 where element e is a head and 1 elsewhere, so q * keep + x either continues the sum or restarts
 // it (products with 0 and 1 are exact, so this rounds like the additions alone).
@@ -120,61 +106,6 @@ __device__ __forceinline__ void lane_keep_scan(half8 x, half8 keep, float (&p)[8
     for (int e = 0; e < 8; ++e) {
         q = __builtin_fmaf(q, (float)keep[e], term<KIND, C>(x[e]));
         p[e] = q;
-    }
-}
-
-// Per sub-tile: the pair of every lane's predecessors and the sub-tile's own pair, chained over the
-// wavefront's U sub-tiles.  `run` / `chunk_flag` leave as the pair of the wavefront's whole share.
-template <int U, int CH = 1>
-struct WaveShare {
-    uint32_t heads[U];            // bits 0..7: heads among the lane's 8 elements; bit 8: a head in a lane in front
-    uint32_t seen_before[U];
-    float lane_value[CH][U], before[CH][U];
-    float run[CH];
-    uint32_t chunk_flag;
-};
-
-template <int U, int KIND = kSum>
-__device__ __forceinline__ void wave_share_scan(WaveShare<U, channels<KIND>()>& w, const half8 (&x)[U], const uint8_t* head_bytes,
-                                                bool has_heads, int lane) {
-    constexpr int CH = channels<KIND>();
-#pragma unroll
-    for (int c = 0; c < CH; ++c) w.run[c] = 0.0f;
-    w.chunk_flag = 0u;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        w.heads[u] = has_heads ? (uint32_t)head_bytes[(kTile / 8) * u + lane] : 0u;
-        uint32_t f = w.heads[u] != 0u ? 1u : 0u;
-        float v[CH];
-        lane_tail_sum<KIND>(x[u], w.heads[u], v);
-        wave_seg_scan_inclusive<CH>(f, v);
-        w.heads[u] |= wave_shr1_u32(f) << 8;
-        const uint32_t sub_flag = (uint32_t)__builtin_amdgcn_readlane((int)f, 63);
-        w.seen_before[u] = w.chunk_flag;
-#pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            w.lane_value[c][u] = wave_shr1(v[c]);
-            const float sub_value = read_lane(v[c], 63);
-            w.before[c][u] = w.run[c];
-            w.run[c] = sub_flag ? sub_value : w.run[c] + sub_value;
-        }
-        w.chunk_flag |= sub_flag;
-    }
-}
-
-// Running sums (channel C) of a lane's 8 elements of sub-tile u, given the sum `ext` that reaches the
-// wavefront's share from in front of it.
-template <int U, int EXCL = 0, int KIND = kSum, int C = 0>
-__device__ __forceinline__ void wave_share_finish(const WaveShare<U, channels<KIND>()>& w, const half8 (&x)[U], int u, float ext,
-                                                  float (&p)[8]) {
-    const float into_sub = w.seen_before[u] ? w.before[C][u] : w.before[C][u] + ext;
-    float q = (w.heads[u] >> 8) ? w.lane_value[C][u] : w.lane_value[C][u] + into_sub;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        q = (w.heads[u] >> e) & 1u ? 0.0f : q;
-        if constexpr (EXCL) p[e] = q;
-        q += term<KIND, C>(x[u][e]);
-        if constexpr (!EXCL) p[e] = q;
     }
 }
 
@@ -293,6 +224,8 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
     __shared__ uint32_t s_ready;              // set once s_prefix holds the carry from earlier tiles
     __shared__ uint32_t s_tile;
     __shared__ uint64_t s_bound[2];
+    // the eight factors of a lane by the byte of its head bits: binary16 0 where the bit is set, 1 elsewhere
+    __shared__ __attribute__((aligned(16))) uint32_t s_factors[256][4];
 
     const ScanWorkspace ws = resolve_workspace(ws_arg);
     const int lane = threadIdx.x & (kWave - 1);
@@ -315,6 +248,11 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
         }
     }
     for (uint32_t i = threadIdx.x; i < kBlockTile / 32; i += WAVES * kWave) s_heads[i] = 0u;
+    for (uint32_t b = threadIdx.x; b < 256u; b += WAVES * kWave) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            s_factors[b][k] = ((b >> (2 * k)) & 1u ? 0u : 0x3c00u) | ((b >> (2 * k + 1)) & 1u ? 0u : 0x3c000000u);
+    }
     __syncthreads();
     const uint32_t tile = s_tile;
     if (!SECOND && tile == 0 && threadIdx.x == 0 && ws.state != nullptr && !ws.device_managed) ws.state[0] = ws.epoch;
@@ -355,11 +293,38 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
         __syncthreads();
     }
 
-    WaveShare<U> w;
-    wave_share_scan<U>(w, x, reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8), has_heads, lane);
+    // Running sums inside a lane as fused multiply-adds with the factors (sum * factor + element restarts where
+    // the factor is 0): here for the sum behind the lane's last head, below once more from the sum that reaches
+    // the lane.  The pairs (head in the lane, that sum) are combined across the lanes with the flags as a lane
+    // mask in scalar registers, and across the wavefront's sub-tiles in registers.
+    uint32_t bits[U];                             // the lane's head bits (its factors are looked up again for the second pass)
+    uint64_t flag_before[U];                      // bit l: a head in a lane in front of lane l inside the sub-tile
+    uint32_t seen_before[U];                      // a head in a sub-tile in front
+    float lane_value[U], before[U], run = 0.0f;
+    uint32_t chunk_flag = 0u;
+    const uint8_t* head_bytes = reinterpret_cast<const uint8_t*>(s_heads) + wave * (kChunk / 8);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        bits[u] = has_heads ? (uint32_t)head_bytes[(kTile / 8) * u + lane] : 0u;
+        const uint64_t heads_in = __ballot(bits[u] != 0u);
+        uint64_t flags = heads_in;
+        const half8 keep = *reinterpret_cast<const half8*>(s_factors[bits[u]]);
+        float v[1] = {0.0f};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[0] = __builtin_fmaf(v[0], (float)keep[e], (float)x[u][e]);
+        flags = wave_seg_scan_inclusive_bits<1>(flags, v);
+        flag_before[u] = flags << 1;
+        const uint32_t sub_flag = (uint32_t)(flags >> 63);
+        seen_before[u] = chunk_flag;
+        lane_value[u] = wave_shr1(v[0]);
+        const float sub_value = read_lane(v[0], 63);
+        before[u] = run;
+        run = sub_flag ? sub_value : run + sub_value;
+        chunk_flag |= sub_flag;
+    }
     if (lane == 0) {
-        s_wave_value[wave] = w.run[0];
-        s_wave_flag[wave] = w.chunk_flag;
+        s_wave_value[wave] = run;
+        s_wave_flag[wave] = chunk_flag;
     }
     __syncthreads();
 
@@ -417,8 +382,20 @@ __device__ __forceinline__ void irregular_scan_tile(const _Float16* __restrict__
     void* const dst = F16 ? static_cast<void*>(static_cast<_Float16*>(out) + base) : static_cast<void*>(static_cast<float*>(out) + base);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
+        const float into_sub = seen_before[u] ? before[u] : before[u] + ext;
+        float q = __builtin_amdgcn_inverse_ballot_w64(flag_before[u]) ? lane_value[u] : lane_value[u] + into_sub;
+        const half8 keep = *reinterpret_cast<const half8*>(s_factors[bits[u]]);
         float p[8];
-        wave_share_finish<U, EXCL>(w, x, u, ext, p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if constexpr (EXCL) {
+                p[e] = q * (float)keep[e];
+                q = p[e] + (float)x[u][e];
+            } else {
+                q = __builtin_fmaf(q, (float)keep[e], (float)x[u][e]);
+                p[e] = q;
+            }
+        }
         const uint32_t k = (uint32_t)(kTile * u + 8 * lane);
         if (inside) {
             store8_t<F16>(dst, k, (float4v){p[0], p[1], p[2], p[3]}, (float4v){p[4], p[5], p[6], p[7]});
