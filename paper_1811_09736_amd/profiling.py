@@ -10,6 +10,7 @@ writes text.  Usage (the rocprofv3 commands themselves are quoted in every summa
     python -m paper_1811_09736_amd.profiling irregular     <kt dir> <fetch dir> <write dir>  (three times, one per length mix)
     python -m paper_1811_09736_amd.profiling counters      <name> <title> <kernel-stats dir> <pmc dir> [<pmc dir> ...]
     python -m paper_1811_09736_amd.profiling chain-gap     <kernel-stats dir> <SQ counters dir> <TCC counters dir>
+    python -m paper_1811_09736_amd.profiling irregular-counters <kernel-stats dir of the mix> <three SQ counter dirs>
     python -m paper_1811_09736_amd.profiling repeatability <bench JSON line file> ...
     python -m paper_1811_09736_amd.profiling tile-load     <five bench JSON line files>
 """
@@ -277,7 +278,7 @@ def irregular(dirs) -> None:
     _write("irregular_n2^28_kernels_and_traffic.md", out)
 
 
-def counters(name: str, title: str, kt_dir: str, pmc_dirs, commands=None, reading=None) -> None:
+def counters(name: str, title: str, kt_dir: str, pmc_dirs, commands=None, reading=None, only: str = "") -> None:
     """A table of arbitrary PMC counters per tcr kernel (averages per launch) next to the launch durations."""
     dur = _durations(kt_dir)
     table = collections.defaultdict(dict)
@@ -285,7 +286,7 @@ def counters(name: str, title: str, kt_dir: str, pmc_dirs, commands=None, readin
     for d in pmc_dirs:
         agg, _ = _counters(d)
         for k, cs in agg.items():
-            if not k.startswith("tcr::"):
+            if not k.startswith("tcr::") or only not in k:
                 continue
             for c, v in cs.items():
                 table[k][c] = sum(v) / len(v)
@@ -306,18 +307,40 @@ def chain_gap(kt_dir: str, sq_dir: str, tcc_dir: str) -> None:
                 "    rocprofv3 --pmc TCC_EA0_RDREQ_DRAM_CREDIT_STALL_sum TCC_EA0_WRREQ_STALL_sum TCC_EA0_RD_UNCACHED_32B_sum TCC_ATOMIC --output-format csv -d <out> -o bench -- python3 bench.py --no-cpu-baseline --steps 2 --warmup 1 --no-context", "",
                 *TEMPLATE_NOTE]
     reading = ["Reading (scan_chain_kernel<0,4,16,0,0>, seg_len 2^16 and 2^20, against scan_block_kernel<0,1,2,0,0> and <0,1,8,0,0>,",
-               "seg_len 2^10 and 2^12, same bytes): the chain adds 57 000 wavefront-level loads per launch (the descriptor reads: one",
-               "window of aggregates per tile) and 8 960 atomics (the tickets) -- a hundredth of a percent of the traffic.  What",
-               "differs is how much work is in flight: SQ_WAVE_CYCLES is 0.63e9 against 1.03-1.07e9, i.e. the persistent kernel",
-               "keeps its 16 wavefronts per compute unit (three tiles, 96 KiB of loads and 192 KiB of stores) while the one-tile",
-               "kernels average 26 short-lived wavefronts per compute unit, and the memory side shows it: the DRAM read-credit",
-               "stalls are a tenth (0.09e6 against 0.6-0.9e6) and the write-request stalls a fifth to a half -- the chain does not",
-               "press on the memory system as hard; it loses its 4-5 % to the two workgroup barriers per tile and the round trip",
-               "of the carry between them, not to extra bytes.  More tiles in flight would need more registers than 16",
-               "wavefronts of 128 leave (three tiles take 122)."]
+               "seg_len 2^10 and 2^12, same bytes): the chain adds some 57 000 wavefront-level loads per launch (SQ_INSTS_VMEM_RD:",
+               "the descriptor reads, one window of aggregates per tile) and 8 960 atomics (TCC_ATOMIC: the tickets) -- a",
+               "hundredth of a percent of the traffic.  What differs is how much work is in flight: SQ_WAVE_CYCLES is about",
+               "0.6e9 against 1.0-1.1e9, i.e. the persistent kernel keeps its 16 wavefronts per compute unit (three tiles, 96 KiB",
+               "of loads and 192 KiB of stores) while the one-tile kernels average 26 short-lived wavefronts per compute unit, and",
+               "the memory side shows it: the DRAM read-credit stalls are a tenth of the carry-free kernels' and the",
+               "write-request stalls lower as well -- the chain does not press on the memory system as hard; it loses its 4-5 %",
+               "to the two workgroup barriers per tile and the round trip of the carry between them, not to extra bytes.  More",
+               "tiles in flight would need more registers than 16 wavefronts of 128 leave (three tiles take 122)."]
     counters("scan_chain_vs_block_counters_n2^28.md",
              "Where the chained scan loses against the carry-free one: SQ and L2 counters per launch (n = 2^28)", kt_dir,
              [sq_dir, tcc_dir], commands, reading)
+
+
+def irregular_counters(kt_dir: str, sq1: str, sq2: str, sq3: str) -> None:
+    """SQ counters of the irregular kernels on the mix with 16 elements per segment on average."""
+    flt = '--context-filter "uniform on 0..32"'
+    commands = ["Commands (each its own run, from /tmp with TMPDIR=/tmp; durations from the kernel-trace run of the same mix in",
+                "irregular_n2^28_kernels_and_traffic.md; counters are sums over the chip per launch, averaged over launches):", "",
+                f"    rocprofv3 --pmc SQ_WAVES SQ_WAVE_CYCLES SQ_BUSY_CYCLES SQ_ACTIVE_INST_VALU SQ_ACTIVE_INST_LDS SQ_ACTIVE_INST_SCA SQ_WAIT_INST_LDS SQ_WAIT_ANY --output-format csv -d <out> -o bench -- python3 bench.py --no-cpu-baseline --steps 1 --warmup 0 {flt}",
+                f"    rocprofv3 --pmc SQ_INSTS_VALU SQ_INSTS_SALU SQ_INSTS_LDS SQ_INSTS_VMEM_RD SQ_INSTS_VMEM_WR SQ_INSTS_SMEM SQ_INSTS_BRANCH SQ_WAIT_INST_ANY --output-format csv -d <out> -o bench -- python3 bench.py --no-cpu-baseline --steps 1 --warmup 0 {flt}",
+                f"    rocprofv3 --pmc SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_LDS_ADDR_CONFLICT SQ_INST_LEVEL_LDS SQ_INST_LEVEL_VMEM --output-format csv -d <out> -o bench -- python3 bench.py --no-cpu-baseline --steps 1 --warmup 0 {flt}", "",
+                *TEMPLATE_NOTE]
+    reading = ["Reading.  A launch covers 2^28 elements = 524288 sub-tiles of 512; irregular_reduce_kernel<4,4,0,0> runs 131072",
+               "wavefronts of four sub-tiles.  SQ_INSTS_VALU / 524288 is the vector instructions per 512 elements, all of the",
+               "kernel included (marking the segment starts, the sums, the walk over the segment ends); SQ_LDS_IDX_ACTIVE / 256 is",
+               "the LDS busy cycles per compute unit, to be held against the launch's duration times the clock.  The same",
+               "counters on earlier forms of this kernel, same input: with per-element selects for the restarts and the",
+               "results corrected before staging, 7.8e7 vector instructions (149 per 512 elements), 4.0e7 LDS cycles of which",
+               "2.4e7 bank conflicts, 156 us; with the fused multiply-adds but one LDS addition per segment end, 6.2e7 / 5.2e7 /",
+               "2.6e7 and SQ_WAIT_INST_LDS up fivefold, 144 us -- the 64 additions to one LDS word per trip took 64 turns."]
+    counters("irregular_uniform16_sq_counters_n2^28.md",
+             "Irregular kernels on 16.8 million segments of 0..32 elements: SQ counters per launch (n = 2^28)", kt_dir, [sq1, sq2, sq3],
+             commands, reading, only="irregular")
 
 
 def repeatability(json_files) -> None:
@@ -386,6 +409,8 @@ def main(argv) -> int:
         irregular(args)
     elif kind == "counters":
         counters(args[0], args[1], args[2], args[3:])
+    elif kind == "irregular-counters":
+        irregular_counters(*args)
     elif kind == "chain-gap":
         chain_gap(*args)
     elif kind == "repeatability":
