@@ -448,11 +448,16 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         const bool mf = tuned_formulation(kTuneReduce, cls) == kMfma;
         if (!whole && seg_len <= kTile) return mf ? "reduce_small_kernel<mfma>" : "reduce_small_kernel<dpp>";
         const ReducePlan p = plan_reduce(n, seg_len, whole);
-        if (p.combine == 1) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
-        if (p.per == 1) return mf ? "reduce_span_kernel<mfma,block>" : "reduce_span_kernel<dpp,block>";
+        // <formulation, wave | block (wavefronts of a workgroup combined)>, and what adds up the partials, if any are left
         const uint64_t nseg = whole ? 1 : n / seg_len;
-        if (g_variant.reduce_fused && nseg * p.per <= kFusedPartialsMax)
-            return mf ? "reduce_span_kernel<mfma,block,finish>" : "reduce_span_kernel<dpp,block,finish>";
+        const bool fused = p.per > 1 && g_variant.reduce_fused && nseg * p.per <= kFusedPartialsMax;
+        if (p.combine == 1) {
+            if (p.per == 1) return mf ? "reduce_span_kernel<mfma,wave>" : "reduce_span_kernel<dpp,wave>";
+            if (fused) return mf ? "reduce_span_kernel<mfma,wave,finish>" : "reduce_span_kernel<dpp,wave,finish>";
+            return mf ? "reduce_span_kernel<mfma,wave>+reduce_final_kernel" : "reduce_span_kernel<dpp,wave>+reduce_final_kernel";
+        }
+        if (p.per == 1) return mf ? "reduce_span_kernel<mfma,block>" : "reduce_span_kernel<dpp,block>";
+        if (fused) return mf ? "reduce_span_kernel<mfma,block,finish>" : "reduce_span_kernel<dpp,block,finish>";
         return mf ? "reduce_span_kernel<mfma,block>+reduce_final_kernel" : "reduce_span_kernel<dpp,block>+reduce_final_kernel";
     }
     if (op == 1 || op == 3) {

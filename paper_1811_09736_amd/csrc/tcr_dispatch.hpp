@@ -201,8 +201,13 @@ inline ReducePlan plan_reduce(uint64_t n, uint64_t seg_len, bool whole) {
     const int count = reduce_candidates(n, seg_len, whole, cand);
     int pick = tuned_id(kTuneReduce, tuning_class(seg_len, whole));
     if (pick < 0 || pick >= count) {
-        // frozen defaults: segments of 8192 .. 32768 elements are split over 2 or 4 wavefronts
-        pick = (whole || seg_len < 8192 || seg_len > 32768) ? 0 : (seg_len == 8192 ? 1 : 2);
+        // frozen defaults: segments of 8192 .. 32768 elements are split over 2 or 4 wavefronts; from 2^18 elements
+        // on (and for one segment) every wavefront leaves a partial of its own for the second kernel -- combining
+        // the wavefronts of a workgroup first holds each back to the slowest (n = 2^28: 81.5-81.9 us against
+        // 83.9-86.1 us with 4 combined; 8 or 16 combined, which make a segment of 2^19 or 2^20 elements one
+        // workgroup's and the second kernel unnecessary, 84.1 and 90.8 us)
+        if (whole || seg_len >= (1ull << 18)) pick = count > 1 ? 1 : 0;
+        else pick = (seg_len < 8192 || seg_len > 32768) ? 0 : (seg_len == 8192 ? 1 : 2);
     }
     ReducePlan p;
     p.span = cand[pick].span;

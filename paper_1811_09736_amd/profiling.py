@@ -129,8 +129,9 @@ def dispatcher_names(k: str):
     if name == "scan_chain_kernel":
         return [f"scan_chain_kernel<{form}>"] if args[3] == 0 else []
     if name == "reduce_span_kernel":
-        return ([f"reduce_span_kernel<{form},wave>"] if args[3] == 0
-                else [f"reduce_span_kernel<{form},block>", f"reduce_span_kernel<{form},block>+reduce_final_kernel"])
+        # (COMBINE 0: one result or partial per wavefront; the second kernel, where one runs, moves next to nothing)
+        kind = "wave" if args[3] == 0 else "block"
+        return [f"reduce_span_kernel<{form},{kind}>", f"reduce_span_kernel<{form},{kind}>+reduce_final_kernel"]
     if name == "scan_block_kernel":
         if args[4] != 0:
             return []

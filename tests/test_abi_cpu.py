@@ -106,11 +106,12 @@ def test_dispatch_by_segment_length(lib):
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_block_kernel<mfma,ticket>"
     for e in (15, 16, 20, 24):                             # the persistent, pipelined chain
         assert k(lib.OP_SEGMENTED_SCAN, n, 1 << e) == "scan_chain_kernel<mfma>"
-    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,block>"
-    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20).endswith("block>+reduce_final_kernel")
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 17) == "reduce_span_kernel<mfma,block>"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 18) == "reduce_span_kernel<mfma,wave>+reduce_final_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20) == "reduce_span_kernel<mfma,wave>+reduce_final_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 24).endswith("+reduce_final_kernel")
     lib.set_variant("reduce_finish", "fused")
-    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20) == "reduce_span_kernel<mfma,block,finish>"
+    assert k(lib.OP_SEGMENTED_REDUCE, n, 1 << 20) == "reduce_span_kernel<mfma,wave,finish>"
     assert k(lib.OP_SEGMENTED_REDUCE, 1 << 36, 1 << 24).endswith("+reduce_final_kernel")   # 2^18 partials: too many for one workgroup
     lib.set_variant("reset")
     assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
@@ -165,8 +166,8 @@ def test_tuning_table_text_round_trip(lib):
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
         lib.tuning_import("scan:14=4;")
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,nocarry>"
-        lib.tuning_import("reduce:20=1;")
-        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == "reduce_span_kernel<mfma,wave>"
+        lib.tuning_import("reduce:20=0;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 1 << 28, 1 << 20) == "reduce_span_kernel<mfma,block>+reduce_final_kernel"
         # ... and ignores a shape whose share cannot hold the segment
         lib.tuning_import("scan:16=0;")
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 16) == "scan_chain_kernel<mfma>"
