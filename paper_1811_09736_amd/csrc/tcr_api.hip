@@ -537,11 +537,13 @@ extern "C" uint64_t tcr_workspace_bytes(int op, uint64_t n, uint64_t seg_len) {
     if (!irregular) {
         // Regular calls run the tiled kernels above for some lengths and alignments; otherwise, over every variant
         // and launch shape: one descriptor per 16384-element share (the smallest share handed out by ticket),
-        // and at most one binary32 partial per 16384 elements (the smallest span a reduction leaves a partial
-        // for is 65536, as is the share of the multi-kernel scans; the moments keep two per span).
+        // and at most one binary32 partial per 4096 elements (the smallest span a wavefront of the one-segment
+        // reduction leaves a partial for; segmented reductions and the multi-kernel scans leave one per 65536, the
+        // moments two).
         const uint64_t shares = ceil_div(n, 16384);
         if (scan && shares > desc) desc = shares;
-        if (ceil_div(shares, 2) > words) words = ceil_div(shares, 2);
+        const uint64_t partials = ceil_div(n, 4096);
+        if (ceil_div(partials, 2) > words) words = ceil_div(partials, 2);
     }
     const uint64_t bytes = 8 * (desc > words ? desc : words);
     return kWorkspaceHeader + 2 * ((bytes + 255) / 256 * 256);

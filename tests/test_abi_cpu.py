@@ -212,7 +212,9 @@ def test_workspace_bytes_is_a_host_side_bound(lib):
     assert wb(8, 1 << 20, 16) == 0
     small, big = wb(lib.OP_SCAN, 1 << 20, 0), wb(lib.OP_SCAN, 1 << 28, 0)
     assert 768 <= small < big
-    exact = 256 + 2 * (1 << 28) // 16384 * 8                # header + descriptors + partials: one per 16384 elements
+    # header + two areas of one size: descriptors, one per 16384 elements (8 bytes), and partials, one binary32 per
+    # 4096 elements (what the one-segment reduction leaves when every wavefront writes its own)
+    exact = 256 + 2 * max((1 << 28) // 16384 * 8, (1 << 28) // 4096 * 4)
     assert exact <= big <= exact + 512                      # (+ one tile for an array that starts 7 elements into a tile)
     assert big % 256 == 0
     # irregular segments: look-up tables and per-tile pairs (reduce), one descriptor per 32768-element tile (scan)
@@ -251,3 +253,4 @@ def test_workspace_bytes_covers_the_tiled_kernels_behind_regular_calls(lib, n):
     # the long power-of-two paths: a descriptor per 16384-element share, a partial per 65536-element span
     assert area(lib.OP_SEGMENTED_SCAN, 1) >= 8 * -(-n // 16384)
     assert area(lib.OP_SEGMENTED_REDUCE, 1) >= 4 * -(-n // 65536) * 2
+    assert area(lib.OP_REDUCE, 0) >= 4 * -(-n // 4096)                     # one segment: a partial per wavefront span
