@@ -43,6 +43,14 @@ __device__ __forceinline__ float row_shr(float x) {
 template <int GROUP>
 __device__ __forceinline__ float row_scan_inclusive(float x, int j) {
     static_assert(GROUP == 1 || GROUP == 2 || GROUP == 4 || GROUP == 8 || GROUP == 16, "");
+    if constexpr (GROUP == 16) {
+        // (the row is the group: what row_shr delivers from outside it is already 0)
+        x += row_shr<1>(x);
+        x += row_shr<2>(x);
+        x += row_shr<4>(x);
+        x += row_shr<8>(x);
+        return x;
+    }
     const int p = j & (GROUP - 1);
     if constexpr (GROUP > 1) { float v = row_shr<1>(x); x += (p >= 1) ? v : 0.0f; }
     if constexpr (GROUP > 2) { float v = row_shr<2>(x); x += (p >= 2) ? v : 0.0f; }
@@ -110,6 +118,11 @@ __device__ __forceinline__ half8 const_ones() {
     return c;
 }
 
+__device__ __forceinline__ half8 splat_half(float v) {
+    const _Float16 h = (_Float16)v;
+    return (half8){h, h, h, h, h, h, h, h};
+}
+
 // Eight binary16 values of which the first `count` (clamped to 0..8) are 1 and the rest 0: one
 // register quadruple of a triangular constant.  Built with two 64-bit shifts instead of eight
 // compares so that a one-tile wavefront spends few VALU instructions on its constants.
@@ -131,16 +144,27 @@ __device__ __forceinline__ half8 leading_ones(int count) {
 // Lane (i, g) holds k = 8g .. 8g+7, so its registers are a run of ones followed by zeros.
 // EXCL = 1 drops the diagonal (k < i): the exclusive scan, the strict triangle that Section 5
 // uses for its column scans.
+// All three constants are one pattern -- the run of ones that lanes (i, 0) and (i, 1) hold of tri_lo -- placed in
+// the lower or the upper pair of lane rows, with zeros or ones in the other pair: tri_lo is zero for k >= 16
+// (lane rows 2 and 3), tri_hi is all ones for k < 16 and repeats tri_lo's pattern 16 positions on.  Written this
+// way the pattern is computed once per wavefront however many of the constants a kernel uses.
+template <int EXCL>
+__device__ __forceinline__ half8 tri_pattern(const LaneId& id) { return leading_ones(id.j - 8 * (id.g & 1) + 1 - EXCL); }
+__device__ __forceinline__ half8 select8(bool take, half8 a, half8 b) {
+    const u64x2 x = __builtin_bit_cast(u64x2, a), y = __builtin_bit_cast(u64x2, b);
+    u64x2 r;
+    r[0] = take ? x[0] : y[0];
+    r[1] = take ? x[1] : y[1];
+    return __builtin_bit_cast(half8, r);
+}
 template <int EXCL = 0>
-__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) { return leading_ones(id.j - 8 * id.g + 1 - EXCL); }
+__device__ __forceinline__ half8 const_tri_lo(const LaneId& id) { return select8(id.g < 2, tri_pattern<EXCL>(id), splat_half(0.0f)); }
 template <int EXCL = 0>
-__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) { return leading_ones(16 + id.j - 8 * id.g + 1 - EXCL); }
+__device__ __forceinline__ half8 const_tri_hi(const LaneId& id) { return select8(id.g < 2, splat_half(1.0f), tri_pattern<EXCL>(id)); }
 // Same, for rows that hold two independent segments of 16: the second half starts afresh
 // (1 iff 16 <= k <= 16 + i).
 template <int EXCL = 0>
-__device__ __forceinline__ half8 const_tri_hi_seg16(const LaneId& id) {
-    return leading_ones(id.g >= 2 ? id.j - 8 * (id.g - 2) + 1 - EXCL : 0);
-}
+__device__ __forceinline__ half8 const_tri_hi_seg16(const LaneId& id) { return select8(id.g < 2, splat_half(0.0f), tri_pattern<EXCL>(id)); }
 // Two half-row sums at once: output rows 0..7 add up k < 16, rows 8..15 add up k >= 16.
 __device__ __forceinline__ half8 const_half_rows(const LaneId& id) {
     const bool one = (id.g >= 2) == (id.j >= 8);
@@ -173,10 +197,7 @@ __device__ __forceinline__ float4v mfma(half8 constant, half8 data, float4v acc)
 }
 
 __device__ __forceinline__ float4v splat(float v) { return (float4v){v, v, v, v}; }
-__device__ __forceinline__ half8 splat_half(float v) {
-    const _Float16 h = (_Float16)v;
-    return (half8){h, h, h, h, h, h, h, h};
-}
+
 
 // ---------------------------------------------------------------- loads and stores
 
