@@ -63,9 +63,9 @@ typedef enum {
  *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
- * seg_len == n.  Other lengths: reductions of 32 to 8160 elements take whole segments per workgroup and mask the
+ * seg_len == n.  Other lengths: reductions of 17 to 8160 elements take whole segments per workgroup and mask the
  * data operand of the products row by row where a segment ends (the masking that Section 4 proposes for
- * arbitrary segment sizes, moved from the constant matrix to the data; no workspace); reductions of 8 to 31
+ * arbitrary segment sizes, moved from the constant matrix to the data; no workspace); reductions of 5 to 15
  * elements and all scans run on fixed tiles of the array with the segment starts marked (the kernels of the
  * irregular calls below; they use the workspace), except scans of a multiple of 8 elements above 512, which have
  * one workgroup per segment or, from 65536 elements, the chained scan; longer reductions run one wavefront per
@@ -162,9 +162,9 @@ tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *
  * sum, sumsq: n/seg_len floats each, 4-byte aligned, distinct.  Every seg_len >= 1 that divides n, including
  * seg_len == n.  The sums of squares come from products of the data with itself on the matrix cores (exact
  * products, binary32 accumulation); both are exact for integer-valued inputs while the sums stay below 2^24.
- * Powers of two up to 512: a tile per wavefront like the reductions; other lengths from 32 to 2999: whole
+ * Powers of two up to 512: a tile per wavefront like the reductions; other lengths from 17 to 2999: whole
  * segments per workgroup with the data operand masked row by row, the squares from the masked operand times
- * itself; from 8 to 31: the fixed tiles of the irregular kernels with both moments in one pass (they use the
+ * itself; from 9 to 15: the fixed tiles of the irregular kernels with both moments in one pass (they use the
  * workspace); longer ones: one wavefront per segment (per 65536-element piece of a long one).
  */
 tcr_status tcr_segmented_moments(const void *in, float *sum, float *sumsq, uint64_t n, uint64_t seg_len, void *stream);
@@ -196,7 +196,7 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
  *                  paper's own kernels) | "lds_dma" (the same with gfx950's load from memory into LDS).  Applies
  *                  to tcr_segmented_reduce / tcr_segmented_scan with seg_len 16 .. 512 in their default launch
  *                  shape; kept for the measurement that chose "direct"
- *   "untuned_reduce" "rows" (default: reductions and moments of 32 .. 8160 elements, no power of two, as masked
+ *   "untuned_reduce" "rows" (default: reductions and moments of 17 .. 8160 elements, no power of two, as masked
  *                  row products) | "tiles" (the fixed tiles with marked segment starts / one wavefront per segment
  *                  that took these lengths before; kept as the measured alternative)
  *   "irregular_scan" "auto" (default: one kernel or two by the number of segments) | "single" (always the one

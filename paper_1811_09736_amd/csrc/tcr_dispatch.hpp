@@ -694,13 +694,14 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
     return check_launch("irregular_carry_kernel");
 }
 
-// Regular segments from 32 elements on, no power of two: whole segments per workgroup, masked row products
+// Regular segments from 17 elements on, no power of two: whole segments per workgroup, masked row products
 // (tcr_rows.hpp).  `in` needs only 2-byte alignment.  kind: kSum, or kBoth with the sums of squares in out2.
 // Measured at n = 2^28 against the kernels that took these lengths before: sums 77-98 us from 33 to 8000
 // elements (fixed tiles with marked starts: 114-157 us below 1000; one wavefront per segment over masked tiles:
 // 114 us at 1000, 89 at 2000, 80 from 3000 on); both moments 88-108 us (fixed tiles 184-249 us; masked tiles 119 us
-// at 1000, 93 at 2000, 82 from 3000 on, where they stay).
-constexpr uint64_t kRowsReduceMin = 32, kRowsReduceMax = kRowsMaxSegLen, kRowsMomentsMax = 2999;
+// at 1000, 93 at 2000, 82 from 3000 on, where they stay).  From 17 to 31 elements (two boundaries per row): sums
+// 102-110 us (fixed tiles 117-150 us), both moments 140-170 us (177-217 us).
+constexpr uint64_t kRowsReduceMin = 17, kRowsReduceMax = kRowsMaxSegLen, kRowsMomentsMax = 2999;
 inline bool rows_reduce_takes(uint64_t seg_len, int kind = kSum) {
     return g_variant.rows_reduce && seg_len >= kRowsReduceMin && seg_len <= (kind == kBoth ? kRowsMomentsMax : kRowsReduceMax);
 }
@@ -716,8 +717,13 @@ inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2
     grid.per_group = (uint32_t)(kRowsGroupElems / seg_len);
     grid.magic = (uint32_t)(((1ull << 32) + seg_len - 1) / seg_len);
     const dim3 blocks((unsigned)ceil_div(grid.nseg, grid.per_group)), block(W * kWave);
-    if (kind == kBoth) rows_reduce_kernel<kBoth, U, W><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
-    else rows_reduce_kernel<kSum, U, W><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);
+    if (seg_len < 32) {              // two boundaries per row
+        if (kind == kBoth) rows_reduce_kernel<kBoth, U, W, true><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
+        else rows_reduce_kernel<kSum, U, W, true><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);
+    } else {
+        if (kind == kBoth) rows_reduce_kernel<kBoth, U, W><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
+        else rows_reduce_kernel<kSum, U, W><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);
+    }
     return check_launch("rows_reduce_kernel");
 }
 

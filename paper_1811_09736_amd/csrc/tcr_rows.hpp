@@ -1,4 +1,4 @@
-// Regular segments whose length is no power of two, from 32 elements up to a few thousand: sums (and sums of
+// Regular segments whose length is no power of two, from 17 elements up to a few thousand: sums (and sums of
 // squares) with every addition of the data itself on the matrix cores.
 //
 // The paper handles such lengths by padding the data or by masking the constant matrix P (Section 4, "Support
@@ -15,6 +15,8 @@
 // the 16 rows of a sub-tile (four cross-lane steps on (flag, value) pairs), chained through the sub-tiles of a
 // wavefront in registers and through the wavefronts of a workgroup in LDS.  A row that holds the end of a
 // segment writes that segment's result: what arrives from the rows in front plus its own head.
+// With 16 < seg_len < 32 a row holds one or two boundaries, and between two of them lies a whole segment: a third
+// masked product, whose row sum is that segment's result as it stands.
 //
 // A workgroup owns WHOLE segments (as many as fit into 16320 elements), so no sum crosses workgroups: one
 // launch, no workspace, the same order of additions in every run.  Its rows are rows of the ARRAY (aligned 64-byte
@@ -51,7 +53,10 @@ __device__ __forceinline__ void rows_seg_scan_inclusive(uint32_t& f, float (&v)[
 }
 
 // KIND: kSum (out) or kBoth (out: sums, out2: sums of squares).
-template <int KIND, int U, int WAVES>
+// SHORT: 16 <= seg_len < 32.  A row then holds one or two boundaries, seg_len apart: its head, possibly one whole
+// segment between the two boundaries -- a third masked product, whose row sum is that segment's result as it
+// stands -- and its tail behind the last boundary.
+template <int KIND, int U, int WAVES, bool SHORT = false>
 __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float16* __restrict__ in,
                                                                     float* __restrict__ out, float* __restrict__ out2,
                                                                     RowsGrid grid) {
@@ -94,6 +99,8 @@ __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float
     }
 
     float head[CH][U], carry_in[CH][U];      // per row: its head piece; the sum arriving from the rows in front (this sub-tile only)
+    float whole[CH][SHORT ? U : 1];          // SHORT: the segment between the row's two boundaries
+    uint32_t whole_which[SHORT ? U : 1];     // ... and which one it is (counted inside the workgroup, from 1; 0: none)
     uint32_t flag_in[U];                     // a boundary lies in an earlier row of the sub-tile
     uint32_t which[U];                       // the segment (counted inside the workgroup, from 1) that ends in this row; 0: none
     uint32_t seen_before[U];                 // a boundary lies in an earlier sub-tile of this wavefront
@@ -114,7 +121,17 @@ __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float
         which[u] = (has && k >= 1u && k <= count) ? k : 0u;
         const int lead = (int)c - 8 * id.g;                     // of this lane's eight elements, those in front of the boundary
         const half8 xh = keep_leading(x[u], has ? lead : 8);
-        const half8 xt = drop_leading(x[u], has ? lead : 8);
+        half8 xt = drop_leading(x[u], has ? lead : 8);
+        if constexpr (SHORT) {
+            // a second boundary seg_len further on: the elements between the two are segment k + 1 (from 1), whole
+            const bool second = c + L < 32u;                    // (c < seg_len < 32: the row always has the first)
+            whole_which[u] = (second && k < count) ? k + 1u : 0u;
+            const int lead2 = second ? lead + (int)L : 0;        // (none: nothing is kept for it, the tail stays as it is)
+            const half8 xm = keep_leading(xt, lead2);
+            xt = drop_leading(xt, lead2);
+            whole[0][u] = mfma(const_ones(), xm, splat(0.0f))[0];
+            if constexpr (CH == 2) whole[CH - 1][u] = row_squares(xm, id);
+        }
         float v[CH];
         head[0][u] = mfma(const_ones(), xh, splat(0.0f))[0];
         const float tail = mfma(const_ones(), xt, splat(0.0f))[0];
@@ -163,6 +180,13 @@ __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float
             if constexpr (CH == 2) {
                 const float into_sub = seen_before[u] ? before[CH - 1][u] : before[CH - 1][u] + ext[CH - 1];
                 out2[s] = (flag_in[u] ? carry_in[CH - 1][u] : carry_in[CH - 1][u] + into_sub) + head[CH - 1][u];
+            }
+        }
+        if constexpr (SHORT) {
+            if (whole_which[u] != 0u && id.g == 0) {
+                const uint64_t s = s0 + (uint64_t)(whole_which[u] - 1u);
+                out[s] = whole[0][u];
+                if constexpr (CH == 2) out2[s] = whole[CH - 1][u];
             }
         }
     }

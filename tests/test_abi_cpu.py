@@ -134,8 +134,8 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 3) == "generic_thread_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6).startswith("irregular_reduce_kernel<regular>")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 24).startswith("irregular_reduce_kernel<regular>+")   # boundaries share tile rows
-    for seg in (33, 48, 999, 1001, 8160):                  # from 32 elements: masked row products, whole segments per workgroup
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 12).startswith("irregular_reduce_kernel<regular>+")   # several boundaries per tile row
+    for seg in (17, 24, 33, 48, 999, 1001, 8160):          # from 17 elements: masked row products, whole segments per workgroup
         assert k(lib.OP_SEGMENTED_REDUCE, seg * 5, seg) == "rows_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 8168 * 5, 8168) == "masked_wave_reduce_kernel"
     lib.set_variant("untuned_reduce", "tiles")
@@ -236,7 +236,7 @@ def _tiled_reduce_words(n, channels):
 
 @pytest.mark.parametrize("n", [1, 9, 16384, 16385, (1 << 20) - 7, 1 << 20, (1 << 28) + 24])
 def test_workspace_bytes_covers_the_tiled_kernels_behind_regular_calls(lib, n):
-    # A regular call lands on the tiled kernels of the irregular calls for some lengths (reductions of 8 .. 31
+    # A regular call lands on the tiled kernels of the irregular calls for some lengths (reductions of 5 .. 15
     # elements that are no power of two) and for every length when `in` is not 16-byte aligned; the bound must
     # hold for those too, for both moments as well, and one area must hold the scan's descriptors.
     wb = lib.workspace_bytes

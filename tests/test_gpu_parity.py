@@ -497,20 +497,20 @@ def test_caller_supplied_workspace(tcr, oracle):
 
 
 def test_caller_workspace_of_exactly_the_documented_size_serves_the_tiled_kernels(tcr, oracle):
-    # regular calls that land on the fixed tiles of the irregular kernels: reductions of 8 .. 31 elements that are
+    # regular calls that land on the fixed tiles of the irregular kernels: reductions of 5 .. 15 elements that are
     # no power of two, and views that are not 16-byte aligned (the tiles start at the boundary below them)
-    n = 24 * 30011
+    n = 24 * 30011                                       # (a multiple of 12 as well)
     x = workloads.make_input(n + 1, "int8", 41)
     xd = dev(x)
-    cases = [("segmented_reduce seg_len 24", tcr.OP_SEGMENTED_REDUCE, n, 24, lambda: tcr.segmented_reduce(xd[:n], 24),
-              lambda: oracle.segmented_reduce(x[:n], 24)),
+    cases = [("segmented_reduce seg_len 12", tcr.OP_SEGMENTED_REDUCE, n, 12, lambda: tcr.segmented_reduce(xd[:n], 12),
+              lambda: oracle.segmented_reduce(x[:n], 12)),
              ("segmented_reduce seg_len 16 behind x[1:]", tcr.OP_SEGMENTED_REDUCE, n - 8, 16,
               lambda: tcr.segmented_reduce(xd[1:n - 7], 16), lambda: oracle.segmented_reduce(x[1:n - 7].copy(), 16)),
              ("reduce behind x[1:]", tcr.OP_REDUCE, n, 0, lambda: tcr.reduce(xd[1:]), lambda: np.array([oracle.reduce(x[1:].copy())])),
              ("segmented_scan seg_len 24 behind x[1:]", tcr.OP_SEGMENTED_SCAN, n, 24,
               lambda: tcr.segmented_scan(xd[1:], 24), lambda: oracle.segmented_scan(x[1:].copy(), 24)),
-             ("segmented_moments seg_len 24", tcr.OP_SEGMENTED_MOMENTS, n, 24, lambda: tcr.segmented_moments(xd[:n], 24)[1],
-              lambda: oracle.segmented_moments(x[:n], 24)[1])]
+             ("segmented_moments seg_len 12", tcr.OP_SEGMENTED_MOMENTS, n, 12, lambda: tcr.segmented_moments(xd[:n], 12)[1],
+              lambda: oracle.segmented_moments(x[:n], 12)[1])]
     try:
         for what, op, nn, seg, run, ref in cases:
             need = tcr.workspace_bytes(op, nn, seg)

@@ -1,5 +1,6 @@
-"""Regular segments of a length that is no power of two, from 32 elements on (rows_reduce_kernel: masked row
-products, whole segments per workgroup): tcr_segmented_reduce and tcr_segmented_moments against the oracle.
+"""Regular segments of a length that is no power of two, from 17 elements on (rows_reduce_kernel: masked row
+products, whole segments per workgroup; below 32 elements a row of 32 holds two boundaries and, between them, a
+whole segment): tcr_segmented_reduce and tcr_segmented_moments against the oracle.
 
 Integer-valued inputs must match exactly; real-valued ones within |y - ref| <= 1e-3 * max(|ref|, rho), rho = the
 root of the segment's sum of squares (for the sums of squares, whose terms are all positive: plain relative error).
@@ -27,7 +28,7 @@ def tcr():
     binding.check_device_flags()
 
 
-LENGTHS = [33, 35, 48, 63, 65, 96, 97, 100, 127, 129, 196, 255, 257, 480, 511, 513, 784, 999, 1000, 1001, 2040,
+LENGTHS = [17, 18, 19, 21, 23, 24, 25, 27, 29, 30, 31, 33, 35, 48, 63, 65, 96, 97, 100, 127, 129, 196, 255, 257, 480, 511, 513, 784, 999, 1000, 1001, 2040,
            3000, 4097, 5440, 8159, 8160]
 
 
@@ -57,7 +58,7 @@ def test_sums_and_moments_are_exact_on_integers(tcr, oracle, seg):
 
 
 @pytest.mark.parametrize("dist", ["uniform_pm1", "normal", "uniform_01"])
-@pytest.mark.parametrize("seg", [33, 100, 196, 999, 3001, 8160])
+@pytest.mark.parametrize("seg", [17, 24, 31, 33, 100, 196, 999, 3001, 8160])
 def test_real_valued_inputs(tcr, oracle, seg, dist):
     nseg = 5 * (16320 // seg) + 3
     x = workloads.make_input(seg * nseg, dist, seg)
