@@ -701,9 +701,12 @@ inline tcr_status launch_irregular_reduce(const _Float16* in, const uint64_t* of
 // 114 us at 1000, 89 at 2000, 80 from 3000 on); both moments 88-108 us (fixed tiles 184-249 us; masked tiles 119 us
 // at 1000, 93 at 2000, 82 from 3000 on, where they stay).  From 17 to 31 elements (two boundaries per row): sums
 // 102-110 us (fixed tiles 117-150 us), both moments 140-170 us (177-217 us).
-constexpr uint64_t kRowsReduceMin = 17, kRowsReduceMax = kRowsMaxSegLen, kRowsMomentsMax = 2999;
+// (Below 17 -- two or three whole segments per row -- it only equals the fixed tiles at 11-15 elements, 123-130 us
+// either way, and loses to them at 9 and 10, 170 against 144-168 us.)
+constexpr uint64_t kRowsReduceMin = 17, kRowsMomentsMin = 17, kRowsReduceMax = kRowsMaxSegLen, kRowsMomentsMax = 2999;
 inline bool rows_reduce_takes(uint64_t seg_len, int kind = kSum) {
-    return g_variant.rows_reduce && seg_len >= kRowsReduceMin && seg_len <= (kind == kBoth ? kRowsMomentsMax : kRowsReduceMax);
+    return g_variant.rows_reduce && seg_len >= (kind == kBoth ? kRowsMomentsMin : kRowsReduceMin) &&
+           seg_len <= (kind == kBoth ? kRowsMomentsMax : kRowsReduceMax);
 }
 inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2, uint64_t n, uint64_t seg_len, int kind,
                                      hipStream_t s) {
@@ -717,9 +720,9 @@ inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2
     grid.per_group = (uint32_t)(kRowsGroupElems / seg_len);
     grid.magic = (uint32_t)(((1ull << 32) + seg_len - 1) / seg_len);
     const dim3 blocks((unsigned)ceil_div(grid.nseg, grid.per_group)), block(W * kWave);
-    if (seg_len < 32) {              // two boundaries per row
-        if (kind == kBoth) rows_reduce_kernel<kBoth, U, W, true><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
-        else rows_reduce_kernel<kSum, U, W, true><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);
+    if (seg_len < 32) {              // 17 .. 31: two boundaries per row and a whole segment between them
+        if (kind == kBoth) rows_reduce_kernel<kBoth, U, W, 1><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
+        else rows_reduce_kernel<kSum, U, W, 1><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);
     } else {
         if (kind == kBoth) rows_reduce_kernel<kBoth, U, W><<<blocks, block, 0, s>>>(in - shift, out, out2, grid);
         else rows_reduce_kernel<kSum, U, W><<<blocks, block, 0, s>>>(in - shift, out, nullptr, grid);

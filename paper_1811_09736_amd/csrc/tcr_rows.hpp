@@ -15,8 +15,9 @@
 // the 16 rows of a sub-tile (four cross-lane steps on (flag, value) pairs), chained through the sub-tiles of a
 // wavefront in registers and through the wavefronts of a workgroup in LDS.  A row that holds the end of a
 // segment writes that segment's result: what arrives from the rows in front plus its own head.
-// With 16 < seg_len < 32 a row holds one or two boundaries, and between two of them lies a whole segment: a third
-// masked product, whose row sum is that segment's result as it stands.
+// With seg_len < 32 a row holds several boundaries, and between two of them lies a whole segment: one more masked
+// product each, whose row sum is that segment's result as it stands (dispatched from 17 elements on: one whole
+// segment per row at most; with two or three, 9 to 15 elements, the kernel is no faster than the fixed tiles).
 //
 // A workgroup owns WHOLE segments (as many as fit into 16320 elements), so no sum crosses workgroups: one
 // launch, no workspace, the same order of additions in every run.  Its rows are rows of the ARRAY (aligned 64-byte
@@ -53,10 +54,10 @@ __device__ __forceinline__ void rows_seg_scan_inclusive(uint32_t& f, float (&v)[
 }
 
 // KIND: kSum (out) or kBoth (out: sums, out2: sums of squares).
-// SHORT: 16 <= seg_len < 32.  A row then holds one or two boundaries, seg_len apart: its head, possibly one whole
-// segment between the two boundaries -- a third masked product, whose row sum is that segment's result as it
-// stands -- and its tail behind the last boundary.
-template <int KIND, int U, int WAVES, bool SHORT = false>
+// WHOLES > 0: seg_len < 32.  A row then holds up to WHOLES + 1 boundaries, seg_len apart (one more than 32 /
+// seg_len rounded down): its head, up to WHOLES whole segments between neighbouring boundaries -- one more masked
+// product each, whose row sum is that segment's result as it stands -- and its tail behind the last boundary.
+template <int KIND, int U, int WAVES, int WHOLES = 0>
 __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float16* __restrict__ in,
                                                                     float* __restrict__ out, float* __restrict__ out2,
                                                                     RowsGrid grid) {
@@ -99,8 +100,9 @@ __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float
     }
 
     float head[CH][U], carry_in[CH][U];      // per row: its head piece; the sum arriving from the rows in front (this sub-tile only)
-    float whole[CH][SHORT ? U : 1];          // SHORT: the segment between the row's two boundaries
-    uint32_t whole_which[SHORT ? U : 1];     // ... and which one it is (counted inside the workgroup, from 1; 0: none)
+    constexpr int kWholes = WHOLES > 0 ? WHOLES : 1;
+    float whole[CH][kWholes][U];             // WHOLES > 0: the segments between the row's boundaries
+    uint32_t whole_which[kWholes][U];        // ... and which they are (counted inside the workgroup, from 1; 0: none)
     uint32_t flag_in[U];                     // a boundary lies in an earlier row of the sub-tile
     uint32_t which[U];                       // the segment (counted inside the workgroup, from 1) that ends in this row; 0: none
     uint32_t seen_before[U];                 // a boundary lies in an earlier sub-tile of this wavefront
@@ -122,15 +124,20 @@ __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float
         const int lead = (int)c - 8 * id.g;                     // of this lane's eight elements, those in front of the boundary
         const half8 xh = keep_leading(x[u], has ? lead : 8);
         half8 xt = drop_leading(x[u], has ? lead : 8);
-        if constexpr (SHORT) {
-            // a second boundary seg_len further on: the elements between the two are segment k + 1 (from 1), whole
-            const bool second = c + L < 32u;                    // (c < seg_len < 32: the row always has the first)
-            whole_which[u] = (second && k < count) ? k + 1u : 0u;
-            const int lead2 = second ? lead + (int)L : 0;        // (none: nothing is kept for it, the tail stays as it is)
-            const half8 xm = keep_leading(xt, lead2);
-            xt = drop_leading(xt, lead2);
-            whole[0][u] = mfma(const_ones(), xm, splat(0.0f))[0];
-            if constexpr (CH == 2) whole[CH - 1][u] = row_squares(xm, id);
+        if constexpr (WHOLES > 0) {
+            // further boundaries, seg_len apart: the elements between boundary w and w + 1 of the row are segment
+            // k + w + 1 (from 1), whole.  (c < seg_len < 32: the row always has the first boundary.)
+#pragma unroll
+            for (int w = 0; w < WHOLES; ++w) {
+                const bool present = c + (uint32_t)(w + 1) * L < 32u;
+                whole_which[w][u] = (present && k + (uint32_t)w < count) ? k + (uint32_t)w + 1u : 0u;
+                // (not there: nothing is kept for it and the tail stays as it is)
+                const int upto = present ? lead + (w + 1) * (int)L : 0;
+                const half8 xm = keep_leading(xt, upto);
+                xt = drop_leading(xt, upto);
+                whole[0][w][u] = mfma(const_ones(), xm, splat(0.0f))[0];
+                if constexpr (CH == 2) whole[CH - 1][w][u] = row_squares(xm, id);
+            }
         }
         float v[CH];
         head[0][u] = mfma(const_ones(), xh, splat(0.0f))[0];
@@ -182,11 +189,14 @@ __global__ __launch_bounds__(WAVES * kWave) void rows_reduce_kernel(const _Float
                 out2[s] = (flag_in[u] ? carry_in[CH - 1][u] : carry_in[CH - 1][u] + into_sub) + head[CH - 1][u];
             }
         }
-        if constexpr (SHORT) {
-            if (whole_which[u] != 0u && id.g == 0) {
-                const uint64_t s = s0 + (uint64_t)(whole_which[u] - 1u);
-                out[s] = whole[0][u];
-                if constexpr (CH == 2) out2[s] = whole[CH - 1][u];
+        if constexpr (WHOLES > 0) {
+#pragma unroll
+            for (int w = 0; w < WHOLES; ++w) {
+                if (whole_which[w][u] != 0u && id.g == 0) {
+                    const uint64_t s = s0 + (uint64_t)(whole_which[w][u] - 1u);
+                    out[s] = whole[0][w][u];
+                    if constexpr (CH == 2) out2[s] = whole[CH - 1][w][u];
+                }
             }
         }
     }
