@@ -468,7 +468,9 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         int shape = strategy == kStrategyLookback ? pick_scan_shape(seg_len, whole) : -1;
         if (shape == kScanIdReduceThenScan) strategy = kStrategyReduceThenScan;
         if (shape == kScanIdScanThenPropagate) strategy = kStrategyScanThenPropagate;
+        if (shape == kScanIdChainTail) return mf ? "scan_chain_kernel<mfma>+scan_tail_kernel" : "scan_chain_kernel<dpp>+scan_tail_kernel";
         if (shape >= kScanShapeCount) shape = default_scan_shape(seg_len, whole, mf ? kMfma : kDpp);
+        if (shape == kScanIdChainTail) shape = 9;
         const bool table = strategy != kStrategyLookback;
         if (table && seg_len <= kCarryTile)
             return mf ? "scan_block_kernel<mfma,nocarry>" : "scan_block_kernel<dpp,nocarry>";

@@ -329,11 +329,13 @@ constexpr ScanShape kScanShapes[] = {{1, 2, false, 0}, {1, 4, false, 0}, {1, 8, 
 constexpr int kScanShapeCount = 12;
 // Two more ids choose a multi-kernel carry strategy instead of a single-pass shape (segments longer than one
 // 65536-element share only): the paper's three-kernel scan-then-propagate (Section 5) and reduce-then-scan.
-constexpr int kScanIdReduceThenScan = 12, kScanIdScanThenPropagate = 13, kScanIdCount = 14;
+// (14: one segment whose n is no multiple of 8 -- the chain over the whole groups of 8, then scan_tail_kernel)
+constexpr int kScanIdReduceThenScan = 12, kScanIdScanThenPropagate = 13, kScanIdChainTail = 14, kScanIdCount = 15;
 inline uint64_t scan_shape_tile(int id) { return (uint64_t)kTile * kScanShapes[id].u * kScanShapes[id].w; }
 
 inline bool scan_shape_valid(int id, uint64_t len, bool whole) {      // len: seg_len, or n for the one-segment scan
     if (id == kScanIdReduceThenScan || id == kScanIdScanThenPropagate) return len > kCarryTile;
+    if (id == kScanIdChainTail) return whole && len % 8 != 0 && len >= 2 * scan_shape_tile(10) && g_variant.scan_carry == kStrategyLookback;
     if (id < 0 || id >= kScanShapeCount) return false;
     if (kScanShapes[id].persistent)                             // (whole: len == n, which must be a multiple of 8)
         return whole ? len % 8 == 0 : len >= scan_shape_tile(id);
@@ -362,7 +364,9 @@ inline int default_scan_shape(uint64_t len, bool whole, int form) {
     // the pipelined chain: segments of 32768 and more, one segment with n % 8 == 0.  (16 wavefronts of 4 tiles
     // for the matrix cores; the DPP arithmetic needs more registers and takes 8 wavefronts of 8 tiles.)
     if (scan_shape_valid(10, len, whole)) return form == kMfma ? 10 : 11;
-    // n not a multiple of 8: scan_block_kernel shares of 65536 / 32768 elements with decoupled look-back
+    // n not a multiple of 8: the chain over the whole groups of 8 and a second, tiny kernel for the rest (measured
+    // at n = 2^28 - 3: 297 us against 307-323 us for scan_block_kernel with decoupled look-back, which short arrays keep)
+    if (scan_shape_valid(kScanIdChainTail, len, whole)) return kScanIdChainTail;
     return (whole || len >= (1u << 20)) ? 9 : 8;
 }
 
@@ -405,7 +409,8 @@ inline int nocarry_shape_for(uint64_t fit) {
 // The persistent chain (shape 10 or 11) over segments of `seg_len` elements: any multiple of 8 that is at
 // least one tile, or one segment of n elements (n a multiple of 8).
 template <int FORM, int MODE>
-tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, uint64_t seg_len, hipStream_t s) {
+tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, uint64_t seg_len, hipStream_t s,
+                        ScanWorkspace* used = nullptr, uint32_t* used_tiles = nullptr) {
     const uint64_t tile = scan_shape_tile(shape);
     const uint64_t per_segment = ceil_div(seg_len, tile);
     const uint64_t tiles = (n / seg_len) * per_segment;
@@ -427,7 +432,21 @@ tcr_status launch_chain(int shape, const _Float16* in, void* out, uint64_t n, ui
         return st;
     }
     ws->tickets_issued += (uint32_t)(tiles + 3 * groups);   // three drawn at the start of every workgroup, one per tile
+    if (used != nullptr) *used = dev;
+    if (used_tiles != nullptr) *used_tiles = (uint32_t)tiles;
     return TCR_OK;
+}
+
+// One segment of n elements, n no multiple of 8: the chain over the first n - n % 8, then the rest.
+template <int FORM, int MODE>
+tcr_status launch_chain_tail(const _Float16* in, void* out, uint64_t n, hipStream_t s) {
+    const uint64_t n8 = n & ~7ull;
+    ScanWorkspace dev = {};
+    uint32_t tiles = 0;
+    tcr_status st = launch_chain<FORM, MODE>(FORM == kMfma ? 10 : 11, in, out, n8, n8, s, &dev, &tiles);
+    if (st != TCR_OK) return st;
+    scan_tail_kernel<MODE><<<dim3(1), dim3(kTailThreads), 0, s>>>(in, out, n8, n, dev, tiles);
+    return check_launch("scan_tail_kernel");
 }
 
 // seg_len >= 1024 (power of two), or the full scan (seg_len == n, any n).
@@ -441,7 +460,9 @@ inline tcr_status scan_long(const _Float16* in, void* out, uint64_t n, uint64_t 
     int shape = strategy == kStrategyLookback ? pick_scan_shape(host_seg_len, whole) : -1;
     if (shape == kScanIdReduceThenScan) strategy = kStrategyReduceThenScan;
     if (shape == kScanIdScanThenPropagate) strategy = MODE == 0 ? kStrategyScanThenPropagate : kStrategyLookback;
+    if (shape == kScanIdChainTail) return launch_chain_tail<FORM, MODE>(in, out, n, s);
     if (shape >= kScanShapeCount) shape = default_scan_shape(host_seg_len, whole, FORM);    // (the strategies have fixed shapes)
+    if (shape == kScanIdChainTail) shape = 9;             // (a forced multi-kernel strategy: its no-carry shares do not use it)
     const bool table = strategy != kStrategyLookback;     // the two multi-kernel strategies
     if (table && host_seg_len <= kCarryTile) {
         const ScanWorkspace none = {};

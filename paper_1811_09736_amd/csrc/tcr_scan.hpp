@@ -734,6 +734,46 @@ __global__ __launch_bounds__(WAVES * kWave) void scan_chain_kernel(const _Float1
     }
 }
 
+// The last n - n8 (1 .. 7) elements of a one-segment scan whose n is no multiple of 8, after scan_chain_kernel has
+// scanned the first n8 = n - n % 8 (the chain's tiles end with whole groups of 8 elements).  One workgroup: the
+// sum of everything in front is the sum of the chain's tile totals, which all lie in its descriptor table once it
+// has finished (eight reads per thread on their way at a time: the table is uncached); one thread then runs over
+// the remaining elements.  MODE as for the chain.
+constexpr int kTailThreads = 1024;
+template <int MODE>
+__global__ __launch_bounds__(kTailThreads) void scan_tail_kernel(const _Float16* __restrict__ in, void* __restrict__ out,
+                                                                 uint64_t n8, uint64_t n, ScanWorkspace ws_arg, uint32_t tiles) {
+    constexpr int EXCL = MODE & 1, F16 = MODE >> 1;
+    __shared__ float s_part[kTailThreads / kWave];
+    const ScanWorkspace ws = resolve_workspace(ws_arg);
+    float part = 0.0f;
+    for (uint32_t t0 = threadIdx.x; t0 < tiles; t0 += 8u * kTailThreads) {
+        unsigned long long d[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t t = t0 + (uint32_t)(q * kTailThreads);
+            d[q] = load_descriptor(&ws.desc[t < tiles ? t : t0]);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (t0 + (uint32_t)(q * kTailThreads) < tiles) part += __builtin_bit_cast(float, (uint32_t)d[q]);
+    }
+    part = wave_sum(part);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_part[threadIdx.x >> 6] = part;
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    float acc = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kTailThreads / kWave; ++w) acc += s_part[w];
+    for (uint64_t k = n8; k < n; ++k) {
+        const float x = (float)in[k];
+        const float r = EXCL ? acc : acc + x;
+        acc += x;
+        if constexpr (F16) static_cast<_Float16*>(out)[k] = (_Float16)r;
+        else static_cast<float*>(out)[k] = r;
+    }
+}
+
 // ------------------------------------------------------------------------------ one workgroup per segment, any length
 // Segment lengths that are no power of two (the paper pads such segments, Section 4): workgroup s scans
 // segment s, whose length is a multiple of 8 and at most WAVES * U tiles.  The tiles are laid out from the

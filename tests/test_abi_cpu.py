@@ -117,7 +117,8 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_REDUCE, n, n).endswith("+reduce_final_kernel")
     assert k(lib.OP_REDUCE, 1000, 1000) == "reduce_span_kernel<mfma,wave>"
     assert k(lib.OP_SCAN, n, n) == "scan_chain_kernel<mfma>"
-    assert k(lib.OP_SCAN, n - 3, n - 3) == "scan_block_kernel<mfma,lookback>"      # n not a multiple of 8
+    assert k(lib.OP_SCAN, n - 3, n - 3) == "scan_chain_kernel<mfma>+scan_tail_kernel"      # n not a multiple of 8
+    assert k(lib.OP_SCAN, 40003, 40003).startswith("scan_block_kernel<mfma,")              # ... under two chain tiles: one kernel
     lib.set_variant("formulation", "dpp")
     try:
         assert k(lib.OP_SCAN, n, n) == "scan_chain_kernel<dpp>"
@@ -175,7 +176,7 @@ def test_tuning_table_text_round_trip(lib):
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 16) == "scan_block_kernel<mfma,lookback>"
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
         lib.tuning_import("scan:16=0;")
-        for bad in ("scan:14", "scan:99=1;", "scan:14=14;", "reduce:20=4;", "sort:3=1;", "scan:14=8", "scan:14=64;",
+        for bad in ("scan:14", "scan:99=1;", "scan:14=15;", "reduce:20=4;", "sort:3=1;", "scan:14=8", "scan:14=64;",
                     "scan_any:6=32;", "reduce_any:6=4;", "irregular:2=0;", "irregular:0=3;", "scan_an:6=1;"):
             with pytest.raises(lib.TcrError):
                 lib.tuning_import(bad)
