@@ -126,7 +126,7 @@ def main() -> int:
             tcr.autotune(ids[op], x, out_scan, 1 << e)
         tcr.autotune(tcr.OP_REDUCE, x, out_scan, 0)
         tcr.autotune(tcr.OP_SCAN, x, out_scan, 0)
-        for seg in (100, 196, 3000, 3001, 3 << 20):          # the lengths of the context rows without a tuned path
+        for seg in (100, 196, 3000, 3001, 3584, 3 << 20):          # the lengths of the context rows without a tuned path
             m = (n // seg) * seg
             if m:
                 tcr.autotune(tcr.OP_SEGMENTED_SCAN, x[:m], out_scan, seg)
@@ -191,6 +191,7 @@ def main() -> int:
     big = 3 << 20
     nb = (n // big) * big
     n3 = (n // 3000) * 3000
+    n35 = (n // 3584) * 3584
     n1, n100 = (n // 3001) * 3001, (n // 100) * 100
     out_g = torch.empty(n3 // 3000, dtype=torch.float32, device="cuda")
     out_h100 = torch.empty(n100 // 100, dtype=torch.float32, device="cuda")
@@ -274,8 +275,10 @@ def main() -> int:
              lambda: tcr.segmented_scan(x[:nb], big, out=out_scan[:nb]), nb, (2 * nb, 4 * nb)),
             ("segmented_reduce seg_len=3000 (no power of two: masked row products)", lambda: tcr.segmented_reduce(x[:n3], 3000, out=out_g), n3,
              (2 * n3, 4 * (n3 // 3000))),
-            ("segmented_scan seg_len=3000 (no power of two: one workgroup per segment)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
+            ("segmented_scan seg_len=3000 (no power of two: fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n3], 3000, out=out_scan[:n3]), n3,
              (2 * n3, 4 * n3)),
+            ("segmented_scan seg_len=3584 (aligned, seven eighths of 8 tiles: one workgroup per segment)",
+             lambda: tcr.segmented_scan(x[:n35], 3584, out=out_scan[:n35]), n35, (2 * n35, 4 * n35)),
             ("segmented_scan seg_len=3001 (odd: fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n1], 3001, out=out_scan[:n1]), n1,
              (2 * n1, 4 * n1)),
             ("segmented_scan seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n100], 100, out=out_scan[:n100]), n100,

@@ -67,8 +67,10 @@ typedef enum {
  * data operand of the products row by row where a segment ends (the masking that Section 4 proposes for
  * arbitrary segment sizes, moved from the constant matrix to the data; no workspace); reductions of 5 to 15
  * elements and all scans run on fixed tiles of the array with the segment starts marked (the kernels of the
- * irregular calls below; they use the workspace), except scans of a multiple of 8 elements above 512, which have
- * one workgroup per segment or, from 65536 elements, the chained scan; longer reductions run one wavefront per
+ * irregular calls below; they use the workspace), except scans of a multiple of 8 elements from 65536 on (the
+ * chained scan) and of a multiple of 64 elements up to 8192 that fills a workgroup's tiles to four fifths (one
+ * workgroup per segment; the tuning table can give it every multiple of 8 between 520 and 65528); longer
+ * reductions run one wavefront per
  * segment (per 65536-element piece of one, from 131072 elements) over zero-masked tiles of the array, the
  * paper's padding of such segments (Section 4) applied in registers.
  */

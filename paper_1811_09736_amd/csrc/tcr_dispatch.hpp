@@ -956,7 +956,7 @@ inline bool chain_takes_any_length(uint64_t seg_len) {
 }
 
 // Which kernel takes a scan whose seg_len is no power of two (or below 16); class = floor(log2(seg_len)).  The
-// default is the first valid one of: chain, segment, tiles.
+// default: the chain where it is valid, one workgroup per segment where that is known to win, else the tiles.
 enum ScanAny { kScanAnyTiles = 0, kScanAnyTilesAlt = 1, kScanAnySegment = 2, kScanAnyChain = 3, kScanAnyCount = 4 };
 inline bool scan_any_valid(int id, uint64_t seg_len) {
     switch (id) {
@@ -967,11 +967,22 @@ inline bool scan_any_valid(int id, uint64_t seg_len) {
         default: return false;
     }
 }
+// One workgroup per segment beats the fixed tiles (284-291 us at n = 2^28 whatever the length) where the segments
+// start on 128-byte boundaries and fill at least four fifths of the workgroup's share of one tile per wavefront:
+// 270-282 us at 1280, 1536, 2560, 3584, 7168 and 8000 elements; 293-372 us at 520, 1000, 2056, 3000, 4088, 4104
+// (short of the share, or rows of the tiles that straddle cache lines), 300-315 us from 12000 elements on (two
+// tiles per wavefront).
+inline bool segment_kernel_preferred(uint64_t seg_len) {
+    if (!segment_kernel_takes(seg_len) || seg_len % 64 != 0 || seg_len > 16 * (uint64_t)kTile) return false;
+    const uint64_t t = ceil_div(seg_len, kTile);
+    const uint64_t share = t <= 4 ? t : (t <= 6 ? 6 : (t <= 8 ? 8 : (t <= 12 ? 12 : 16)));     // as launch_scan_segment picks it
+    return 5 * seg_len >= 4 * share * kTile;
+}
 inline int pick_scan_any(uint64_t seg_len) {
     const int tuned = tuned_id(kTuneScanAny, floor_log2(seg_len));
     if (scan_any_valid(tuned, seg_len)) return tuned;
     if (scan_any_valid(kScanAnyChain, seg_len)) return kScanAnyChain;
-    if (scan_any_valid(kScanAnySegment, seg_len)) return kScanAnySegment;
+    if (segment_kernel_preferred(seg_len)) return kScanAnySegment;
     return kScanAnyTiles;
 }
 

@@ -150,8 +150,10 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_REDUCE, 3 << 24, 3 << 20) == "masked_span_reduce_kernel+reduce_final_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 3 << 24, 3 << 20) == "scan_chain_kernel<mfma>"        # long, a multiple of 8
     assert k(lib.OP_SEGMENTED_SCAN, 100003 * 5, 100003) == "irregular_scan_kernel<regular>"   # long, odd
-    assert k(lib.OP_SEGMENTED_SCAN, 40000 * 5, 40000) == "scan_segment_kernel"             # under two chain tiles
-    assert k(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "scan_segment_kernel"             # a multiple of 8: one workgroup each
+    assert k(lib.OP_SEGMENTED_SCAN, 40000 * 5, 40000) == "irregular_scan_kernel<regular>"   # under two chain tiles
+    assert k(lib.OP_SEGMENTED_SCAN, 3584 * 7, 3584) == "scan_segment_kernel"             # aligned, fills its workgroup: one each
+    assert k(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "irregular_scan_kernel<regular>"   # a multiple of 8 that does not
+    assert k(lib.OP_SEGMENTED_SCAN, 4160 * 7, 4160) == "irregular_scan_kernel<regular>"   # aligned, two thirds of 12 tiles
     assert k(lib.OP_SEGMENTED_SCAN, 3001 * 7, 3001) == "irregular_scan_kernel<regular>"
     assert k(lib.OP_SEGMENTED_SCAN, 200 * 7, 200) == "irregular_scan_kernel<regular>"
     assert k(lib.OP_SEGMENTED_SCAN, n, 3) == ""           # 3 does not divide n: the call reports an invalid argument

@@ -86,10 +86,10 @@ def test_variants_exact(tcr, oracle, seg, flags):
 
 @pytest.mark.parametrize("flags", [EXCL, F16, EXCL | F16])
 @pytest.mark.parametrize("dist", ["uniform_01", "uniform_pm1"])
-@pytest.mark.parametrize("seg", [16, 256, 2048, 16384, 1 << 17, 100, 3000, 3 << 16])
+@pytest.mark.parametrize("seg", [16, 256, 2048, 16384, 1 << 17, 100, 3000, 3584, 3 << 16])
 def test_variants_real(tcr, oracle, seg, flags, dist):
     # seg_len 16 .. 2048: no carry between workgroups; 16384: tiles by ticket; 2^17, 3 * 2^16: the chain;
-    # 100: fixed tiles with the segment starts marked; 3000: one workgroup per segment.
+    # 100, 3000: fixed tiles with the segment starts marked; 3584: one workgroup per segment.
     # uniform_pm1 is zero-mean: outputs cross zero, the rho part of the rule decides there.
     nseg = 3 if seg >= 8192 else (3 * 8192 // seg + 3)
     n = seg * nseg
@@ -199,21 +199,40 @@ def test_irregular_behind_unaligned_pointers(tcr, oracle):
     assert np.array_equal(red, oracle.irregular_reduce(x[1:].copy(), off))
 
 
-@pytest.mark.parametrize("seg", [256 + 8, 511, 513, 520, 1000, 3000, 8200, 3001, 40000, 65528, 100003])
+def _segment_kernel_by_default(seg):
+    # one workgroup per segment where the segments start on 128-byte boundaries and fill four fifths of the
+    # workgroup's share (2, 3, 4, 6, 8, 12 or 16 tiles of 512 elements)
+    if seg % 64 or seg <= 512 or seg > 8192:
+        return False
+    t = -(-seg // 512)
+    share = t if t <= 4 else 6 if t <= 6 else 8 if t <= 8 else 12 if t <= 12 else 16
+    return 5 * seg >= 4 * share * 512
+
+
+@pytest.mark.parametrize("seg", [256 + 8, 511, 513, 520, 1000, 1280, 1536, 3000, 3584, 8000, 8192 - 64, 8200, 3001, 40000, 65528, 100003])
 @pytest.mark.parametrize("flags", [0, 1, 2, 3])
 def test_other_segment_lengths_take_every_flag(tcr, oracle, seg, flags):
-    # multiples of 8 above one tile: one workgroup per segment; everything else: fixed tiles of the array with
-    # the segment starts marked
+    # by default: one workgroup per segment where that is known to win, else fixed tiles of the array with the
+    # segment starts marked; every multiple of 8 above one tile is also run through the kernel with one workgroup
+    # per segment
     nseg = max(3, (200000 // seg) | 1)
     x = workloads.make_input(seg * nseg, "int4", seg % 89)
     xd = torch.from_numpy(x).cuda()
-    want = "scan_segment_kernel" if seg % 8 == 0 and seg > 512 else "irregular_scan_kernel<regular>"
+    want = "scan_segment_kernel" if _segment_kernel_by_default(seg) else "irregular_scan_kernel<regular>"
     assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, x.size, seg) == want
     ref = oracle.segmented_scan_exclusive(x, seg) if flags & 1 else oracle.segmented_scan(x, seg)
-    got = tcr.segmented_scan_ex(xd, seg, flags).cpu().numpy().astype(np.float64)
     if flags & 2:
         ref = ref.astype(np.float16).astype(np.float64)            # integer sums: one correct rounding
+    got = tcr.segmented_scan_ex(xd, seg, flags).cpu().numpy().astype(np.float64)
     assert np.array_equal(got, ref)
+    if seg % 8 == 0 and seg > 512 and want != "scan_segment_kernel":
+        tcr.tuning_import(f"scan_any:{seg.bit_length() - 1}=2;")
+        try:
+            assert tcr.kernel_name(tcr.OP_SEGMENTED_SCAN, x.size, seg) == "scan_segment_kernel"
+            got = tcr.segmented_scan_ex(xd, seg, flags).cpu().numpy().astype(np.float64)
+        finally:
+            tcr.tuning_import("")
+        assert np.array_equal(got, ref)
     assert np.array_equal(tcr.segmented_reduce(xd, seg).cpu().numpy().astype(np.float64), oracle.segmented_reduce(x, seg))
 
 
