@@ -16,6 +16,7 @@ extern "C" tcr_status tcr_segmented_reduce(const void* in, float* out, uint64_t 
     // the tuned kernels load 128 bits at a time; an input that is not aligned for that takes the fixed tiles laid
     // out from the 16-byte boundary below it
     if (!aligned(in, 16)) {
+        if (aligned(in, 4) && packed_reduce_takes(seg_len)) return launch_packed_reduce(x, out, nullptr, n, seg_len, kSum, s);
         if (rows_reduce_takes(seg_len)) return launch_rows_reduce(x, out, nullptr, n, seg_len, kSum, s);    // (any length it fits)
         return launch_irregular_reduce(x, nullptr, out, n, n / seg_len, seg_len, s);
     }
@@ -187,6 +188,8 @@ extern "C" tcr_status tcr_segmented_moments(const void* in, float* sum, float* s
     tcr_status st = validate(in, sum, n, seg_len, 4);
     if (st != TCR_OK || n == 0) return st;
     if (sumsq == nullptr || !aligned(sumsq, 4)) return TCR_ERR_INVALID_ARG;
+    if (!aligned(in, 16) && aligned(in, 4) && packed_reduce_takes(seg_len))
+        return launch_packed_reduce(static_cast<const _Float16*>(in), sum, sumsq, n, seg_len, kBoth, static_cast<hipStream_t>(stream));
     if (!aligned(in, 16) && rows_reduce_takes(seg_len, kBoth))
         return launch_rows_reduce(static_cast<const _Float16*>(in), sum, sumsq, n, seg_len, kBoth, static_cast<hipStream_t>(stream));
     if (!aligned(in, 16))                    // the tiled reduction with both moments as its two channels
@@ -432,8 +435,9 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
         if (op != 0 && op != 1) return "";
         if (op == 0) {
             if (is_pow2(seg_len) && seg_len <= 8) return "tiny_reduce_kernel";       // (16-byte aligned results)
-            if (seg_len < kTiledReduceMin) return "generic_thread_kernel";
             const int pick = pick_reduce_any(seg_len);
+            if (pick == kReduceAnyPacked || pick == kReduceAnyPackedAlt) return "packed_rows_reduce_kernel";
+            if (seg_len < kTiledReduceMin) return "generic_thread_kernel";
             if (pick == kReduceAnyRows) return "rows_reduce_kernel";
             if (pick == kReduceAnyTiles || pick == kReduceAnyTilesAlt) return "irregular_reduce_kernel<regular>+irregular_groups_kernel+irregular_carry_kernel";
             return seg_len <= 2 * kWaveSpanMax ? "masked_wave_reduce_kernel" : "masked_span_reduce_kernel+reduce_final_kernel";

@@ -751,6 +751,38 @@ inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2
     return check_launch("rows_reduce_kernel");
 }
 
+// Regular segments of 3 to 30 elements that pack into rows of an even number of at most 32 elements (every even
+// length that is no power of two, odd lengths up to 15): one product per 16 rows with a masked constant matrix
+// (tcr_packed.hpp).  `in` 4-byte aligned.  kind: kSum, or kBoth with the sums of squares in out2.
+// Measured at n = 2^28 against the kernels that took these lengths before -- sums: 3 elements 162 us (one thread per
+// segment: 274), 5 to 7 107-116 (fixed tiles with marked starts 162-183), 9 to 15 98-104 (125-148), even lengths
+// from 18 to 30 91-99 (masked rows of the array 102-106); both moments: 3 elements 310 (one thread per segment
+// 320-345), 5 to 7 153-190 (213-250), 9 to 15 110-134 (180-216), 18 to 30 100-110 (140-170).
+// Two launch shapes: eight tiles per wavefront where a row's width is no multiple of 8 (rows of 18 elements: 99
+// against 113 us; 22: 97 against 105; 26 to 30: 94-96 against 97-99), four where it is (24: 90 against 96 us); twelve
+// or sixteen tiles, or two or eight wavefronts, change nothing.  (U, W) = (8, 4) and (4, 4).
+inline bool packed_reduce_takes(uint64_t seg_len) { return g_variant.rows_reduce && packed_per_row(seg_len) != 0 && !is_pow2(seg_len); }
+template <int KIND, int U, int W>
+inline void launch_packed_shape(const _Float16* in, float* out, float* out2, const PackedGrid& grid, hipStream_t s) {
+    const uint64_t rows = ceil_div(grid.nseg, (uint64_t)grid.per_row);
+    const size_t staging = (size_t)W * channels<KIND>() * 16 * U * grid.per_row * sizeof(float);      // at most 40 KiB
+    packed_rows_reduce_kernel<KIND, U, W><<<dim3((unsigned)ceil_div(rows, (uint64_t)(16 * U * W))), dim3(W * kWave), staging, s>>>(in, out, out2, grid);
+}
+// alt: the other launch shape than the one the row width calls for.
+inline tcr_status launch_packed_reduce(const _Float16* in, float* out, float* out2, uint64_t n, uint64_t seg_len, int kind,
+                                       hipStream_t s, bool alt = false) {
+    const PackedGrid grid = {n, n / seg_len, (uint32_t)seg_len, packed_per_row(seg_len)};
+    const bool four = ((grid.seg_len * grid.per_row) % 8u == 0) != alt;
+    if (kind == kBoth) {
+        if (four) launch_packed_shape<kBoth, 4, 4>(in, out, out2, grid, s);
+        else launch_packed_shape<kBoth, 8, 4>(in, out, out2, grid, s);
+    } else {
+        if (four) launch_packed_shape<kSum, 4, 4>(in, out, nullptr, grid, s);
+        else launch_packed_shape<kSum, 8, 4>(in, out, nullptr, grid, s);
+    }
+    return check_launch("packed_rows_reduce_kernel");
+}
+
 // Any other seg_len >= 1 (no power of two, or below 16): no kernel is tuned for it.
 // Scans from 2 elements on and reductions of 8 to 999 elements run on the fixed tiles of the irregular
 // kernels with the multiples of seg_len as segment starts.  Measured at n = 2^28: scans 300-325 us
@@ -766,7 +798,7 @@ constexpr uint64_t kTiledReduceMin = 5, kTiledMomentsMin = 8, kTiledReduceMax = 
 // Which kernel takes a reduction whose seg_len is no power of two (or below 16); class = floor(log2(seg_len)).
 // The default is the first valid one of: rows, tiles, the rest (one wavefront per segment over masked tiles from
 // 1000 elements, one thread per segment below 5).
-enum ReduceAny { kReduceAnyRows = 0, kReduceAnyTiles = 1, kReduceAnyTilesAlt = 2, kReduceAnyMasked = 3, kReduceAnyCount = 4 };
+enum ReduceAny { kReduceAnyRows = 0, kReduceAnyTiles = 1, kReduceAnyTilesAlt = 2, kReduceAnyMasked = 3, kReduceAnyPacked = 4, kReduceAnyPackedAlt = 5, kReduceAnyCount = 6 };
 constexpr uint64_t kMaskedReduceMin = 256;              // (valid for any length; pointless for short segments)
 inline bool reduce_any_valid(int id, uint64_t seg_len) {
     switch (id) {
@@ -774,12 +806,16 @@ inline bool reduce_any_valid(int id, uint64_t seg_len) {
         case kReduceAnyTiles:
         case kReduceAnyTilesAlt: return seg_len >= kTiledReduceMin && seg_len < kTiledReduceMax;
         case kReduceAnyMasked: return seg_len >= kMaskedReduceMin;
+        case kReduceAnyPacked:
+        case kReduceAnyPackedAlt: return packed_reduce_takes(seg_len);
         default: return false;
     }
 }
-inline int pick_reduce_any(uint64_t seg_len) {
+// packed_ok: the array is 4-byte aligned (the packed rows need that; kernel names are given for aligned arrays)
+inline int pick_reduce_any(uint64_t seg_len, bool packed_ok = true) {
     const int tuned = tuned_id(kTuneReduceAny, floor_log2(seg_len));
-    if (reduce_any_valid(tuned, seg_len)) return tuned;
+    if (reduce_any_valid(tuned, seg_len) && ((tuned != kReduceAnyPacked && tuned != kReduceAnyPackedAlt) || packed_ok)) return tuned;
+    if (packed_ok && reduce_any_valid(kReduceAnyPacked, seg_len)) return kReduceAnyPacked;
     if (reduce_any_valid(kReduceAnyRows, seg_len)) return kReduceAnyRows;
     if (reduce_any_valid(kReduceAnyTiles, seg_len)) return kReduceAnyTiles;
     return kReduceAnyMasked;                            // (or one thread per segment, below 8 elements)
@@ -822,13 +858,15 @@ inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint
             }
         }
     } else {
-        const int pick = pick_reduce_any(seg_len);
+        const int pick = pick_reduce_any(seg_len, aligned(in, 4));
+        if (pick == kReduceAnyPacked || pick == kReduceAnyPackedAlt)
+            return launch_packed_reduce(in, static_cast<float*>(out), nullptr, n, seg_len, kSum, s, pick == kReduceAnyPackedAlt);
         if (pick == kReduceAnyRows) return launch_rows_reduce(in, static_cast<float*>(out), nullptr, n, seg_len, kSum, s);
         if (pick == kReduceAnyTiles || pick == kReduceAnyTilesAlt)
             return launch_irregular_reduce(in, nullptr, static_cast<float*>(out), n, nseg, seg_len, s, kSum, nullptr,
                                            pick == kReduceAnyTilesAlt ? 1 : 0);
     }
-    if (SCAN || seg_len < kTiledReduceMin) {
+    if (SCAN || seg_len < kTiledReduceMin) {         // (also reductions of 3 elements from an array that is not 4-byte aligned)
         generic_thread_kernel<SCAN><<<dim3((unsigned)ceil_div(nseg, kGenericThreads)), dim3(kGenericThreads), 0, s>>>(
             in, out, nseg, seg_len, excl, f16);
         return check_launch("generic_thread_kernel");
@@ -884,6 +922,7 @@ inline tcr_status launch_moments(const _Float16* in, float* sum, float* sumsq, u
         }
         return check_launch("moments_small_kernel");
     }
+    if (packed_reduce_takes(seg_len) && aligned(in, 4)) return launch_packed_reduce(in, sum, sumsq, n, seg_len, kBoth, s);
     if (rows_reduce_takes(seg_len, kBoth)) return launch_rows_reduce(in, sum, sumsq, n, seg_len, kBoth, s);
     if (seg_len >= kTiledMomentsMin && seg_len < kTiledReduceMax) {
         // fixed tiles with the segment starts marked, both moments as two channels of one pass

@@ -18,6 +18,7 @@
 #include "tcr_generic.hpp"
 #include "tcr_irregular.hpp"
 #include "tcr_rows.hpp"
+#include "tcr_packed.hpp"
 #include "tcr_half.hpp"
 
 namespace tcr {
@@ -45,7 +46,7 @@ struct Variant {
     bool reduce_fused = false;      // long reductions: a second kernel adds the partials (true: the last workgroup does)
     int tile_load = kLoadDirect;    // small power-of-two segments, default shape and mode: how tiles reach the operand registers
     int irregular_scan = 0;         // 0: one kernel or two by the number of segments; 1: always one; 2: always two (where possible)
-    bool rows_reduce = true;        // untuned lengths from 32 elements: masked row products (false: the fixed tiles with marked starts)
+    bool rows_reduce = true;        // untuned lengths: the row-product kernels (false: the fixed tiles with marked starts)
 };
 inline Variant g_variant;
 

@@ -132,14 +132,16 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "irregular_scan_kernel<regular>"     # untuned lengths: fixed tiles
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 1) == "tiny_scan_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 8) == "tiny_scan_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 3) == "generic_thread_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6).startswith("irregular_reduce_kernel<regular>")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 12).startswith("irregular_reduce_kernel<regular>+")   # several boundaries per tile row
-    for seg in (17, 24, 33, 48, 999, 1001, 8160):          # from 17 elements: masked row products, whole segments per workgroup
+    for seg in (3, 5, 6, 7, 9, 12, 15, 18, 24, 30):        # rows of whole segments, an even number of at most 32 elements
+        assert k(lib.OP_SEGMENTED_REDUCE, seg * 1000, seg) == "packed_rows_reduce_kernel"
+    for seg in (17, 25, 31, 33, 48, 999, 1001, 8160):      # masked rows of the array, whole segments per workgroup
         assert k(lib.OP_SEGMENTED_REDUCE, seg * 5, seg) == "rows_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 8168 * 5, 8168) == "masked_wave_reduce_kernel"
     lib.set_variant("untuned_reduce", "tiles")
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 3) == "generic_thread_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6).startswith("irregular_reduce_kernel<regular>")
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 12).startswith("irregular_reduce_kernel<regular>+")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 48).startswith("irregular_reduce_kernel<regular>+")
     assert k(lib.OP_SEGMENTED_REDUCE, 1001 * 5, 1001) == "masked_wave_reduce_kernel"
     lib.set_variant("reset")
@@ -179,7 +181,7 @@ def test_tuning_table_text_round_trip(lib):
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 1 << 28, 1 << 14) == "scan_block_kernel<mfma,ticket>"
         lib.tuning_import("scan:16=0;")
         for bad in ("scan:14", "scan:99=1;", "scan:14=15;", "reduce:20=4;", "sort:3=1;", "scan:14=8", "scan:14=64;",
-                    "scan_any:6=32;", "reduce_any:6=4;", "irregular:2=0;", "irregular:0=3;", "scan_an:6=1;"):
+                    "scan_any:6=32;", "reduce_any:6=6;", "irregular:2=0;", "irregular:0=3;", "scan_an:6=1;"):
             with pytest.raises(lib.TcrError):
                 lib.tuning_import(bad)
         assert lib.tuning_export() == "scan:16=0;"       # a rejected text leaves the table untouched
@@ -199,6 +201,10 @@ def test_tuning_table_text_round_trip(lib):
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 3000 * 7, 3000) == "irregular_scan_kernel<regular>"
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, 3 << 20, 3 << 16) == "irregular_scan_kernel<regular>"
         assert lib.kernel_name(lib.OP_SEGMENTED_SCAN, n, 1 << 12) == "scan_block_kernel<mfma,nocarry>"   # a strategy needs long segments
+        lib.tuning_import("reduce_any:3=1;reduce_any:4=0;reduce_any:6=4;")
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 12 * 500, 12).startswith("irregular_reduce_kernel<regular>")
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 24 * 500, 24) == "rows_reduce_kernel"
+        assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 100 * 500, 100) == "rows_reduce_kernel"    # no packed rows of 100: the default stays
         lib.tuning_import("reduce_any:5=1;")                 # tiles are for 8 .. 999 elements; 33 fits, ...
         assert lib.kernel_name(lib.OP_SEGMENTED_REDUCE, 33 * 5, 33).startswith("irregular_reduce_kernel<regular>")
         lib.tuning_import("reduce_any:12=1;")                # ... 5000 does not: the default stays
