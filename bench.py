@@ -126,7 +126,7 @@ def main() -> int:
             tcr.autotune(ids[op], x, out_scan, 1 << e)
         tcr.autotune(tcr.OP_REDUCE, x, out_scan, 0)
         tcr.autotune(tcr.OP_SCAN, x, out_scan, 0)
-        for seg in (100, 196, 3000, 3001, 3584, 3 << 20):          # the lengths of the context rows without a tuned path
+        for seg in (12, 100, 196, 3000, 3001, 3584, 3 << 20):          # the lengths of the context rows without a tuned path
             m = (n // seg) * seg
             if m:
                 tcr.autotune(tcr.OP_SEGMENTED_SCAN, x[:m], out_scan, seg)
@@ -193,6 +193,8 @@ def main() -> int:
     n3 = (n // 3000) * 3000
     n35 = (n // 3584) * 3584
     n1, n100 = (n // 3001) * 3001, (n // 100) * 100
+    n12 = (n // 12) * 12
+    out_h12 = torch.empty(n12 // 12, dtype=torch.float32, device="cuda")
     out_g = torch.empty(n3 // 3000, dtype=torch.float32, device="cuda")
     out_h100 = torch.empty(n100 // 100, dtype=torch.float32, device="cuda")
     out_h = torch.empty(n, dtype=torch.float16, device="cuda")
@@ -213,6 +215,9 @@ def main() -> int:
     n196 = (n // 196) * 196
     variant_rows.append(("segmented_moments seg_len=196 (14x14 feature maps: masked row products, sums and sums of squares)",
                          lambda: tcr.segmented_moments(x[:n196], 196), n196, (2 * n196, 8 * (n196 // 196))))
+    n24 = (n // 24) * 24
+    variant_rows.append(("segmented_moments seg_len=24 (6x4 windows: rows of one segment each, masked constant matrix)",
+                         lambda: tcr.segmented_moments(x[:n24], 24), n24, (2 * n24, 8 * (n24 // 24))))
     if args.formulation == "mfma":
         variant_rows.append(("segmented_scan_ex seg_len=2^12 exclusive",
                              lambda: tcr.segmented_scan_ex(x, 1 << 12, tcr.SCAN_EXCLUSIVE, out=out_scan), n, (2 * n, 4 * n)))
@@ -284,7 +289,9 @@ def main() -> int:
             ("segmented_scan seg_len=100 (fixed tiles, segment starts marked)", lambda: tcr.segmented_scan(x[:n100], 100, out=out_scan[:n100]), n100,
              (2 * n100, 4 * n100)),
             ("segmented_reduce seg_len=100 (no power of two: masked row products)", lambda: tcr.segmented_reduce(x[:n100], 100, out=out_h100), n100,
-             (2 * n100, 4 * (n100 // 100)))] if args.context_filter in row[0]]:
+             (2 * n100, 4 * (n100 // 100))),
+            ("segmented_reduce seg_len=12 (rows of two whole segments: one product with a masked constant matrix)",
+             lambda: tcr.segmented_reduce(x[:n12], 12, out=out_h12), n12, (2 * n12, 4 * (n12 // 12)))] if args.context_filter in row[0]]:
         fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

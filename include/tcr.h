@@ -63,10 +63,13 @@ typedef enum {
  *   out[s] = sum_{k < seg_len} in[s*seg_len + k],  s = 0 .. n/seg_len - 1.
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
- * seg_len == n.  Other lengths: reductions of 17 to 8160 elements take whole segments per workgroup and mask the
- * data operand of the products row by row where a segment ends (the masking that Section 4 proposes for
- * arbitrary segment sizes, moved from the constant matrix to the data; no workspace); reductions of 5 to 15
- * elements and all scans run on fixed tiles of the array with the segment starts marked (the kernels of the
+ * seg_len == n.  Other lengths: reductions of 3 to 30 elements that pack into rows of an even number of at most 32
+ * elements (every even length, odd ones up to 15) take one product per 16 such rows with a masked constant matrix
+ * (the masking that Section 4 proposes for arbitrary segment sizes; `in` 4-byte aligned, no workspace);
+ * reductions of 17 to 8160 elements otherwise take whole segments per workgroup and mask the data operand of the
+ * products row by row where a segment ends (the same masking moved from the constant matrix to the data; no
+ * workspace); reductions of 5 to 15 elements from arrays that are not 4-byte aligned and all scans run on fixed
+ * tiles of the array with the segment starts marked (the kernels of the
  * irregular calls below; they use the workspace), except scans of a multiple of 8 elements from 65536 on (the
  * chained scan) and of a multiple of 64 elements up to 8192 that fills a workgroup's tiles to four fifths (one
  * workgroup per segment; the tuning table can give it every multiple of 8 between 520 and 65528); longer
@@ -164,10 +167,13 @@ tcr_status tcr_irregular_scan_ex(const void *in, const uint64_t *offsets, void *
  * sum, sumsq: n/seg_len floats each, 4-byte aligned, distinct.  Every seg_len >= 1 that divides n, including
  * seg_len == n.  The sums of squares come from products of the data with itself on the matrix cores (exact
  * products, binary32 accumulation); both are exact for integer-valued inputs while the sums stay below 2^24.
- * Powers of two up to 512: a tile per wavefront like the reductions; other lengths from 17 to 2999: whole
- * segments per workgroup with the data operand masked row by row, the squares from the masked operand times
- * itself; from 9 to 15: the fixed tiles of the irregular kernels with both moments in one pass (they use the
- * workspace); longer ones: one wavefront per segment (per 65536-element piece of a long one).
+ * Powers of two up to 512: a tile per wavefront like the reductions; 3 to 30 elements that pack into rows of an
+ * even number of at most 32 elements: the masked constant matrix of tcr_segmented_reduce for the sums, and for the
+ * squares one product per segment of a row, of the row's elements of that segment with the row; other lengths
+ * from 17 to 2999: whole segments per workgroup with the data operand masked row by row, the squares from the
+ * masked operand times itself; 8 to 15 elements from arrays that are not 4-byte aligned: the fixed tiles of the
+ * irregular kernels with both moments in one pass (they use the workspace); longer ones: one wavefront per segment
+ * (per 65536-element piece of a long one).
  */
 tcr_status tcr_segmented_moments(const void *in, float *sum, float *sumsq, uint64_t n, uint64_t seg_len, void *stream);
 /* The same for irregular segments (offsets, n, nseg as for tcr_irregular_reduce; empty segments give 0 and 0):
@@ -198,9 +204,10 @@ tcr_status tcr_scan(const void *in, float *out, uint64_t n, void *stream);
  *                  paper's own kernels) | "lds_dma" (the same with gfx950's load from memory into LDS).  Applies
  *                  to tcr_segmented_reduce / tcr_segmented_scan with seg_len 16 .. 512 in their default launch
  *                  shape; kept for the measurement that chose "direct"
- *   "untuned_reduce" "rows" (default: reductions and moments of 17 .. 8160 elements, no power of two, as masked
- *                  row products) | "tiles" (the fixed tiles with marked segment starts / one wavefront per segment
- *                  that took these lengths before; kept as the measured alternative)
+ *   "untuned_reduce" "rows" (default: reductions and moments of 3 .. 8160 elements, no power of two, as products
+ *                  over rows of whole segments or masked rows of the array) | "tiles" (the fixed tiles with marked
+ *                  segment starts / one thread or one wavefront per segment that took these lengths before; kept
+ *                  as the measured alternative)
  *   "irregular_scan" "auto" (default: one kernel or two by the number of segments) | "single" (always the one
  *                  kernel of chained tiles) | "chain" (always two, where the launch allows it: default tile shape,
  *                  16-byte aligned arrays, matrix-core formulation)
@@ -222,9 +229,10 @@ tcr_status tcr_set_variant(const char *key, const char *value);
  *   longer powers of two and the one-segment operations (class 41): the launch shape -- scans: 12 shapes of
  *     share size, ticketed or not, persistent chain or not, plus the two multi-kernel carry strategies of
  *     tcr_set_variant("scan_carry"); reductions: span per wavefront and wavefronts combined -- and the formulation;
- *   every other length from 8 elements (class floor(log2(seg_len))): which kernel takes it -- scans: fixed tiles
- *     with marked starts (two tile shapes), one workgroup per segment, the chain on a per-segment tile grid;
- *     reductions: masked row products, fixed tiles (two shapes), one wavefront per segment over masked tiles.
+ *   every other length (class floor(log2(seg_len))): which kernel takes it -- scans: fixed tiles with marked
+ *     starts (two tile shapes), one workgroup per segment, the chain on a per-segment tile grid; reductions: rows
+ *     of whole segments (two launch shapes), masked row products, fixed tiles (two shapes), one wavefront per
+ *     segment over masked tiles.
  * tcr_autotune_irregular does the same for the tile shape of tcr_irregular_reduce (op 4; also used by
  * tcr_irregular_moments) and tcr_irregular_scan (op 5) on the caller's offsets.
  * Both SYNCHRONISE the stream and overwrite `out` with (correct) results several times; they are no-ops where

@@ -331,7 +331,7 @@ extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t 
     std::vector<int> cand;
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
         // lengths without a tuned path: which kernel takes them
-        if (seg_len < 8 || (is_pow2(seg_len) && seg_len <= 8)) return TCR_OK;
+        if (is_pow2(seg_len) && seg_len <= 8) return TCR_OK;
         for (int id = 0; id < (is_scan ? (int)kScanAnyCount : (int)kReduceAnyCount); ++id)
             if (is_scan ? scan_any_valid(id, seg_len) : reduce_any_valid(id, seg_len)) cand.push_back(id);
         return tune_entry(is_scan ? kTuneScanAny : kTuneReduceAny, floor_log2(seg_len), cand, call, s);

@@ -95,7 +95,7 @@ def _write(name: str, lines) -> None:
 
 TEMPLATE_NOTE = [
     "Template arguments: reduce_small<FORM,LOG2L,U,W,LOAD>, scan_small<FORM,LOG2L,U,W,MODE,LOAD>, reduce_span<FORM,U,W,COMBINE,FINISH>,",
-    "scan_block<FORM,U,W,CARRY,MODE>, scan_chain<FORM,U,W,MODE>, rows_reduce<KIND,U,W>, scan_half<U,W,CARRY,EXCL>; FORM 0 = MFMA, 1 = DPP;",
+    "scan_block<FORM,U,W,CARRY,MODE>, scan_chain<FORM,U,W,MODE>, rows_reduce<KIND,U,W>, packed_rows_reduce<KIND,U,W>, scan_half<U,W,CARRY,EXCL>; FORM 0 = MFMA, 1 = DPP;",
     "CARRY 0 = none, 1 = look-back; irregular_scan<U,W,REGULAR,MODE>, irregular_reduce<U,W,REGULAR,KIND> (REGULAR 1: regular segments",
     "of an untuned length; the context rows mix three offset arrays).",
 ]

@@ -204,11 +204,15 @@ def test_autotune_searches_every_class(tcr, oracle, data):
         tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:n100], out, 100)
         tcr.autotune(tcr.OP_SEGMENTED_REDUCE, xd[:n100], out, 100)
         tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:n3k], out, 3000)
+        n6 = (N // 6) * 6
+        tcr.autotune(tcr.OP_SEGMENTED_REDUCE, xd[:n6], out, 6)
         tcr.autotune_irregular(tcr.OP_IRREGULAR_REDUCE, xd[:N], od, out)
         tcr.autotune_irregular(tcr.OP_IRREGULAR_SCAN, xd[:N], od, out)
         tcr.autotune(tcr.OP_SEGMENTED_SCAN, xd[:N], out, 4)              # a single kernel: no entry
         table = dict(item.split("=") for item in tcr.tuning_export().split(";") if item)
-        assert set(table) == {"scan:6", "reduce:6", "scan_any:6", "reduce_any:6", "scan_any:11", "irregular:0", "irregular:1"}
+        assert set(table) == {"scan:6", "reduce:6", "scan_any:6", "reduce_any:6", "reduce_any:2", "scan_any:11", "irregular:0", "irregular:1"}
+        assert int(table["reduce_any:2"]) in (1, 2, 4, 5)                # rows of whole segments or tiles, two shapes each
+        assert np.array_equal(tcr.segmented_reduce(xd[:n6], 6).cpu().numpy().astype(np.float64), oracle.segmented_reduce(x[:n6], 6))
         assert int(table["scan:6"]) % 32 in range(4) and int(table["reduce:6"]) % 32 in range(4)
         assert int(table["reduce_any:6"]) in (0, 1, 2)                   # rows or tiles; the masked tiles start at 256
         assert int(table["scan_any:11"]) in (0, 1, 2)                    # tiles or one workgroup per segment
