@@ -263,3 +263,24 @@ def test_workspace_bytes_covers_the_tiled_kernels_behind_regular_calls(lib, n):
     assert area(lib.OP_SEGMENTED_SCAN, 1) >= 8 * -(-n // 16384)
     assert area(lib.OP_SEGMENTED_REDUCE, 1) >= 4 * -(-n // 65536) * 2
     assert area(lib.OP_REDUCE, 0) >= 4 * -(-n // 4096)                     # one segment: a partial per wavefront span
+
+
+def test_cxx_header_compiles_and_forwards_every_call(lib, tmp_path):
+    # include/tcr.hpp: the paper's API names (Section 6) as inline calls of the C ABI; C++11, warnings as errors
+    import shutil
+    import subprocess
+    from paper_1811_09736_amd import build as b
+    if shutil.which("g++") is None:
+        pytest.skip("no g++")
+    exe = str(tmp_path / "cxx_api")
+    cmd = ["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-I" + os.path.join(ROOT, "include"), "-o", exe,
+           os.path.join(ROOT, "tests", "sanitize", "cxx_api_driver.cpp"), b.LIB_PATH, "-Wl,-rpath," + os.path.dirname(b.LIB_PATH)]
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert proc.returncode == 0, proc.stdout[-3000:]
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert run.returncode == 0 and run.stdout.strip().endswith("ok"), run.stdout[-3000:]
+    # every entry point of the operations has a wrapper
+    text = open(os.path.join(ROOT, "include", "tcr.hpp")).read()
+    for name in ("tcr_segmented_reduce", "tcr_reduce", "tcr_segmented_scan", "tcr_scan", "tcr_segmented_scan_ex", "tcr_scan_ex",
+                 "tcr_irregular_reduce", "tcr_irregular_scan", "tcr_irregular_scan_ex", "tcr_segmented_moments", "tcr_irregular_moments"):
+        assert name + "(" in text, name
