@@ -64,7 +64,7 @@ typedef enum {
  * out: n/seg_len floats, 4-byte aligned.  n == 0 is a no-op.  seg_len must divide n.
  * Every seg_len >= 1 is accepted; the tuned paths are the powers of two from 16 upwards and
  * seg_len == n.  Other lengths: reductions of 3 to 30 elements that pack into rows of an even number of at most 32
- * elements (every even length, odd ones up to 15) take one product per 16 such rows with a masked constant matrix
+ * elements (every even length that is no power of two, 4 and 8, odd ones up to 15) take one product per 16 such rows with a masked constant matrix
  * (the masking that Section 4 proposes for arbitrary segment sizes; `in` 4-byte aligned, no workspace);
  * reductions of 17 to 8160 elements otherwise take whole segments per workgroup and mask the data operand of the
  * products row by row where a segment ends (the same masking moved from the constant matrix to the data; no

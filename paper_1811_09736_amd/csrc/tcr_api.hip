@@ -331,7 +331,7 @@ extern "C" tcr_status tcr_autotune(int op, const void* in, float* out, uint64_t 
     std::vector<int> cand;
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
         // lengths without a tuned path: which kernel takes them
-        if (is_pow2(seg_len) && seg_len <= 8) return TCR_OK;
+        if (is_pow2(seg_len) && seg_len <= 8 && (is_scan || seg_len < 4)) return TCR_OK;     // (a single kernel)
         for (int id = 0; id < (is_scan ? (int)kScanAnyCount : (int)kReduceAnyCount); ++id)
             if (is_scan ? scan_any_valid(id, seg_len) : reduce_any_valid(id, seg_len)) cand.push_back(id);
         return tune_entry(is_scan ? kTuneScanAny : kTuneReduceAny, floor_log2(seg_len), cand, call, s);
@@ -434,8 +434,9 @@ extern "C" const char* tcr_kernel_name(int op, uint64_t n, uint64_t seg_len) {
     if (!whole && (!is_pow2(seg_len) || seg_len < 16)) {
         if (op != 0 && op != 1) return "";
         if (op == 0) {
-            if (is_pow2(seg_len) && seg_len <= 8) return "tiny_reduce_kernel";       // (16-byte aligned results)
             const int pick = pick_reduce_any(seg_len);
+            if (is_pow2(seg_len) && seg_len <= 8 && pick != kReduceAnyPacked && pick != kReduceAnyPackedAlt)
+                return "tiny_reduce_kernel";                                         // (16-byte aligned results)
             if (pick == kReduceAnyPacked || pick == kReduceAnyPackedAlt) return "packed_rows_reduce_kernel";
             if (seg_len < kTiledReduceMin) return "generic_thread_kernel";
             if (pick == kReduceAnyRows) return "rows_reduce_kernel";

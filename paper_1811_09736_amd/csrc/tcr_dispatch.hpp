@@ -761,7 +761,12 @@ inline tcr_status launch_rows_reduce(const _Float16* in, float* out, float* out2
 // Two launch shapes: eight tiles per wavefront where a row's width is no multiple of 8 (rows of 18 elements: 99
 // against 113 us; 22: 97 against 105; 26 to 30: 94-96 against 97-99), four where it is (24: 90 against 96 us); twelve
 // or sixteen tiles, or two or eight wavefronts, change nothing.  (U, W) = (8, 4) and (4, 4).
-inline bool packed_reduce_takes(uint64_t seg_len) { return g_variant.rows_reduce && packed_per_row(seg_len) != 0 && !is_pow2(seg_len); }
+// (4 and 8 elements as well: sums 117 and 102 us against 125 and 110 for the kernel with whole segments inside a
+// lane's eight elements, both moments 208 and 128 against 272 and 219 with one thread per segment; 2 elements: 178
+// against 167 us, and 16 rows of P for the squares -- left where they are)
+inline bool packed_reduce_takes(uint64_t seg_len) {
+    return g_variant.rows_reduce && packed_per_row(seg_len) != 0 && (!is_pow2(seg_len) || seg_len == 4 || seg_len == 8);
+}
 template <int KIND, int U, int W>
 inline void launch_packed_shape(const _Float16* in, float* out, float* out2, const PackedGrid& grid, hipStream_t s) {
     const uint64_t rows = ceil_div(grid.nseg, (uint64_t)grid.per_row);
@@ -828,7 +833,10 @@ inline tcr_status launch_generic(const _Float16* in, void* out, uint64_t n, uint
     const bool excl = (flags & TCR_SCAN_EXCLUSIVE) != 0, f16 = (flags & TCR_OUT_F16) != 0;
     // 1, 2, 4 or 8 elements (scans: the plain binary32 inclusive one): whole segments inside a lane's 8 elements.
     // `out` is 16-byte aligned for scans; reductions need it for their 128-bit stores.
-    if (is_pow2(seg_len) && seg_len <= 8 && (SCAN ? flags == 0 : aligned(out, 16))) {
+    // 4 and 8 elements: reductions on rows of whole segments unless the tuning table or the variant says otherwise
+    const bool packed_first = !SCAN && (seg_len == 4 || seg_len == 8) && packed_reduce_takes(seg_len) && aligned(in, 4) &&
+                              (pick_reduce_any(seg_len) == kReduceAnyPacked || pick_reduce_any(seg_len) == kReduceAnyPackedAlt);
+    if (is_pow2(seg_len) && seg_len <= 8 && !packed_first && (SCAN ? flags == 0 : aligned(out, 16))) {
         const dim3 grid((unsigned)ceil_div(n, (uint64_t)kGenericThreads * 8)), block(kGenericThreads);
         float* o = static_cast<float*>(out);
         if constexpr (SCAN) {

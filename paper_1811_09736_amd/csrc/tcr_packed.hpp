@@ -1,4 +1,4 @@
-// Regular segments of 3 to 30 elements whose length is no power of two: sums (and sums of squares) as ONE product
+// Regular segments of 3 to 30 elements (no power of two, or 4 or 8): sums (and sums of squares) as ONE product
 // per 16 rows with a masked constant matrix, the rows laid out by the segments instead of by the array.
 //
 // The paper reduces segments that do not fill a tile row by masking the constant matrix P (Section 4, "Support for

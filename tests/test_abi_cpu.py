@@ -132,14 +132,15 @@ def test_dispatch_by_segment_length(lib):
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 48) == "irregular_scan_kernel<regular>"     # untuned lengths: fixed tiles
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 1) == "tiny_scan_kernel"
     assert k(lib.OP_SEGMENTED_SCAN, 48000, 8) == "tiny_scan_kernel"
-    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
-    for seg in (3, 5, 6, 7, 9, 12, 15, 18, 24, 30):        # rows of whole segments, an even number of at most 32 elements
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 2) == "tiny_reduce_kernel"
+    for seg in (3, 4, 5, 6, 7, 8, 9, 12, 15, 18, 24, 30):        # rows of whole segments, an even number of at most 32 elements
         assert k(lib.OP_SEGMENTED_REDUCE, seg * 1000, seg) == "packed_rows_reduce_kernel"
     for seg in (17, 25, 31, 33, 48, 999, 1001, 8160):      # masked rows of the array, whole segments per workgroup
         assert k(lib.OP_SEGMENTED_REDUCE, seg * 5, seg) == "rows_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 8168 * 5, 8168) == "masked_wave_reduce_kernel"
     lib.set_variant("untuned_reduce", "tiles")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 3) == "generic_thread_kernel"
+    assert k(lib.OP_SEGMENTED_REDUCE, 48000, 8) == "tiny_reduce_kernel"
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 6).startswith("irregular_reduce_kernel<regular>")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 12).startswith("irregular_reduce_kernel<regular>+")
     assert k(lib.OP_SEGMENTED_REDUCE, 48000, 48).startswith("irregular_reduce_kernel<regular>+")

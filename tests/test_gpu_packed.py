@@ -1,4 +1,4 @@
-"""Regular segments of 3 to 30 elements that are no power of two (packed_rows_reduce_kernel: rows of m whole segments,
+"""Regular segments of 3 to 30 elements that are no power of two, or 4 or 8 (packed_rows_reduce_kernel: rows of m whole segments,
 m * seg_len even and at most 32, one product per 16 rows with a masked constant matrix): tcr_segmented_reduce and
 tcr_segmented_moments against the oracle.
 
@@ -16,7 +16,7 @@ from paper_1811_09736_amd import workloads
 
 pytestmark = pytest.mark.gpu
 
-LENGTHS = [3, 5, 6, 7, 9, 10, 11, 12, 13, 14, 15, 18, 20, 22, 24, 26, 28, 30]
+LENGTHS = [3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 18, 20, 22, 24, 26, 28, 30]
 PACKED, PACKED_ALT, ROWS, TILES = 4, 5, 0, 1
 
 
@@ -126,6 +126,18 @@ def test_the_earlier_kernels_stay_available(tcr, oracle):
     finally:
         tcr.tuning_import("")
     assert np.array_equal(tcr.segmented_reduce(xd, 12).cpu().numpy().astype(np.float64), ref)
+    # 4 and 8 elements: whole segments inside a lane's eight elements, one thread per segment for the moments
+    for seg in (4, 8):
+        m = x.size // seg * seg
+        ref, (ra, rq) = oracle.segmented_reduce(x[:m], seg), oracle.segmented_moments(x[:m], seg)
+        tcr.set_variant("untuned_reduce", "tiles")
+        try:
+            assert tcr.kernel_name(tcr.OP_SEGMENTED_REDUCE, m, seg) == "tiny_reduce_kernel"
+            assert np.array_equal(tcr.segmented_reduce(xd[:m], seg).cpu().numpy().astype(np.float64), ref)
+            a, q = tcr.segmented_moments(xd[:m], seg)
+            assert np.array_equal(a.cpu().numpy().astype(np.float64), ra) and np.array_equal(q.cpu().numpy().astype(np.float64), rq)
+        finally:
+            tcr.set_variant("reset")
 
 
 @pytest.mark.parametrize("seg", [5, 12, 30])
